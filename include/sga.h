@@ -1,0 +1,174 @@
+/*
+ * sga -- sparse graph attention for AMD MI355X (gfx950).  C ABI of libsga.so.
+ *
+ * The library computes masked attention as a graph computation (Section IV of
+ * "Longer Attention Span: Increasing Transformer Context Length with Sparse
+ * Graph Processing Techniques"): tokens are vertices carrying (Q_i, K_i, V_i),
+ * the 0/1 attention mask A (rows = queries, columns = keys) is the edge set,
+ * and for every query row i only the edges (i, j) with A_ij = 1 are visited
+ * (Algorithm 1): W = scale * (Q_i . K_j), a numerically stable running softmax
+ * over the row's neighbours, and the softmax-weighted sum of the V_j rows.
+ *
+ * Conventions that hold for every entry point
+ *   - Pointers marked "device" are device (HBM) addresses owned by the caller;
+ *     pointers marked "host" are ordinary host addresses.  The library never
+ *     allocates, frees or retains memory and keeps no state between calls.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls enqueue work on it and return without synchronising the host.
+ *   - Argument errors are detected on the host before anything is enqueued and
+ *     reported as a negative sga_status; nothing is thrown.  HIP launch errors
+ *     map to SGA_ERR_HIP.
+ *   - Tensors Q, K, V, O are [H][L][d] row-major (one contiguous L x d matrix per
+ *     head: the single-head problem of Algorithm 1 repeated H times with one
+ *     shared mask).  Storage is fp32 or IEEE fp16; all arithmetic accumulates in
+ *     fp32; an fp16 output is rounded once (to nearest even) at the store.
+ *   - CSR: row_ptr is int64 [L+1] (edge counts can pass 2^31), col_idx is int32
+ *     [nnz] (L < 2^31).  row_ptr[0] = 0, non-decreasing; within a row col_idx is
+ *     strictly increasing and in [0, L).  Duplicate or out-of-range columns are
+ *     undefined behaviour of the forward.
+ *   - A row with no neighbour yields O_i = 0 and lse_i = -inf (the initial state
+ *     of Algorithm 1: O = 0, l = 0, m = -inf).
+ *   - Supported head dimension: d = 64.
+ */
+#ifndef SGA_H_
+#define SGA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  SGA_OK = 0,
+  SGA_ERR_INVALID_ARG = -1,
+  SGA_ERR_UNSUPPORTED = -2,
+  SGA_ERR_WORKSPACE = -3,
+  SGA_ERR_OVERFLOW = -4,
+  SGA_ERR_HIP = -5
+} sga_status;
+
+/* Storage type of Q, K, V and O.  Accumulation is always fp32. */
+typedef enum { SGA_F32 = 0, SGA_F16 = 1 } sga_dtype;
+
+/* Mask families of Section II-C. */
+typedef enum {
+  SGA_MASK_SLIDING = 0,      /* local window:   |i-j| <= window                          */
+  SGA_MASK_DILATED = 1,      /* 1-D dilated:    (i-j) mod stride == 0, |i-j| <= window*stride
+                                (the paper's dilation factor r is stride-1)               */
+  SGA_MASK_GLOBAL_LOCAL = 2, /* local window plus global tokens 0..n_global-1, symmetric:
+                                |i-j| <= window  or  i < n_global  or  j < n_global       */
+  SGA_MASK_BIGBIRD = 3       /* block mask (block x block tiles, L % block == 0):
+                                query blocks 0..n_global_blocks-1 attend every key block;
+                                every other query block b attends the global key blocks,
+                                key blocks b-window_blocks..b+window_blocks, and
+                                n_random_blocks further distinct key blocks chosen by the
+                                counter-based generator described at sga_build_mask      */
+} sga_mask_kind;
+
+/* Attention-specific parameters P_a of Algorithm 1.  Plain data, host memory. */
+typedef struct {
+  uint32_t struct_bytes;     /* = sizeof(sga_mask_desc); rejects mismatched layouts       */
+  int32_t kind;              /* sga_mask_kind                                             */
+  int64_t L;                 /* context length, 1 <= L < 2^31                             */
+  int32_t window;            /* half-width in steps, >= 0                                 */
+  int32_t stride;            /* >= 1; only DILATED reads it (others behave as stride 1)   */
+  int32_t n_global;          /* GLOBAL_LOCAL: 0 <= n_global <= L                          */
+  int32_t block;             /* BIGBIRD: block edge in tokens, 1..1024                    */
+  int32_t window_blocks;     /* BIGBIRD                                                   */
+  int32_t n_global_blocks;   /* BIGBIRD                                                   */
+  int32_t n_random_blocks;   /* BIGBIRD: 0..16; needs L/block >= 2*window_blocks+1
+                                + n_global_blocks + n_random_blocks                       */
+  uint64_t seed;             /* BIGBIRD                                                   */
+} sga_mask_desc;
+
+/* Which kernels the forward may use (tests pin one; callers pass SGA_PATH_AUTO). */
+typedef enum {
+  SGA_PATH_AUTO = 0,    /* tile path where the mask is block-dense enough, gather elsewhere */
+  SGA_PATH_GATHER = 1,  /* one wavefront per query row, per-edge K/V row gathers           */
+  SGA_PATH_TILE = 2     /* 32x32 MFMA tiles with per-tile bit masks; rows whose tile does
+                           not qualify still go through the gather kernels                */
+} sga_path;
+
+const char* sga_status_string(sga_status s);
+
+/*
+ * Edge count of a mask in closed form (NNZ of the sparsity factor S_f = NNZ/L^2,
+ * Section II-D).  desc: host.  nnz_out: host.  No device work.
+ * Errors: SGA_ERR_INVALID_ARG for a null pointer, wrong struct_bytes or parameters
+ * outside the ranges stated at sga_mask_desc.
+ */
+sga_status sga_mask_nnz(const sga_mask_desc* desc, int64_t* nnz_out);
+
+/*
+ * Mask -> graph (explicit form of Get_Neighbors, Section IV-B "CSR"): writes
+ * the CSR of the mask, row offsets and sorted column indices; the mask is
+ * binary so no values vector exists.
+ *   row_ptr  device, int64 [L+1], written
+ *   col_idx  device, int32 [col_capacity], the first nnz entries are written
+ *   col_capacity must be >= the count sga_mask_nnz returns (else SGA_ERR_WORKSPACE).
+ * Random key blocks of SGA_MASK_BIGBIRD: with mix64 the splitmix64 output
+ * function and GOLD = 0x9E3779B97F4A7C15, query block b owns the stream key
+ * mix64(seed + GOLD*(b+1)); attempts a = 0, 1, 2, ... propose key block
+ * mix64(key + GOLD*(a+1)) mod (L/block), rejected when that block is already
+ * attended (window, global or an earlier pick), until n_random_blocks are taken.
+ * The result is bit-reproducible: one correct byte image per desc.
+ */
+sga_status sga_build_mask(const sga_mask_desc* desc, int64_t* row_ptr, int32_t* col_idx,
+                          int64_t col_capacity, void* stream);
+
+/*
+ * Workspace size the forward calls can use for the given problem.
+ *   nnz: edge count of the explicit mask, or -1 for the implicit entry point.
+ * bytes_out (host) receives a size that is sufficient for every path; a smaller
+ * (or null) workspace is legal and only disables the split-row and tile paths.
+ */
+sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, int64_t nnz,
+                               size_t* bytes_out);
+
+/*
+ * Algorithm 1 over an explicit CSR mask (Section IV-B): for every head h and row i
+ *   O[h][i] = sum_j softmax_j( scale * Q[h][i].K[h][j] ) V[h][j],  j in col_idx[row_ptr[i]..row_ptr[i+1])
+ * with the running-max / running-sum recurrence of Algorithm 1 (any evaluation
+ * order of the recurrence gives the same real number; results are deterministic
+ * run to run for a given workspace size).
+ *   Q, K, V   device, [H][L][d], dtype storage, read only
+ *   row_ptr   device, int64 [L+1];  col_idx  device, int32 [row_ptr[L]]
+ *   O         device, [H][L][d], dtype storage, written
+ *   scale     multiplies the fp32 dot product (Eq. 1 uses 1/sqrt(d_k))
+ *   dtype     sga_dtype
+ *   lse       device, float [H][L], optional (NULL): m_i + ln l_i of the row
+ *   workspace device, 256-byte aligned, optional (NULL): partial states of split
+ *             high-degree rows and per-tile block lists.  Its contents need not be
+ *             preserved between calls; concurrent calls need separate workspaces.
+ *   path      sga_path
+ * Errors: SGA_ERR_INVALID_ARG (null pointer, L < 1 or >= 2^31, H < 1, unknown
+ * dtype/path, misaligned pointers), SGA_ERR_UNSUPPORTED (d != 64),
+ * SGA_ERR_WORKSPACE (path = SGA_PATH_TILE without a sufficient workspace).
+ */
+sga_status sga_attention_forward(const void* Q, const void* K, const void* V,
+                                 const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                 int64_t L, int32_t H, int32_t d, float scale, void* stream,
+                                 int32_t dtype, float* lse, void* workspace,
+                                 size_t workspace_bytes, int32_t path);
+
+/*
+ * Algorithm 1 with an implicit mask (Section IV-B "Local", "1D Dilation"): the
+ * neighbours of row i are computed from desc inside the kernel (index
+ * arithmetic, no stored graph), so memory stays O(L) and L is bounded only by
+ * Q, K, V, O themselves.  Supports SGA_MASK_SLIDING and SGA_MASK_DILATED;
+ * other kinds return SGA_ERR_UNSUPPORTED (build their CSR instead).
+ * Arguments as in sga_attention_forward; desc: host; desc->L must equal L.
+ * Element offsets are 64-bit (L*d may pass 2^31).
+ */
+sga_status sga_attention_forward_implicit(const void* Q, const void* K, const void* V,
+                                          const sga_mask_desc* desc, void* O, int64_t L,
+                                          int32_t H, int32_t d, float scale, void* stream,
+                                          int32_t dtype, float* lse, void* workspace,
+                                          size_t workspace_bytes, int32_t path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SGA_H_ */

@@ -1,0 +1,20 @@
+"""sga: sparse graph attention for AMD MI355X (gfx950).
+
+Thin Python binding over the C ABI of libsga.so (include/sga.h).  Every step of
+the attention path runs in the HIP kernels; Python only marshals arguments, and
+PyTorch only provides device memory and streams.
+"""
+from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, load, lib_path,
+                      mask_nnz, build_mask, workspace_bytes, alloc_workspace,
+                      attention_forward, attention_forward_implicit,
+                      sga_mask_nnz, sga_build_mask, sga_workspace_bytes,
+                      sga_attention_forward, sga_attention_forward_implicit,
+                      sga_status_string)
+
+__all__ = [
+    "SgaError", "PATH_AUTO", "PATH_GATHER", "PATH_TILE", "load", "lib_path",
+    "mask_nnz", "build_mask", "workspace_bytes", "alloc_workspace",
+    "attention_forward", "attention_forward_implicit",
+    "sga_mask_nnz", "sga_build_mask", "sga_workspace_bytes",
+    "sga_attention_forward", "sga_attention_forward_implicit", "sga_status_string",
+]

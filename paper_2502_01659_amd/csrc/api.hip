@@ -1,0 +1,111 @@
+// C ABI of libsga.so: argument validation and dispatch.  See include/sga.h for the contract.
+#include "sga_internal.h"
+
+using namespace sga;
+
+namespace {
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+sga_status check_common(const void* Q, const void* K, const void* V, const void* O, int64_t L,
+                        int32_t H, int32_t d, int32_t dtype, int32_t path, const void* ws,
+                        size_t ws_bytes) {
+  if (!Q || !K || !V || !O) return SGA_ERR_INVALID_ARG;
+  if (L < 1 || L >= (int64_t(1) << 31) || H < 1 || H > 65535) return SGA_ERR_INVALID_ARG;
+  if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
+  if (path != SGA_PATH_AUTO && path != SGA_PATH_GATHER && path != SGA_PATH_TILE)
+    return SGA_ERR_INVALID_ARG;
+  if (d != kHeadDim) return SGA_ERR_UNSUPPORTED;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return SGA_ERR_INVALID_ARG;
+  if (ws && (reinterpret_cast<uintptr_t>(ws) & 255u)) return SGA_ERR_INVALID_ARG;
+  if (!ws && ws_bytes != 0) return SGA_ERR_INVALID_ARG;
+  return SGA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* sga_status_string(sga_status s) {
+  switch (s) {
+    case SGA_OK: return "ok";
+    case SGA_ERR_INVALID_ARG: return "invalid argument";
+    case SGA_ERR_UNSUPPORTED: return "unsupported configuration";
+    case SGA_ERR_WORKSPACE: return "workspace or output capacity too small";
+    case SGA_ERR_OVERFLOW: return "size overflow";
+    case SGA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+sga_status sga_mask_nnz(const sga_mask_desc* desc, int64_t* nnz_out) {
+  if (!nnz_out) return SGA_ERR_INVALID_ARG;
+  const sga_status st = mask_validate(desc);
+  if (st != SGA_OK) return st;
+  *nnz_out = mask_total_edges(*desc);
+  return SGA_OK;
+}
+
+sga_status sga_build_mask(const sga_mask_desc* desc, int64_t* row_ptr, int32_t* col_idx,
+                          int64_t col_capacity, void* stream) {
+  const sga_status st = mask_validate(desc);
+  if (st != SGA_OK) return st;
+  if (!row_ptr || !col_idx) return SGA_ERR_INVALID_ARG;
+  if (col_capacity < mask_total_edges(*desc)) return SGA_ERR_WORKSPACE;
+  return launch_build_mask(*desc, row_ptr, col_idx, static_cast<hipStream_t>(stream));
+}
+
+sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, int64_t nnz,
+                               size_t* bytes_out) {
+  if (!bytes_out) return SGA_ERR_INVALID_ARG;
+  if (L < 1 || L >= (int64_t(1) << 31) || H < 1 || H > 65535) return SGA_ERR_INVALID_ARG;
+  if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
+  if (d != kHeadDim) return SGA_ERR_UNSUPPORTED;
+  if (nnz < -1 || nnz > L * L) return SGA_ERR_INVALID_ARG;
+  *bytes_out = plan_workspace(L, H, nnz).total_bytes;
+  return SGA_OK;
+}
+
+sga_status sga_attention_forward(const void* Q, const void* K, const void* V, const int64_t* row_ptr,
+                                 const int32_t* col_idx, void* O, int64_t L, int32_t H, int32_t d,
+                                 float scale, void* stream, int32_t dtype, float* lse,
+                                 void* workspace, size_t workspace_bytes, int32_t path) {
+  const sga_status st = check_common(Q, K, V, O, L, H, d, dtype, path, workspace, workspace_bytes);
+  if (st != SGA_OK) return st;
+  if (!row_ptr || !col_idx) return SGA_ERR_INVALID_ARG;
+  AttnArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
+  a.L = L; a.H = H; a.scale = scale; a.dtype = dtype;
+  a.stream = static_cast<hipStream_t>(stream);
+  a.row_ptr = row_ptr; a.col_idx = col_idx;
+  a.ws = workspace; a.ws_bytes = workspace_bytes;
+  if (path == SGA_PATH_TILE && (!workspace || workspace_bytes < 256)) return SGA_ERR_WORKSPACE;
+  if (workspace && workspace_bytes >= 256) clear_workspace_counters(workspace, a.stream);
+  if (path == SGA_PATH_GATHER) return launch_gather_explicit(a, true, nullptr);
+  return launch_tile_explicit(a);
+}
+
+sga_status sga_attention_forward_implicit(const void* Q, const void* K, const void* V,
+                                          const sga_mask_desc* desc, void* O, int64_t L, int32_t H,
+                                          int32_t d, float scale, void* stream, int32_t dtype,
+                                          float* lse, void* workspace, size_t workspace_bytes,
+                                          int32_t path) {
+  sga_status st = check_common(Q, K, V, O, L, H, d, dtype, path, workspace, workspace_bytes);
+  if (st != SGA_OK) return st;
+  st = mask_validate(desc);
+  if (st != SGA_OK) return st;
+  if (desc->L != L) return SGA_ERR_INVALID_ARG;
+  if (desc->kind != SGA_MASK_SLIDING && desc->kind != SGA_MASK_DILATED) return SGA_ERR_UNSUPPORTED;
+  AttnArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
+  a.L = L; a.H = H; a.scale = scale; a.dtype = dtype;
+  a.stream = static_cast<hipStream_t>(stream);
+  a.stride = desc->kind == SGA_MASK_DILATED ? desc->stride : 1;
+  const int64_t wmax = (L - 1) / a.stride;
+  a.window = (int32_t)(desc->window < wmax ? desc->window : wmax);
+  a.ws = workspace; a.ws_bytes = workspace_bytes;
+  if (path == SGA_PATH_GATHER) return launch_gather_implicit(a);
+  return launch_tile_implicit(a);
+}
+
+}  // extern "C"

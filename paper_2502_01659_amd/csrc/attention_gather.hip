@@ -1,0 +1,414 @@
+// Gather path of Algorithm 1: one wavefront per query row, per-edge K/V row gathers.
+//
+// Lane layout (d = 64).  A K or V row is 256 B (fp32) or 128 B (fp16); a group of
+// LPK lanes reads one row with one 16-byte load per lane (LPK = 16 for fp32, 8 for fp16),
+// so a wavefront pulls G = 64/LPK rows per load instruction and every row is a fully
+// coalesced 128/256-byte gather.  The dot product Q_i.K_j is reduced inside the lane
+// group with DPP adds (no LDS); each group keeps its own running (m, l, acc) state of
+// the recurrence in Algorithm 1 for the keys it has seen, and the G group states are
+// merged with wavefront shuffles once per row.  The accumulator is kept un-normalised
+// and divided by l once at the end, which is the same real number as the per-step
+// normalisation printed in Algorithm 1.
+//
+// Rows with more than kSplitThreshold neighbours (global tokens) are split into chunks
+// that separate wavefronts reduce to partial (m, l, acc) states; a merge kernel combines
+// the partials in chunk order, so the result is deterministic.
+#include "sga_internal.h"
+
+namespace sga {
+namespace {
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kMinusHuge = -1.0e30f;   // finite stand-in for m = -inf (keeps m - m finite)
+constexpr int kUnroll = 4;               // keys per lane group per loop trip
+
+template <int CTRL>
+__device__ __forceinline__ float dpp(float x) {
+  return __builtin_bit_cast(
+      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, false));
+}
+
+// Sum over the LPK consecutive lanes of a group; every lane of the group gets the total.
+template <int LPK>
+__device__ __forceinline__ float group_sum(float x) {
+  x += dpp<0xB1>(x);    // quad_perm [1,0,3,2]
+  x += dpp<0x4E>(x);    // quad_perm [2,3,0,1]
+  x += dpp<0x141>(x);   // row_half_mirror: lane k <-> 7-k of each 8
+  if (LPK == 16) x += dpp<0x140>(x);  // row_mirror: lane k <-> 15-k of each 16
+  return x;
+}
+
+template <typename T>
+struct Row;
+
+template <>
+struct Row<float> {
+  static constexpr int LPK = 16, VEC = 4;
+  __device__ static void load(const float* p, float (&v)[4]) {
+    const float4 t = *reinterpret_cast<const float4*>(p);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+  }
+  __device__ static void store(float* p, const float (&v)[4]) {
+    *reinterpret_cast<float4*>(p) = make_float4(v[0], v[1], v[2], v[3]);
+  }
+};
+
+template <>
+struct Row<__half> {
+  static constexpr int LPK = 8, VEC = 8;
+  __device__ static void load(const __half* p, float (&v)[8]) {
+    const uint4 t = *reinterpret_cast<const uint4*>(p);
+    const uint32_t w[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const __half2 h = __builtin_bit_cast(__half2, w[k]);
+      v[2 * k] = __low2float(h);
+      v[2 * k + 1] = __high2float(h);
+    }
+  }
+  __device__ static void store(__half* p, const float (&v)[8]) {
+    uint32_t w[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k)
+      w[k] = __builtin_bit_cast(uint32_t, __floats2half2_rn(v[2 * k], v[2 * k + 1]));
+    *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+};
+
+__device__ __forceinline__ void store_scalar(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_scalar(__half* p, float v) { *p = __float2half_rn(v); }
+
+struct CsrNeighbours {      // Get_Neighbors, explicit: slice of col_idx
+  const int32_t* cols;
+  __device__ int64_t operator()(int64_t e) const { return cols[e]; }
+};
+
+struct WindowNeighbours {   // Get_Neighbors, implicit: j = first + e*step
+  int64_t first, step;
+  __device__ int64_t operator()(int64_t e) const { return first + e * step; }
+};
+
+// Running state of one lane group for the channels this lane owns.
+template <int VEC>
+struct State {
+  float m, l, acc[VEC];
+  __device__ void init() {
+    m = kMinusHuge;
+    l = 0.f;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
+  }
+};
+
+// Visit edges [e0, e1) of one row.  q holds this lane's channels of Q_i * scale * log2(e).
+template <typename T, typename Nbr>
+__device__ __forceinline__ void attend_range(const T* __restrict__ Kh, const T* __restrict__ Vh,
+                                             const float (&q)[Row<T>::VEC], const Nbr& nbr,
+                                             int64_t e0, int64_t e1, int lane,
+                                             State<Row<T>::VEC>& st) {
+  constexpr int LPK = Row<T>::LPK, VEC = Row<T>::VEC, G = kWave / LPK;
+  const int grp = lane / LPK;
+  const int cofs = (lane % LPK) * VEC;
+  for (int64_t base = e0; base < e1; base += G * kUnroll) {
+    float kf[kUnroll][VEC], vf[kUnroll][VEC];
+    bool valid[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const int64_t e = base + u * G + grp;
+      valid[u] = e < e1;
+      const int64_t j = nbr(valid[u] ? e : e1 - 1);   // out-of-range lanes re-read a real neighbour
+      Row<T>::load(Kh + j * kHeadDim + cofs, kf[u]);
+      Row<T>::load(Vh + j * kHeadDim + cofs, vf[u]);
+    }
+    float s[kUnroll];
+    float smax = st.m;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      float part = 0.f;
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) part = __builtin_fmaf(q[c], kf[u][c], part);
+      part = group_sum<LPK>(part);
+      s[u] = valid[u] ? part : -INFINITY;
+      smax = fmaxf(smax, s[u]);
+    }
+    const float alpha = __builtin_amdgcn_exp2f(st.m - smax);
+    st.l *= alpha;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) st.acc[c] *= alpha;
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const float p = __builtin_amdgcn_exp2f(s[u] - smax);
+      st.l += p;
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) st.acc[c] = __builtin_fmaf(p, vf[u][c], st.acc[c]);
+    }
+    st.m = smax;
+  }
+}
+
+// Merge the G lane-group states of a wavefront; afterwards every group holds the row's state.
+template <int LPK, int VEC>
+__device__ __forceinline__ void merge_groups(State<VEC>& st) {
+#pragma unroll
+  for (int off = LPK; off < kWave; off <<= 1) {
+    const float m2 = __shfl_xor(st.m, off, kWave);
+    const float l2 = __shfl_xor(st.l, off, kWave);
+    const float mn = fmaxf(st.m, m2);
+    const float a1 = __builtin_amdgcn_exp2f(st.m - mn);
+    const float a2 = __builtin_amdgcn_exp2f(m2 - mn);
+    st.l = st.l * a1 + l2 * a2;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+      const float o = __shfl_xor(st.acc[c], off, kWave);
+      st.acc[c] = st.acc[c] * a1 + o * a2;
+    }
+    st.m = mn;
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ void load_query(const T* Qrow, float scale, int lane,
+                                           float (&q)[Row<T>::VEC]) {
+  Row<T>::load(Qrow + (lane % Row<T>::LPK) * Row<T>::VEC, q);
+  const float c = scale * kLog2e;
+#pragma unroll
+  for (int k = 0; k < Row<T>::VEC; ++k) q[k] *= c;
+}
+
+template <typename T>
+__device__ __forceinline__ void finish_row(T* Orow, float* lse_i, int lane,
+                                           State<Row<T>::VEC>& st) {
+  constexpr int LPK = Row<T>::LPK, VEC = Row<T>::VEC;
+  merge_groups<LPK, VEC>(st);
+  const bool empty = !(st.l > 0.f);
+  const float inv = empty ? 0.f : 1.0f / st.l;
+  float o[VEC];
+#pragma unroll
+  for (int c = 0; c < VEC; ++c) o[c] = st.acc[c] * inv;
+  if (lane < LPK) Row<T>::store(Orow + lane * VEC, o);
+  if (lse_i && lane == 0)
+    *lse_i = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(st.l)) * kLn2;
+}
+
+__host__ __device__ inline void split_shape(int64_t deg, int32_t& nchunks, int32_t& len) {
+  int64_t n = (deg + kSplitChunk - 1) / kSplitChunk;
+  if (n > kMaxSplit) n = kMaxSplit;
+  int64_t l = (deg + n - 1) / n;
+  l = (l + 31) / 32 * 32;
+  len = (int32_t)l;
+  nchunks = (int32_t)((deg + l - 1) / l);
+}
+
+// ---- kernels ----------------------------------------------------------------
+
+__global__ void clear_counters_kernel(uint32_t* ctr) {
+  if (threadIdx.x < kNumCounters) ctr[threadIdx.x] = 0;
+}
+
+// One thread per row: rows over the split threshold reserve chunk work items.
+__global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __restrict__ row_ptr,
+                                                            int64_t L, int32_t H, void* ws,
+                                                            size_t ws_bytes) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= L) return;
+  const int64_t deg = row_ptr[i + 1] - row_ptr[i];
+  if (deg <= kSplitThreshold) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  if (pl.total_bytes > ws_bytes) return;
+  uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
+  int32_t n, len;
+  split_shape(deg, n, len);
+  atomicAdd(&ctr[kCtrChunksNeeded], (uint32_t)n);
+  const uint32_t base = atomicAdd(&ctr[kCtrItemsAlloc], (uint32_t)n);
+  if ((int64_t)base + n > pl.cap_items) return;
+  int2* items = reinterpret_cast<int2*>(static_cast<char*>(ws) + pl.off_items);
+  for (int c = 0; c < n; ++c) items[base + c] = make_int2((int)i, c);
+  const uint32_t slot = atomicAdd(&ctr[kCtrLongRows], 1u);
+  int4* lr = reinterpret_cast<int4*>(static_cast<char*>(ws) + pl.off_long);
+  lr[slot] = make_int4((int)i, (int)base, n, len);
+}
+
+// True when the long rows of this call are handled by the chunk kernels.
+__device__ __forceinline__ bool split_active(const int64_t* row_ptr, int64_t L, int32_t H,
+                                             const void* ws, size_t ws_bytes) {
+  if (!ws) return false;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  if (pl.total_bytes > ws_bytes) return false;
+  const uint32_t need = reinterpret_cast<const uint32_t*>(ws)[kCtrChunksNeeded];
+  return (int64_t)need <= pl.cap_items;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gather_csr_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+    int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split,
+    const uint8_t* __restrict__ tile_done) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  if (i >= L) return;
+  if (tile_done && tile_done[i >> 5]) return;   // row already produced by the tile path
+  const int64_t h = blockIdx.y;
+  const int64_t r0 = row_ptr[i], r1 = row_ptr[i + 1];
+  if (use_split && r1 - r0 > kSplitThreshold &&
+      split_active(row_ptr, L, (int32_t)gridDim.y, ws, ws_bytes))
+    return;
+  const int64_t hoff = h * L * kHeadDim;
+  float q[Row<T>::VEC];
+  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
+  State<Row<T>::VEC> st;
+  st.init();
+  CsrNeighbours nbr{col_idx + r0};
+  attend_range<T>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
+  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gather_window_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, int64_t L, int64_t W, int64_t s, float scale) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  if (i >= L) return;
+  const int64_t h = blockIdx.y;
+  const int64_t hoff = h * L * kHeadDim;
+  const int64_t kl = min(W, i / s), kr = min(W, (L - 1 - i) / s);
+  float q[Row<T>::VEC];
+  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
+  State<Row<T>::VEC> st;
+  st.init();
+  WindowNeighbours nbr{i - kl * s, s};
+  attend_range<T>(K + hoff, V + hoff, q, nbr, 0, kl + kr + 1, lane, st);
+  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st);
+}
+
+// One wavefront per (chunk item, head): partial state of a slice of a long row.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_chunk_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t L, float scale,
+    void* ws, size_t ws_bytes) {
+  const int32_t H = (int32_t)gridDim.y;
+  if (!split_active(row_ptr, L, H, ws, ws_bytes)) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  const uint32_t n_items = reinterpret_cast<const uint32_t*>(ws)[kCtrItemsAlloc];
+  const int2* items = reinterpret_cast<const int2*>(static_cast<char*>(ws) + pl.off_items);
+  float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_partials);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int waves = blockDim.x / kWave;
+  const int64_t h = blockIdx.y;
+  const int64_t hoff = h * L * kHeadDim;
+  for (uint32_t it = blockIdx.x * waves + threadIdx.x / kWave; it < n_items;
+       it += gridDim.x * waves) {
+    const int2 item = items[it];
+    const int64_t i = item.x;
+    const int64_t r0 = row_ptr[i], deg = row_ptr[i + 1] - r0;
+    int32_t n, len;
+    split_shape(deg, n, len);
+    const int64_t e0 = (int64_t)item.y * len;
+    const int64_t e1 = min(deg, e0 + len);
+    float q[Row<T>::VEC];
+    load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
+    State<Row<T>::VEC> st;
+    st.init();
+    CsrNeighbours nbr{col_idx + r0};
+    attend_range<T>(K + hoff, V + hoff, q, nbr, e0, e1, lane, st);
+    merge_groups<Row<T>::LPK, Row<T>::VEC>(st);
+    float* p = partials + ((int64_t)it * H + h) * kPartialStride;
+    if (lane < Row<T>::LPK) {
+#pragma unroll
+      for (int c = 0; c < Row<T>::VEC; ++c) p[lane * Row<T>::VEC + c] = st.acc[c];
+    }
+    if (lane == 0) {
+      p[kHeadDim] = st.m;
+      p[kHeadDim + 1] = st.l;
+    }
+  }
+}
+
+// One wavefront per (long row, head): combine the row's partials in chunk order.
+template <typename T>
+__global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
+                                                           const int64_t* __restrict__ row_ptr,
+                                                           int64_t L, void* ws, size_t ws_bytes) {
+  const int32_t H = (int32_t)gridDim.y;
+  if (!split_active(row_ptr, L, H, ws, ws_bytes)) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrLongRows];
+  const int4* lr = reinterpret_cast<const int4*>(static_cast<char*>(ws) + pl.off_long);
+  const float* partials = reinterpret_cast<const float*>(static_cast<char*>(ws) + pl.off_partials);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int waves = blockDim.x / kWave;
+  const int64_t h = blockIdx.y;
+  for (uint32_t r = blockIdx.x * waves + threadIdx.x / kWave; r < n_long; r += gridDim.x * waves) {
+    const int4 rec = lr[r];
+    const int64_t i = rec.x;
+    const float* p0 = partials + ((int64_t)rec.y * H + h) * kPartialStride;
+    const int64_t step = (int64_t)H * kPartialStride;
+    float M = kMinusHuge;
+    for (int c = 0; c < rec.z; ++c) M = fmaxf(M, p0[c * step + kHeadDim]);
+    float l = 0.f, acc = 0.f;
+    for (int c = 0; c < rec.z; ++c) {
+      const float w = __builtin_amdgcn_exp2f(p0[c * step + kHeadDim] - M);
+      l = __builtin_fmaf(p0[c * step + kHeadDim + 1], w, l);
+      acc = __builtin_fmaf(p0[c * step + lane], w, acc);
+    }
+    const bool empty = !(l > 0.f);
+    const float o = empty ? 0.f : acc / l;
+    store_scalar(O + h * L * kHeadDim + i * kHeadDim + lane, o);
+    if (lse && lane == 0)
+      lse[h * L + i] = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+  }
+}
+
+template <typename T>
+sga_status run_explicit(const AttnArgs& a, bool allow_split, const uint8_t* tile_done) {
+  const T* Q = static_cast<const T*>(a.Q);
+  const T* K = static_cast<const T*>(a.K);
+  const T* V = static_cast<const T*>(a.V);
+  T* O = static_cast<T*>(a.O);
+  const bool split = allow_split && a.ws && a.ws_bytes >= 256 && a.L > kSplitThreshold;
+  if (split) {
+    hipLaunchKernelGGL(split_prepass_kernel, dim3((unsigned)((a.L + 255) / 256)), dim3(256), 0,
+                       a.stream, a.row_ptr, a.L, a.H, a.ws, a.ws_bytes);
+  }
+  const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
+  hipLaunchKernelGGL(gather_csr_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
+                     a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0, tile_done);
+  if (split) {
+    hipLaunchKernelGGL(gather_chunk_kernel<T>, dim3(1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
+                       K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
+    hipLaunchKernelGGL(gather_merge_kernel<T>, dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
+                       a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);
+  }
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+void clear_workspace_counters(void* ws, hipStream_t stream) {
+  hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, stream,
+                     reinterpret_cast<uint32_t*>(ws));
+}
+
+sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, const uint8_t* tile_done) {
+  return a.dtype == SGA_F32 ? run_explicit<float>(a, allow_split, tile_done)
+                            : run_explicit<__half>(a, allow_split, tile_done);
+}
+
+template <typename T>
+static sga_status run_implicit(const AttnArgs& a) {
+  const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
+  hipLaunchKernelGGL(gather_window_kernel<T>, grid, dim3(256), 0, a.stream,
+                     static_cast<const T*>(a.Q), static_cast<const T*>(a.K),
+                     static_cast<const T*>(a.V), static_cast<T*>(a.O), a.lse, a.L,
+                     (int64_t)a.window, (int64_t)a.stride, a.scale);
+  return hip_status(hipGetLastError());
+}
+
+sga_status launch_gather_implicit(const AttnArgs& a) {
+  return a.dtype == SGA_F32 ? run_implicit<float>(a) : run_implicit<__half>(a);
+}
+
+}  // namespace sga

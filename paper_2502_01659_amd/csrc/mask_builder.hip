@@ -1,0 +1,228 @@
+// Mask -> graph: CSR row offsets and sorted column indices of the mask families of
+// Section II-C (explicit form of Get_Neighbors, Section IV-B "CSR").
+//
+// Every row of every family is a short ordered list of arithmetic column runs
+// ("segments": start, length, step), so
+//   - the row offset is a closed-form prefix sum evaluated independently per row
+//     (no scan over the rows is needed), and
+//   - a row is filled by one workgroup that derives the row's segments once and
+//     then streams them out with coalesced int32 stores.
+#include "sga_internal.h"
+
+namespace sga {
+namespace {
+
+constexpr int kMaxRandom = 16;
+constexpr int kMaxSegments = kMaxRandom + 2;
+constexpr uint64_t kGold = 0x9E3779B97F4A7C15ull;
+
+__host__ __device__ inline uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+
+__host__ __device__ inline int64_t imin(int64_t a, int64_t b) { return a < b ? a : b; }
+__host__ __device__ inline int64_t imax(int64_t a, int64_t b) { return a > b ? a : b; }
+
+// sum_{t=0}^{n-1} min(W, t div s)
+__host__ __device__ inline int64_t clipped_steps_prefix(int64_t n, int64_t W, int64_t s) {
+  if (n >= W * s) return s * (W * (W - 1) / 2) + (n - W * s) * W;
+  const int64_t q = n / s, r = n - q * s;
+  return s * (q * (q - 1) / 2) + r * q;
+}
+
+// Edges in rows [0, i) of the window family: row t has 1 + min(W, t div s) + min(W, (L-1-t) div s).
+__host__ __device__ inline int64_t window_prefix(int64_t i, int64_t L, int64_t W, int64_t s) {
+  return i + clipped_steps_prefix(i, W, s) + clipped_steps_prefix(L, W, s) -
+         clipped_steps_prefix(L - i, W, s);
+}
+
+// sum_{t=0}^{n-1} min(L, t + w + 1)
+__host__ __device__ inline int64_t upper_prefix(int64_t n, int64_t L, int64_t w) {
+  const int64_t n1 = imin(n, imax(0, L - w));
+  return n1 * (n1 - 1) / 2 + n1 * (w + 1) + (n - n1) * L;
+}
+
+// sum_{t=0}^{n-1} max(t - w, g)
+__host__ __device__ inline int64_t lower_prefix(int64_t n, int64_t w, int64_t g) {
+  const int64_t n2 = imin(n, g + w);
+  return n2 * g + (n * (n - 1) / 2 - n2 * (n2 - 1) / 2) - (n - n2) * w;
+}
+
+// Edges in rows [0, i) of "window w plus g leading global tokens" over L tokens, with
+// `extra` further neighbours on every non-global row (0 here; the random picks at block level).
+// Row t < g has L neighbours; row t >= g has g + min(L, t+w+1) - max(t-w, g) + extra.
+__host__ __device__ inline int64_t global_local_prefix(int64_t i, int64_t L, int64_t w, int64_t g,
+                                                       int64_t extra) {
+  if (i <= g) return i * L;
+  return g * L + (g + extra) * (i - g) + (upper_prefix(i, L, w) - upper_prefix(g, L, w)) -
+         (lower_prefix(i, w, g) - lower_prefix(g, w, g));
+}
+
+struct MaskParams {
+  int32_t kind;
+  int64_t L;
+  int64_t W;       // clamped half-width in steps
+  int64_t s;       // stride
+  int64_t g;       // clamped global token count
+  int64_t B, nb, wb, G, R;
+  uint64_t seed;
+};
+
+__host__ __device__ inline int64_t row_offset(const MaskParams& p, int64_t i) {
+  switch (p.kind) {
+    case SGA_MASK_SLIDING:
+    case SGA_MASK_DILATED:
+      return window_prefix(i, p.L, p.W, p.s);
+    case SGA_MASK_GLOBAL_LOCAL:
+      return global_local_prefix(i, p.L, p.W, p.g, 0);
+    default: {  // block mask: all rows of a query block have the same degree
+      const int64_t b = i / p.B;
+      const int64_t before = global_local_prefix(b, p.nb, p.wb, p.G, p.R);
+      const int64_t cnt = global_local_prefix(b + 1, p.nb, p.wb, p.G, p.R) - before;
+      return p.B * (p.B * before + (i - b * p.B) * cnt);
+    }
+  }
+}
+
+MaskParams make_params(const sga_mask_desc& d) {
+  MaskParams p{};
+  p.kind = d.kind;
+  p.L = d.L;
+  p.s = (d.kind == SGA_MASK_DILATED) ? d.stride : 1;
+  p.W = imin(d.window, (d.L - 1) / p.s);
+  p.g = imin(d.n_global, d.L);
+  p.B = d.block > 0 ? d.block : 1;
+  p.nb = d.L / p.B;
+  p.wb = imin(d.window_blocks, p.nb > 0 ? p.nb - 1 : 0);
+  p.G = imin(d.n_global_blocks, p.nb);
+  p.R = d.n_random_blocks;
+  p.seed = d.seed;
+  return p;
+}
+
+__global__ __launch_bounds__(256) void row_ptr_kernel(MaskParams p, int64_t* __restrict__ row_ptr) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i <= p.L) row_ptr[i] = row_offset(p, i);
+}
+
+struct Segment {
+  int32_t start, len, step;
+};
+
+// One workgroup per row: thread 0 derives the row's segments, all threads write them.
+__global__ __launch_bounds__(256) void fill_kernel(MaskParams p, const int64_t* __restrict__ row_ptr,
+                                                   int32_t* __restrict__ col_idx) {
+  __shared__ Segment seg[kMaxSegments];
+  __shared__ int n_seg;
+  __shared__ int64_t picks[kMaxRandom];
+  const int64_t i = blockIdx.x;
+  if (threadIdx.x == 0) {
+    int n = 0;
+    if (p.kind == SGA_MASK_SLIDING || p.kind == SGA_MASK_DILATED) {
+      const int64_t kl = imin(p.W, i / p.s), kr = imin(p.W, (p.L - 1 - i) / p.s);
+      seg[n++] = {(int32_t)(i - kl * p.s), (int32_t)(kl + kr + 1), (int32_t)p.s};
+    } else if (p.kind == SGA_MASK_GLOBAL_LOCAL) {
+      const int64_t lo = imax(0, i - p.W), hi = imin(p.L - 1, i + p.W);
+      if (i < p.g) {
+        seg[n++] = {0, (int32_t)p.L, 1};
+      } else if (lo <= p.g) {
+        seg[n++] = {0, (int32_t)(hi + 1), 1};
+      } else {
+        if (p.g > 0) seg[n++] = {0, (int32_t)p.g, 1};
+        seg[n++] = {(int32_t)lo, (int32_t)(hi - lo + 1), 1};
+      }
+    } else {
+      const int64_t b = i / p.B;
+      if (b < p.G) {
+        seg[n++] = {0, (int32_t)p.L, 1};
+      } else {
+        const int64_t lo = imax(0, b - p.wb), hi = imin(p.nb - 1, b + p.wb);
+        // random key blocks: rejection sampling over the counter-based stream of block b
+        const uint64_t key = mix64(p.seed + kGold * (uint64_t)(b + 1));
+        int got = 0;
+        uint64_t a = 0;
+        while (got < (int)p.R) {
+          const int64_t cand = (int64_t)(mix64(key + kGold * (a + 1)) % (uint64_t)p.nb);
+          ++a;
+          bool taken = cand < p.G || (cand >= lo && cand <= hi);
+          for (int t = 0; t < got; ++t) taken = taken || picks[t] == cand;
+          if (!taken) {
+            // keep picks sorted (insertion)
+            int pos = got;
+            while (pos > 0 && picks[pos - 1] > cand) {
+              picks[pos] = picks[pos - 1];
+              --pos;
+            }
+            picks[pos] = cand;
+            ++got;
+          }
+        }
+        int t = 0;
+        if (lo <= p.G) {
+          // global blocks and the window form one run [0, hi]
+          seg[n++] = {0, (int32_t)((hi + 1) * p.B), 1};
+        } else {
+          if (p.G > 0) seg[n++] = {0, (int32_t)(p.G * p.B), 1};
+          for (; t < got && picks[t] < lo; ++t)
+            seg[n++] = {(int32_t)(picks[t] * p.B), (int32_t)p.B, 1};
+          seg[n++] = {(int32_t)(lo * p.B), (int32_t)((hi - lo + 1) * p.B), 1};
+        }
+        for (; t < got; ++t) seg[n++] = {(int32_t)(picks[t] * p.B), (int32_t)p.B, 1};
+      }
+    }
+    n_seg = n;
+  }
+  __syncthreads();
+  int32_t* out = col_idx + row_ptr[i];
+  const int n = n_seg;
+  for (int k = 0; k < n; ++k) {
+    const Segment sg = seg[k];
+    for (int32_t t = threadIdx.x; t < sg.len; t += blockDim.x) out[t] = sg.start + t * sg.step;
+    out += sg.len;
+  }
+}
+
+}  // namespace
+
+sga_status mask_validate(const sga_mask_desc* d) {
+  if (!d) return SGA_ERR_INVALID_ARG;
+  if (d->struct_bytes != sizeof(sga_mask_desc)) return SGA_ERR_INVALID_ARG;
+  if (d->L < 1 || d->L >= (int64_t(1) << 31)) return SGA_ERR_INVALID_ARG;
+  if (d->window < 0) return SGA_ERR_INVALID_ARG;
+  switch (d->kind) {
+    case SGA_MASK_SLIDING:
+      return SGA_OK;
+    case SGA_MASK_DILATED:
+      return d->stride >= 1 ? SGA_OK : SGA_ERR_INVALID_ARG;
+    case SGA_MASK_GLOBAL_LOCAL:
+      return d->n_global >= 0 ? SGA_OK : SGA_ERR_INVALID_ARG;
+    case SGA_MASK_BIGBIRD: {
+      if (d->block < 1 || d->block > 1024 || d->L % d->block != 0) return SGA_ERR_INVALID_ARG;
+      if (d->window_blocks < 0 || d->n_global_blocks < 0) return SGA_ERR_INVALID_ARG;
+      if (d->n_random_blocks < 0 || d->n_random_blocks > kMaxRandom) return SGA_ERR_INVALID_ARG;
+      const int64_t nb = d->L / d->block;
+      const int64_t need = 2 * (int64_t)d->window_blocks + 1 + d->n_global_blocks + d->n_random_blocks;
+      return nb >= need ? SGA_OK : SGA_ERR_INVALID_ARG;
+    }
+    default:
+      return SGA_ERR_INVALID_ARG;
+  }
+}
+
+int64_t mask_total_edges(const sga_mask_desc& d) {
+  const MaskParams p = make_params(d);
+  return row_offset(p, p.L);
+}
+
+sga_status launch_build_mask(const sga_mask_desc& d, int64_t* row_ptr, int32_t* col_idx,
+                             hipStream_t stream) {
+  const MaskParams p = make_params(d);
+  const unsigned nblk = (unsigned)((p.L + 1 + 255) / 256);
+  hipLaunchKernelGGL(row_ptr_kernel, dim3(nblk), dim3(256), 0, stream, p, row_ptr);
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)p.L), dim3(256), 0, stream, p, row_ptr, col_idx);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace sga

@@ -1,0 +1,93 @@
+"""The C-ABI library loads and exports every symbol include/sga.h declares; host-side
+argument checks return status codes (CPU only: nothing here launches a kernel)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2502_01659_amd as sga
+from sga_inputs import MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD, WORKLOADS
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "sga.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sga_[a-z_]+)\s*\(", text)))
+
+
+def test_header_symbols_are_exported():
+    lib = ctypes.CDLL(sga.lib_path()) if os.path.exists(sga.lib_path()) else sga.load()
+    names = _declared_symbols()
+    assert {"sga_build_mask", "sga_attention_forward", "sga_attention_forward_implicit",
+            "sga_mask_nnz", "sga_workspace_bytes", "sga_status_string"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_binding_has_same_names():
+    for n in _declared_symbols():
+        assert hasattr(sga, n), n
+
+
+def test_status_strings():
+    assert sga.sga_status_string(0) == "ok"
+    for code in (-1, -2, -3, -4, -5):
+        assert sga.sga_status_string(code) not in ("ok", "unknown status")
+    assert sga.sga_status_string(-99) == "unknown status"
+
+
+def test_mask_nnz_of_the_five_workloads():
+    want = {"cfg1_sliding_4k": 265184, "cfg2_longformer_64k": 18919024,
+            "cfg3_dilated_1m": 135257984, "cfg4_bigbird_1m": 671014912,
+            "cfg5_sliding_160m": 5279999728}
+    for name, wl in WORKLOADS.items():
+        assert sga.mask_nnz(wl.mask) == want[name]
+
+
+@pytest.mark.parametrize("spec", [
+    MaskSpec(KIND_SLIDING, 0, window=1),
+    MaskSpec(KIND_SLIDING, 1 << 31, window=1),
+    MaskSpec(KIND_SLIDING, 10, window=-1),
+    MaskSpec(KIND_DILATED, 10, window=1, stride=0),
+    MaskSpec(KIND_GLOBAL_LOCAL, 10, window=1, n_global=-2),
+    MaskSpec(KIND_BIGBIRD, 100, block=8, window_blocks=1, n_global_blocks=2, n_random_blocks=3),
+    MaskSpec(KIND_BIGBIRD, 64, block=8, window_blocks=1, n_global_blocks=2, n_random_blocks=4),
+    MaskSpec(KIND_BIGBIRD, 64, block=0),
+    MaskSpec(7, 64),
+])
+def test_invalid_mask_descriptors_are_rejected(spec):
+    st, _ = sga.sga_mask_nnz(spec)
+    assert st == -1
+    with pytest.raises(sga.SgaError):
+        sga.mask_nnz(spec)
+
+
+def test_forward_argument_errors_without_touching_the_gpu():
+    ok = 0x1000     # any non-null, 16-byte aligned address: validation fails before it is used
+    f = sga.sga_attention_forward
+    assert f(None, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
+    assert f(ok, ok, ok, None, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
+    assert f(ok, ok, ok, ok, ok, ok, 0, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
+    assert f(ok, ok, ok, ok, ok, ok, 64, 0, 64, 0.1, None, 0, None, None, 0, 0) == -1
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 32, 0.1, None, 0, None, None, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 5, None, None, 0, 0) == -1
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 9) == -1
+    assert f(ok + 4, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, sga.PATH_TILE) == -3
+    g = sga.sga_attention_forward_implicit
+    spec = MaskSpec(KIND_GLOBAL_LOCAL, 64, window=2, n_global=1)
+    assert g(ok, ok, ok, spec, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -2
+    spec = MaskSpec(KIND_SLIDING, 65, window=2)
+    assert g(ok, ok, ok, spec, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
+
+
+def test_workspace_bytes():
+    st, n = sga.sga_workspace_bytes(65536, 8, 64, 0, 18919024)
+    assert st == 0 and n % 256 == 0 and n > 0
+    assert sga.sga_workspace_bytes(65536, 8, 128, 0, 10)[0] == -2
+    assert sga.sga_workspace_bytes(0, 8, 64, 0, 10)[0] == -1
+    st, n_impl = sga.sga_workspace_bytes(160_000_000, 1, 64, 1, -1)
+    assert st == 0 and n_impl < (1 << 28)

@@ -1,0 +1,187 @@
+"""Attention parity on the GPU: the HIP path, called through the C ABI, against the CPU
+oracle on the same seeded, stored input values.
+
+Tolerances (max-abs-error): 1e-5 for fp32, 2e-3 for fp16 storage with fp32 accumulation.
+The small cases span several 32/64-row tiles with a ragged tail; every case runs through
+each kernel path the entry point offers.
+"""
+import math
+
+import numpy as np
+import pytest
+
+import paper_2502_01659_amd as sga
+from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD,
+                        numpy_qkv, small_variants, Workload)
+from oracle import reference as R
+from gpu_util import TOL, to_device, small_inputs, oracle_full, max_err
+
+pytestmark = pytest.mark.gpu
+
+PATHS = [sga.PATH_GATHER, sga.PATH_TILE, sga.PATH_AUTO]
+PATH_IDS = ["gather", "tile", "auto"]
+
+
+def _run_explicit(wl, Q, K, V, path, with_ws=True):
+    dQ, dK, dV = to_device(Q, K, V)
+    rp, ci = sga.build_mask(wl.mask)
+    ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, int(rp[-1])) if with_ws else None
+    O, lse = sga.attention_forward(dQ, dK, dV, rp, ci, wl.scale, workspace=ws, path=path,
+                                   want_lse=True)
+    return O.cpu().numpy(), lse.cpu().numpy()
+
+
+def _run_implicit(wl, Q, K, V, path):
+    dQ, dK, dV = to_device(Q, K, V)
+    ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, -1)
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, wl.mask, wl.scale, workspace=ws,
+                                            path=path, want_lse=True)
+    return O.cpu().numpy(), lse.cpu().numpy()
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("wl", small_variants(), ids=lambda w: w.name)
+def test_small_workloads_explicit(wl, path):
+    print("case", wl.name, path, flush=True)
+    Q, K, V = small_inputs(wl)
+    O, lse = _run_explicit(wl, Q, K, V, path)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    assert max_err(O, O_ref) <= TOL[wl.dtype]
+    assert max_err(lse, lse_ref) <= 1e-4
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("wl", [w for w in small_variants() if w.mask.kind in (KIND_SLIDING, KIND_DILATED)],
+                         ids=lambda w: w.name)
+def test_small_workloads_implicit(wl, path):
+    print("case", wl.name, path, flush=True)
+    Q, K, V = small_inputs(wl)
+    O, lse = _run_implicit(wl, Q, K, V, path)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    assert max_err(O, O_ref) <= TOL[wl.dtype]
+    assert max_err(lse, lse_ref) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("spec", [
+    MaskSpec(KIND_SLIDING, 1, window=3),
+    MaskSpec(KIND_SLIDING, 31, window=2),
+    MaskSpec(KIND_SLIDING, 33, window=40),
+    MaskSpec(KIND_SLIDING, 700, window=0),
+    MaskSpec(KIND_DILATED, 515, window=6, stride=3),
+    MaskSpec(KIND_DILATED, 200, window=64, stride=2),
+    MaskSpec(KIND_GLOBAL_LOCAL, 257, window=3, n_global=1),
+    MaskSpec(KIND_BIGBIRD, 16 * 20, block=16, window_blocks=1, n_global_blocks=1,
+             n_random_blocks=2, seed=9),
+], ids=lambda s: f"{s.name}-L{s.L}")
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_ragged_and_degenerate_shapes(spec, dtype, path):
+    print("case", spec, dtype, path, flush=True)
+    wl = Workload("t", H=3, L=spec.L, d=64, dtype=dtype, sigma=0.8, mask=spec, explicit=True, seed=77)
+    Q, K, V = small_inputs(wl)
+    O, lse = _run_explicit(wl, Q, K, V, path)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    assert max_err(O, O_ref) <= TOL[dtype]
+    assert max_err(lse, lse_ref) <= 1e-4
+    if spec.kind in (KIND_SLIDING, KIND_DILATED):
+        O2, _ = _run_implicit(wl, Q, K, V, path)
+        assert max_err(O2, O_ref) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("sf", [1.0, 0.5, 0.1, 0.01])
+def test_verification_protocol_bernoulli_masks(sf, path):
+    """Section V-A protocol (L=256, U[0,1) inputs, Bernoulli masks of several sparsity factors,
+    allclose atol 1e-8 / rtol 1e-5 against a dense masked reference, empty rows equal), with
+    d=64 (the supported head size) and the fp64 oracle as the dense reference; the fp32 kernel
+    is held to its own bar of 1e-5 max-abs."""
+    import torch
+    L, d = 256, 64
+    Q, K, V = numpy_qkv(2, L, d, "f32", 1.0, 500, dist="uniform")
+    mask = np.random.default_rng(17).random((L, L)) < sf
+    rp, ci = R.csr_from_dense(mask)
+    dQ, dK, dV = to_device(Q, K, V)
+    drp, dci = to_device(rp, ci if len(ci) else np.zeros(1, np.int32))
+    ws = sga.alloc_workspace(L, 2, d, "f32", int(rp[-1]))
+    O, lse = sga.attention_forward(dQ, dK, dV, drp, dci, 1 / math.sqrt(d), workspace=ws, path=path,
+                                   want_lse=True)
+    O = O.cpu().numpy()
+    lse = lse.cpu().numpy()
+    for h in range(2):
+        O_ref, lse_ref = R.attention_dense(Q[h], K[h], V[h], mask, 1 / math.sqrt(d))
+        assert max_err(O[h], O_ref) <= 1e-5
+        empty = ~mask.any(axis=1)
+        assert (O[h][empty] == 0).all() and np.isneginf(lse[h][empty]).all()
+        assert max_err(lse[h][~empty], lse_ref[~empty]) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_single_neighbour_rows_return_v_exactly(dtype, path):
+    L, d = 200, 64
+    Q, K, V = numpy_qkv(1, L, d, dtype, 1.0, 41)
+    perm = np.random.default_rng(2).permutation(L)
+    rp = np.arange(L + 1, dtype=np.int64)
+    ci = perm.astype(np.int32)
+    dQ, dK, dV, drp, dci = to_device(Q, K, V, rp, ci)
+    ws = sga.alloc_workspace(L, 1, d, dtype, L)
+    O = sga.attention_forward(dQ, dK, dV, drp, dci, 0.125, workspace=ws, path=path).cpu().numpy()
+    assert np.array_equal(O[0], V[0][perm])
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_ones_v_gives_ones_everywhere(dtype, path):
+    wl = [w for w in small_variants() if w.name == "cfg2_small"][0]
+    Q, K, V = numpy_qkv(wl.H, wl.L, wl.d, dtype, 1.0, 3)
+    V = np.ones_like(V)
+    O, _ = _run_explicit(Workload("t", wl.H, wl.L, wl.d, dtype, 1.0, wl.mask, True), Q, K, V, path)
+    assert np.abs(O.astype(np.float64) - 1.0).max() <= (1e-6 if dtype == "f32" else 1e-3)
+
+
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_large_scores_are_stable_and_shift_invariant(path):
+    spec = MaskSpec(KIND_GLOBAL_LOCAL, 400, window=20, n_global=2)
+    wl = Workload("t", H=1, L=400, d=64, dtype="f32", sigma=1.0, mask=spec, explicit=True, seed=5)
+    Q, K, V = small_inputs(wl)
+    Qb = (Q * 12.0).astype(np.float32)           # scores of magnitude ~100
+    O, lse = _run_explicit(wl, Qb, K, V, path)
+    assert np.isfinite(O).all() and np.isfinite(lse).all()
+    O_ref, _ = oracle_full(wl, Qb, K, V)
+    assert max_err(O, O_ref) <= 1e-4             # |s| ~ 100: fp32 score rounding ~1e-5 relative
+    t = np.random.default_rng(1).standard_normal(64).astype(np.float32)
+    O1, _ = _run_explicit(wl, Q, K, V, path)
+    O2, _ = _run_explicit(wl, Q, (K + t).astype(np.float32), V, path)
+    assert max_err(O1, O2) <= 2e-5
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_split_rows_high_degree(dtype, path):
+    """Global tokens over L=20,000: rows of degree 20,000 go through the split-row path."""
+    L = 20000
+    spec = MaskSpec(KIND_GLOBAL_LOCAL, L, window=5, n_global=3)
+    wl = Workload("t", H=2, L=L, d=64, dtype=dtype, sigma=0.7, mask=spec, explicit=True, seed=9)
+    Q, K, V = small_inputs(wl)
+    O, lse = _run_explicit(wl, Q, K, V, path)
+    rows = np.concatenate([np.arange(0, 40), np.arange(9990, 10010), np.arange(L - 20, L)])
+    O_ref, lse_ref = R.attention_masked(Q, K, V, spec, wl.scale, rows=rows)
+    assert max_err(O[:, rows], O_ref) <= TOL[dtype]
+    assert max_err(lse[:, rows], lse_ref) <= 1e-4
+    # without a workspace the long rows run unsplit: same values within tolerance
+    O_ns, _ = _run_explicit(wl, Q, K, V, sga.PATH_GATHER, with_ws=False)
+    assert max_err(O_ns[:, rows], O_ref) <= TOL[dtype]
+    # deterministic: a second run is bit-identical
+    O_b, _ = _run_explicit(wl, Q, K, V, path)
+    assert np.array_equal(O, O_b)
+
+
+def test_explicit_and_implicit_paths_agree():
+    """The same mask through the CSR entry point and the implicit entry point (the paper's
+    own cross-check between its CSR and ordered-sparsity kernels, Section V-F)."""
+    wl = [w for w in small_variants() if w.name == "cfg3_small"][0]
+    Q, K, V = small_inputs(wl)
+    for path in PATHS:
+        O1, _ = _run_explicit(wl, Q, K, V, path)
+        O2, _ = _run_implicit(wl, Q, K, V, path)
+        assert max_err(O1, O2) <= 2 * TOL[wl.dtype]
