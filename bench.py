@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse-graph-attention hot path on one MI355X.
+
+One *step* is one pass of the whole hot path over one batch of seeded synthetic input that is
+already resident in HBM: mask -> CSR (sga_build_mask, explicit workloads only) followed by
+the fused attention forward (sga_attention_forward / sga_attention_forward_implicit).
+The headline metric is attention edges per second (q.k pairs = H * NNZ per step).
+
+Prints ONE JSON line.  `roofline` describes the attention forward (the dominant kernel), timed
+live with events on the launch stream; `cpu_baseline` is the CPU oracle timed on a bounded
+row sample of the same workload; `sweep` carries the other workloads (edges/s and ms/head
+versus sequence length).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E
+MFMA_F32_PEAK_TFLOPS = 157.3    # dense fp32 MFMA
+ALU_F32_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz (unpacked fp32 FMA)
+FLOPS_PER_EDGE = 256            # 2d (q.k) + 2d (p*v accumulate), d = 64
+
+DEFAULT_WORKLOAD = "cfg2_longformer_64k"
+
+# HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (see profiles/); None where not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(wl, nnz):
+    """Compulsory HBM bytes of one forward: Q, K, V read once and O written once
+    (4*d*sizeof per row and head) plus, for explicit masks, col_idx (4 B/edge) and
+    row_ptr (8 B/row) read once for all heads."""
+    size = 4 if wl.dtype == "f32" else 2
+    b = 4 * wl.d * size * wl.L * wl.H
+    if wl.explicit:
+        b += 4 * nnz + 8 * (wl.L + 1)
+    return b
+
+
+class Runner:
+    """Holds device buffers of one workload and runs steps."""
+
+    def __init__(self, wl, path):
+        import torch
+        import paper_2502_01659_amd as sga
+        from sga_inputs import torch_qkv
+        self.torch, self.sga, self.wl, self.path = torch, sga, wl, path
+        dev = "cuda:0"
+        self.nnz = sga.mask_nnz(wl.mask)
+        self.Q, self.K, self.V = torch_qkv(wl.H, wl.L, wl.d, wl.dtype, wl.sigma, wl.seed, dev)
+        self.O = torch.empty_like(self.Q)
+        if wl.explicit:
+            self.row_ptr = torch.empty(wl.L + 1, dtype=torch.int64, device=dev)
+            self.col_idx = torch.empty(self.nnz, dtype=torch.int32, device=dev)
+        self.ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, self.nnz if wl.explicit else -1,
+                                      device=dev)
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.dt = 0 if wl.dtype == "f32" else 1
+
+    def build(self):
+        st = self.sga.sga_build_mask(self.wl.mask, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+                                     self.col_idx.numel(), self.stream)
+        if st != 0:
+            raise self.sga.SgaError(st, "sga_build_mask")
+
+    def forward(self):
+        wl, sga = self.wl, self.sga
+        if wl.explicit:
+            st = sga.sga_attention_forward(self.Q.data_ptr(), self.K.data_ptr(), self.V.data_ptr(),
+                                           self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+                                           self.O.data_ptr(), wl.L, wl.H, wl.d, wl.scale, self.stream,
+                                           self.dt, None, self.ws.data_ptr(), self.ws.numel(), self.path)
+        else:
+            st = sga.sga_attention_forward_implicit(self.Q.data_ptr(), self.K.data_ptr(),
+                                                    self.V.data_ptr(), wl.mask, self.O.data_ptr(),
+                                                    wl.L, wl.H, wl.d, wl.scale, self.stream, self.dt,
+                                                    None, self.ws.data_ptr(), self.ws.numel(), self.path)
+        if st != 0:
+            raise sga.SgaError(st, "sga_attention_forward")
+
+    def step(self):
+        if self.wl.explicit:
+            self.build()
+        self.forward()
+
+    def timed(self, steps, warmup):
+        """-> (wall ms per step, mean forward ms, mean build ms)"""
+        torch = self.torch
+        for _ in range(warmup):
+            self.step()
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(steps):
+            ev[k][0].record()
+            if self.wl.explicit:
+                self.build()
+            ev[k][1].record()
+            self.forward()
+            ev[k][2].record()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        fwd = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+        bld = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+        return (t1 - t0) * 1e3 / steps, fwd, bld
+
+
+def roofline_of(wl, nnz, fwd_ms, path_used):
+    edges = nnz * wl.H
+    t = fwd_ms * 1e-3
+    if wl.dtype == "f32":
+        flops = FLOPS_PER_EDGE * edges
+        if path_used == "gather":
+            bound, peak = "alu", ALU_F32_PEAK_TFLOPS
+        else:
+            bound, peak = "mfma", MFMA_F32_PEAK_TFLOPS
+        ach = flops / t / 1e12
+        unit = "TFLOP/s"
+    else:
+        bound, peak, unit = "hbm", HBM_PEAK_GBPS, "GB/s"
+        ach = algorithmic_bytes(wl, nnz) / t / 1e9
+    return {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
+            "hbm_algorithmic_GBps": algorithmic_bytes(wl, nnz) / t / 1e9,
+            "kernel_ms": fwd_ms}
+
+
+def cpu_baseline(wl, runner, budget_s=12.0):
+    """The oracle (row scan over all keys, two-pass softmax, float64) on a bounded row sample
+    of head 0 of the same workload, on the host cores of this machine."""
+    import numpy as np
+    from oracle import rowscan
+    torch = runner.torch
+    threads = rowscan.num_threads()
+    rng = np.random.default_rng(wl.seed + 4)
+    spec = wl.mask
+    if wl.L <= (1 << 21):
+        Qh = runner.Q[0].float().cpu().numpy()
+        Kh = runner.K[0].float().cpu().numpy()
+        Vh = runner.V[0].float().cpu().numpy()
+
+        def run(rows):
+            t0 = time.perf_counter()
+            _, _, edges = rowscan.attend_rows(spec, Qh, Kh, Vh, wl.scale, rows)
+            return time.perf_counter() - t0, edges
+    else:
+        def run(rows):
+            # K/V stay on the device; only the neighbours' rows are fetched
+            t0 = time.perf_counter()
+            edges = 0
+            q = runner.Q[0][torch.from_numpy(rows).cuda()].float().cpu().numpy()
+            for r, i in enumerate(rows):
+                nb = rowscan.row_neighbors(spec, int(i))
+                idx = torch.from_numpy(nb).cuda()
+                Kg = runner.K[0][idx].float().cpu().numpy()
+                Vg = runner.V[0][idx].float().cpu().numpy()
+                rowscan.attend_gathered(q[r], Kg, Vg, wl.scale)
+                edges += len(nb)
+            return time.perf_counter() - t0, edges
+    probe = np.sort(rng.choice(wl.L, size=min(wl.L, 8 * threads), replace=False)).astype(np.int64)
+    t_probe, _ = run(probe)
+    per_row = max(t_probe / len(probe), 1e-7)
+    n = int(min(wl.L, max(len(probe), budget_s / per_row)))
+    rows = np.sort(rng.choice(wl.L, size=n, replace=False)).astype(np.int64)
+    t, edges = run(rows)
+    return {"value": edges / t, "unit": "edges/s", "cores": threads, "kind": "oracle",
+            "sample": f"{n} seeded random query rows of head 0 of {wl.name} (each row scans all "
+                      f"{wl.L} keys through the mask predicate), {edges} edges in {t:.2f} s",
+            "seconds": t, "us_per_row": t / n * 1e6,
+            "extrapolated_full_workload_s": t / n * wl.L * wl.H}
+
+
+def path_name(path, wl):
+    return {0: "auto", 1: "gather", 2: "tile"}[path]
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=15)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--path", default="auto", choices=["auto", "gather", "tile"])
+    ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (the hot path is a single-GPU kernel; "
+              "no collectives exist). Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from sga_inputs import WORKLOADS
+    path = {"auto": 0, "gather": 1, "tile": 2}[args.path]
+    wl = WORKLOADS[args.workload]
+    run = Runner(wl, path)
+    ms_step, fwd_ms, bld_ms = run.timed(args.steps, args.warmup)
+    edges = run.nnz * wl.H
+    out = {
+        "metric": "attention edges/s (q.k pairs)",
+        "value": edges / (ms_step * 1e-3),
+        "unit": "edges/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "H": wl.H, "L": wl.L, "d": wl.d,
+                   "mask": wl.mask.name, "explicit_csr": wl.explicit, "edges_per_step": edges,
+                   "path": args.path, "seed": wl.seed,
+                   "step": "sga_build_mask + sga_attention_forward" if wl.explicit
+                           else "sga_attention_forward_implicit"},
+        "forward_ms": fwd_ms, "build_mask_ms": bld_ms,
+        "ms_per_head": fwd_ms / wl.H,
+        "forward_edges_per_s": edges / (fwd_ms * 1e-3),
+        "roofline": roofline_of(wl, run.nnz, fwd_ms, args.path),
+    }
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(wl, run)
+    del run
+    torch.cuda.empty_cache()
+
+    if not args.no_sweep:
+        sweep = []
+        for name, w in WORKLOADS.items():
+            if name == wl.name:
+                continue
+            try:
+                r = Runner(w, path)
+                ms, f, b = r.timed(5, 2)
+                e = r.nnz * w.H
+                sweep.append({"workload": name, "L": w.L, "H": w.H, "dtype": w.dtype,
+                              "edges_per_step": e, "ms_per_step": ms, "forward_ms": f,
+                              "build_mask_ms": b, "ms_per_head": f / w.H,
+                              "forward_edges_per_s": e / (f * 1e-3),
+                              "roofline": roofline_of(w, r.nnz, f, args.path)})
+                del r
+            except Exception as ex:    # a sweep entry must not lose the headline line
+                sweep.append({"workload": name, "error": repr(ex)})
+            torch.cuda.empty_cache()
+        out["sweep"] = sweep
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

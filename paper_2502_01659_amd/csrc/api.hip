@@ -52,6 +52,7 @@ sga_status sga_build_mask(const sga_mask_desc* desc, int64_t* row_ptr, int32_t* 
   if (st != SGA_OK) return st;
   if (!row_ptr || !col_idx) return SGA_ERR_INVALID_ARG;
   if (col_capacity < mask_total_edges(*desc)) return SGA_ERR_WORKSPACE;
+  (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   return launch_build_mask(*desc, row_ptr, col_idx, static_cast<hipStream_t>(stream));
 }
 
@@ -80,6 +81,7 @@ sga_status sga_attention_forward(const void* Q, const void* K, const void* V, co
   a.row_ptr = row_ptr; a.col_idx = col_idx;
   a.ws = workspace; a.ws_bytes = workspace_bytes;
   if (path == SGA_PATH_TILE && (!workspace || workspace_bytes < 256)) return SGA_ERR_WORKSPACE;
+  (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   if (workspace && workspace_bytes >= 256) clear_workspace_counters(workspace, a.stream);
   if (path == SGA_PATH_GATHER) return launch_gather_explicit(a, true, nullptr);
   return launch_tile_explicit(a);
@@ -104,6 +106,7 @@ sga_status sga_attention_forward_implicit(const void* Q, const void* K, const vo
   const int64_t wmax = (L - 1) / a.stride;
   a.window = (int32_t)(desc->window < wmax ? desc->window : wmax);
   a.ws = workspace; a.ws_bytes = workspace_bytes;
+  (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   if (path == SGA_PATH_GATHER) return launch_gather_implicit(a);
   return launch_tile_implicit(a);
 }
