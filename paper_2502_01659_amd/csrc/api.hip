@@ -83,7 +83,7 @@ sga_status sga_attention_forward(const void* Q, const void* K, const void* V, co
   if (path == SGA_PATH_TILE && (!workspace || workspace_bytes < 256)) return SGA_ERR_WORKSPACE;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   if (workspace && workspace_bytes >= 256) clear_workspace_counters(workspace, a.stream);
-  if (path == SGA_PATH_GATHER) return launch_gather_explicit(a, true, nullptr);
+  if (path == SGA_PATH_GATHER) return launch_gather_explicit(a, true, false);
   return launch_tile_explicit(a);
 }
 

@@ -209,13 +209,16 @@ __global__ void clear_counters_kernel(uint32_t* ctr) {
 // One thread per row: rows over the split threshold reserve chunk work items.
 __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __restrict__ row_ptr,
                                                             int64_t L, int32_t H, void* ws,
-                                                            size_t ws_bytes) {
+                                                            size_t ws_bytes, int skip_tiled) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= L) return;
   const int64_t deg = row_ptr[i + 1] - row_ptr[i];
   if (deg <= kSplitThreshold) return;
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
   if (pl.total_bytes > ws_bytes) return;
+  if (skip_tiled &&
+      reinterpret_cast<const int32_t*>(static_cast<const char*>(ws) + pl.off_tile_nblk)[i / kTile] >= 0)
+    return;
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   int32_t n, len;
   split_shape(deg, n, len);
@@ -239,29 +242,40 @@ __device__ __forceinline__ bool split_active(const int64_t* row_ptr, int64_t L, 
   return (int64_t)need <= pl.cap_items;
 }
 
+// True when this call's tile path produced row i (its 32-row tile has a block list).
+__device__ __forceinline__ bool row_done_by_tiles(const int64_t* row_ptr, int64_t L, int32_t H,
+                                                  const void* ws, size_t ws_bytes, int64_t i) {
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  if (pl.total_bytes > ws_bytes) return false;
+  const int32_t* nblk =
+      reinterpret_cast<const int32_t*>(static_cast<const char*>(ws) + pl.off_tile_nblk);
+  return nblk[i / kTile] >= 0;
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void gather_csr_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-    int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split,
-    const uint8_t* __restrict__ tile_done) {
+    int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split, int skip_tiled) {
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
-  if (i >= L) return;
-  if (tile_done && tile_done[i >> 5]) return;   // row already produced by the tile path
+  const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
-  const int64_t r0 = row_ptr[i], r1 = row_ptr[i + 1];
-  if (use_split && r1 - r0 > kSplitThreshold &&
-      split_active(row_ptr, L, (int32_t)gridDim.y, ws, ws_bytes))
-    return;
+  const int32_t H = (int32_t)gridDim.y;
   const int64_t hoff = h * L * kHeadDim;
-  float q[Row<T>::VEC];
-  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
-  State<Row<T>::VEC> st;
-  st.init();
-  CsrNeighbours nbr{col_idx + r0};
-  attend_range<T>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
-  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st);
+  for (int64_t i = (int64_t)blockIdx.x * waves + (threadIdx.x / kWave); i < L;
+       i += (int64_t)gridDim.x * waves) {
+    if (skip_tiled && row_done_by_tiles(row_ptr, L, H, ws, ws_bytes, i)) continue;
+    const int64_t r0 = row_ptr[i], r1 = row_ptr[i + 1];
+    if (use_split && r1 - r0 > kSplitThreshold && split_active(row_ptr, L, H, ws, ws_bytes))
+      continue;
+    float q[Row<T>::VEC];
+    load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
+    State<Row<T>::VEC> st;
+    st.init();
+    CsrNeighbours nbr{col_idx + r0};
+    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
+    finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st);
+  }
 }
 
 template <typename T>
@@ -363,7 +377,7 @@ __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, fl
 }
 
 template <typename T>
-sga_status run_explicit(const AttnArgs& a, bool allow_split, const uint8_t* tile_done) {
+sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   const T* Q = static_cast<const T*>(a.Q);
   const T* K = static_cast<const T*>(a.K);
   const T* V = static_cast<const T*>(a.V);
@@ -371,11 +385,15 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, const uint8_t* tile
   const bool split = allow_split && a.ws && a.ws_bytes >= 256 && a.L > kSplitThreshold;
   if (split) {
     hipLaunchKernelGGL(split_prepass_kernel, dim3((unsigned)((a.L + 255) / 256)), dim3(256), 0,
-                       a.stream, a.row_ptr, a.L, a.H, a.ws, a.ws_bytes);
+                       a.stream, a.row_ptr, a.L, a.H, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
   }
-  const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
+  // after the tile path only leftover rows remain: a small grid strides over the rows
+  int64_t nwg = (a.L + 3) / 4;
+  if (skip_tiled && nwg > 2048) nwg = 2048;
+  const dim3 grid((unsigned)nwg, (unsigned)a.H);
   hipLaunchKernelGGL(gather_csr_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
-                     a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0, tile_done);
+                     a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
+                     skip_tiled ? 1 : 0);
   if (split) {
     hipLaunchKernelGGL(gather_chunk_kernel<T>, dim3(1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
@@ -392,9 +410,9 @@ void clear_workspace_counters(void* ws, hipStream_t stream) {
                      reinterpret_cast<uint32_t*>(ws));
 }
 
-sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, const uint8_t* tile_done) {
-  return a.dtype == SGA_F32 ? run_explicit<float>(a, allow_split, tile_done)
-                            : run_explicit<__half>(a, allow_split, tile_done);
+sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
+  return a.dtype == SGA_F32 ? run_explicit<float>(a, allow_split, skip_tiled)
+                            : run_explicit<__half>(a, allow_split, skip_tiled);
 }
 
 template <typename T>

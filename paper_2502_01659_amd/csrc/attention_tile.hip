@@ -1,9 +1,596 @@
-// Tile path placeholder: routes to the gather kernels until the MFMA tile kernels land.
+// Tile path of Algorithm 1: 32 query rows x 32 keys per MFMA tile.
+//
+// The graph is regrouped into a "tile graph": for every tile of 32 consecutive query rows,
+// the sorted list of 32-key blocks that hold at least one of its edges, each with a 32x32
+// bit mask (word r, bit j = edge between row 32t+r and key 32b+j).  Explicit CSR masks are
+// converted on the device by tile_analyze_kernel into workspace slots derived from row_ptr
+// alone (no scan, no host round trip); window masks generate the same lists by index
+// arithmetic inside the attention kernel (implicit Get_Neighbors).
+//
+// One wavefront owns one tile and walks its block list.  Per block it computes, on the
+// matrix cores,
+//     S^T[key][query] = K_blk Q_tile^T                       (SDDMM restricted to the block)
+//     O^T[chan][query] += V_blk^T P^T                        (SpMM)
+// with the online-softmax recurrence of Algorithm 1 applied per block instead of per key.
+// Both products are laid out transposed so that a lane always owns one query (lane % 32):
+// the running max m, the running sum l, the rescale factor and the mask word of a query
+// live in that query's lanes and no cross-lane traffic is needed except one exchange
+// between the two half-waves per block.  Entries outside the mask are set to -inf before
+// the softmax, so they contribute exactly 0; blocks whose 1024 bits are all set skip the
+// masking.
+//
+// fp32 storage uses v_mfma_f32_32x32x2_f32 (true fp32 products), fp16 storage uses
+// v_mfma_f32_32x32x16_f16 with fp32 accumulation; P is rounded to fp16 only as the MFMA
+// operand, l is summed in fp32.
+//
+// Tiles with very long block lists (global-token rows) are cut into chunks that are
+// processed by extra wavefronts of the same launch; their partial (m, l, acc) states are
+// merged in chunk order by tile_merge_kernel (deterministic).
 #include "sga_internal.h"
 
 namespace sga {
+namespace {
 
-sga_status launch_tile_explicit(const AttnArgs& a) { return launch_gather_explicit(a, true, nullptr); }
-sga_status launch_tile_implicit(const AttnArgs& a) { return launch_gather_implicit(a); }
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kMinusHuge = -1.0e30f;
+constexpr int kFullBit = 1 << 30;
+constexpr int kVPitch = 144;          // bytes per staged fp16 V row in LDS (128 + 16 pad)
+
+// Key (within a 32-key block) held in accumulator register r of half-wave h after an
+// MFMA 32x32 whose M index is the key: rows 8*(r/4) + 4*h + r%4.
+__device__ __forceinline__ constexpr int acc_row(int r, int h) { return 8 * (r / 4) + 4 * h + (r % 4); }
+
+struct BlockInfo {
+  int64_t row0;     // tensor row of the block's first key
+  int64_t stride;   // tensor rows between consecutive keys of the block
+  int nvalid;       // keys of the block that exist (1..32); others are masked off
+  uint32_t word;    // mask bits of this lane's query against the block's 32 keys
+  bool full;        // all 32x32 bits set (wave-uniform)
+};
+
+// Block list of an explicit tile, as written by tile_analyze_kernel.
+struct ExplicitBlocks {
+  const int32_t* blk;
+  const uint32_t* mask;
+  int64_t L;
+  __device__ BlockInfo get(int k, int n) const {
+    BlockInfo b;
+    const int id = blk[k];
+    b.full = (id & kFullBit) != 0;
+    b.row0 = (int64_t)(id & ~kFullBit) * kTile;
+    b.stride = 1;
+    const int64_t left = L - b.row0;
+    b.nvalid = left < kTile ? (int)left : kTile;
+    b.word = mask[(int64_t)k * kTile + n];
+    return b;
+  }
+};
+
+// Block list of a window tile in one residue class p of stride s: queries u0..u0+31 and keys
+// v of the class (token = s*index + p), edge iff |u - v| <= W.
+struct WindowBlocks {
+  int64_t kb0, Lc, s, p, u0, W;
+  __device__ BlockInfo get(int k, int n) const {
+    BlockInfo b;
+    const int64_t v0 = (kb0 + k) * kTile;
+    b.row0 = s * v0 + p;
+    b.stride = s;
+    const int64_t left = Lc - v0;
+    b.nvalid = left < kTile ? (int)left : kTile;
+    const int64_t u = u0 + n;
+    int64_t lo = u - W - v0, hi = u + W - v0;
+    if (hi > b.nvalid - 1) hi = b.nvalid - 1;
+    if (lo < 0) lo = 0;
+    b.word = (lo > hi || u >= Lc) ? 0u : ((~0u >> (31 - (int)hi)) & (~0u << (int)lo));
+    // every query of the tile sees every key of the block
+    b.full = b.nvalid == kTile && u0 + kTile <= Lc && v0 >= u0 + (kTile - 1) - W &&
+             v0 + (kTile - 1) <= u0 + W;
+    return b;
+  }
+};
+
+// Per-lane running state: lane owns query n = lane % 32; channels of O^T are spread over the
+// 16 accumulator registers of both 32-channel halves.
+struct TileState {
+  float m;          // running max (log2 domain), identical in both half-waves
+  float l;          // running sum of this half-wave's keys
+  floatx16 o[2];    // o[cb][r]: channel cb*32 + acc_row(r, h), un-normalised
+  __device__ void init() {
+    m = kMinusHuge;
+    l = 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) { o[0][r] = 0.f; o[1][r] = 0.f; }
+  }
+};
+
+// Mask, running max/sum update and rescale for one block.  s: raw scores of this lane's
+// query against keys acc_row(r, h); returns the block's softmax numerators in p.
+__device__ __forceinline__ void softmax_block(const floatx16& s, float c, const BlockInfo& b, int h,
+                                              TileState& st, float (&p)[16]) {
+  float sv[16];
+  float bm = -INFINITY;
+  if (b.full) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      sv[r] = s[r] * c;
+      bm = fmaxf(bm, sv[r]);
+    }
+  } else {
+    const uint32_t wh = b.word >> (4 * h);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const bool valid = (wh >> acc_row(r, 0)) & 1u;
+      sv[r] = valid ? s[r] * c : -INFINITY;
+      bm = fmaxf(bm, sv[r]);
+    }
+  }
+  bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+  const float m_new = fmaxf(st.m, bm);
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+  st.m = m_new;
+  float lsum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    p[r] = __builtin_amdgcn_exp2f(sv[r] - m_new);
+    lsum += p[r];
+  }
+  st.l = st.l * alpha + lsum;
+  if (__any(alpha != 1.0f)) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      st.o[0][r] *= alpha;
+      st.o[1][r] *= alpha;
+    }
+  }
+}
+
+// ---- fp32 storage ---------------------------------------------------------------------------
+struct CoreF32 {
+  float qf[32];   // Q[query n][h*32 + t]
+
+  __device__ void load_q(const float* Qrow, int h) {
+    const float4* src = reinterpret_cast<const float4*>(Qrow + h * 32);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float4 v = src[t];
+      qf[4 * t] = v.x; qf[4 * t + 1] = v.y; qf[4 * t + 2] = v.z; qf[4 * t + 3] = v.w;
+    }
+  }
+
+  template <typename Src>
+  __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
+                      int k0, int k1, float c, int lane, TileState& st, char* /*lds*/) {
+    const int n = lane & 31, h = lane >> 5;
+    for (int k = k0; k < k1; ++k) {
+      const BlockInfo b = src.get(k, n);
+      const int krow = n < b.nvalid ? n : b.nvalid - 1;
+      const float4* kp =
+          reinterpret_cast<const float4*>(Kh + (b.row0 + krow * b.stride) * kHeadDim + h * 32);
+      float kf[32];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const float4 v = kp[t];
+        kf[4 * t] = v.x; kf[4 * t + 1] = v.y; kf[4 * t + 2] = v.z; kf[4 * t + 3] = v.w;
+      }
+      // V[key acc_row(r,h)][cb*32 + n]
+      float vf[2][16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        int key = acc_row(r, 0) + 4 * h;
+        key = key < b.nvalid ? key : b.nvalid - 1;
+        const float* vp = Vh + (b.row0 + key * b.stride) * kHeadDim + n;
+        vf[0][r] = vp[0];
+        vf[1][r] = vp[32];
+      }
+      floatx16 s = {0};
+#pragma unroll
+      for (int t = 0; t < 32; ++t)
+        s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
+      float p[16];
+      softmax_block(s, c, b, h, st, p);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vf[0][r], p[r], st.o[0], 0, 0, 0);
+        st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vf[1][r], p[r], st.o[1], 0, 0, 0);
+      }
+    }
+  }
+
+  __device__ static void store_row(float* Orow, const TileState& st, float inv, int h) {
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const float4 v = make_float4(st.o[cb][4 * g] * inv, st.o[cb][4 * g + 1] * inv,
+                                     st.o[cb][4 * g + 2] * inv, st.o[cb][4 * g + 3] * inv);
+        *reinterpret_cast<float4*>(Orow + cb * 32 + 8 * g + 4 * h) = v;
+      }
+  }
+};
+
+// ---- fp16 storage ---------------------------------------------------------------------------
+struct CoreF16 {
+  half8 qf[4];    // Q[query n][h*32 + 8s .. +7], s = 0..3
+
+  __device__ void load_q(const __half* Qrow, int h) {
+    const half8* src = reinterpret_cast<const half8*>(Qrow + h * 32);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) qf[s] = src[s];
+  }
+
+  template <typename Src>
+  __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
+                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
+    const int n = lane & 31, h = lane >> 5;
+    for (int k = k0; k < k1; ++k) {
+      const BlockInfo b = src.get(k, n);
+      const int krow = n < b.nvalid ? n : b.nvalid - 1;
+      const int64_t roff = (b.row0 + krow * b.stride) * kHeadDim + h * 32;
+      const half8* kp = reinterpret_cast<const half8*>(Kh + roff);
+      const uint4* vp = reinterpret_cast<const uint4*>(Vh + roff);
+      half8 kf[4];
+      uint4 vraw[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        kf[s] = kp[s];
+        vraw[s] = vp[s];
+      }
+      // stage the V block row-major in this wavefront's LDS slice: row = key n, 64 B per half-wave
+      __builtin_amdgcn_wave_barrier();   // earlier reads of the slice are done (in-order LDS queue)
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        *reinterpret_cast<uint4*>(lds + n * kVPitch + h * 64 + 16 * s) = vraw[s];
+      floatx16 sacc = {0};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
+      float p[16];
+      softmax_block(sacc, c, b, h, st, p);
+      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      __builtin_amdgcn_wave_barrier();
+      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        half8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[8 * u + e];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          // A operand: V^T[channel cb*32+n][key of slot (u,h,e)] = staged V[key][channel]
+          half8 va;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const int key = acc_row(8 * u + e, 0) + 4 * h;
+            va[e] = *reinterpret_cast<const _Float16*>(lds + key * kVPitch + (cb * 32 + n) * 2);
+          }
+          st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
+        }
+      }
+    }
+  }
+
+  __device__ static void store_row(__half* Orow, const TileState& st, float inv, int h) {
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const __half2 a = __floats2half2_rn(st.o[cb][4 * g] * inv, st.o[cb][4 * g + 1] * inv);
+        const __half2 bq = __floats2half2_rn(st.o[cb][4 * g + 2] * inv, st.o[cb][4 * g + 3] * inv);
+        uint2 w;
+        w.x = __builtin_bit_cast(uint32_t, a);
+        w.y = __builtin_bit_cast(uint32_t, bq);
+        *reinterpret_cast<uint2*>(Orow + cb * 32 + 8 * g + 4 * h) = w;
+      }
+  }
+};
+
+template <typename T> struct CoreOf;
+template <> struct CoreOf<float> { using type = CoreF32; };
+template <> struct CoreOf<__half> { using type = CoreF16; };
+
+// Normalise and store the tile's rows (row(n) = tensor row of query n, < 0 if it does not exist).
+template <typename T>
+__device__ __forceinline__ void finish_tile(T* Oh, float* lse_h, int64_t row, int64_t lse_idx,
+                                            bool exists, TileState& st, int h) {
+  const float l = st.l + __shfl_xor(st.l, 32, kWave);
+  if (!exists) return;
+  const bool empty = !(l > 0.f);
+  const float inv = empty ? 0.f : 1.0f / l;
+  CoreOf<T>::type::store_row(Oh + row * kHeadDim, st, inv, h);
+  if (lse_h && h == 0) lse_h[lse_idx] = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(l)) * kLn2;
+}
+
+// Un-normalised partial of a chunk: o[32][64], m[32], l[32].
+__device__ __forceinline__ void store_partial(float* part, TileState& st, int n, int h) {
+  const float l = st.l + __shfl_xor(st.l, 32, kWave);
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+      *reinterpret_cast<float4*>(part + n * 64 + cb * 32 + 8 * g + 4 * h) =
+          make_float4(st.o[cb][4 * g], st.o[cb][4 * g + 1], st.o[cb][4 * g + 2], st.o[cb][4 * g + 3]);
+  if (h == 0) {
+    part[kTile * 64 + n] = st.m;
+    part[kTile * 64 + kTile + n] = l;
+  }
+}
+
+__host__ __device__ inline void tile_split_shape(int nblk, int& nchunks, int& len) {
+  int n = (nblk + kTileChunk - 1) / kTileChunk;
+  if (n > kTileMaxSplit) n = kTileMaxSplit;
+  len = (nblk + n - 1) / n;
+  nchunks = (nblk + len - 1) / len;
+}
+
+__device__ __forceinline__ int half_min(int v) {   // min over the 32 lanes of a half-wave
+#pragma unroll
+  for (int off = 16; off > 0; off >>= 1) {
+    const int o = __shfl_xor(v, off, kWave);
+    v = o < v ? o : v;
+  }
+  return v;
+}
+
+// ---- CSR -> tile graph ------------------------------------------------------------------------
+// One wavefront per tile; lane r < 32 walks row 32t + r.  A 32-way merge by key block id:
+// every round takes the smallest block id at the head of any row and lets each row consume
+// its columns inside that block into a 32-bit word.
+__global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __restrict__ row_ptr,
+                                                           const int32_t* __restrict__ col_idx,
+                                                           int64_t L, int32_t H, void* ws,
+                                                           size_t ws_bytes) {
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  if (pl.total_bytes > ws_bytes) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t t = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (t >= pl.n_tiles) return;
+  char* base_ws = static_cast<char*>(ws);
+  int32_t* tile_nblk = reinterpret_cast<int32_t*>(base_ws + pl.off_tile_nblk);
+  int32_t* pair_blk = reinterpret_cast<int32_t*>(base_ws + pl.off_pair_blk);
+  uint32_t* pair_mask = reinterpret_cast<uint32_t*>(base_ws + pl.off_pair_mask);
+  const int64_t row_first = t * kTile;
+  const int64_t row_last = row_first + kTile < L ? row_first + kTile : L;
+  const int64_t slot0 = row_ptr[row_first] / kPairEdges;
+  const int64_t cap = row_ptr[row_last] / kPairEdges - slot0;
+  const int64_t row = row_first + lane;
+  const bool active = lane < kTile && row < L;
+  int64_t pos = active ? row_ptr[row] : 0;
+  const int64_t end = active ? row_ptr[row + 1] : 0;
+  int nblk = 0;
+  bool overflow = false;
+  while (true) {
+    const int cur = pos < end ? (col_idx[pos] >> 5) : INT32_MAX;
+    const int b = __shfl(half_min(cur), 0, kWave);
+    if (b == INT32_MAX) break;
+    if (nblk >= cap) {
+      overflow = true;
+      break;
+    }
+    uint32_t word = 0;
+    if (cur == b) {
+      const int c0 = col_idx[pos];
+      if ((c0 & 31) == 0 && pos + 31 < end && col_idx[pos + 31] == c0 + 31) {
+        word = ~0u;   // 32 consecutive columns: the whole block row
+        pos += 32;
+      } else {
+        while (pos < end) {
+          const int cc = col_idx[pos];
+          if ((cc >> 5) != b) break;
+          word |= 1u << (cc & 31);
+          ++pos;
+        }
+      }
+    }
+    const bool full = __all(lane >= kTile || word == ~0u);
+    if (lane < kTile) pair_mask[(slot0 + nblk) * kTile + lane] = word;
+    if (lane == 0) pair_blk[slot0 + nblk] = b | (full ? kFullBit : 0);
+    ++nblk;
+  }
+  if (lane != 0) return;
+  tile_nblk[t] = overflow ? -1 : nblk;
+  if (!overflow && nblk > kTileSplitThreshold && pl.cap_titems > 0) {
+    uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
+    int n, len;
+    tile_split_shape(nblk, n, len);
+    atomicAdd(&ctr[kCtrTileChunksNeeded], (uint32_t)n);
+    const uint32_t first = atomicAdd(&ctr[kCtrTileItems], (uint32_t)n);
+    if ((int64_t)first + n <= pl.cap_titems) {
+      int2* items = reinterpret_cast<int2*>(base_ws + pl.off_titems);
+      for (int c = 0; c < n; ++c) items[first + c] = make_int2((int)t, c);
+      const uint32_t slot = atomicAdd(&ctr[kCtrTileLong], 1u);
+      reinterpret_cast<int4*>(base_ws + pl.off_tlong)[slot] = make_int4((int)t, (int)first, n, len);
+    }
+  }
+}
+
+__device__ __forceinline__ bool tile_split_active(const WorkspacePlan& pl, const void* ws) {
+  return pl.cap_titems > 0 &&
+         (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTileChunksNeeded] <= pl.cap_titems;
+}
+
+// Wave slots [0, kTileItemSlots) are chunk items of split tiles (dispatched first: they are the
+// longest pieces of work), the remaining slots are whole tiles.
+template <typename T>
+__global__ __launch_bounds__(256) void tile_attend_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
+    size_t ws_bytes) {
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * kTile * kVPitch];
+  const int32_t H = (int32_t)gridDim.y;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  if (pl.total_bytes > ws_bytes) return;
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int n = lane & 31, h = lane >> 5;
+  char* lds = lds_all + wave * kTile * kVPitch;
+  char* base_ws = static_cast<char*>(ws);
+  const int32_t* tile_nblk = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_nblk);
+  const int64_t slot = (int64_t)blockIdx.x * 4 + wave;
+  const bool split = tile_split_active(pl, ws);
+  int64_t t;
+  int k0, k1;
+  float* part = nullptr;
+  if (slot < kTileItemSlots) {
+    if (!split) return;
+    const uint32_t n_items = reinterpret_cast<const uint32_t*>(ws)[kCtrTileItems];
+    if (slot >= n_items) return;
+    const int2 item = reinterpret_cast<const int2*>(base_ws + pl.off_titems)[slot];
+    t = item.x;
+    int nch, len;
+    tile_split_shape(tile_nblk[t], nch, len);
+    k0 = item.y * len;
+    k1 = k0 + len < tile_nblk[t] ? k0 + len : tile_nblk[t];
+    part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
+           (slot * H + blockIdx.y) * (int64_t)kTilePartialFloats;
+  } else {
+    t = slot - kTileItemSlots;
+    if (t >= pl.n_tiles) return;
+    const int nblk = tile_nblk[t];
+    if (nblk < 0) return;                                   // tile left to the gather path
+    if (nblk > kTileSplitThreshold && split) return;        // handled by chunk items
+    k0 = 0;
+    k1 = nblk;
+  }
+  const int64_t hoff = (int64_t)blockIdx.y * L * kHeadDim;
+  const int64_t slot0 = row_ptr[t * kTile] / kPairEdges;
+  ExplicitBlocks src{reinterpret_cast<const int32_t*>(base_ws + pl.off_pair_blk) + slot0,
+                     reinterpret_cast<const uint32_t*>(base_ws + pl.off_pair_mask) + slot0 * kTile, L};
+  const int64_t qrow = t * kTile + n;
+  const bool exists = qrow < L;
+  typename CoreOf<T>::type core;
+  core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h);
+  TileState st;
+  st.init();
+  core.run(K + hoff, V + hoff, src, k0, k1, scale * kLog2e, lane, st, lds);
+  if (part) {
+    store_partial(part, st, n, h);
+  } else {
+    finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.y * L : nullptr, qrow, qrow, exists, st, h);
+  }
+}
+
+__device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
+__device__ __forceinline__ void store_out(__half* p, float v) { *p = __float2half_rn(v); }
+
+// One wavefront per (split tile, head): lane = channel; rows one after another, chunks in order.
+template <typename T>
+__global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
+                                                         const int64_t* __restrict__ row_ptr, int64_t L,
+                                                         void* ws, size_t ws_bytes) {
+  const int32_t H = (int32_t)gridDim.y;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  if (pl.total_bytes > ws_bytes || !tile_split_active(pl, ws)) return;
+  char* base_ws = static_cast<char*>(ws);
+  const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrTileLong];
+  const int4* tl = reinterpret_cast<const int4*>(base_ws + pl.off_tlong);
+  const float* parts = reinterpret_cast<const float*>(base_ws + pl.off_tpartials);
+  const int lane = threadIdx.x & (kWave - 1);
+  const int waves = blockDim.x / kWave;
+  const int64_t hd = blockIdx.y;
+  // work unit = (split tile, row of the tile)
+  for (int64_t w = (int64_t)blockIdx.x * waves + threadIdx.x / kWave; w < (int64_t)n_long * kTile;
+       w += (int64_t)gridDim.x * waves) {
+    const int4 rec = tl[w / kTile];
+    const int r = (int)(w % kTile);
+    const int64_t row = (int64_t)rec.x * kTile + r;
+    if (row >= L) continue;
+    const float* p0 = parts + ((int64_t)rec.y * H + hd) * kTilePartialFloats;
+    const int64_t step = (int64_t)H * kTilePartialFloats;
+    float M = kMinusHuge;
+    for (int c = 0; c < rec.z; ++c) M = fmaxf(M, p0[c * step + kTile * 64 + r]);
+    float l = 0.f, acc = 0.f;
+    for (int c = 0; c < rec.z; ++c) {
+      const float wgt = __builtin_amdgcn_exp2f(p0[c * step + kTile * 64 + r] - M);
+      l = __builtin_fmaf(p0[c * step + kTile * 64 + kTile + r], wgt, l);
+      acc = __builtin_fmaf(p0[c * step + r * 64 + lane], wgt, acc);
+    }
+    const bool empty = !(l > 0.f);
+    store_out(O + hd * L * kHeadDim + row * kHeadDim + lane, empty ? 0.f : acc / l);
+    if (lse && lane == 0)
+      lse[hd * L + row] = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+  }
+}
+
+// Implicit window masks: grid.x = tiles of a residue class (4 per workgroup), grid.y = class,
+// grid.z = head.
+template <typename T>
+__global__ __launch_bounds__(256) void tile_window_kernel(const T* __restrict__ Q,
+                                                          const T* __restrict__ K,
+                                                          const T* __restrict__ V, T* __restrict__ O,
+                                                          float* __restrict__ lse, int64_t L, int64_t W,
+                                                          int64_t s, float scale) {
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * kTile * kVPitch];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int n = lane & 31, h = lane >> 5;
+  char* lds = lds_all + wave * kTile * kVPitch;
+  const int64_t p = blockIdx.y;
+  if (p >= L) return;
+  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
+  const int64_t u0 = ((int64_t)blockIdx.x * 4 + wave) * kTile;
+  if (u0 >= Lc) return;
+  const int64_t hd = blockIdx.z;
+  const int64_t hoff = hd * L * kHeadDim;
+  const int64_t vlo = u0 - W > 0 ? u0 - W : 0;
+  const int64_t vhi = u0 + kTile - 1 + W < Lc - 1 ? u0 + kTile - 1 + W : Lc - 1;
+  WindowBlocks src{vlo / kTile, Lc, s, p, u0, W};
+  const int nblk = (int)(vhi / kTile - vlo / kTile + 1);
+  const int64_t u = u0 + n;
+  const bool exists = u < Lc;
+  const int64_t qrow = s * (exists ? u : Lc - 1) + p;
+  typename CoreOf<T>::type core;
+  core.load_q(Q + hoff + qrow * kHeadDim, h);
+  TileState st;
+  st.init();
+  core.run(K + hoff, V + hoff, src, 0, nblk, scale * kLog2e, lane, st, lds);
+  finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h);
+}
+
+template <typename T>
+sga_status run_tile_explicit(const AttnArgs& a) {
+  const T* Q = static_cast<const T*>(a.Q);
+  const T* K = static_cast<const T*>(a.K);
+  const T* V = static_cast<const T*>(a.V);
+  T* O = static_cast<T*>(a.O);
+  const int64_t n_tiles = (a.L + kTile - 1) / kTile;
+  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)((n_tiles + 3) / 4)), dim3(256), 0, a.stream,
+                     a.row_ptr, a.col_idx, a.L, a.H, a.ws, a.ws_bytes);
+  const unsigned nwg = (unsigned)((kTileItemSlots + n_tiles + 3) / 4);
+  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3(nwg, (unsigned)a.H), dim3(256), 0, a.stream, Q, K, V,
+                     O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
+  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O, a.lse,
+                     a.row_ptr, a.L, a.ws, a.ws_bytes);
+  return hip_status(hipGetLastError());
+}
+
+template <typename T>
+sga_status run_tile_implicit(const AttnArgs& a) {
+  const int64_t s = a.stride;
+  const int64_t Lc = (a.L + s - 1) / s;
+  const int64_t n_tiles = (Lc + kTile - 1) / kTile;
+  const dim3 grid((unsigned)((n_tiles + 3) / 4), (unsigned)s, (unsigned)a.H);
+  hipLaunchKernelGGL(tile_window_kernel<T>, grid, dim3(256), 0, a.stream, static_cast<const T*>(a.Q),
+                     static_cast<const T*>(a.K), static_cast<const T*>(a.V), static_cast<T*>(a.O),
+                     a.lse, a.L, (int64_t)a.window, s, a.scale);
+  return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+sga_status launch_tile_explicit(const AttnArgs& a) {
+  if (!a.ws || a.ws_bytes < 256) return launch_gather_explicit(a, false, false);
+  sga_status st = a.dtype == SGA_F32 ? run_tile_explicit<float>(a) : run_tile_explicit<__half>(a);
+  if (st != SGA_OK) return st;
+  // rows of tiles that did not qualify (or everything, if the workspace is too small)
+  return launch_gather_explicit(a, true, true);
+}
+
+sga_status launch_tile_implicit(const AttnArgs& a) {
+  if (a.stride > 65535 || a.H > 65535) return launch_gather_implicit(a);
+  return a.dtype == SGA_F32 ? run_tile_implicit<float>(a) : run_tile_implicit<__half>(a);
+}
 
 }  // namespace sga
