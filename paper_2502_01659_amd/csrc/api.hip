@@ -63,7 +63,7 @@ sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, i
   if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
   if (d != kHeadDim) return SGA_ERR_UNSUPPORTED;
   if (nnz < -1 || nnz > L * L) return SGA_ERR_INVALID_ARG;
-  *bytes_out = plan_workspace(L, H, nnz).total_bytes;
+  *bytes_out = plan_workspace(L, H, nnz, dtype).total_bytes;
   return SGA_OK;
 }
 
@@ -82,7 +82,7 @@ sga_status sga_attention_forward(const void* Q, const void* K, const void* V, co
   a.ws = workspace; a.ws_bytes = workspace_bytes;
   if (path == SGA_PATH_TILE && (!workspace || workspace_bytes < 256)) return SGA_ERR_WORKSPACE;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
-  if (workspace && workspace_bytes >= 256) clear_workspace_counters(workspace, a.stream);
+  if (workspace && workspace_bytes >= 256) clear_workspace(a, path != SGA_PATH_GATHER);
   if (path == SGA_PATH_GATHER) return launch_gather_explicit(a, true, false);
   return launch_tile_explicit(a);
 }

@@ -202,22 +202,34 @@ __host__ __device__ inline void split_shape(int64_t deg, int32_t& nchunks, int32
 
 // ---- kernels ----------------------------------------------------------------
 
-__global__ void clear_counters_kernel(uint32_t* ctr) {
-  if (threadIdx.x < kNumCounters) ctr[threadIdx.x] = 0;
+// Zeroes the counters and (tile_flags != 0) the per-tile flags of the tile path.
+__global__ __launch_bounds__(256) void clear_workspace_kernel(void* ws, size_t ws_bytes,
+                                                              const int64_t* row_ptr, int64_t L,
+                                                              int32_t H, int32_t dtype,
+                                                              int tile_flags) {
+  uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
+  if (blockIdx.x == 0 && threadIdx.x < kNumCounters) ctr[threadIdx.x] = 0;
+  if (!tile_flags) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  if (pl.total_bytes > ws_bytes) return;
+  int32_t* bad = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + pl.off_tile_bad);
+  for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < pl.n_tiles;
+       t += (int64_t)gridDim.x * blockDim.x)
+    bad[t] = 0;
 }
 
 // One thread per row: rows over the split threshold reserve chunk work items.
 __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __restrict__ row_ptr,
-                                                            int64_t L, int32_t H, void* ws,
-                                                            size_t ws_bytes, int skip_tiled) {
+                                                            int64_t L, int32_t H, int32_t dtype,
+                                                            void* ws, size_t ws_bytes,
+                                                            int skip_tiled) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= L) return;
   const int64_t deg = row_ptr[i + 1] - row_ptr[i];
   if (deg <= kSplitThreshold) return;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
   if (pl.total_bytes > ws_bytes) return;
-  if (skip_tiled &&
-      reinterpret_cast<const int32_t*>(static_cast<const char*>(ws) + pl.off_tile_nblk)[i / kTile] >= 0)
+  if (skip_tiled && (tiles_cover_everything(pl, ws) || tile_handled(pl, ws, row_ptr, L, dtype, i / kTile)))
     return;
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   int32_t n, len;
@@ -234,9 +246,9 @@ __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __res
 
 // True when the long rows of this call are handled by the chunk kernels.
 __device__ __forceinline__ bool split_active(const int64_t* row_ptr, int64_t L, int32_t H,
-                                             const void* ws, size_t ws_bytes) {
+                                             int32_t dtype, const void* ws, size_t ws_bytes) {
   if (!ws) return false;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
   if (pl.total_bytes > ws_bytes) return false;
   const uint32_t need = reinterpret_cast<const uint32_t*>(ws)[kCtrChunksNeeded];
   return (int64_t)need <= pl.cap_items;
@@ -244,12 +256,11 @@ __device__ __forceinline__ bool split_active(const int64_t* row_ptr, int64_t L, 
 
 // True when this call's tile path produced row i (its 32-row tile has a block list).
 __device__ __forceinline__ bool row_done_by_tiles(const int64_t* row_ptr, int64_t L, int32_t H,
-                                                  const void* ws, size_t ws_bytes, int64_t i) {
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+                                                  int32_t dtype, const void* ws, size_t ws_bytes,
+                                                  int64_t i) {
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
   if (pl.total_bytes > ws_bytes) return false;
-  const int32_t* nblk =
-      reinterpret_cast<const int32_t*>(static_cast<const char*>(ws) + pl.off_tile_nblk);
-  return nblk[i / kTile] >= 0;
+  return tile_handled(pl, ws, row_ptr, L, dtype, i / kTile);
 }
 
 template <typename T>
@@ -262,11 +273,15 @@ __global__ __launch_bounds__(256) void gather_csr_kernel(
   const int64_t h = blockIdx.y;
   const int32_t H = (int32_t)gridDim.y;
   const int64_t hoff = h * L * kHeadDim;
+  if (skip_tiled) {
+    const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
+    if (pl.total_bytes <= ws_bytes && tiles_cover_everything(pl, ws)) return;
+  }
   for (int64_t i = (int64_t)blockIdx.x * waves + (threadIdx.x / kWave); i < L;
        i += (int64_t)gridDim.x * waves) {
-    if (skip_tiled && row_done_by_tiles(row_ptr, L, H, ws, ws_bytes, i)) continue;
+    if (skip_tiled && row_done_by_tiles(row_ptr, L, H, DtypeOf<T>::code, ws, ws_bytes, i)) continue;
     const int64_t r0 = row_ptr[i], r1 = row_ptr[i + 1];
-    if (use_split && r1 - r0 > kSplitThreshold && split_active(row_ptr, L, H, ws, ws_bytes))
+    if (use_split && r1 - r0 > kSplitThreshold && split_active(row_ptr, L, H, DtypeOf<T>::code, ws, ws_bytes))
       continue;
     float q[Row<T>::VEC];
     load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
@@ -304,8 +319,9 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
     const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t L, float scale,
     void* ws, size_t ws_bytes) {
   const int32_t H = (int32_t)gridDim.y;
-  if (!split_active(row_ptr, L, H, ws, ws_bytes)) return;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  constexpr int32_t dtype = DtypeOf<T>::code;
+  if (!split_active(row_ptr, L, H, dtype, ws, ws_bytes)) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
   const uint32_t n_items = reinterpret_cast<const uint32_t*>(ws)[kCtrItemsAlloc];
   const int2* items = reinterpret_cast<const int2*>(static_cast<char*>(ws) + pl.off_items);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_partials);
@@ -347,8 +363,9 @@ __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, fl
                                                            const int64_t* __restrict__ row_ptr,
                                                            int64_t L, void* ws, size_t ws_bytes) {
   const int32_t H = (int32_t)gridDim.y;
-  if (!split_active(row_ptr, L, H, ws, ws_bytes)) return;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  constexpr int32_t dtype = DtypeOf<T>::code;
+  if (!split_active(row_ptr, L, H, dtype, ws, ws_bytes)) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
   const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrLongRows];
   const int4* lr = reinterpret_cast<const int4*>(static_cast<char*>(ws) + pl.off_long);
   const float* partials = reinterpret_cast<const float*>(static_cast<char*>(ws) + pl.off_partials);
@@ -385,7 +402,7 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   const bool split = allow_split && a.ws && a.ws_bytes >= 256 && a.L > kSplitThreshold;
   if (split) {
     hipLaunchKernelGGL(split_prepass_kernel, dim3((unsigned)((a.L + 255) / 256)), dim3(256), 0,
-                       a.stream, a.row_ptr, a.L, a.H, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
+                       a.stream, a.row_ptr, a.L, a.H, a.dtype, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
   }
   // after the tile path only leftover rows remain: a small grid strides over the rows
   int64_t nwg = (a.L + 3) / 4;
@@ -405,9 +422,12 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
 
 }  // namespace
 
-void clear_workspace_counters(void* ws, hipStream_t stream) {
-  hipLaunchKernelGGL(clear_counters_kernel, dim3(1), dim3(64), 0, stream,
-                     reinterpret_cast<uint32_t*>(ws));
+void clear_workspace(const AttnArgs& a, bool tile_flags) {
+  const int64_t n_tiles = (a.L + kTile - 1) / kTile;
+  int64_t nwg = tile_flags ? (n_tiles + 255) / 256 : 1;
+  if (nwg > 1024) nwg = 1024;
+  hipLaunchKernelGGL(clear_workspace_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.ws,
+                     a.ws_bytes, a.row_ptr, a.L, a.H, a.dtype, tile_flags ? 1 : 0);
 }
 
 sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {

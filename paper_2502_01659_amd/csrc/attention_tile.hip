@@ -23,9 +23,9 @@
 // v_mfma_f32_32x32x16_f16 with fp32 accumulation; P is rounded to fp16 only as the MFMA
 // operand, l is summed in fp32.
 //
-// Tiles with very long block lists (global-token rows) are cut into chunks that are
-// processed by extra wavefronts of the same launch; their partial (m, l, acc) states are
-// merged in chunk order by tile_merge_kernel (deterministic).
+// Tiles with many edges (global-token rows) are cut into segments of their key-block span;
+// each segment is one more work item of the same launches, leaves a partial (m, l, acc)
+// state, and tile_merge_kernel combines the partials in segment order (deterministic).
 #include "sga_internal.h"
 
 namespace sga {
@@ -34,6 +34,7 @@ namespace {
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
@@ -74,10 +75,10 @@ struct ExplicitBlocks {
 // Block list of a window tile in one residue class p of stride s: queries u0..u0+31 and keys
 // v of the class (token = s*index + p), edge iff |u - v| <= W.
 struct WindowBlocks {
-  int64_t kb0, Lc, s, p, u0, W;
+  int64_t vfirst, Lc, s, p, u0, W;   // blocks start at the tile's first key, not at multiples of 32
   __device__ BlockInfo get(int k, int n) const {
     BlockInfo b;
-    const int64_t v0 = (kb0 + k) * kTile;
+    const int64_t v0 = vfirst + (int64_t)k * kTile;
     b.row0 = s * v0 + p;
     b.stride = s;
     const int64_t left = Lc - v0;
@@ -108,7 +109,13 @@ struct TileState {
   }
 };
 
-// Mask, running max/sum update and rescale for one block.  s: raw scores of this lane's
+// The running max m of Algorithm 1 only has to bound the scores for the exponentials to stay
+// finite, so it is raised lazily: a block moves m (and rescales l and O) only when its largest
+// score exceeds m by more than kRescaleSlack (log2 units).  Softmax numerators are then at most
+// 2^kRescaleSlack, well inside fp16/fp32 range, and the quotient acc/l is unchanged.
+constexpr float kRescaleSlack = 8.0f;
+
+// Mask, running max/sum update and (rare) rescale for one block.  s: raw scores of this lane's
 // query against keys acc_row(r, h); returns the block's softmax numerators in p.
 __device__ __forceinline__ void softmax_block(const floatx16& s, float c, const BlockInfo& b, int h,
                                               TileState& st, float (&p)[16]) {
@@ -124,29 +131,32 @@ __device__ __forceinline__ void softmax_block(const floatx16& s, float c, const 
     const uint32_t wh = b.word >> (4 * h);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      const bool valid = (wh >> acc_row(r, 0)) & 1u;
-      sv[r] = valid ? s[r] * c : -INFINITY;
+      // all-ones where the edge exists, else zero; then select score or -inf bitwise
+      const int keep = ((int)(wh << (31 - acc_row(r, 0)))) >> 31;
+      const int bits = (__builtin_bit_cast(int, s[r] * c) & keep) | ((int)0xff800000 & ~keep);
+      sv[r] = __builtin_bit_cast(float, bits);
       bm = fmaxf(bm, sv[r]);
     }
   }
   bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
-  const float m_new = fmaxf(st.m, bm);
-  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
-  st.m = m_new;
-  float lsum = 0.f;
-#pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    p[r] = __builtin_amdgcn_exp2f(sv[r] - m_new);
-    lsum += p[r];
-  }
-  st.l = st.l * alpha + lsum;
-  if (__any(alpha != 1.0f)) {
+  if (__any(bm > st.m + kRescaleSlack)) {
+    const float m_new = bm > st.m + kRescaleSlack ? bm : st.m;
+    const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+    st.l *= alpha;
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       st.o[0][r] *= alpha;
       st.o[1][r] *= alpha;
     }
   }
+  float lsum = 0.f;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    p[r] = __builtin_amdgcn_exp2f(sv[r] - st.m);
+    lsum += p[r];
+  }
+  st.l += lsum;
 }
 
 // ---- fp32 storage ---------------------------------------------------------------------------
@@ -162,21 +172,31 @@ struct CoreF32 {
     }
   }
 
+  __device__ static void load_k(const float* __restrict__ Kh, const BlockInfo& b, int n, int h,
+                                float (&kf)[32]) {
+    const int krow = n < b.nvalid ? n : b.nvalid - 1;
+    const float4* kp =
+        reinterpret_cast<const float4*>(Kh + (b.row0 + krow * b.stride) * kHeadDim + h * 32);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float4 v = kp[t];
+      kf[4 * t] = v.x; kf[4 * t + 1] = v.y; kf[4 * t + 2] = v.z; kf[4 * t + 3] = v.w;
+    }
+  }
+
+  // Block ids and mask words are fetched one block ahead, so the K/V loads of a block never
+  // wait on a dependent chain id -> address -> data; with two wavefronts per SIMD one
+  // wavefront's loads overlap the other's matrix work.
   template <typename Src>
   __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* /*lds*/) {
+    if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
+    BlockInfo b_next = src.get(k0, n);
     for (int k = k0; k < k1; ++k) {
-      const BlockInfo b = src.get(k, n);
-      const int krow = n < b.nvalid ? n : b.nvalid - 1;
-      const float4* kp =
-          reinterpret_cast<const float4*>(Kh + (b.row0 + krow * b.stride) * kHeadDim + h * 32);
+      const BlockInfo b = b_next;
       float kf[32];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const float4 v = kp[t];
-        kf[4 * t] = v.x; kf[4 * t + 1] = v.y; kf[4 * t + 2] = v.z; kf[4 * t + 3] = v.w;
-      }
+      load_k(Kh, b, n, h, kf);
       // V[key acc_row(r,h)][cb*32 + n]
       float vf[2][16];
 #pragma unroll
@@ -187,6 +207,7 @@ struct CoreF32 {
         vf[0][r] = vp[0];
         vf[1][r] = vp[32];
       }
+      if (k + 1 < k1) b_next = src.get(k + 1, n);
       floatx16 s = {0};
 #pragma unroll
       for (int t = 0; t < 32; ++t)
@@ -223,32 +244,54 @@ struct CoreF16 {
     for (int s = 0; s < 4; ++s) qf[s] = src[s];
   }
 
+  __device__ static void load_kv(const __half* __restrict__ Kh, const __half* __restrict__ Vh,
+                                 const BlockInfo& b, int n, int h, half8 (&kf)[4], uint4 (&vraw)[4]) {
+    const int krow = n < b.nvalid ? n : b.nvalid - 1;
+    const int64_t roff = (b.row0 + krow * b.stride) * kHeadDim + h * 32;
+    const half8* kp = reinterpret_cast<const half8*>(Kh + roff);
+    const uint4* vp = reinterpret_cast<const uint4*>(Vh + roff);
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      kf[s] = kp[s];
+      vraw[s] = vp[s];
+    }
+  }
+
+  // 4 keys x 1 channel per lane out of the row-major staged V block, using the LDS transpose
+  // read of gfx950: inside a 16-lane group, lane i receives element (i % 4) of the 8 bytes
+  // addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4.  Lane i therefore addresses key
+  // (key0 + i/4) at channels 4*(i%4).. of its group's 16 channels, and ends up with channel i of
+  // the group for keys key0..key0+3: the K-contiguous A operand of V^T.
+  __device__ static half4 read_vt(const char* lds, int key0, int cb, int lane) {
+    const int i = lane & 15, grp16 = (lane >> 4) & 1;
+    const char* p = lds + (key0 + (i >> 2)) * kVPitch + (cb * 32 + grp16 * 16 + 4 * (i & 3)) * 2;
+    const short4v raw =
+        __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
+    return __builtin_bit_cast(half4, raw);
+  }
+
+  // Block ids and mask words are fetched one block ahead (see CoreF32::run).
   template <typename Src>
   __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
+    if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
+    BlockInfo b_next = src.get(k0, n);
     for (int k = k0; k < k1; ++k) {
-      const BlockInfo b = src.get(k, n);
-      const int krow = n < b.nvalid ? n : b.nvalid - 1;
-      const int64_t roff = (b.row0 + krow * b.stride) * kHeadDim + h * 32;
-      const half8* kp = reinterpret_cast<const half8*>(Kh + roff);
-      const uint4* vp = reinterpret_cast<const uint4*>(Vh + roff);
+      const BlockInfo b = b_next;
       half8 kf[4];
       uint4 vraw[4];
+      load_kv(Kh, Vh, b, n, h, kf, vraw);
+      if (k + 1 < k1) b_next = src.get(k + 1, n);
+      floatx16 sacc = {0};
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        kf[s] = kp[s];
-        vraw[s] = vp[s];
-      }
+      for (int s = 0; s < 4; ++s)
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
       // stage the V block row-major in this wavefront's LDS slice: row = key n, 64 B per half-wave
       __builtin_amdgcn_wave_barrier();   // earlier reads of the slice are done (in-order LDS queue)
 #pragma unroll
       for (int s = 0; s < 4; ++s)
         *reinterpret_cast<uint4*>(lds + n * kVPitch + h * 64 + 16 * s) = vraw[s];
-      floatx16 sacc = {0};
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
       float p[16];
       softmax_block(sacc, c, b, h, st, p);
       __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
@@ -261,13 +304,10 @@ struct CoreF16 {
         for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[8 * u + e];
 #pragma unroll
         for (int cb = 0; cb < 2; ++cb) {
-          // A operand: V^T[channel cb*32+n][key of slot (u,h,e)] = staged V[key][channel]
-          half8 va;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const int key = acc_row(8 * u + e, 0) + 4 * h;
-            va[e] = *reinterpret_cast<const _Float16*>(lds + key * kVPitch + (cb * 32 + n) * 2);
-          }
+          // A operand: V^T[channel cb*32+n][slot (u,h,e)], slot key = 16u + 8(e/4) + 4h + e%4
+          const half4 lo = read_vt(lds, 16 * u + 4 * h, cb, lane);
+          const half4 hi = read_vt(lds, 16 * u + 8 + 4 * h, cb, lane);
+          const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
           st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
         }
       }
@@ -320,13 +360,6 @@ __device__ __forceinline__ void store_partial(float* part, TileState& st, int n,
   }
 }
 
-__host__ __device__ inline void tile_split_shape(int nblk, int& nchunks, int& len) {
-  int n = (nblk + kTileChunk - 1) / kTileChunk;
-  if (n > kTileMaxSplit) n = kTileMaxSplit;
-  len = (nblk + n - 1) / n;
-  nchunks = (nblk + len - 1) / len;
-}
-
 __device__ __forceinline__ int half_min(int v) {   // min over the 32 lanes of a half-wave
 #pragma unroll
   for (int off = 16; off > 0; off >>= 1) {
@@ -336,85 +369,196 @@ __device__ __forceinline__ int half_min(int v) {   // min over the 32 lanes of a
   return v;
 }
 
+__device__ __forceinline__ int half_max(int v) {
+#pragma unroll
+  for (int off = 16; off > 0; off >>= 1) {
+    const int o = __shfl_xor(v, off, kWave);
+    v = o > v ? o : v;
+  }
+  return v;
+}
+
+// First position in [lo, hi) of the sorted column list whose column is >= key.
+__device__ __forceinline__ int64_t lower_bound_col(const int32_t* __restrict__ col, int64_t lo,
+                                                   int64_t hi, int64_t key) {
+  while (lo < hi) {
+    const int64_t mid = lo + ((hi - lo) >> 1);
+    if (col[mid] < key) lo = mid + 1; else hi = mid;
+  }
+  return lo;
+}
+
+// Work item w -> (tile, item index within the tile, segments of the tile).  With S = seg_edges
+// and f(t) = t + row_ptr[min(32t, L)] / S, tile t owns the items [f(t), f(t+1)); items with
+// index >= segments are idle.
+struct WorkId {
+  int64_t tile;
+  int32_t seg, nseg;
+};
+
+__device__ __forceinline__ WorkId locate_work(const int64_t* __restrict__ row_ptr, int64_t L,
+                                              int64_t S, int64_t n_tiles, int64_t n_work, int64_t w) {
+  // interpolation guess, then galloping, then bisection: largest t with f(t) <= w
+  int64_t lo, hi;
+  int64_t g = (int64_t)((double)w * (double)n_tiles / (double)n_work);
+  if (g >= n_tiles) g = n_tiles - 1;
+  if (work_first(row_ptr, L, S, g) <= w) {
+    lo = g;
+    int64_t step = 1;
+    hi = n_tiles;
+    while (lo + step < n_tiles) {
+      if (work_first(row_ptr, L, S, lo + step) <= w) { lo += step; step <<= 1; }
+      else { hi = lo + step; break; }
+    }
+  } else {
+    hi = g;
+    int64_t step = 1;
+    lo = 0;
+    while (hi - step > 0) {
+      if (work_first(row_ptr, L, S, hi - step) > w) { hi -= step; step <<= 1; }
+      else { lo = hi - step; break; }
+    }
+  }
+  while (hi - lo > 1) {
+    const int64_t mid = lo + ((hi - lo) >> 1);
+    if (work_first(row_ptr, L, S, mid) <= w) lo = mid; else hi = mid;
+  }
+  WorkId id;
+  id.tile = lo;
+  const int64_t f0 = work_first(row_ptr, L, S, lo);
+  id.seg = (int32_t)(w - f0);
+  id.nseg = tile_segments(row_ptr, L, S, lo);
+  return id;
+}
+
 // ---- CSR -> tile graph ------------------------------------------------------------------------
-// One wavefront per tile; lane r < 32 walks row 32t + r.  A 32-way merge by key block id:
-// every round takes the smallest block id at the head of any row and lets each row consume
-// its columns inside that block into a 32-bit word.
+// One wavefront per work item (a tile, or one key-block range of a tile with many edges);
+// lane r < 32 walks row 32t + r.  A 32-way merge by key block id: every round takes the
+// smallest block id at the head of any row and lets each row consume its columns inside that
+// block into a 32-bit word.  A row whose remaining columns are consecutive integers (windows,
+// global rows) is walked arithmetically without reading col_idx again.
 __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __restrict__ row_ptr,
                                                            const int32_t* __restrict__ col_idx,
-                                                           int64_t L, int32_t H, void* ws,
-                                                           size_t ws_bytes) {
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+                                                           int64_t L, int32_t H, int32_t dtype,
+                                                           void* ws, size_t ws_bytes) {
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
   if (pl.total_bytes > ws_bytes) return;
+  const int64_t S = seg_edges(dtype);
   const int lane = threadIdx.x & (kWave - 1);
-  const int64_t t = (int64_t)blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  if (t >= pl.n_tiles) return;
+  const int waves = blockDim.x / kWave;
   char* base_ws = static_cast<char*>(ws);
-  int32_t* tile_nblk = reinterpret_cast<int32_t*>(base_ws + pl.off_tile_nblk);
+  int32_t* seg_tile = reinterpret_cast<int32_t*>(base_ws + pl.off_seg_tile);
+  int2* seg_meta = reinterpret_cast<int2*>(base_ws + pl.off_seg_meta);
+  int32_t* seg_count = reinterpret_cast<int32_t*>(base_ws + pl.off_seg_count);
+  int32_t* tile_bad = reinterpret_cast<int32_t*>(base_ws + pl.off_tile_bad);
+  int32_t* tile_pbase = reinterpret_cast<int32_t*>(base_ws + pl.off_tile_pbase);
   int32_t* pair_blk = reinterpret_cast<int32_t*>(base_ws + pl.off_pair_blk);
   uint32_t* pair_mask = reinterpret_cast<uint32_t*>(base_ws + pl.off_pair_mask);
-  const int64_t row_first = t * kTile;
-  const int64_t row_last = row_first + kTile < L ? row_first + kTile : L;
-  const int64_t slot0 = row_ptr[row_first] / kPairEdges;
-  const int64_t cap = row_ptr[row_last] / kPairEdges - slot0;
-  const int64_t row = row_first + lane;
-  const bool active = lane < kTile && row < L;
-  int64_t pos = active ? row_ptr[row] : 0;
-  const int64_t end = active ? row_ptr[row + 1] : 0;
-  int nblk = 0;
-  bool overflow = false;
-  while (true) {
-    const int cur = pos < end ? (col_idx[pos] >> 5) : INT32_MAX;
-    const int b = __shfl(half_min(cur), 0, kWave);
-    if (b == INT32_MAX) break;
-    if (nblk >= cap) {
-      overflow = true;
-      break;
+  uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
+  for (int64_t w = (int64_t)blockIdx.x * waves + threadIdx.x / kWave; w < pl.n_work;
+       w += (int64_t)gridDim.x * waves) {
+    const WorkId id = locate_work(row_ptr, L, S, pl.n_tiles, pl.n_work, w);
+    if (id.seg >= id.nseg) {          // spare item of a tile whose edge range crosses a multiple of S
+      if (lane == 0) seg_tile[w] = -1;
+      continue;
     }
-    uint32_t word = 0;
-    if (cur == b) {
-      const int c0 = col_idx[pos];
-      if ((c0 & 31) == 0 && pos + 31 < end && col_idx[pos + 31] == c0 + 31) {
-        word = ~0u;   // 32 consecutive columns: the whole block row
-        pos += 32;
-      } else {
-        while (pos < end) {
-          const int cc = col_idx[pos];
-          if ((cc >> 5) != b) break;
-          word |= 1u << (cc & 31);
-          ++pos;
-        }
+    const int64_t t = id.tile;
+    const int64_t row_first = t * kTile;
+    const int64_t row_last = row_first + kTile < L ? row_first + kTile : L;
+    const int64_t slot_t = row_ptr[row_first] / kPairEdges;
+    const int64_t cap_t = row_ptr[row_last] / kPairEdges - slot_t;
+    const int64_t cap = cap_t / id.nseg;
+    const int64_t slot0 = slot_t + (int64_t)id.seg * cap;
+    const int64_t row = row_first + lane;
+    const bool active = lane < kTile && row < L;
+    int64_t pos = active ? row_ptr[row] : 0;
+    int64_t end = active ? row_ptr[row + 1] : 0;
+    if (id.nseg > 1) {
+      // this segment's share of the tile's key-block span
+      const int first_c = pos < end ? col_idx[pos] : INT32_MAX;
+      const int last_c = pos < end ? col_idx[end - 1] : -1;
+      const int64_t bmin = __shfl(half_min(first_c), 0, kWave) >> 5;
+      const int64_t bmax = __shfl(half_max(last_c), 0, kWave) >> 5;
+      const int64_t span = bmax - bmin + 1;
+      const int64_t B0 = bmin + span * id.seg / id.nseg;
+      const int64_t B1 = bmin + span * (id.seg + 1) / id.nseg;
+      pos = lower_bound_col(col_idx, pos, end, B0 * kTile);
+      end = lower_bound_col(col_idx, pos, end, B1 * kTile);
+    }
+    // a row whose remaining columns are one run of consecutive integers needs no more loads
+    int run_lo = 0, run_hi = -1;
+    bool arith = false;
+    if (pos < end) {
+      const int c0 = col_idx[pos], c1 = col_idx[end - 1];
+      if ((int64_t)c1 - c0 == end - 1 - pos) {
+        arith = true;
+        run_lo = c0;
+        run_hi = c1;
       }
     }
-    const bool full = __all(lane >= kTile || word == ~0u);
-    if (lane < kTile) pair_mask[(slot0 + nblk) * kTile + lane] = word;
-    if (lane == 0) pair_blk[slot0 + nblk] = b | (full ? kFullBit : 0);
-    ++nblk;
-  }
-  if (lane != 0) return;
-  tile_nblk[t] = overflow ? -1 : nblk;
-  if (!overflow && nblk > kTileSplitThreshold && pl.cap_titems > 0) {
-    uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
-    int n, len;
-    tile_split_shape(nblk, n, len);
-    atomicAdd(&ctr[kCtrTileChunksNeeded], (uint32_t)n);
-    const uint32_t first = atomicAdd(&ctr[kCtrTileItems], (uint32_t)n);
-    if ((int64_t)first + n <= pl.cap_titems) {
-      int2* items = reinterpret_cast<int2*>(base_ws + pl.off_titems);
-      for (int c = 0; c < n; ++c) items[first + c] = make_int2((int)t, c);
-      const uint32_t slot = atomicAdd(&ctr[kCtrTileLong], 1u);
-      reinterpret_cast<int4*>(base_ws + pl.off_tlong)[slot] = make_int4((int)t, (int)first, n, len);
+    int nblk = 0;
+    bool overflow = false;
+    while (true) {
+      int cur;
+      if (arith) cur = run_lo <= run_hi ? (run_lo >> 5) : INT32_MAX;
+      else cur = pos < end ? (col_idx[pos] >> 5) : INT32_MAX;
+      const int b = __shfl(half_min(cur), 0, kWave);
+      if (b == INT32_MAX) break;
+      if (nblk >= cap) {
+        overflow = true;
+        break;
+      }
+      uint32_t word = 0;
+      if (cur == b) {
+        if (arith) {
+          const int lo = run_lo & 31;
+          const int hi = run_hi < (b << 5) + 31 ? (run_hi & 31) : 31;
+          word = (~0u >> (31 - hi)) & (~0u << lo);
+          run_lo = (b + 1) << 5;
+        } else {
+          const int c0 = col_idx[pos];
+          if ((c0 & 31) == 0 && pos + 31 < end && col_idx[pos + 31] == c0 + 31) {
+            word = ~0u;   // 32 consecutive columns: the whole block row
+            pos += 32;
+          } else {
+            while (pos < end) {
+              const int cc = col_idx[pos];
+              if ((cc >> 5) != b) break;
+              word |= 1u << (cc & 31);
+              ++pos;
+            }
+          }
+        }
+      }
+      const bool full = __all(lane >= kTile || word == ~0u);
+      if (lane < kTile) pair_mask[(slot0 + nblk) * kTile + lane] = word;
+      if (lane == 0) pair_blk[slot0 + nblk] = b | (full ? kFullBit : 0);
+      ++nblk;
+    }
+    if (lane == 0) {
+      seg_tile[w] = (int32_t)t;
+      seg_meta[w] = make_int2(id.seg, id.nseg);
+      seg_count[w] = overflow ? -1 : nblk;
+      if (overflow && atomicOr(&tile_bad[t], 1) == 0) atomicAdd(&ctr[kCtrTilesBad], 1u);
+      if (id.seg == 0 && id.nseg > 1) {
+        // reserve the tile's partial slots; if the call needs more than exist, every
+        // multi-segment tile goes to the gather path (all-or-nothing keeps runs reproducible)
+        atomicAdd(&ctr[kCtrTilePartsNeeded], (uint32_t)id.nseg);
+        const uint32_t first = atomicAdd(&ctr[kCtrTilePartsAlloc], (uint32_t)id.nseg);
+        tile_pbase[t] = (int64_t)first + id.nseg <= pl.cap_tparts ? (int32_t)first : -1;
+        const uint32_t mi = atomicAdd(&ctr[kCtrMultiTiles], 1u);
+        if ((int64_t)mi < pl.cap_tparts)
+          reinterpret_cast<int32_t*>(base_ws + pl.off_multi_tiles)[mi] = (int32_t)t;
+      }
     }
   }
 }
 
-__device__ __forceinline__ bool tile_split_active(const WorkspacePlan& pl, const void* ws) {
-  return pl.cap_titems > 0 &&
-         (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTileChunksNeeded] <= pl.cap_titems;
+__device__ __forceinline__ bool tile_parts_fit(const WorkspacePlan& pl, const void* ws) {
+  return (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTilePartsNeeded] <= pl.cap_tparts;
 }
 
-// Wave slots [0, kTileItemSlots) are chunk items of split tiles (dispatched first: they are the
-// longest pieces of work), the remaining slots are whole tiles.
+// One wavefront per work item; a segment of a multi-segment tile leaves a partial state.
 template <typename T>
 __global__ __launch_bounds__(256) void tile_attend_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
@@ -422,96 +566,113 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     size_t ws_bytes) {
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kTile * kVPitch];
   const int32_t H = (int32_t)gridDim.y;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
   if (pl.total_bytes > ws_bytes) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n = lane & 31, h = lane >> 5;
   char* lds = lds_all + wave * kTile * kVPitch;
   char* base_ws = static_cast<char*>(ws);
-  const int32_t* tile_nblk = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_nblk);
-  const int64_t slot = (int64_t)blockIdx.x * 4 + wave;
-  const bool split = tile_split_active(pl, ws);
-  int64_t t;
-  int k0, k1;
-  float* part = nullptr;
-  if (slot < kTileItemSlots) {
-    if (!split) return;
-    const uint32_t n_items = reinterpret_cast<const uint32_t*>(ws)[kCtrTileItems];
-    if (slot >= n_items) return;
-    const int2 item = reinterpret_cast<const int2*>(base_ws + pl.off_titems)[slot];
-    t = item.x;
-    int nch, len;
-    tile_split_shape(tile_nblk[t], nch, len);
-    k0 = item.y * len;
-    k1 = k0 + len < tile_nblk[t] ? k0 + len : tile_nblk[t];
-    part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
-           (slot * H + blockIdx.y) * (int64_t)kTilePartialFloats;
-  } else {
-    t = slot - kTileItemSlots;
-    if (t >= pl.n_tiles) return;
-    const int nblk = tile_nblk[t];
-    if (nblk < 0) return;                                   // tile left to the gather path
-    if (nblk > kTileSplitThreshold && split) return;        // handled by chunk items
-    k0 = 0;
-    k1 = nblk;
-  }
+  const int32_t* seg_tile = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_tile);
+  const int2* seg_meta = reinterpret_cast<const int2*>(base_ws + pl.off_seg_meta);
+  const int32_t* seg_count = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_count);
+  const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
+  const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
+  const bool parts_fit = tile_parts_fit(pl, ws);
   const int64_t hoff = (int64_t)blockIdx.y * L * kHeadDim;
-  const int64_t slot0 = row_ptr[t * kTile] / kPairEdges;
-  ExplicitBlocks src{reinterpret_cast<const int32_t*>(base_ws + pl.off_pair_blk) + slot0,
-                     reinterpret_cast<const uint32_t*>(base_ws + pl.off_pair_mask) + slot0 * kTile, L};
-  const int64_t qrow = t * kTile + n;
-  const bool exists = qrow < L;
-  typename CoreOf<T>::type core;
-  core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h);
-  TileState st;
-  st.init();
-  core.run(K + hoff, V + hoff, src, k0, k1, scale * kLog2e, lane, st, lds);
-  if (part) {
-    store_partial(part, st, n, h);
-  } else {
-    finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.y * L : nullptr, qrow, qrow, exists, st, h);
+  for (int64_t w = (int64_t)blockIdx.x * 4 + wave; w < pl.n_work; w += (int64_t)gridDim.x * 4) {
+    const int64_t t = seg_tile[w];
+    if (t < 0 || tile_bad[t]) continue;                     // idle item / tile left to the gather path
+    const int2 meta = seg_meta[w];
+    if (meta.y > 1 && !parts_fit) continue;
+    const int64_t row_first = t * kTile;
+    const int64_t row_last = row_first + kTile < L ? row_first + kTile : L;
+    const int64_t slot_t = row_ptr[row_first] / kPairEdges;
+    const int64_t cap = (row_ptr[row_last] / kPairEdges - slot_t) / meta.y;
+    const int64_t slot0 = slot_t + (int64_t)meta.x * cap;
+    ExplicitBlocks src{reinterpret_cast<const int32_t*>(base_ws + pl.off_pair_blk) + slot0,
+                       reinterpret_cast<const uint32_t*>(base_ws + pl.off_pair_mask) + slot0 * kTile, L};
+    const int64_t qrow = row_first + n;
+    const bool exists = qrow < L;
+    typename CoreOf<T>::type core;
+    core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h);
+    TileState st;
+    st.init();
+    core.run(K + hoff, V + hoff, src, 0, seg_count[w], scale * kLog2e, lane, st, lds);
+    if (meta.y > 1) {
+      float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
+                    (((int64_t)tile_pbase[t] + meta.x) * H + blockIdx.y) * (int64_t)kTilePartialFloats;
+      store_partial(part, st, n, h);
+    } else {
+      finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.y * L : nullptr, qrow, qrow, exists, st, h);
+    }
   }
 }
 
 __device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(__half* p, float v) { *p = __float2half_rn(v); }
 
-// One wavefront per (split tile, head): lane = channel; rows one after another, chunks in order.
+// Merge of a multi-segment tile's partial states.  grid = (tiles of the merge list, head,
+// groups of 4 rows); the 4 wavefronts of a workgroup take every 4th segment of a row, reduce
+// theirs in segment order, and wavefront 0 combines the four results in wavefront order, so
+// the summation order is fixed.  lane = channel.
 template <typename T>
 __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                          const int64_t* __restrict__ row_ptr, int64_t L,
                                                          void* ws, size_t ws_bytes) {
+  __shared__ float sm_acc[4][kHeadDim];
+  __shared__ float sm_m[4], sm_l[4];
   const int32_t H = (int32_t)gridDim.y;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L]);
-  if (pl.total_bytes > ws_bytes || !tile_split_active(pl, ws)) return;
+  constexpr int32_t dtype = DtypeOf<T>::code;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  if (pl.total_bytes > ws_bytes || !tile_parts_fit(pl, ws)) return;
   char* base_ws = static_cast<char*>(ws);
-  const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrTileLong];
-  const int4* tl = reinterpret_cast<const int4*>(base_ws + pl.off_tlong);
+  const uint32_t n_multi = reinterpret_cast<const uint32_t*>(ws)[kCtrMultiTiles];
+  const int32_t* multi = reinterpret_cast<const int32_t*>(base_ws + pl.off_multi_tiles);
+  const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
+  const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
   const float* parts = reinterpret_cast<const float*>(base_ws + pl.off_tpartials);
   const int lane = threadIdx.x & (kWave - 1);
-  const int waves = blockDim.x / kWave;
+  const int wave = threadIdx.x / kWave;
   const int64_t hd = blockIdx.y;
-  // work unit = (split tile, row of the tile)
-  for (int64_t w = (int64_t)blockIdx.x * waves + threadIdx.x / kWave; w < (int64_t)n_long * kTile;
-       w += (int64_t)gridDim.x * waves) {
-    const int4 rec = tl[w / kTile];
-    const int r = (int)(w % kTile);
-    const int64_t row = (int64_t)rec.x * kTile + r;
-    if (row >= L) continue;
-    const float* p0 = parts + ((int64_t)rec.y * H + hd) * kTilePartialFloats;
+  const int64_t S = seg_edges(dtype);
+  for (uint32_t i = blockIdx.x; i < n_multi; i += gridDim.x) {
+    const int64_t t = multi[i];
+    if (tile_bad[t]) continue;
+    const int nseg = tile_segments(row_ptr, L, S, t);
+    const float* p0 = parts + ((int64_t)tile_pbase[t] * H + hd) * kTilePartialFloats;
     const int64_t step = (int64_t)H * kTilePartialFloats;
-    float M = kMinusHuge;
-    for (int c = 0; c < rec.z; ++c) M = fmaxf(M, p0[c * step + kTile * 64 + r]);
-    float l = 0.f, acc = 0.f;
-    for (int c = 0; c < rec.z; ++c) {
-      const float wgt = __builtin_amdgcn_exp2f(p0[c * step + kTile * 64 + r] - M);
-      l = __builtin_fmaf(p0[c * step + kTile * 64 + kTile + r], wgt, l);
-      acc = __builtin_fmaf(p0[c * step + r * 64 + lane], wgt, acc);
+    for (int r = blockIdx.z * 4; r < blockIdx.z * 4 + 4; ++r) {
+      const int64_t row = t * kTile + r;
+      float M = kMinusHuge;
+      for (int c = wave; c < nseg; c += 4) M = fmaxf(M, p0[c * step + kTile * 64 + r]);
+      float l = 0.f, acc = 0.f;
+      for (int c = wave; c < nseg; c += 4) {
+        const float wgt = __builtin_amdgcn_exp2f(p0[c * step + kTile * 64 + r] - M);
+        l = __builtin_fmaf(p0[c * step + kTile * 64 + kTile + r], wgt, l);
+        acc = __builtin_fmaf(p0[c * step + r * 64 + lane], wgt, acc);
+      }
+      __syncthreads();            // previous row's combine has read the shared arrays
+      sm_acc[wave][lane] = acc;
+      if (lane == 0) {
+        sm_m[wave] = M;
+        sm_l[wave] = l;
+      }
+      __syncthreads();
+      if (wave == 0 && row < L) {
+        float Mt = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
+        float lt = 0.f, at = 0.f;
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float wgt = __builtin_amdgcn_exp2f(sm_m[v] - Mt);
+          lt = __builtin_fmaf(sm_l[v], wgt, lt);
+          at = __builtin_fmaf(sm_acc[v][lane], wgt, at);
+        }
+        const bool empty = !(lt > 0.f);
+        store_out(O + hd * L * kHeadDim + row * kHeadDim + lane, empty ? 0.f : at / lt);
+        if (lse && lane == 0)
+          lse[hd * L + row] = empty ? -INFINITY : (Mt + __builtin_amdgcn_logf(lt)) * kLn2;
+      }
     }
-    const bool empty = !(l > 0.f);
-    store_out(O + hd * L * kHeadDim + row * kHeadDim + lane, empty ? 0.f : acc / l);
-    if (lse && lane == 0)
-      lse[hd * L + row] = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
   }
 }
 
@@ -536,8 +697,8 @@ __global__ __launch_bounds__(256) void tile_window_kernel(const T* __restrict__ 
   const int64_t hoff = hd * L * kHeadDim;
   const int64_t vlo = u0 - W > 0 ? u0 - W : 0;
   const int64_t vhi = u0 + kTile - 1 + W < Lc - 1 ? u0 + kTile - 1 + W : Lc - 1;
-  WindowBlocks src{vlo / kTile, Lc, s, p, u0, W};
-  const int nblk = (int)(vhi / kTile - vlo / kTile + 1);
+  WindowBlocks src{vlo, Lc, s, p, u0, W};
+  const int nblk = (int)((vhi - vlo) / kTile + 1);
   const int64_t u = u0 + n;
   const bool exists = u < Lc;
   const int64_t qrow = s * (exists ? u : Lc - 1) + p;
@@ -555,14 +716,17 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   const T* K = static_cast<const T*>(a.K);
   const T* V = static_cast<const T*>(a.V);
   T* O = static_cast<T*>(a.O);
+  // The number of work items depends on row_ptr[L], which only the device knows: the kernels
+  // stride over the items with grids sized from L alone.
   const int64_t n_tiles = (a.L + kTile - 1) / kTile;
-  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)((n_tiles + 3) / 4)), dim3(256), 0, a.stream,
-                     a.row_ptr, a.col_idx, a.L, a.H, a.ws, a.ws_bytes);
-  const unsigned nwg = (unsigned)((kTileItemSlots + n_tiles + 3) / 4);
-  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3(nwg, (unsigned)a.H), dim3(256), 0, a.stream, Q, K, V,
-                     O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
-  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O, a.lse,
-                     a.row_ptr, a.L, a.ws, a.ws_bytes);
+  int64_t nwg = (n_tiles + 3) / 4 + 64;
+  if (nwg > 16384) nwg = 16384;
+  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
+                     a.col_idx, a.L, a.H, a.dtype, a.ws, a.ws_bytes);
+  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)nwg, (unsigned)a.H), dim3(256), 0, a.stream,
+                     Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
+  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
+                     O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);
   return hip_status(hipGetLastError());
 }
 

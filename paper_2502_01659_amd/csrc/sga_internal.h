@@ -20,29 +20,39 @@ constexpr int kMaxSplit = 64;         // at most this many chunks per row
 // ---- tile path parameters -----------------------------------------------------
 constexpr int kTile = 32;                 // query rows per tile = keys per block
 constexpr int kPairEdges = 128;           // a tile qualifies if it averages >= this many edges per block
-constexpr int kTileSplitThreshold = 64;   // tiles with more key blocks are split
-constexpr int kTileChunk = 16;            // target key blocks per chunk
-constexpr int kTileMaxSplit = 128;        // at most this many chunks per tile
-constexpr int kTileItemSlots = 2048;      // upper bound of split-tile work items per call
+constexpr int kMaxTilePartials = 4096;    // partial states of split tiles per call
 constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32], l[32]
+
+// Edges per unit of tile work.  Tile t owns the work items [f(t), f(t+1)) with
+// f(t) = t + (edges before tile t)/S, i.e. one item plus one per multiple of S its edge range
+// crosses; the first max(1, edges(t)/S) of them are the tile's segments, the rest stay idle.
+// The mapping follows from row_ptr alone and needs neither a scan nor atomics.  A dense
+// 32x32 block is 1024 edges: S is 32 dense blocks of fp32 MFMA work or 256 of fp16 work.
+__host__ __device__ inline int64_t seg_edges(int32_t dtype) { return dtype == SGA_F32 ? 32768 : 262144; }
 
 // ---- workspace layout -------------------------------------------------------
 // [0, 256)            counters (uint32): see WsCounter
 // items               cap_items x int2 {row, chunk}                    (gather split)
 // long_rows           cap_items x int4 {row, base, nchunks, chunk_len}
 // partials            cap_items x H x kPartialStride floats {acc[d], m, l}
-// tile_nblk           n_tiles x int32: key blocks of the tile, or -1 (tile goes to the gather path)
+// seg_tile/meta/count n_work entries: tile id (-1: idle item), {segment, segments of the tile},
+//                     key blocks found
+//                     (-1: the segment overflowed its slots)
+// tile_bad            n_tiles x int32: != 0 -> tile is left to the gather path
+// tile_pbase          n_tiles x int32: first partial slot of a multi-segment tile
+// multi_tiles         cap_tparts x int32: ids of the multi-segment tiles (merge list, any order)
 // pair_blk            cap_pairs x int32: key block id (| full flag); tile t owns slots
-//                     [row_ptr[32t]/128, row_ptr[32(t+1)]/128)
+//                     [row_ptr[32t]/128, row_ptr[32(t+1)]/128), split evenly among its segments
 // pair_mask           cap_pairs x 32 x uint32: bit j of word r = edge (row 32t+r, key 32b+j)
-// titems / tlong / tpartials: the split-tile analogue of items / long_rows / partials
+// tpartials           cap_tparts x H x kTilePartialFloats floats
 enum WsCounter : int {
   kCtrChunksNeeded = 0,   // sum of chunk counts of all long rows
   kCtrItemsAlloc = 1,     // bump allocator over items
   kCtrLongRows = 2,       // number of long rows recorded
-  kCtrTileChunksNeeded = 3,
-  kCtrTileItems = 4,      // bump allocator over split-tile work items
-  kCtrTileLong = 5,       // number of split tiles recorded
+  kCtrTilePartsNeeded = 3,  // sum of segment counts of all multi-segment tiles
+  kCtrTilePartsAlloc = 4,   // bump allocator over tile partial slots
+  kCtrTilesBad = 5,         // tiles whose block lists overflowed (left to the gather path)
+  kCtrMultiTiles = 6,       // multi-segment tiles recorded in the merge list
   kNumCounters = 64
 };
 
@@ -52,19 +62,21 @@ struct WorkspacePlan {
   size_t off_items, off_long, off_partials;
   // tile path
   int64_t n_tiles;        // ceil(L / 32)
+  int64_t n_work;         // tile work items (segments)
   int64_t cap_pairs;      // capacity of the (tile, key block) pair arrays
-  int64_t cap_titems;     // capacity of split-tile work items
-  size_t off_tile_nblk, off_pair_blk, off_pair_mask, off_titems, off_tlong,
-      off_tpartials;
+  int64_t cap_tparts;     // capacity of tile partial states
+  size_t off_seg_tile, off_seg_meta, off_seg_count, off_tile_bad, off_tile_pbase, off_multi_tiles,
+      off_pair_blk, off_pair_mask, off_tpartials;
   size_t total_bytes;
 };
 
 constexpr int kPartialStride = 68;    // floats per row partial: acc[64], m, l, 2 pad
 
-// Sizes every region for (L, H, nnz); nnz < 0 means implicit mask (no tile lists).
+// Sizes every region for (L, H, nnz, dtype); nnz < 0 means implicit mask (no tile lists).
 // Evaluated identically on the host (sga_workspace_bytes) and inside the kernels
 // (with nnz = row_ptr[L]), so no layout has to be passed around.
-__host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, int64_t nnz) {
+__host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, int64_t nnz,
+                                                        int32_t dtype) {
   WorkspacePlan p{};
   size_t off = 256;   // counters
   const int64_t e = nnz < 0 ? 0 : nnz;
@@ -80,29 +92,70 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   p.off_partials = off;
   off = (off + (size_t)cap * H * kPartialStride * sizeof(float) + 255) & ~size_t(255);
   // tile path
-  p.n_tiles = (L + kTile - 1) / kTile;
-  p.cap_pairs = nnz < 0 ? 0 : e / kPairEdges + 1;
-  p.off_tile_nblk = off;
-  off = (off + (size_t)p.n_tiles * sizeof(int32_t) + 255) & ~size_t(255);
+  const bool tiles = nnz >= 0;
+  p.n_tiles = tiles ? (L + kTile - 1) / kTile : 0;
+  p.n_work = tiles ? p.n_tiles + e / seg_edges(dtype) : 0;
+  p.cap_pairs = tiles ? e / kPairEdges + 1 : 0;
+  p.cap_tparts = tiles ? e / seg_edges(dtype) + 1 : 0;
+  if (p.cap_tparts > kMaxTilePartials) p.cap_tparts = kMaxTilePartials;
+  p.off_seg_tile = off;
+  off = (off + (size_t)p.n_work * 4 + 255) & ~size_t(255);
+  p.off_seg_meta = off;
+  off = (off + (size_t)p.n_work * 8 + 255) & ~size_t(255);
+  p.off_seg_count = off;
+  off = (off + (size_t)p.n_work * 4 + 255) & ~size_t(255);
+  p.off_tile_bad = off;
+  off = (off + (size_t)p.n_tiles * 4 + 255) & ~size_t(255);
+  p.off_tile_pbase = off;
+  off = (off + (size_t)p.n_tiles * 4 + 255) & ~size_t(255);
+  p.off_multi_tiles = off;
+  off = (off + (size_t)p.cap_tparts * 4 + 255) & ~size_t(255);
   p.off_pair_blk = off;
   off = (off + (size_t)p.cap_pairs * sizeof(int32_t) + 255) & ~size_t(255);
   p.off_pair_mask = off;
   off = (off + (size_t)p.cap_pairs * kTile * sizeof(uint32_t) + 255) & ~size_t(255);
-  int64_t n_tlong = p.cap_pairs / (kTileSplitThreshold + 1);
-  if (n_tlong > p.n_tiles) n_tlong = p.n_tiles;
-  int64_t tcap = p.cap_pairs / kTileChunk + n_tlong;
-  if (tcap > (int64_t)kTileMaxSplit * n_tlong) tcap = (int64_t)kTileMaxSplit * n_tlong;
-  if (tcap > kTileItemSlots) tcap = kTileItemSlots;
-  p.cap_titems = tcap;
-  p.off_titems = off;
-  off = (off + (size_t)tcap * 8 + 255) & ~size_t(255);
-  p.off_tlong = off;
-  off = (off + (size_t)tcap * 16 + 255) & ~size_t(255);
   p.off_tpartials = off;
-  off = (off + (size_t)tcap * H * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
+  off = (off + (size_t)p.cap_tparts * H * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
   p.total_bytes = off;
   return p;
 }
+
+// First work item of tile t: f(t) = t + row_ptr[min(32t, L)] / S.
+__device__ __forceinline__ int64_t work_first(const int64_t* __restrict__ row_ptr, int64_t L,
+                                              int64_t S, int64_t t) {
+  const int64_t r = t * kTile;
+  return t + row_ptr[r < L ? r : L] / S;
+}
+
+// Segments tile t is cut into: max(1, edges(t) / S).
+__device__ __forceinline__ int32_t tile_segments(const int64_t* __restrict__ row_ptr, int64_t L,
+                                                 int64_t S, int64_t t) {
+  const int64_t r0 = t * kTile, r1 = r0 + kTile < L ? r0 + kTile : L;
+  const int64_t n = (row_ptr[r1] - row_ptr[r0]) / S;
+  return n < 1 ? 1 : (int32_t)n;
+}
+
+// True when the tile path of this call produces the rows of tile t: its block lists fitted
+// their slots and, if it is a multi-segment tile, the call's partial states fitted theirs.
+__device__ __forceinline__ bool tile_handled(const WorkspacePlan& pl, const void* ws,
+                                             const int64_t* __restrict__ row_ptr, int64_t L,
+                                             int32_t dtype, int64_t t) {
+  const char* base = static_cast<const char*>(ws);
+  if (reinterpret_cast<const int32_t*>(base + pl.off_tile_bad)[t] != 0) return false;
+  const int64_t S = seg_edges(dtype);
+  if (tile_segments(row_ptr, L, S, t) == 1) return true;
+  return (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTilePartsNeeded] <= pl.cap_tparts;
+}
+
+// True when the tile path of this call left no row to the gather path.
+__device__ __forceinline__ bool tiles_cover_everything(const WorkspacePlan& pl, const void* ws) {
+  const uint32_t* ctr = reinterpret_cast<const uint32_t*>(ws);
+  return ctr[kCtrTilesBad] == 0 && (int64_t)ctr[kCtrTilePartsNeeded] <= pl.cap_tparts;
+}
+
+template <typename T> struct DtypeOf;
+template <> struct DtypeOf<float> { static constexpr int32_t code = SGA_F32; };
+template <> struct DtypeOf<__half> { static constexpr int32_t code = SGA_F16; };
 
 struct AttnArgs {
   const void* Q;
@@ -127,8 +180,9 @@ struct AttnArgs {
 };
 
 // gather path (attention_gather.hip)
-void clear_workspace_counters(void* ws, hipStream_t stream);
-// skip_tiled: rows whose 32-row tile was produced by the tile path (tile_nblk >= 0 in the
+// Zeroes the counters (and, when row_ptr is given, the per-tile flags of the tile path).
+void clear_workspace(const AttnArgs& a, bool tile_flags);
+// skip_tiled: rows whose 32-row tile was produced by the tile path (tile_bad == 0 in the
 // workspace) are skipped, and a small grid strides over the rows.
 sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled);
 sga_status launch_gather_implicit(const AttnArgs& a);
