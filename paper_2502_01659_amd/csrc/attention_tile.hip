@@ -40,11 +40,20 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMinusHuge = -1.0e30f;
 constexpr int kFullBit = 1 << 30;
-constexpr int kVPitch = 144;          // bytes per staged fp16 V row in LDS (128 + 16 pad)
 
 // Key (within a 32-key block) held in accumulator register r of half-wave h after an
 // MFMA 32x32 whose M index is the key: rows 8*(r/4) + 4*h + r%4.
 __device__ __forceinline__ constexpr int acc_row(int r, int h) { return 8 * (r / 4) + 4 * h + (r % 4); }
+
+// Global -> LDS copy of 16 bytes per lane without passing through registers: lane l's 16 bytes
+// land at dst + 16*l (dst is wave-uniform).  Completion is tracked by vmcnt.
+__device__ __forceinline__ void copy16_to_lds(const void* src, char* dst) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                   (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
+}
+
+// s_waitcnt vmcnt(0): every outstanding global load, LDS copies included, has landed.
+__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
 
 struct BlockInfo {
   int64_t row0;     // tensor row of the block's first key
@@ -184,41 +193,54 @@ struct CoreF32 {
     }
   }
 
-  // Block ids and mask words are fetched one block ahead, so the K/V loads of a block never
-  // wait on a dependent chain id -> address -> data; with two wavefronts per SIMD one
-  // wavefront's loads overlap the other's matrix work.
+  static constexpr int kLdsBytes = kTile * kHeadDim * 4;   // one staged V block per wavefront
+
+  // Software pipeline per block k: the K fragment of block k+1 is prefetched into registers, the V
+  // block k is copied global -> LDS behind the S^T matrix work, and block ids / mask words are
+  // fetched two blocks ahead, so no load sits on the critical path of the matrix cores.
+  // Staged V layout: row-major [key][64 channels]; copy s moves keys 4s..4s+3 (16 lanes per row).
   template <typename Src>
   __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
-                      int k0, int k1, float c, int lane, TileState& st, char* /*lds*/) {
+                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
-    BlockInfo b_next = src.get(k0, n);
+    BlockInfo b = src.get(k0, n);
+    BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    float kf_next[32];
+    load_k(Kh, b, n, h, kf_next);
+    const float* vread = reinterpret_cast<const float*>(lds) + h * 4 * kHeadDim + n;
     for (int k = k0; k < k1; ++k) {
-      const BlockInfo b = b_next;
       float kf[32];
-      load_k(Kh, b, n, h, kf);
-      // V[key acc_row(r,h)][cb*32 + n]
-      float vf[2][16];
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        int key = acc_row(r, 0) + 4 * h;
+      for (int t = 0; t < 32; ++t) kf[t] = kf_next[t];
+      if (k + 1 < k1) load_k(Kh, b1, n, h, kf_next);
+      __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
+#pragma unroll
+      for (int s = 0; s < 8; ++s) {
+        int key = 4 * s + (lane >> 4);
         key = key < b.nvalid ? key : b.nvalid - 1;
-        const float* vp = Vh + (b.row0 + key * b.stride) * kHeadDim + n;
-        vf[0][r] = vp[0];
-        vf[1][r] = vp[32];
+        copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 15) * 4, lds + s * 1024);
       }
-      if (k + 1 < k1) b_next = src.get(k + 1, n);
+      BlockInfo b2 = b1;
+      if (k + 2 < k1) b2 = src.get(k + 2, n);
       floatx16 s = {0};
 #pragma unroll
       for (int t = 0; t < 32; ++t)
         s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
       float p[16];
       softmax_block(s, c, b, h, st, p);
+      wait_all_loads();
+      __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(vf[0][r], p[r], st.o[0], 0, 0, 0);
-        st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(vf[1][r], p[r], st.o[1], 0, 0, 0);
+        // A operand: V^T[channel cb*32+n][key acc_row(r,h)] = staged V[key][channel]
+        const float v0 = vread[acc_row(r, 0) * kHeadDim];
+        const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
+        st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
+        st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
       }
+      b = b1;
+      b1 = b2;
     }
   }
 
@@ -244,17 +266,15 @@ struct CoreF16 {
     for (int s = 0; s < 4; ++s) qf[s] = src[s];
   }
 
-  __device__ static void load_kv(const __half* __restrict__ Kh, const __half* __restrict__ Vh,
-                                 const BlockInfo& b, int n, int h, half8 (&kf)[4], uint4 (&vraw)[4]) {
+  static constexpr int kLdsBytes = kTile * kHeadDim * 2;   // one staged V block per wavefront
+
+  __device__ static void load_k(const __half* __restrict__ Kh, const BlockInfo& b, int n, int h,
+                                half8 (&kf)[4]) {
     const int krow = n < b.nvalid ? n : b.nvalid - 1;
-    const int64_t roff = (b.row0 + krow * b.stride) * kHeadDim + h * 32;
-    const half8* kp = reinterpret_cast<const half8*>(Kh + roff);
-    const uint4* vp = reinterpret_cast<const uint4*>(Vh + roff);
+    const half8* kp =
+        reinterpret_cast<const half8*>(Kh + (b.row0 + krow * b.stride) * kHeadDim + h * 32);
 #pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      kf[s] = kp[s];
-      vraw[s] = vp[s];
-    }
+    for (int s = 0; s < 4; ++s) kf[s] = kp[s];
   }
 
   // 4 keys x 1 channel per lane out of the row-major staged V block, using the LDS transpose
@@ -264,39 +284,45 @@ struct CoreF16 {
   // the group for keys key0..key0+3: the K-contiguous A operand of V^T.
   __device__ static half4 read_vt(const char* lds, int key0, int cb, int lane) {
     const int i = lane & 15, grp16 = (lane >> 4) & 1;
-    const char* p = lds + (key0 + (i >> 2)) * kVPitch + (cb * 32 + grp16 * 16 + 4 * (i & 3)) * 2;
+    const char* p = lds + (key0 + (i >> 2)) * (kHeadDim * 2) + (cb * 32 + grp16 * 16 + 4 * (i & 3)) * 2;
     const short4v raw =
         __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
     return __builtin_bit_cast(half4, raw);
   }
 
-  // Block ids and mask words are fetched one block ahead (see CoreF32::run).
+  // Same software pipeline as CoreF32::run.  Staged V layout: row-major [key][64 channels] fp16;
+  // copy s moves keys 8s..8s+7 (8 lanes per 128-byte row).
   template <typename Src>
   __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
-    BlockInfo b_next = src.get(k0, n);
+    BlockInfo b = src.get(k0, n);
+    BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    half8 kf_next[4];
+    load_k(Kh, b, n, h, kf_next);
     for (int k = k0; k < k1; ++k) {
-      const BlockInfo b = b_next;
       half8 kf[4];
-      uint4 vraw[4];
-      load_kv(Kh, Vh, b, n, h, kf, vraw);
-      if (k + 1 < k1) b_next = src.get(k + 1, n);
+#pragma unroll
+      for (int s = 0; s < 4; ++s) kf[s] = kf_next[s];
+      if (k + 1 < k1) load_k(Kh, b1, n, h, kf_next);
+      __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        int key = 8 * s + (lane >> 3);
+        key = key < b.nvalid ? key : b.nvalid - 1;
+        copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 7) * 8, lds + s * 1024);
+      }
+      BlockInfo b2 = b1;
+      if (k + 2 < k1) b2 = src.get(k + 2, n);
       floatx16 sacc = {0};
 #pragma unroll
       for (int s = 0; s < 4; ++s)
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
-      // stage the V block row-major in this wavefront's LDS slice: row = key n, 64 B per half-wave
-      __builtin_amdgcn_wave_barrier();   // earlier reads of the slice are done (in-order LDS queue)
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        *reinterpret_cast<uint4*>(lds + n * kVPitch + h * 64 + 16 * s) = vraw[s];
       float p[16];
       softmax_block(sacc, c, b, h, st, p);
-      __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+      wait_all_loads();
       __builtin_amdgcn_wave_barrier();
-      __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         half8 pb;
@@ -311,6 +337,8 @@ struct CoreF16 {
           st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
         }
       }
+      b = b1;
+      b1 = b2;
     }
   }
 
@@ -564,13 +592,13 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
     size_t ws_bytes) {
-  __shared__ __attribute__((aligned(16))) char lds_all[4 * kTile * kVPitch];
-  const int32_t H = (int32_t)gridDim.y;
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * CoreOf<T>::type::kLdsBytes];
+  const int32_t H = (int32_t)gridDim.x;   // head-major grid: the long work items of every head are dispatched first
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
   if (pl.total_bytes > ws_bytes) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n = lane & 31, h = lane >> 5;
-  char* lds = lds_all + wave * kTile * kVPitch;
+  char* lds = lds_all + wave * CoreOf<T>::type::kLdsBytes;
   char* base_ws = static_cast<char*>(ws);
   const int32_t* seg_tile = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_tile);
   const int2* seg_meta = reinterpret_cast<const int2*>(base_ws + pl.off_seg_meta);
@@ -578,8 +606,8 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
   const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
   const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
   const bool parts_fit = tile_parts_fit(pl, ws);
-  const int64_t hoff = (int64_t)blockIdx.y * L * kHeadDim;
-  for (int64_t w = (int64_t)blockIdx.x * 4 + wave; w < pl.n_work; w += (int64_t)gridDim.x * 4) {
+  const int64_t hoff = (int64_t)blockIdx.x * L * kHeadDim;
+  for (int64_t w = (int64_t)blockIdx.y * 4 + wave; w < pl.n_work; w += (int64_t)gridDim.y * 4) {
     const int64_t t = seg_tile[w];
     if (t < 0 || tile_bad[t]) continue;                     // idle item / tile left to the gather path
     const int2 meta = seg_meta[w];
@@ -600,10 +628,10 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     core.run(K + hoff, V + hoff, src, 0, seg_count[w], scale * kLog2e, lane, st, lds);
     if (meta.y > 1) {
       float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
-                    (((int64_t)tile_pbase[t] + meta.x) * H + blockIdx.y) * (int64_t)kTilePartialFloats;
+                    (((int64_t)tile_pbase[t] + meta.x) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
       store_partial(part, st, n, h);
     } else {
-      finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.y * L : nullptr, qrow, qrow, exists, st, h);
+      finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.x * L : nullptr, qrow, qrow, exists, st, h);
     }
   }
 }
@@ -684,10 +712,10 @@ __global__ __launch_bounds__(256) void tile_window_kernel(const T* __restrict__ 
                                                           const T* __restrict__ V, T* __restrict__ O,
                                                           float* __restrict__ lse, int64_t L, int64_t W,
                                                           int64_t s, float scale) {
-  __shared__ __attribute__((aligned(16))) char lds_all[4 * kTile * kVPitch];
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * CoreOf<T>::type::kLdsBytes];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n = lane & 31, h = lane >> 5;
-  char* lds = lds_all + wave * kTile * kVPitch;
+  char* lds = lds_all + wave * CoreOf<T>::type::kLdsBytes;
   const int64_t p = blockIdx.y;
   if (p >= L) return;
   const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
@@ -723,7 +751,7 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   if (nwg > 16384) nwg = 16384;
   hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
                      a.col_idx, a.L, a.H, a.dtype, a.ws, a.ws_bytes);
-  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)nwg, (unsigned)a.H), dim3(256), 0, a.stream,
+  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)a.H, (unsigned)nwg), dim3(256), 0, a.stream,
                      Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
   hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
                      O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);
