@@ -12,7 +12,8 @@
  * Conventions that hold for every entry point
  *   - Pointers marked "device" are device (HBM) addresses owned by the caller;
  *     pointers marked "host" are ordinary host addresses.  The library never
- *     allocates, frees or retains memory and keeps no state between calls.
+ *     allocates, frees or retains memory and keeps no state between calls (the
+ *     benchmark hook sga_profile_* at the end of this header is the one exception).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *     Calls enqueue work on it and return without synchronising the host.
  *   - Argument errors are detected on the host before anything is enqueued and
@@ -167,6 +168,24 @@ sga_status sga_attention_forward_implicit(const void* Q, const void* K, const vo
                                           int32_t H, int32_t d, float scale, void* stream,
                                           int32_t dtype, float* lse, void* workspace,
                                           size_t workspace_bytes, int32_t path);
+
+/*
+ * Benchmark hook: timing of the dominant attention kernel of each forward call.
+ * For callers that measure kernel time on the launch stream (a benchmark computing a
+ * roofline); it is the one piece of process-wide state in the library and is not
+ * thread-safe.  While enabled, every forward call records a pair of HIP events around the
+ * launch of its main attention kernel (the fused SDDMM -> softmax -> SpMM kernel of
+ * Algorithm 1; helper kernels such as mask analysis and partial merges are outside the
+ * pair) on the call's stream.
+ *   sga_profile_enable(on)   on != 0 starts a fresh recording, 0 stops it.
+ *   sga_profile_collect      waits for the recorded calls, writes up to `capacity` durations
+ *                            in milliseconds (oldest first) to ms_out (host), their count to
+ *                            n_out (host), and clears the recording.
+ * Errors: SGA_ERR_INVALID_ARG for null outputs or negative capacity, SGA_ERR_HIP if an
+ * event cannot be read.
+ */
+sga_status sga_profile_enable(int32_t on);
+sga_status sga_profile_collect(float* ms_out, int32_t capacity, int32_t* n_out);
 
 #ifdef __cplusplus
 }

@@ -9,7 +9,7 @@ from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, load, lib_pat
                       attention_forward, attention_forward_implicit,
                       sga_mask_nnz, sga_build_mask, sga_workspace_bytes,
                       sga_attention_forward, sga_attention_forward_implicit,
-                      sga_status_string)
+                      sga_status_string, sga_profile_enable, sga_profile_collect)
 
 __all__ = [
     "SgaError", "PATH_AUTO", "PATH_GATHER", "PATH_TILE", "load", "lib_path",
@@ -17,4 +17,5 @@ __all__ = [
     "attention_forward", "attention_forward_implicit",
     "sga_mask_nnz", "sga_build_mask", "sga_workspace_bytes",
     "sga_attention_forward", "sga_attention_forward_implicit", "sga_status_string",
+    "sga_profile_enable", "sga_profile_collect",
 ]

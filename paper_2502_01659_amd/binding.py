@@ -63,6 +63,10 @@ def load():
     lib.sga_attention_forward_implicit.restype = ctypes.c_int
     lib.sga_attention_forward_implicit.argtypes = [vp, vp, vp, P(_MaskDesc), vp, i64, i32, i32,
                                                    f32, vp, i32, vp, vp, ctypes.c_size_t, i32]
+    lib.sga_profile_enable.restype = ctypes.c_int
+    lib.sga_profile_enable.argtypes = [i32]
+    lib.sga_profile_collect.restype = ctypes.c_int
+    lib.sga_profile_collect.argtypes = [P(ctypes.c_float), i32, P(ctypes.c_int32)]
     _lib = lib
     return lib
 
@@ -110,6 +114,18 @@ def sga_attention_forward_implicit(Q, K, V, spec, O, L, H, d, scale, stream, dty
     return load().sga_attention_forward_implicit(Q, K, V, ctypes.byref(dsc), O, L, H, d, scale,
                                                  stream, dtype_code, lse, workspace,
                                                  workspace_bytes_, path)
+
+
+def sga_profile_enable(on):
+    return load().sga_profile_enable(int(on))
+
+
+def sga_profile_collect(capacity=4096):
+    """-> (status, [kernel durations in ms])"""
+    buf = (ctypes.c_float * capacity)()
+    n = ctypes.c_int32(0)
+    st = load().sga_profile_collect(buf, capacity, ctypes.byref(n))
+    return st, [buf[i] for i in range(n.value)]
 
 
 # ---- tensor-level helpers ---------------------------------------------------------

@@ -1,9 +1,20 @@
 // C ABI of libsga.so: argument validation and dispatch.  See include/sga.h for the contract.
 #include "sga_internal.h"
 
+#include <vector>
+
 using namespace sga;
 
 namespace {
+
+// Profiling state (benchmark use only; not thread-safe).  Event pairs are created lazily and
+// kept until the process ends.
+struct ProfileState {
+  bool on = false;
+  size_t used = 0;
+  std::vector<hipEvent_t> start, stop;
+};
+ProfileState g_prof;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -24,7 +35,51 @@ sga_status check_common(const void* Q, const void* K, const void* V, const void*
 
 }  // namespace
 
+namespace sga {
+
+void profile_mark_begin(hipStream_t stream) {
+  if (!g_prof.on) return;
+  if (g_prof.used == g_prof.start.size()) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+      g_prof.on = false;
+      return;
+    }
+    g_prof.start.push_back(a);
+    g_prof.stop.push_back(b);
+  }
+  (void)hipEventRecord(g_prof.start[g_prof.used], stream);
+}
+
+void profile_mark_end(hipStream_t stream) {
+  if (!g_prof.on || g_prof.used >= g_prof.stop.size()) return;
+  (void)hipEventRecord(g_prof.stop[g_prof.used], stream);
+  ++g_prof.used;
+}
+
+}  // namespace sga
+
 extern "C" {
+
+sga_status sga_profile_enable(int32_t on) {
+  g_prof.on = on != 0;
+  g_prof.used = 0;
+  return SGA_OK;
+}
+
+sga_status sga_profile_collect(float* ms_out, int32_t capacity, int32_t* n_out) {
+  if (!n_out || (capacity > 0 && !ms_out) || capacity < 0) return SGA_ERR_INVALID_ARG;
+  int32_t n = 0;
+  for (size_t i = 0; i < g_prof.used && n < capacity; ++i) {
+    if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return SGA_ERR_HIP;
+    float ms = 0.f;
+    if (hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess) return SGA_ERR_HIP;
+    ms_out[n++] = ms;
+  }
+  *n_out = n;
+  g_prof.used = 0;
+  return SGA_OK;
+}
 
 const char* sga_status_string(sga_status s) {
   switch (s) {

@@ -408,9 +408,11 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   int64_t nwg = (a.L + 3) / 4;
   if (skip_tiled && nwg > 2048) nwg = 2048;
   const dim3 grid((unsigned)nwg, (unsigned)a.H);
+  if (!skip_tiled) profile_mark_begin(a.stream);
   hipLaunchKernelGGL(gather_csr_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
                      a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
                      skip_tiled ? 1 : 0);
+  if (!skip_tiled) profile_mark_end(a.stream);
   if (split) {
     hipLaunchKernelGGL(gather_chunk_kernel<T>, dim3(1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
@@ -438,10 +440,12 @@ sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, bool skip
 template <typename T>
 static sga_status run_implicit(const AttnArgs& a) {
   const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
+  profile_mark_begin(a.stream);
   hipLaunchKernelGGL(gather_window_kernel<T>, grid, dim3(256), 0, a.stream,
                      static_cast<const T*>(a.Q), static_cast<const T*>(a.K),
                      static_cast<const T*>(a.V), static_cast<T*>(a.O), a.lse, a.L,
                      (int64_t)a.window, (int64_t)a.stride, a.scale);
+  profile_mark_end(a.stream);
   return hip_status(hipGetLastError());
 }
 

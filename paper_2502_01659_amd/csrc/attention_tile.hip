@@ -751,8 +751,10 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   if (nwg > 16384) nwg = 16384;
   hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
                      a.col_idx, a.L, a.H, a.dtype, a.ws, a.ws_bytes);
+  profile_mark_begin(a.stream);
   hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)a.H, (unsigned)nwg), dim3(256), 0, a.stream,
                      Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
+  profile_mark_end(a.stream);
   hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
                      O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);
   return hip_status(hipGetLastError());
@@ -764,9 +766,11 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const int64_t Lc = (a.L + s - 1) / s;
   const int64_t n_tiles = (Lc + kTile - 1) / kTile;
   const dim3 grid((unsigned)((n_tiles + 3) / 4), (unsigned)s, (unsigned)a.H);
+  profile_mark_begin(a.stream);
   hipLaunchKernelGGL(tile_window_kernel<T>, grid, dim3(256), 0, a.stream, static_cast<const T*>(a.Q),
                      static_cast<const T*>(a.K), static_cast<const T*>(a.V), static_cast<T*>(a.O),
                      a.lse, a.L, (int64_t)a.window, s, a.scale);
+  profile_mark_end(a.stream);
   return hip_status(hipGetLastError());
 }
 

@@ -197,6 +197,11 @@ int64_t mask_total_edges(const sga_mask_desc& d);
 sga_status launch_build_mask(const sga_mask_desc& d, int64_t* row_ptr, int32_t* col_idx,
                              hipStream_t stream);
 
+// Benchmark hook (api.hip): when enabled, brackets the dominant attention kernel of a forward
+// call with a pair of events on the call's stream.
+void profile_mark_begin(hipStream_t stream);
+void profile_mark_end(hipStream_t stream);
+
 inline sga_status hip_status(hipError_t e) { return e == hipSuccess ? SGA_OK : SGA_ERR_HIP; }
 
 }  // namespace sga
