@@ -206,6 +206,10 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "gather", "tile"])
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run a plain device copy of known size (1 GiB read + 1 GiB written) and "
+                         "exit: the reference against which rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "readings are scaled")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (the hot path is a single-GPU kernel; "
@@ -214,6 +218,16 @@ def main():
 
     import torch
     from sga_inputs import WORKLOADS
+    if args.calibrate_copy:
+        n = 1 << 30
+        src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": True, "bytes_read_per_copy": n,
+                          "bytes_written_per_copy": n, "copies": 5}))
+        return
     path = {"auto": 0, "gather": 1, "tile": 2}[args.path]
     wl = WORKLOADS[args.workload]
     run = Runner(wl, path)
