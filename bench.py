@@ -30,7 +30,9 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
-MEASURED_TRAFFIC_BYTES = {}
+MEASURED_TRAFFIC_BYTES = {
+    "cfg2_longformer_64k": 938_140_672,
+}
 
 
 def algorithmic_bytes(wl, nnz):

@@ -11,7 +11,7 @@ import os
 from sga_inputs.masks import MaskSpec
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "libsga.so")
+_LIB_PATH = os.environ.get("SGA_LIB", os.path.join(_HERE, "libsga.so"))
 _lib = None
 
 PATH_AUTO, PATH_GATHER, PATH_TILE = 0, 1, 2

@@ -704,24 +704,31 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
   }
 }
 
-// Implicit window masks: grid.x = tiles of a residue class (4 per workgroup), grid.y = class,
-// grid.z = head.
+// Implicit window masks.  grid.x = workgroups (4 tiles each) over all residue classes, grid.y = head.
+// Workgroups are dealt round-robin to the 8 XCDs, each with its own L2, and neighbouring tiles
+// share most of their K/V rows, so the linear workgroup id is remapped to give every XCD one
+// contiguous range of the sequence; inside it consecutive workgroups alternate between the
+// residue classes, so that the interleaved rows of all classes are touched together.
 template <typename T>
-__global__ __launch_bounds__(256) void tile_window_kernel(const T* __restrict__ Q,
+__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_kernel(const T* __restrict__ Q,
                                                           const T* __restrict__ K,
                                                           const T* __restrict__ V, T* __restrict__ O,
                                                           float* __restrict__ lse, int64_t L, int64_t W,
-                                                          int64_t s, float scale) {
+                                                          int64_t s, int64_t n_groups, float scale) {
   __shared__ __attribute__((aligned(16))) char lds_all[4 * CoreOf<T>::type::kLdsBytes];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n = lane & 31, h = lane >> 5;
   char* lds = lds_all + wave * CoreOf<T>::type::kLdsBytes;
-  const int64_t p = blockIdx.y;
+  // gridDim.x is a multiple of 8: XCD x handles the workgroups [x*chunk, (x+1)*chunk)
+  const int64_t chunk = gridDim.x / 8;
+  const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  if (bid >= n_groups * s) return;
+  const int64_t p = bid % s;                       // residue class
   if (p >= L) return;
   const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
-  const int64_t u0 = ((int64_t)blockIdx.x * 4 + wave) * kTile;
+  const int64_t u0 = ((bid / s) * 4 + wave) * kTile;
   if (u0 >= Lc) return;
-  const int64_t hd = blockIdx.z;
+  const int64_t hd = blockIdx.y;
   const int64_t hoff = hd * L * kHeadDim;
   const int64_t vlo = u0 - W > 0 ? u0 - W : 0;
   const int64_t vhi = u0 + kTile - 1 + W < Lc - 1 ? u0 + kTile - 1 + W : Lc - 1;
@@ -763,13 +770,16 @@ sga_status run_tile_explicit(const AttnArgs& a) {
 template <typename T>
 sga_status run_tile_implicit(const AttnArgs& a) {
   const int64_t s = a.stride;
-  const int64_t Lc = (a.L + s - 1) / s;
+  const int64_t Lc = (a.L + s - 1) / s;                 // tokens of the largest residue class
   const int64_t n_tiles = (Lc + kTile - 1) / kTile;
-  const dim3 grid((unsigned)((n_tiles + 3) / 4), (unsigned)s, (unsigned)a.H);
+  const int64_t n_groups = (n_tiles + 3) / 4;           // workgroups per class
+  const int64_t n_wg = (n_groups * s + 7) / 8 * 8;
+  if (n_wg >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;
+  const dim3 grid((unsigned)n_wg, (unsigned)a.H);
   profile_mark_begin(a.stream);
   hipLaunchKernelGGL(tile_window_kernel<T>, grid, dim3(256), 0, a.stream, static_cast<const T*>(a.Q),
                      static_cast<const T*>(a.K), static_cast<const T*>(a.V), static_cast<T*>(a.O),
-                     a.lse, a.L, (int64_t)a.window, s, a.scale);
+                     a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
   profile_mark_end(a.stream);
   return hip_status(hipGetLastError());
 }
@@ -785,7 +795,7 @@ sga_status launch_tile_explicit(const AttnArgs& a) {
 }
 
 sga_status launch_tile_implicit(const AttnArgs& a) {
-  if (a.stride > 65535 || a.H > 65535) return launch_gather_implicit(a);
+  if (a.H > 65535) return launch_gather_implicit(a);
   return a.dtype == SGA_F32 ? run_tile_implicit<float>(a) : run_tile_implicit<__half>(a);
 }
 
