@@ -216,6 +216,10 @@ __global__ __launch_bounds__(256) void clear_workspace_kernel(void* ws, size_t w
   for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < pl.n_tiles;
        t += (int64_t)gridDim.x * blockDim.x)
     bad[t] = 0;
+  uint32_t* next = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + pl.off_work_next);
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < H;
+       i += (int64_t)gridDim.x * blockDim.x)
+    next[i] = 0;
 }
 
 // One thread per row: rows over the split threshold reserve chunk work items.

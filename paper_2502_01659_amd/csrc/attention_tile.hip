@@ -52,8 +52,13 @@ __device__ __forceinline__ void copy16_to_lds(const void* src, char* dst) {
                                    (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
 }
 
-// s_waitcnt vmcnt(0): every outstanding global load, LDS copies included, has landed.
-__device__ __forceinline__ void wait_all_loads() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// s_waitcnt vmcnt(N): all but the N most recently issued vector memory operations (global
+// loads, LDS copies included) have completed; N <= 15 here.
+template <int N>
+__device__ __forceinline__ void wait_loads_except() {
+  static_assert(N >= 0 && N <= 15, "vmcnt immediate");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+}
 
 struct BlockInfo {
   int64_t row0;     // tensor row of the block's first key
@@ -195,10 +200,20 @@ struct CoreF32 {
 
   static constexpr int kLdsBytes = kTile * kHeadDim * 4;   // one staged V block per wavefront
 
+  // Copy the V block b global -> LDS (row-major [key][64 channels]); copy s moves keys 4s..4s+3,
+  // 16 lanes per 256-byte row.
+  __device__ static void stage_v(const float* __restrict__ Vh, const BlockInfo& b, int lane, char* dst) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      int key = 4 * s + (lane >> 4);
+      key = key < b.nvalid ? key : b.nvalid - 1;
+      copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 15) * 4, dst + s * 1024);
+    }
+  }
+
   // Software pipeline per block k: the K fragment of block k+1 is prefetched into registers, the V
   // block k is copied global -> LDS behind the S^T matrix work, and block ids / mask words are
   // fetched two blocks ahead, so no load sits on the critical path of the matrix cores.
-  // Staged V layout: row-major [key][64 channels]; copy s moves keys 4s..4s+3 (16 lanes per row).
   template <typename Src>
   __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
@@ -215,12 +230,7 @@ struct CoreF32 {
       for (int t = 0; t < 32; ++t) kf[t] = kf_next[t];
       if (k + 1 < k1) load_k(Kh, b1, n, h, kf_next);
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-#pragma unroll
-      for (int s = 0; s < 8; ++s) {
-        int key = 4 * s + (lane >> 4);
-        key = key < b.nvalid ? key : b.nvalid - 1;
-        copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 15) * 4, lds + s * 1024);
-      }
+      stage_v(Vh, b, lane, lds);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
       floatx16 s = {0};
@@ -229,7 +239,7 @@ struct CoreF32 {
         s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
       float p[16];
       softmax_block(s, c, b, h, st, p);
-      wait_all_loads();
+      wait_loads_except<0>();
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -268,6 +278,17 @@ struct CoreF16 {
 
   static constexpr int kLdsBytes = kTile * kHeadDim * 2;   // one staged V block per wavefront
 
+  // Copy the V block b global -> LDS (row-major [key][64 channels] fp16); copy s moves keys
+  // 8s..8s+7, 8 lanes per 128-byte row.
+  __device__ static void stage_v(const __half* __restrict__ Vh, const BlockInfo& b, int lane, char* dst) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      int key = 8 * s + (lane >> 3);
+      key = key < b.nvalid ? key : b.nvalid - 1;
+      copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 7) * 8, dst + s * 1024);
+    }
+  }
+
   __device__ static void load_k(const __half* __restrict__ Kh, const BlockInfo& b, int n, int h,
                                 half8 (&kf)[4]) {
     const int krow = n < b.nvalid ? n : b.nvalid - 1;
@@ -290,8 +311,7 @@ struct CoreF16 {
     return __builtin_bit_cast(half4, raw);
   }
 
-  // Same software pipeline as CoreF32::run.  Staged V layout: row-major [key][64 channels] fp16;
-  // copy s moves keys 8s..8s+7 (8 lanes per 128-byte row).
+  // Same software pipeline as CoreF32::run.
   template <typename Src>
   __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
@@ -307,12 +327,7 @@ struct CoreF16 {
       for (int s = 0; s < 4; ++s) kf[s] = kf_next[s];
       if (k + 1 < k1) load_k(Kh, b1, n, h, kf_next);
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-#pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        int key = 8 * s + (lane >> 3);
-        key = key < b.nvalid ? key : b.nvalid - 1;
-        copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 7) * 8, lds + s * 1024);
-      }
+      stage_v(Vh, b, lane, lds);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
       floatx16 sacc = {0};
@@ -321,7 +336,7 @@ struct CoreF16 {
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
       float p[16];
       softmax_block(sacc, c, b, h, st, p);
-      wait_all_loads();
+      wait_loads_except<0>();
       __builtin_amdgcn_wave_barrier();
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
@@ -586,7 +601,10 @@ __device__ __forceinline__ bool tile_parts_fit(const WorkspacePlan& pl, const vo
   return (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTilePartsNeeded] <= pl.cap_tparts;
 }
 
-// One wavefront per work item; a segment of a multi-segment tile leaves a partial state.
+// Persistent wavefronts: every wavefront claims the next unprocessed work item of its head from
+// a device counter until none is left (items are ordered long segments first, so the greedy
+// order balances the load and no workgroup has to be re-launched between items).  A segment
+// of a multi-segment tile leaves a partial state.
 template <typename T>
 __global__ __launch_bounds__(256) void tile_attend_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
@@ -607,7 +625,12 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
   const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
   const bool parts_fit = tile_parts_fit(pl, ws);
   const int64_t hoff = (int64_t)blockIdx.x * L * kHeadDim;
-  for (int64_t w = (int64_t)blockIdx.y * 4 + wave; w < pl.n_work; w += (int64_t)gridDim.y * 4) {
+  uint32_t* work_next = reinterpret_cast<uint32_t*>(base_ws + pl.off_work_next) + blockIdx.x;
+  while (true) {
+    uint32_t claimed = 0;
+    if (lane == 0) claimed = atomicAdd(work_next, 1u);
+    const int64_t w = __builtin_amdgcn_readfirstlane(claimed);
+    if (w >= pl.n_work) break;
     const int64_t t = seg_tile[w];
     if (t < 0 || tile_bad[t]) continue;                     // idle item / tile left to the gather path
     const int2 meta = seg_meta[w];
@@ -758,9 +781,14 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   if (nwg > 16384) nwg = 16384;
   hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
                      a.col_idx, a.L, a.H, a.dtype, a.ws, a.ws_bytes);
+  // resident workgroups: 256 CUs x (2 or 3 wavefronts per SIMD), shared by the heads
+  const int64_t resident = 256 * (a.dtype == SGA_F32 ? 2 : 3);
+  int64_t per_head = resident / a.H;
+  if (per_head < 1) per_head = 1;
+  if (per_head > nwg) per_head = nwg;
   profile_mark_begin(a.stream);
-  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)a.H, (unsigned)nwg), dim3(256), 0, a.stream,
-                     Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
+  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0,
+                     a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
   profile_mark_end(a.stream);
   hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
                      O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);

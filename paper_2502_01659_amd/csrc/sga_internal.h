@@ -45,6 +45,7 @@ __host__ __device__ inline int64_t seg_edges(int32_t dtype) { return dtype == SG
 //                     [row_ptr[32t]/128, row_ptr[32(t+1)]/128), split evenly among its segments
 // pair_mask           cap_pairs x 32 x uint32: bit j of word r = edge (row 32t+r, key 32b+j)
 // tpartials           cap_tparts x H x kTilePartialFloats floats
+// work_next           H x uint32: next unclaimed tile work item of each head (dynamic scheduling)
 enum WsCounter : int {
   kCtrChunksNeeded = 0,   // sum of chunk counts of all long rows
   kCtrItemsAlloc = 1,     // bump allocator over items
@@ -66,7 +67,7 @@ struct WorkspacePlan {
   int64_t cap_pairs;      // capacity of the (tile, key block) pair arrays
   int64_t cap_tparts;     // capacity of tile partial states
   size_t off_seg_tile, off_seg_meta, off_seg_count, off_tile_bad, off_tile_pbase, off_multi_tiles,
-      off_pair_blk, off_pair_mask, off_tpartials;
+      off_pair_blk, off_pair_mask, off_tpartials, off_work_next;
   size_t total_bytes;
 };
 
@@ -116,6 +117,8 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   off = (off + (size_t)p.cap_pairs * kTile * sizeof(uint32_t) + 255) & ~size_t(255);
   p.off_tpartials = off;
   off = (off + (size_t)p.cap_tparts * H * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
+  p.off_work_next = off;
+  off = (off + (tiles ? (size_t)H * 4 : 0) + 255) & ~size_t(255);
   p.total_bytes = off;
   return p;
 }
