@@ -626,14 +626,27 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
   const bool parts_fit = tile_parts_fit(pl, ws);
   const int64_t hoff = (int64_t)blockIdx.x * L * kHeadDim;
   uint32_t* work_next = reinterpret_cast<uint32_t*>(base_ws + pl.off_work_next) + blockIdx.x;
+  // fp32 items are long (4096 matrix-core cycles per block): wavefronts stay resident and claim
+  // the next item of their head from a device counter (greedy balance, no re-launch gaps).
+  // fp16 items are short and bound by the memory path: the 4 wavefronts of a workgroup take 4
+  // neighbouring tiles at the same time (static stride), so that the key blocks they share are
+  // fetched together and hit the CU's L1.
+  constexpr bool kDynamic = DtypeOf<T>::code == SGA_F32;
+  int64_t w_static = (int64_t)blockIdx.y * 4 + wave;
   while (true) {
-    uint32_t claimed = 0;
-    if (lane == 0) claimed = atomicAdd(work_next, 1u);
-    const int64_t w = __builtin_amdgcn_readfirstlane(claimed);
-    if (w >= pl.n_work) break;
-    const int64_t t = seg_tile[w];
+    int64_t w_cur;
+    if (kDynamic) {
+      uint32_t claimed = 0;
+      if (lane == 0) claimed = atomicAdd(work_next, 1u);
+      w_cur = __builtin_amdgcn_readfirstlane(claimed);
+    } else {
+      w_cur = w_static;
+      w_static += (int64_t)gridDim.y * 4;
+    }
+    if (w_cur >= pl.n_work) break;
+    const int64_t t = seg_tile[w_cur];
     if (t < 0 || tile_bad[t]) continue;                     // idle item / tile left to the gather path
-    const int2 meta = seg_meta[w];
+    const int2 meta = seg_meta[w_cur];
     if (meta.y > 1 && !parts_fit) continue;
     const int64_t row_first = t * kTile;
     const int64_t row_last = row_first + kTile < L ? row_first + kTile : L;
@@ -648,7 +661,7 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h);
     TileState st;
     st.init();
-    core.run(K + hoff, V + hoff, src, 0, seg_count[w], scale * kLog2e, lane, st, lds);
+    core.run(K + hoff, V + hoff, src, 0, seg_count[w_cur], scale * kLog2e, lane, st, lds);
     if (meta.y > 1) {
       float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
                     (((int64_t)tile_pbase[t] + meta.x) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
@@ -781,11 +794,14 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   if (nwg > 16384) nwg = 16384;
   hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
                      a.col_idx, a.L, a.H, a.dtype, a.ws, a.ws_bytes);
-  // resident workgroups: 256 CUs x (2 or 3 wavefronts per SIMD), shared by the heads
-  const int64_t resident = 256 * (a.dtype == SGA_F32 ? 2 : 3);
-  int64_t per_head = resident / a.H;
-  if (per_head < 1) per_head = 1;
-  if (per_head > nwg) per_head = nwg;
+  // fp32: resident workgroups only (256 CUs x 2 wavefronts per SIMD, shared by the heads), which
+  // claim items dynamically; fp16: one pass of workgroups over the items of each head
+  int64_t per_head = nwg;
+  if (a.dtype == SGA_F32) {
+    per_head = 512 / a.H;
+    if (per_head < 1) per_head = 1;
+    if (per_head > nwg) per_head = nwg;
+  }
   profile_mark_begin(a.stream);
   hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0,
                      a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
