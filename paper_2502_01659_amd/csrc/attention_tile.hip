@@ -60,6 +60,9 @@ __device__ __forceinline__ void wait_loads_except() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | N);
 }
 
+// s_waitcnt lgkmcnt(0): every LDS read issued so far has returned its data.
+__device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
 struct BlockInfo {
   int64_t row0;     // tensor row of the block's first key
   int64_t stride;   // tensor rows between consecutive keys of the block
@@ -198,7 +201,32 @@ struct CoreF32 {
     }
   }
 
-  static constexpr int kLdsBytes = kTile * kHeadDim * 4;   // one staged V block per wavefront
+  static constexpr int kBlockBytes = kTile * kHeadDim * 4;   // one staged K or V block
+
+  // Copy the K block b global -> LDS.  Copy s moves keys 4s..4s+3, 16 lanes per 256-byte row, so
+  // every row is fetched as whole cache lines.  Inside a row the sixteen 16-byte chunks are
+  // stored XOR-swizzled: chunk c of key r lives at chunk slot c ^ (r & 15) of row r.  The MFMA
+  // operand read (each lane reads 128 contiguous bytes of its own key row, 16 bytes at a time)
+  // then spreads 8 consecutive lanes over the 8 groups of 4 banks instead of hitting one.
+  __device__ static void stage_k(const float* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) {
+#pragma unroll
+    for (int s = 0; s < 8; ++s) {
+      const int row = 4 * s + (lane >> 4);
+      const int key = row < b.nvalid ? row : b.nvalid - 1;
+      const int chunk = (lane & 15) ^ (row & 15);
+      copy16_to_lds(Kh + (b.row0 + key * b.stride) * kHeadDim + chunk * 4, dst + s * 1024);
+    }
+  }
+
+  // kf[t] = K[key n][h*32 + t] out of the swizzled staged block.
+  __device__ static void read_k(const char* ldsk, int n, int h, float (&kf)[32]) {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const int slot = (8 * h + j) ^ (n & 15);
+      const float4 v = *reinterpret_cast<const float4*>(ldsk + (n * 16 + slot) * 16);
+      kf[4 * j] = v.x; kf[4 * j + 1] = v.y; kf[4 * j + 2] = v.z; kf[4 * j + 3] = v.w;
+    }
+  }
 
   // Copy the V block b global -> LDS (row-major [key][64 channels]); copy s moves keys 4s..4s+3,
   // 16 lanes per 256-byte row.
@@ -211,11 +239,63 @@ struct CoreF32 {
     }
   }
 
-  // Software pipeline per block k: the K fragment of block k+1 is prefetched into registers, the V
+  // Variant with the K block staged in LDS (many blocks per tile).  Both K and V blocks travel global -> LDS without registers, as whole
+  // rows (coalesced).  Per block k: the V copy is issued first; the K fragment (copied during
+  // block k-1) is read into registers and the K copy of block k+1 is issued at once, so it lands
+  // behind the matrix work of block k; block ids / mask words are fetched two blocks ahead.
+  template <typename Src>
+  __device__ void run_ldsk(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
+                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
+    if (k0 >= k1) return;
+    const int n = lane & 31, h = lane >> 5;
+    char* ldsk = lds;
+    char* ldsv = lds + kBlockBytes;
+    BlockInfo b = src.get(k0, n);
+    BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
+    stage_k(Kh, b, lane, ldsk);
+    const float* vread = reinterpret_cast<const float*>(ldsv) + h * 4 * kHeadDim + n;
+    for (int k = k0; k < k1; ++k) {
+      const bool more = k + 1 < k1;      // wave-uniform
+      __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
+      stage_v(Vh, b, lane, ldsv);
+      BlockInfo b2 = b1;
+      if (k + 2 < k1) b2 = src.get(k + 2, n);
+      wait_loads_except<8>();            // K block k is older than the 8 V copies just issued
+      __builtin_amdgcn_wave_barrier();
+      float kf[32];
+      read_k(ldsk, n, h, kf);
+      wait_lds_reads();                  // the K buffer may be overwritten now
+      __builtin_amdgcn_wave_barrier();
+      if (more) stage_k(Kh, b1, lane, ldsk);
+      floatx16 s = {0};
+#pragma unroll
+      for (int t = 0; t < 32; ++t)
+        s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
+      float p[16];
+      softmax_block(s, c, b, h, st, p);
+      // V block k is older than the 8 K copies issued above (if any)
+      if (more) wait_loads_except<8>(); else wait_loads_except<0>();
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        // A operand: V^T[channel cb*32+n][key acc_row(r,h)] = staged V[key][channel]
+        const float v0 = vread[acc_row(r, 0) * kHeadDim];
+        const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
+        st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
+        st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
+      }
+      b = b1;
+      b1 = b2;
+    }
+  }
+
+  // Variant with the K fragment in registers (few blocks per tile): the K fragment of block k+1 is
+  // prefetched global -> registers (each lane reads 128 contiguous bytes of its key row), the V
   // block k is copied global -> LDS behind the S^T matrix work, and block ids / mask words are
   // fetched two blocks ahead, so no load sits on the critical path of the matrix cores.
   template <typename Src>
-  __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
+  __device__ void run_regk(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
@@ -254,6 +334,19 @@ struct CoreF32 {
     }
   }
 
+  // kLdsK selects the pipeline: K block staged in LDS (coalesced whole-row copies; best with many
+  // blocks per tile) or K fragment loaded straight into registers (no LDS round trip before the
+  // first product; best with two or three blocks per tile).
+  template <bool kLdsK>
+  static constexpr int lds_bytes() { return kLdsK ? 2 * kBlockBytes : kBlockBytes; }
+
+  template <bool kLdsK, typename Src>
+  __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
+                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
+    if (kLdsK) run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
+    else run_regk(Kh, Vh, src, k0, k1, c, lane, st, lds);
+  }
+
   __device__ static void store_row(float* Orow, const TileState& st, float inv, int h) {
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
@@ -276,7 +369,29 @@ struct CoreF16 {
     for (int s = 0; s < 4; ++s) qf[s] = src[s];
   }
 
-  static constexpr int kLdsBytes = kTile * kHeadDim * 2;   // one staged V block per wavefront
+  static constexpr int kBlockBytes = kTile * kHeadDim * 2;   // one staged K or V block
+
+  // Copy the K block b global -> LDS.  Copy s moves keys 8s..8s+7, 8 lanes per 128-byte row (whole
+  // cache lines); inside a row the eight 16-byte chunks are XOR-swizzled with the row index (see
+  // CoreF32::stage_k) so that the operand reads are free of bank conflicts.
+  __device__ static void stage_k(const __half* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int row = 8 * s + (lane >> 3);
+      const int key = row < b.nvalid ? row : b.nvalid - 1;
+      const int chunk = (lane & 7) ^ (row & 7);
+      copy16_to_lds(Kh + (b.row0 + key * b.stride) * kHeadDim + chunk * 8, dst + s * 1024);
+    }
+  }
+
+  // kf[s] = K[key n][h*32 + 8s .. +7] out of the swizzled staged block.
+  __device__ static void read_k(const char* ldsk, int n, int h, half8 (&kf)[4]) {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const int slot = (4 * h + s) ^ (n & 7);
+      kf[s] = *reinterpret_cast<const half8*>(ldsk + (n * 8 + slot) * 16);
+    }
+  }
 
   // Copy the V block b global -> LDS (row-major [key][64 channels] fp16); copy s moves keys
   // 8s..8s+7, 8 lanes per 128-byte row.
@@ -311,9 +426,62 @@ struct CoreF16 {
     return __builtin_bit_cast(half4, raw);
   }
 
-  // Same software pipeline as CoreF32::run.
+  // Same pipeline as CoreF32::run_ldsk.
   template <typename Src>
-  __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
+  __device__ void run_ldsk(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
+                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
+    if (k0 >= k1) return;
+    const int n = lane & 31, h = lane >> 5;
+    char* ldsk = lds;
+    char* ldsv = lds + kBlockBytes;
+    BlockInfo b = src.get(k0, n);
+    BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
+    stage_k(Kh, b, lane, ldsk);
+    for (int k = k0; k < k1; ++k) {
+      const bool more = k + 1 < k1;      // wave-uniform
+      __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
+      stage_v(Vh, b, lane, ldsv);
+      BlockInfo b2 = b1;
+      if (k + 2 < k1) b2 = src.get(k + 2, n);
+      wait_loads_except<4>();            // K block k is older than the 4 V copies just issued
+      __builtin_amdgcn_wave_barrier();
+      half8 kf[4];
+      read_k(ldsk, n, h, kf);
+      wait_lds_reads();                  // the K buffer may be overwritten now
+      __builtin_amdgcn_wave_barrier();
+      if (more) stage_k(Kh, b1, lane, ldsk);
+      floatx16 sacc = {0};
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
+      float p[16];
+      softmax_block(sacc, c, b, h, st, p);
+      // V block k is older than the 4 K copies issued above (if any)
+      if (more) wait_loads_except<4>(); else wait_loads_except<0>();
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        half8 pb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[8 * u + e];
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          // A operand: V^T[channel cb*32+n][slot (u,h,e)], slot key = 16u + 8(e/4) + 4h + e%4
+          const half4 lo = read_vt(ldsv, 16 * u + 4 * h, cb, lane);
+          const half4 hi = read_vt(ldsv, 16 * u + 8 + 4 * h, cb, lane);
+          const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
+        }
+      }
+      b = b1;
+      b1 = b2;
+    }
+  }
+
+  // Same pipeline as CoreF32::run_regk.
+  template <typename Src>
+  __device__ void run_regk(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
@@ -355,6 +523,19 @@ struct CoreF16 {
       b = b1;
       b1 = b2;
     }
+  }
+
+  // kLdsK selects the pipeline: K block staged in LDS (coalesced whole-row copies; best with many
+  // blocks per tile) or K fragment loaded straight into registers (no LDS round trip before the
+  // first product; best with two or three blocks per tile).
+  template <bool kLdsK>
+  static constexpr int lds_bytes() { return kLdsK ? 2 * kBlockBytes : kBlockBytes; }
+
+  template <bool kLdsK, typename Src>
+  __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
+                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
+    if (kLdsK) run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
+    else run_regk(Kh, Vh, src, k0, k1, c, lane, st, lds);
   }
 
   __device__ static void store_row(__half* Orow, const TileState& st, float inv, int h) {
@@ -605,18 +786,19 @@ __device__ __forceinline__ bool tile_parts_fit(const WorkspacePlan& pl, const vo
 // a device counter until none is left (items are ordered long segments first, so the greedy
 // order balances the load and no workgroup has to be re-launched between items).  A segment
 // of a multi-segment tile leaves a partial state.
-template <typename T>
+template <typename T, bool kLdsK>
 __global__ __launch_bounds__(256) void tile_attend_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
     size_t ws_bytes) {
-  __shared__ __attribute__((aligned(16))) char lds_all[4 * CoreOf<T>::type::kLdsBytes];
+  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kLdsK>();
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int32_t H = (int32_t)gridDim.x;   // head-major grid: the long work items of every head are dispatched first
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
   if (pl.total_bytes > ws_bytes) return;
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n = lane & 31, h = lane >> 5;
-  char* lds = lds_all + wave * CoreOf<T>::type::kLdsBytes;
+  char* lds = lds_all + wave * kLds;
   char* base_ws = static_cast<char*>(ws);
   const int32_t* seg_tile = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_tile);
   const int2* seg_meta = reinterpret_cast<const int2*>(base_ws + pl.off_seg_meta);
@@ -661,7 +843,7 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h);
     TileState st;
     st.init();
-    core.run(K + hoff, V + hoff, src, 0, seg_count[w_cur], scale * kLog2e, lane, st, lds);
+    core.template run<kLdsK>(K + hoff, V + hoff, src, 0, seg_count[w_cur], scale * kLog2e, lane, st, lds);
     if (meta.y > 1) {
       float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
                     (((int64_t)tile_pbase[t] + meta.x) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
@@ -745,16 +927,17 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
 // share most of their K/V rows, so the linear workgroup id is remapped to give every XCD one
 // contiguous range of the sequence; inside it consecutive workgroups alternate between the
 // residue classes, so that the interleaved rows of all classes are touched together.
-template <typename T>
+template <typename T, bool kLdsK>
 __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_kernel(const T* __restrict__ Q,
                                                           const T* __restrict__ K,
                                                           const T* __restrict__ V, T* __restrict__ O,
                                                           float* __restrict__ lse, int64_t L, int64_t W,
                                                           int64_t s, int64_t n_groups, float scale) {
-  __shared__ __attribute__((aligned(16))) char lds_all[4 * CoreOf<T>::type::kLdsBytes];
+  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kLdsK>();
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int n = lane & 31, h = lane >> 5;
-  char* lds = lds_all + wave * CoreOf<T>::type::kLdsBytes;
+  char* lds = lds_all + wave * kLds;
   // gridDim.x is a multiple of 8: XCD x handles the workgroups [x*chunk, (x+1)*chunk)
   const int64_t chunk = gridDim.x / 8;
   const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
@@ -777,7 +960,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   core.load_q(Q + hoff + qrow * kHeadDim, h);
   TileState st;
   st.init();
-  core.run(K + hoff, V + hoff, src, 0, nblk, scale * kLog2e, lane, st, lds);
+  core.template run<kLdsK>(K + hoff, V + hoff, src, 0, nblk, scale * kLog2e, lane, st, lds);
   finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h);
 }
 
@@ -803,8 +986,10 @@ sga_status run_tile_explicit(const AttnArgs& a) {
     if (per_head > nwg) per_head = nwg;
   }
   profile_mark_begin(a.stream);
-  hipLaunchKernelGGL(tile_attend_kernel<T>, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0,
-                     a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
+  // fp32 tiles keep the K fragment in registers; fp16 tiles stage K in LDS (measured best)
+  constexpr bool kLdsK = DtypeOf<T>::code == SGA_F16;
+  hipLaunchKernelGGL((tile_attend_kernel<T, kLdsK>), dim3((unsigned)a.H, (unsigned)per_head), dim3(256),
+                     0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
   profile_mark_end(a.stream);
   hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
                      O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);
@@ -820,10 +1005,19 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const int64_t n_wg = (n_groups * s + 7) / 8 * 8;
   if (n_wg >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;
   const dim3 grid((unsigned)n_wg, (unsigned)a.H);
+  // fp16 windows of four or more key blocks per tile stage K in LDS; narrow windows and fp32 load
+  // the K fragment straight into registers (measured best)
+  const bool lds_k = a.dtype == SGA_F16 && 2 * (int64_t)a.window + kTile > 3 * kTile;
   profile_mark_begin(a.stream);
-  hipLaunchKernelGGL(tile_window_kernel<T>, grid, dim3(256), 0, a.stream, static_cast<const T*>(a.Q),
-                     static_cast<const T*>(a.K), static_cast<const T*>(a.V), static_cast<T*>(a.O),
-                     a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
+  if (lds_k) {
+    hipLaunchKernelGGL((tile_window_kernel<T, true>), grid, dim3(256), 0, a.stream,
+                       static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
+                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
+  } else {
+    hipLaunchKernelGGL((tile_window_kernel<T, false>), grid, dim3(256), 0, a.stream,
+                       static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
+                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
+  }
   profile_mark_end(a.stream);
   return hip_status(hipGetLastError());
 }
