@@ -111,76 +111,109 @@ struct Segment {
   int32_t start, len, step;
 };
 
-// One workgroup per row: thread 0 derives the row's segments, all threads write them.
+// Rows that attend every key (global tokens / global query blocks) come first: rows [0, n_full).
+__host__ __device__ inline int64_t full_rows(const MaskParams& p) {
+  if (p.kind == SGA_MASK_GLOBAL_LOCAL) return p.g;
+  if (p.kind == SGA_MASK_BIGBIRD) return p.G * p.B;
+  return 0;
+}
+
+// Rows of a group share one segment list: the B rows of a query block (block mask), else one row.
+__host__ __device__ inline int64_t group_rows(const MaskParams& p) {
+  return p.kind == SGA_MASK_BIGBIRD ? p.B : 1;
+}
+
+// One wavefront per row group: lane 0 derives the group's segments once, then the wavefront
+// streams every row of the group with coalesced 256-byte stores.  Full rows are left to
+// fill_full_rows_kernel.
 __global__ __launch_bounds__(256) void fill_kernel(MaskParams p, const int64_t* __restrict__ row_ptr,
                                                    int32_t* __restrict__ col_idx) {
-  __shared__ Segment seg[kMaxSegments];
-  __shared__ int n_seg;
-  __shared__ int64_t picks[kMaxRandom];
-  const int64_t i = blockIdx.x;
-  if (threadIdx.x == 0) {
+  __shared__ Segment seg_all[4][kMaxSegments];
+  __shared__ int n_seg_all[4];
+  __shared__ int64_t picks_all[4][kMaxRandom];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+  Segment* seg = seg_all[wave];
+  int64_t* picks = picks_all[wave];
+  const int64_t R = group_rows(p);
+  const int64_t group = (int64_t)blockIdx.x * 4 + wave;
+  const int64_t i = group * R;                      // first row of the group
+  if (i >= p.L || i < full_rows(p)) return;
+  if (lane == 0) {
     int n = 0;
     if (p.kind == SGA_MASK_SLIDING || p.kind == SGA_MASK_DILATED) {
       const int64_t kl = imin(p.W, i / p.s), kr = imin(p.W, (p.L - 1 - i) / p.s);
       seg[n++] = {(int32_t)(i - kl * p.s), (int32_t)(kl + kr + 1), (int32_t)p.s};
     } else if (p.kind == SGA_MASK_GLOBAL_LOCAL) {
       const int64_t lo = imax(0, i - p.W), hi = imin(p.L - 1, i + p.W);
-      if (i < p.g) {
-        seg[n++] = {0, (int32_t)p.L, 1};
-      } else if (lo <= p.g) {
+      if (lo <= p.g) {
         seg[n++] = {0, (int32_t)(hi + 1), 1};
       } else {
         if (p.g > 0) seg[n++] = {0, (int32_t)p.g, 1};
         seg[n++] = {(int32_t)lo, (int32_t)(hi - lo + 1), 1};
       }
     } else {
-      const int64_t b = i / p.B;
-      if (b < p.G) {
-        seg[n++] = {0, (int32_t)p.L, 1};
-      } else {
-        const int64_t lo = imax(0, b - p.wb), hi = imin(p.nb - 1, b + p.wb);
-        // random key blocks: rejection sampling over the counter-based stream of block b
-        const uint64_t key = mix64(p.seed + kGold * (uint64_t)(b + 1));
-        int got = 0;
-        uint64_t a = 0;
-        while (got < (int)p.R) {
-          const int64_t cand = (int64_t)(mix64(key + kGold * (a + 1)) % (uint64_t)p.nb);
-          ++a;
-          bool taken = cand < p.G || (cand >= lo && cand <= hi);
-          for (int t = 0; t < got; ++t) taken = taken || picks[t] == cand;
-          if (!taken) {
-            // keep picks sorted (insertion)
-            int pos = got;
-            while (pos > 0 && picks[pos - 1] > cand) {
-              picks[pos] = picks[pos - 1];
-              --pos;
-            }
-            picks[pos] = cand;
-            ++got;
+      const int64_t b = group;
+      const int64_t lo = imax(0, b - p.wb), hi = imin(p.nb - 1, b + p.wb);
+      // random key blocks: rejection sampling over the counter-based stream of block b
+      const uint64_t key = mix64(p.seed + kGold * (uint64_t)(b + 1));
+      int got = 0;
+      uint64_t a = 0;
+      while (got < (int)p.R) {
+        const int64_t cand = (int64_t)(mix64(key + kGold * (a + 1)) % (uint64_t)p.nb);
+        ++a;
+        bool taken = cand < p.G || (cand >= lo && cand <= hi);
+        for (int t = 0; t < got; ++t) taken = taken || picks[t] == cand;
+        if (!taken) {
+          // keep picks sorted (insertion)
+          int pos = got;
+          while (pos > 0 && picks[pos - 1] > cand) {
+            picks[pos] = picks[pos - 1];
+            --pos;
           }
+          picks[pos] = cand;
+          ++got;
         }
-        int t = 0;
-        if (lo <= p.G) {
-          // global blocks and the window form one run [0, hi]
-          seg[n++] = {0, (int32_t)((hi + 1) * p.B), 1};
-        } else {
-          if (p.G > 0) seg[n++] = {0, (int32_t)(p.G * p.B), 1};
-          for (; t < got && picks[t] < lo; ++t)
-            seg[n++] = {(int32_t)(picks[t] * p.B), (int32_t)p.B, 1};
-          seg[n++] = {(int32_t)(lo * p.B), (int32_t)((hi - lo + 1) * p.B), 1};
-        }
-        for (; t < got; ++t) seg[n++] = {(int32_t)(picks[t] * p.B), (int32_t)p.B, 1};
       }
+      int t = 0;
+      if (lo <= p.G) {
+        // global blocks and the window form one run [0, hi]
+        seg[n++] = {0, (int32_t)((hi + 1) * p.B), 1};
+      } else {
+        if (p.G > 0) seg[n++] = {0, (int32_t)(p.G * p.B), 1};
+        for (; t < got && picks[t] < lo; ++t)
+          seg[n++] = {(int32_t)(picks[t] * p.B), (int32_t)p.B, 1};
+        seg[n++] = {(int32_t)(lo * p.B), (int32_t)((hi - lo + 1) * p.B), 1};
+      }
+      for (; t < got; ++t) seg[n++] = {(int32_t)(picks[t] * p.B), (int32_t)p.B, 1};
     }
-    n_seg = n;
+    n_seg_all[wave] = n;
   }
-  __syncthreads();
-  int32_t* out = col_idx + row_ptr[i];
-  const int n = n_seg;
-  for (int k = 0; k < n; ++k) {
-    const Segment sg = seg[k];
-    for (int32_t t = threadIdx.x; t < sg.len; t += blockDim.x) out[t] = sg.start + t * sg.step;
-    out += sg.len;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+  const int n = n_seg_all[wave];
+  const int64_t rows = imin(R, p.L - i);
+  for (int64_t r = 0; r < rows; ++r) {
+    int32_t* out = col_idx + row_ptr[i + r];
+    for (int k = 0; k < n; ++k) {
+      const Segment sg = seg[k];
+      for (int32_t t = lane; t < sg.len; t += kWave) out[t] = sg.start + t * sg.step;
+      out += sg.len;
+    }
+  }
+}
+
+// Rows [0, n_full) attend every key: col_idx of such a row is 0, 1, ..., L-1.
+// grid = (chunks of 4096 columns, full rows); 16 consecutive entries per thread.
+__global__ __launch_bounds__(256) void fill_full_rows_kernel(int64_t L,
+                                                             const int64_t* __restrict__ row_ptr,
+                                                             int32_t* __restrict__ col_idx) {
+  int32_t* out = col_idx + row_ptr[blockIdx.y];
+  const int64_t base = (int64_t)blockIdx.x * 4096;
+#pragma unroll
+  for (int u = 0; u < 16; ++u) {
+    const int64_t j = base + u * 256 + threadIdx.x;
+    if (j < L) out[j] = (int32_t)j;
   }
 }
 
@@ -221,7 +254,18 @@ sga_status launch_build_mask(const sga_mask_desc& d, int64_t* row_ptr, int32_t* 
   const MaskParams p = make_params(d);
   const unsigned nblk = (unsigned)((p.L + 1 + 255) / 256);
   hipLaunchKernelGGL(row_ptr_kernel, dim3(nblk), dim3(256), 0, stream, p, row_ptr);
-  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)p.L), dim3(256), 0, stream, p, row_ptr, col_idx);
+  const int64_t groups = (p.L + group_rows(p) - 1) / group_rows(p);
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((groups + 3) / 4)), dim3(256), 0, stream, p, row_ptr,
+                     col_idx);
+  const int64_t n_full = full_rows(p) < p.L ? full_rows(p) : p.L;
+  if (n_full > 0) {
+    // grid.y is limited to 65535 rows per launch
+    for (int64_t r0 = 0; r0 < n_full; r0 += 65535) {
+      const int64_t rows = n_full - r0 < 65535 ? n_full - r0 : 65535;
+      hipLaunchKernelGGL(fill_full_rows_kernel, dim3((unsigned)((p.L + 4095) / 4096), (unsigned)rows),
+                         dim3(256), 0, stream, p.L, row_ptr + r0, col_idx);
+    }
+  }
   return hip_status(hipGetLastError());
 }
 
