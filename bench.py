@@ -31,7 +31,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg2_longformer_64k": 938_140_672,
+    "cfg1_sliding_4k": 5_699_200,
+    "cfg2_longformer_64k": 1_091_642_472,
+    "cfg3_dilated_1m": 2_149_410_513,
+    "cfg4_bigbird_1m": 11_124_049_191,
+    "cfg5_sliding_160m": 81_918_574_954,
 }
 
 
