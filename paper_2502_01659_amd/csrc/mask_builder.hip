@@ -5,8 +5,10 @@
 // ("segments": start, length, step), so
 //   - the row offset is a closed-form prefix sum evaluated independently per row
 //     (no scan over the rows is needed), and
-//   - a row is filled by one workgroup that derives the row's segments once and
-//     then streams them out with coalesced int32 stores.
+//   - a group of consecutive rows is filled by one wavefront that derives the
+//     group's segments once and then streams the rows out with coalesced int32
+//     stores; rows that attend every key are written by a kernel of their own,
+//     many workgroups per row.
 #include "sga_internal.h"
 
 namespace sga {
