@@ -64,50 +64,67 @@ __device__ __forceinline__ void wait_loads_except() {
 __device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
 struct BlockInfo {
-  int64_t row0;     // tensor row of the block's first key
-  int64_t stride;   // tensor rows between consecutive keys of the block
-  int nvalid;       // keys of the block that exist (1..32); others are masked off
+  int raw;          // explicit masks: block record as loaded (row0, nvalid, full follow from it)
+  int64_t row0;     // tensor row of the block's first key (wave-uniform)
+  int nvalid;       // keys of the block that exist (1..32); others are masked off (wave-uniform)
   uint32_t word;    // mask bits of this lane's query against the block's 32 keys
   bool full;        // all 32x32 bits set (wave-uniform)
 };
+
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)v);
+  const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)((uint64_t)v >> 32));
+  return (int64_t)(((uint64_t)hi << 32) | lo);
+}
 
 // Block list of an explicit tile, as written by tile_analyze_kernel.
 struct ExplicitBlocks {
   const int32_t* blk;
   const uint32_t* mask;
   int64_t L;
+  __device__ int64_t key_stride() const { return 1; }
+  // get() only issues the loads (two blocks ahead of their use); resolve() turns the loaded
+  // record into wave-uniform values once the block is about to be staged, so that the loads are
+  // not waited for early.
   __device__ BlockInfo get(int k, int n) const {
     BlockInfo b;
-    const int id = blk[k];
-    b.full = (id & kFullBit) != 0;
-    b.row0 = (int64_t)(id & ~kFullBit) * kTile;
-    b.stride = 1;
-    const int64_t left = L - b.row0;
-    b.nvalid = left < kTile ? (int)left : kTile;
+    b.raw = blk[k];
     b.word = mask[(int64_t)k * kTile + n];
     return b;
+  }
+  __device__ void resolve(BlockInfo& b) const {
+    const int id = __builtin_amdgcn_readfirstlane(b.raw);
+    b.full = (id & kFullBit) != 0;
+    b.row0 = (int64_t)(id & ~kFullBit) * kTile;
+    const int64_t left = L - b.row0;
+    b.nvalid = left < kTile ? (int)left : kTile;
   }
 };
 
 // Block list of a window tile in one residue class p of stride s: queries u0..u0+31 and keys
-// v of the class (token = s*index + p), edge iff |u - v| <= W.
+// v of the class (token = s*index + p), edge iff |u - v| <= W.  Everything but the lane's mask
+// word is wave-uniform and is computed from differences that fit 32 bits.
 struct WindowBlocks {
   int64_t vfirst, Lc, s, p, u0, W;   // blocks start at the tile's first key, not at multiples of 32
+  __device__ int64_t key_stride() const { return s; }
+  __device__ static int clamp64(int64_t v) { return v < -64 ? -64 : (v > 64 ? 64 : (int)v); }
+  __device__ void resolve(BlockInfo&) const {}
   __device__ BlockInfo get(int k, int n) const {
     BlockInfo b;
+    b.raw = 0;
     const int64_t v0 = vfirst + (int64_t)k * kTile;
     b.row0 = s * v0 + p;
-    b.stride = s;
     const int64_t left = Lc - v0;
     b.nvalid = left < kTile ? (int)left : kTile;
-    const int64_t u = u0 + n;
-    int64_t lo = u - W - v0, hi = u + W - v0;
-    if (hi > b.nvalid - 1) hi = b.nvalid - 1;
-    if (lo < 0) lo = 0;
-    b.word = (lo > hi || u >= Lc) ? 0u : ((~0u >> (31 - (int)hi)) & (~0u << (int)lo));
+    // query n sees the keys [n + dlo, n + dhi] of the block, clipped to the keys that exist
+    const int dlo = clamp64(u0 - W - v0), dhi = clamp64(u0 + W - v0);
+    const int nq = clamp64(Lc - u0);               // queries of the tile that exist
+    int lo = n + dlo, hi = n + dhi;
+    lo = lo < 0 ? 0 : lo;
+    hi = hi > b.nvalid - 1 ? b.nvalid - 1 : hi;
+    b.word = (lo > hi || n >= nq) ? 0u : ((~0u >> (31 - hi)) & (~0u << lo));
     // every query of the tile sees every key of the block
-    b.full = b.nvalid == kTile && u0 + kTile <= Lc && v0 >= u0 + (kTile - 1) - W &&
-             v0 + (kTile - 1) <= u0 + W;
+    b.full = b.nvalid == kTile && nq >= kTile && dlo + (kTile - 1) <= 0 && dhi >= kTile - 1;
     return b;
   }
 };
@@ -132,30 +149,35 @@ struct TileState {
 // 2^kRescaleSlack, well inside fp16/fp32 range, and the quotient acc/l is unchanged.
 constexpr float kRescaleSlack = 8.0f;
 
-// Mask, running max/sum update and (rare) rescale for one block.  s: raw scores of this lane's
-// query against keys acc_row(r, h); returns the block's softmax numerators in p.
-__device__ __forceinline__ void softmax_block(const floatx16& s, float c, const BlockInfo& b, int h,
+// c = |scale| * log2(e) of p = 2^(c*s - m).  A zero scale (uniform weights over the neighbours)
+// is replaced by 2^-100: every finite product then scales to 0 within rounding, while the -inf of
+// a masked entry stays -inf instead of turning into 0 * inf.
+__device__ __forceinline__ float softmax_factor(float scale) {
+  const float c = __builtin_fabsf(scale) * kLog2e;
+  return c > 0.f ? c : 7.888609052210118e-31f;
+}
+
+// Mask, running max/sum update and (rare) rescale for one block.  sv: raw dot products of this
+// lane's query with keys acc_row(r, h); c > 0 is scale * log2(e) (a negative scale is folded
+// into the sign of Q by the caller), so the block maximum can be taken over the raw products
+// and the scaling fused into the exponent: p = 2^(c*s - m).
+__device__ __forceinline__ void softmax_block(floatx16 sv, float c, const BlockInfo& b, int h,
                                               TileState& st, float (&p)[16]) {
-  float sv[16];
   float bm = -INFINITY;
-  if (b.full) {
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      sv[r] = s[r] * c;
-      bm = fmaxf(bm, sv[r]);
-    }
-  } else {
+  if (!b.full) {
     const uint32_t wh = b.word >> (4 * h);
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
-      // all-ones where the edge exists, else zero; then select score or -inf bitwise
+      // all-ones where the edge exists, else zero; then select the product or -inf bitwise
       const int keep = ((int)(wh << (31 - acc_row(r, 0)))) >> 31;
-      const int bits = (__builtin_bit_cast(int, s[r] * c) & keep) | ((int)0xff800000 & ~keep);
+      const float x = sv[r];   // (a bit cast applied to the vector element itself reads element 0)
+      const int bits = (__builtin_bit_cast(int, x) & keep) | ((int)0xff800000 & ~keep);
       sv[r] = __builtin_bit_cast(float, bits);
-      bm = fmaxf(bm, sv[r]);
     }
   }
-  bm = fmaxf(bm, __shfl_xor(bm, 32, kWave));
+#pragma unroll
+  for (int r = 0; r < 16; ++r) bm = fmaxf(bm, sv[r]);
+  bm = fmaxf(bm, __shfl_xor(bm, 32, kWave)) * c;
   if (__any(bm > st.m + kRescaleSlack)) {
     const float m_new = bm > st.m + kRescaleSlack ? bm : st.m;
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
@@ -168,32 +190,112 @@ __device__ __forceinline__ void softmax_block(const floatx16& s, float c, const 
     }
   }
   float lsum = 0.f;
+  const float neg_m = -st.m;
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
-    p[r] = __builtin_amdgcn_exp2f(sv[r] - st.m);
+    p[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c, neg_m));
     lsum += p[r];
   }
   st.l += lsum;
 }
 
+// Source addresses of the global -> LDS block copies.  A block's rows are row0 + j*stride
+// (j = 0..31); copy i of a block moves kRows consecutive keys, kLanes lanes of 16 bytes per
+// row.  The per-lane part of the address is fixed for a whole work item (32-bit byte offsets
+// from the block's first row); the per-block part is wave-uniform, so a copy costs no vector
+// arithmetic.  Blocks cut short by the end of the sequence (nvalid < 32) re-read their last
+// row instead of running past it; those keys are masked off.
+template <typename T>
+struct StageMap {
+  static constexpr int kRowBytes = kHeadDim * (int)sizeof(T);
+  static constexpr int kLanes = kRowBytes / 16;          // lanes per row
+  static constexpr int kRows = kWave / kLanes;           // rows per copy
+  static constexpr int kCopies = kTile / kRows;          // copies per block
+  int64_t stride_bytes;                                  // bytes between consecutive keys
+  uint32_t voff;                                         // V: lane's row and 16-byte chunk
+  uint32_t koff[kLanes / 4 > 1 ? 4 : 1];                 // K: same with the chunk swizzled, per copy % 4
+
+  __device__ void init(int64_t stride, int lane) {
+    stride_bytes = stride * kRowBytes;
+    const int lr = lane / kLanes, lc = lane % kLanes;
+    const uint32_t rowoff = (uint32_t)(lr * stride_bytes);
+    voff = rowoff + lc * 16;
+    // chunk c of key r is stored at chunk slot c ^ (r % kLanes): the copy reads the chunk that
+    // belongs into the slot this lane writes
+    if (kLanes == 8) {
+      koff[0] = rowoff + ((lc ^ lr) * 16);               // (8i + lr) % 8 = lr for every copy i
+    } else {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) koff[i] = rowoff + ((lc ^ ((4 * i + lr) & 15)) * 16);
+    }
+  }
+  __device__ void stage_v(const T* __restrict__ Vh, const BlockInfo& b, int lane, char* dst) const {
+    if (b.nvalid == kTile) {
+      const char* base = reinterpret_cast<const char*>(Vh) + b.row0 * kRowBytes;
+#pragma unroll
+      for (int i = 0; i < kCopies; ++i)
+        copy16_to_lds(base + i * kRows * stride_bytes + voff, dst + i * 1024);
+    } else {
+#pragma unroll
+      for (int i = 0; i < kCopies; ++i) {
+        int key = kRows * i + lane / kLanes;
+        key = key < b.nvalid ? key : b.nvalid - 1;
+        copy16_to_lds(reinterpret_cast<const char*>(Vh) + b.row0 * kRowBytes + key * stride_bytes +
+                          (lane % kLanes) * 16,
+                      dst + i * 1024);
+      }
+    }
+  }
+  __device__ void stage_k(const T* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) const {
+    if (b.nvalid == kTile) {
+      const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * kRowBytes;
+#pragma unroll
+      for (int i = 0; i < kCopies; ++i)
+        copy16_to_lds(base + i * kRows * stride_bytes + koff[kLanes == 8 ? 0 : i % 4], dst + i * 1024);
+    } else {
+#pragma unroll
+      for (int i = 0; i < kCopies; ++i) {
+        const int row = kRows * i + lane / kLanes;
+        const int key = row < b.nvalid ? row : b.nvalid - 1;
+        const int chunk = (lane % kLanes) ^ (row % kLanes);
+        copy16_to_lds(reinterpret_cast<const char*>(Kh) + b.row0 * kRowBytes + key * stride_bytes +
+                          chunk * 16,
+                      dst + i * 1024);
+      }
+    }
+  }
+};
+
 // ---- fp32 storage ---------------------------------------------------------------------------
 struct CoreF32 {
+  using Stage = StageMap<float>;
   float qf[32];   // Q[query n][h*32 + t]
 
-  __device__ void load_q(const float* Qrow, int h) {
+  __device__ void load_q(const float* Qrow, int h, bool negate) {
     const float4* src = reinterpret_cast<const float4*>(Qrow + h * 32);
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const float4 v = src[t];
       qf[4 * t] = v.x; qf[4 * t + 1] = v.y; qf[4 * t + 2] = v.z; qf[4 * t + 3] = v.w;
     }
+    if (negate) {
+#pragma unroll
+      for (int t = 0; t < 32; ++t) qf[t] = -qf[t];
+    }
   }
 
-  __device__ static void load_k(const float* __restrict__ Kh, const BlockInfo& b, int n, int h,
-                                float (&kf)[32]) {
-    const int krow = n < b.nvalid ? n : b.nvalid - 1;
-    const float4* kp =
-        reinterpret_cast<const float4*>(Kh + (b.row0 + krow * b.stride) * kHeadDim + h * 32);
+  // kf[t] = K[key n of the block][h*32 + t], straight from global memory: 128 contiguous bytes
+  // per lane.  lane_off = byte offset of the lane's key row and half inside a whole block.
+  __device__ static void load_k(const float* __restrict__ Kh, const BlockInfo& b, int64_t stride_bytes,
+                                uint32_t lane_off, int n, int h, float (&kf)[32]) {
+    const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * Stage::kRowBytes;
+    const float4* kp;
+    if (b.nvalid == kTile) {
+      kp = reinterpret_cast<const float4*>(base + lane_off);
+    } else {
+      const int krow = n < b.nvalid ? n : b.nvalid - 1;
+      kp = reinterpret_cast<const float4*>(base + krow * stride_bytes + h * 128);
+    }
 #pragma unroll
     for (int t = 0; t < 8; ++t) {
       const float4 v = kp[t];
@@ -203,22 +305,11 @@ struct CoreF32 {
 
   static constexpr int kBlockBytes = kTile * kHeadDim * 4;   // one staged K or V block
 
-  // Copy the K block b global -> LDS.  Copy s moves keys 4s..4s+3, 16 lanes per 256-byte row, so
-  // every row is fetched as whole cache lines.  Inside a row the sixteen 16-byte chunks are
-  // stored XOR-swizzled: chunk c of key r lives at chunk slot c ^ (r & 15) of row r.  The MFMA
-  // operand read (each lane reads 128 contiguous bytes of its own key row, 16 bytes at a time)
+  // kf[t] = K[key n][h*32 + t] out of the staged block.  The global -> LDS copy moved keys
+  // 4i..4i+3 per instruction, 16 lanes per 256-byte row (whole cache lines), and stored the
+  // sixteen 16-byte chunks of a row XOR-swizzled: chunk c of key r lives at chunk slot
+  // c ^ (r & 15).  This read (each lane 128 contiguous bytes of its own key row, 16 at a time)
   // then spreads 8 consecutive lanes over the 8 groups of 4 banks instead of hitting one.
-  __device__ static void stage_k(const float* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) {
-#pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      const int row = 4 * s + (lane >> 4);
-      const int key = row < b.nvalid ? row : b.nvalid - 1;
-      const int chunk = (lane & 15) ^ (row & 15);
-      copy16_to_lds(Kh + (b.row0 + key * b.stride) * kHeadDim + chunk * 4, dst + s * 1024);
-    }
-  }
-
-  // kf[t] = K[key n][h*32 + t] out of the swizzled staged block.
   __device__ static void read_k(const char* ldsk, int n, int h, float (&kf)[32]) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -228,37 +319,53 @@ struct CoreF32 {
     }
   }
 
-  // Copy the V block b global -> LDS (row-major [key][64 channels]); copy s moves keys 4s..4s+3,
-  // 16 lanes per 256-byte row.
-  __device__ static void stage_v(const float* __restrict__ Vh, const BlockInfo& b, int lane, char* dst) {
+  // S^T = K_blk Q^T, softmax, O^T += V_blk^T P^T for one block whose V rows are staged at ldsv.
+  template <typename WaitV>
+  __device__ void block_math(const float (&kf)[32], const BlockInfo& b, float c, int n, int h,
+                             TileState& st, const char* ldsv, WaitV wait_v) {
+    floatx16 s = {0};
 #pragma unroll
-    for (int s = 0; s < 8; ++s) {
-      int key = 4 * s + (lane >> 4);
-      key = key < b.nvalid ? key : b.nvalid - 1;
-      copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 15) * 4, dst + s * 1024);
+    for (int t = 0; t < 32; ++t)
+      s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
+    float p[16];
+    softmax_block(s, c, b, h, st, p);
+    wait_v();
+    __builtin_amdgcn_wave_barrier();
+    const float* vread = reinterpret_cast<const float*>(ldsv) + h * 4 * kHeadDim + n;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      // A operand: V^T[channel cb*32+n][key acc_row(r,h)] = staged V[key][channel]
+      const float v0 = vread[acc_row(r, 0) * kHeadDim];
+      const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
+      st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
+      st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
     }
   }
 
-  // Variant with the K block staged in LDS (many blocks per tile).  Both K and V blocks travel global -> LDS without registers, as whole
-  // rows (coalesced).  Per block k: the V copy is issued first; the K fragment (copied during
-  // block k-1) is read into registers and the K copy of block k+1 is issued at once, so it lands
-  // behind the matrix work of block k; block ids / mask words are fetched two blocks ahead.
+  // Variant with the K block staged in LDS (many blocks per tile).  Both K and V blocks travel
+  // global -> LDS without registers, as whole rows (coalesced).  Per block k: the V copy is
+  // issued first; the K fragment (copied during block k-1) is read into registers and the K
+  // copy of block k+1 is issued at once, so it lands behind the matrix work of block k; block
+  // ids / mask words are fetched two blocks ahead.
   template <typename Src>
   __device__ void run_ldsk(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
+    Stage sm;
+    sm.init(src.key_stride(), lane);
     char* ldsk = lds;
     char* ldsv = lds + kBlockBytes;
     BlockInfo b = src.get(k0, n);
     BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    src.resolve(b);
     __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
-    stage_k(Kh, b, lane, ldsk);
-    const float* vread = reinterpret_cast<const float*>(ldsv) + h * 4 * kHeadDim + n;
+    sm.stage_k(Kh, b, lane, ldsk);
     for (int k = k0; k < k1; ++k) {
       const bool more = k + 1 < k1;      // wave-uniform
+      src.resolve(b1);
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-      stage_v(Vh, b, lane, ldsv);
+      sm.stage_v(Vh, b, lane, ldsv);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
       wait_loads_except<8>();            // K block k is older than the 8 V copies just issued
@@ -267,24 +374,11 @@ struct CoreF32 {
       read_k(ldsk, n, h, kf);
       wait_lds_reads();                  // the K buffer may be overwritten now
       __builtin_amdgcn_wave_barrier();
-      if (more) stage_k(Kh, b1, lane, ldsk);
-      floatx16 s = {0};
-#pragma unroll
-      for (int t = 0; t < 32; ++t)
-        s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
-      float p[16];
-      softmax_block(s, c, b, h, st, p);
+      if (more) sm.stage_k(Kh, b1, lane, ldsk);
       // V block k is older than the 8 K copies issued above (if any)
-      if (more) wait_loads_except<8>(); else wait_loads_except<0>();
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        // A operand: V^T[channel cb*32+n][key acc_row(r,h)] = staged V[key][channel]
-        const float v0 = vread[acc_row(r, 0) * kHeadDim];
-        const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
-        st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
-        st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
-      }
+      block_math(kf, b, c, n, h, st, ldsv, [more] {
+        if (more) wait_loads_except<8>(); else wait_loads_except<0>();
+      });
       b = b1;
       b1 = b2;
     }
@@ -293,44 +387,36 @@ struct CoreF32 {
   // Variant with the K fragment in registers (few blocks per tile): the K fragment of block k+1 is
   // prefetched global -> registers (each lane reads 128 contiguous bytes of its key row), the V
   // block k is copied global -> LDS behind the S^T matrix work, and block ids / mask words are
-  // fetched two blocks ahead, so no load sits on the critical path of the matrix cores.
+  // fetched two blocks ahead, so no load sits on the critical path of the matrix cores.  The
+  // loop is unrolled over two fragment buffers, so the prefetched fragment is never copied.
   template <typename Src>
   __device__ void run_regk(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
+    Stage sm;
+    sm.init(src.key_stride(), lane);
+    const uint32_t klane = (uint32_t)(n * sm.stride_bytes) + h * 128;
     BlockInfo b = src.get(k0, n);
     BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
-    float kf_next[32];
-    load_k(Kh, b, n, h, kf_next);
-    const float* vread = reinterpret_cast<const float*>(lds) + h * 4 * kHeadDim + n;
-    for (int k = k0; k < k1; ++k) {
-      float kf[32];
-#pragma unroll
-      for (int t = 0; t < 32; ++t) kf[t] = kf_next[t];
-      if (k + 1 < k1) load_k(Kh, b1, n, h, kf_next);
+    src.resolve(b);
+    float kfa[32], kfb[32];
+    load_k(Kh, b, sm.stride_bytes, klane, n, h, kfa);
+    auto step = [&](int k, float (&kf)[32], float (&kf_next)[32]) {
+      src.resolve(b1);
+      if (k + 1 < k1) load_k(Kh, b1, sm.stride_bytes, klane, n, h, kf_next);
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-      stage_v(Vh, b, lane, lds);
+      sm.stage_v(Vh, b, lane, lds);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
-      floatx16 s = {0};
-#pragma unroll
-      for (int t = 0; t < 32; ++t)
-        s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
-      float p[16];
-      softmax_block(s, c, b, h, st, p);
-      wait_loads_except<0>();
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        // A operand: V^T[channel cb*32+n][key acc_row(r,h)] = staged V[key][channel]
-        const float v0 = vread[acc_row(r, 0) * kHeadDim];
-        const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
-        st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
-        st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
-      }
+      block_math(kf, b, c, n, h, st, lds, [] { wait_loads_except<0>(); });
       b = b1;
       b1 = b2;
+    };
+    for (int k = k0; k < k1; k += 2) {
+      step(k, kfa, kfb);
+      if (k + 1 >= k1) break;
+      step(k + 1, kfb, kfa);
     }
   }
 
@@ -361,30 +447,24 @@ struct CoreF32 {
 
 // ---- fp16 storage ---------------------------------------------------------------------------
 struct CoreF16 {
+  using Stage = StageMap<__half>;
   half8 qf[4];    // Q[query n][h*32 + 8s .. +7], s = 0..3
 
-  __device__ void load_q(const __half* Qrow, int h) {
+  __device__ void load_q(const __half* Qrow, int h, bool negate) {
     const half8* src = reinterpret_cast<const half8*>(Qrow + h * 32);
 #pragma unroll
     for (int s = 0; s < 4; ++s) qf[s] = src[s];
+    if (negate) {
+#pragma unroll
+      for (int s = 0; s < 4; ++s) qf[s] = -qf[s];
+    }
   }
 
   static constexpr int kBlockBytes = kTile * kHeadDim * 2;   // one staged K or V block
 
-  // Copy the K block b global -> LDS.  Copy s moves keys 8s..8s+7, 8 lanes per 128-byte row (whole
-  // cache lines); inside a row the eight 16-byte chunks are XOR-swizzled with the row index (see
-  // CoreF32::stage_k) so that the operand reads are free of bank conflicts.
-  __device__ static void stage_k(const __half* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      const int row = 8 * s + (lane >> 3);
-      const int key = row < b.nvalid ? row : b.nvalid - 1;
-      const int chunk = (lane & 7) ^ (row & 7);
-      copy16_to_lds(Kh + (b.row0 + key * b.stride) * kHeadDim + chunk * 8, dst + s * 1024);
-    }
-  }
-
-  // kf[s] = K[key n][h*32 + 8s .. +7] out of the swizzled staged block.
+  // kf[s] = K[key n][h*32 + 8s .. +7] out of the staged block: keys 8i..8i+7 per copy, 8 lanes
+  // per 128-byte row, the eight 16-byte chunks of a row XOR-swizzled with the row index (see
+  // CoreF32::read_k) so that these reads are free of bank conflicts.
   __device__ static void read_k(const char* ldsk, int n, int h, half8 (&kf)[4]) {
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
@@ -393,22 +473,16 @@ struct CoreF16 {
     }
   }
 
-  // Copy the V block b global -> LDS (row-major [key][64 channels] fp16); copy s moves keys
-  // 8s..8s+7, 8 lanes per 128-byte row.
-  __device__ static void stage_v(const __half* __restrict__ Vh, const BlockInfo& b, int lane, char* dst) {
-#pragma unroll
-    for (int s = 0; s < 4; ++s) {
-      int key = 8 * s + (lane >> 3);
-      key = key < b.nvalid ? key : b.nvalid - 1;
-      copy16_to_lds(Vh + (b.row0 + key * b.stride) * kHeadDim + (lane & 7) * 8, dst + s * 1024);
+  __device__ static void load_k(const __half* __restrict__ Kh, const BlockInfo& b, int64_t stride_bytes,
+                                uint32_t lane_off, int n, int h, half8 (&kf)[4]) {
+    const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * Stage::kRowBytes;
+    const half8* kp;
+    if (b.nvalid == kTile) {
+      kp = reinterpret_cast<const half8*>(base + lane_off);
+    } else {
+      const int krow = n < b.nvalid ? n : b.nvalid - 1;
+      kp = reinterpret_cast<const half8*>(base + krow * stride_bytes + h * 64);
     }
-  }
-
-  __device__ static void load_k(const __half* __restrict__ Kh, const BlockInfo& b, int n, int h,
-                                half8 (&kf)[4]) {
-    const int krow = n < b.nvalid ? n : b.nvalid - 1;
-    const half8* kp =
-        reinterpret_cast<const half8*>(Kh + (b.row0 + krow * b.stride) * kHeadDim + h * 32);
 #pragma unroll
     for (int s = 0; s < 4; ++s) kf[s] = kp[s];
   }
@@ -418,12 +492,40 @@ struct CoreF16 {
   // addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4.  Lane i therefore addresses key
   // (key0 + i/4) at channels 4*(i%4).. of its group's 16 channels, and ends up with channel i of
   // the group for keys key0..key0+3: the K-contiguous A operand of V^T.
-  __device__ static half4 read_vt(const char* lds, int key0, int cb, int lane) {
-    const int i = lane & 15, grp16 = (lane >> 4) & 1;
-    const char* p = lds + (key0 + (i >> 2)) * (kHeadDim * 2) + (cb * 32 + grp16 * 16 + 4 * (i & 3)) * 2;
+  __device__ static half4 read_vt(const char* p) {
     const short4v raw =
         __builtin_amdgcn_ds_read_tr16_b64_v4i16((short4v __attribute__((address_space(3)))*)p);
     return __builtin_bit_cast(half4, raw);
+  }
+
+  template <typename WaitV>
+  __device__ void block_math(const half8 (&kf)[4], const BlockInfo& b, float c, int lane, int h,
+                             TileState& st, const char* ldsv, WaitV wait_v) {
+    floatx16 sacc = {0};
+#pragma unroll
+    for (int s = 0; s < 4; ++s)
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
+    float p[16];
+    softmax_block(sacc, c, b, h, st, p);
+    wait_v();
+    __builtin_amdgcn_wave_barrier();
+    // this lane's address for key0 = 4h, channel group 0; the other reads are constant offsets
+    const int i = lane & 15, grp16 = (lane >> 4) & 1;
+    const char* vt = ldsv + (4 * h + (i >> 2)) * (kHeadDim * 2) + (grp16 * 16 + 4 * (i & 3)) * 2;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      half8 pb;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[8 * u + e];
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb) {
+        // A operand: V^T[channel cb*32+n][slot (u,h,e)], slot key = 16u + 8(e/4) + 4h + e%4
+        const half4 lo = read_vt(vt + (16 * u) * (kHeadDim * 2) + cb * 64);
+        const half4 hi = read_vt(vt + (16 * u + 8) * (kHeadDim * 2) + cb * 64);
+        const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
+      }
+    }
   }
 
   // Same pipeline as CoreF32::run_ldsk.
@@ -432,16 +534,20 @@ struct CoreF16 {
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
+    Stage sm;
+    sm.init(src.key_stride(), lane);
     char* ldsk = lds;
     char* ldsv = lds + kBlockBytes;
     BlockInfo b = src.get(k0, n);
     BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    src.resolve(b);
     __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
-    stage_k(Kh, b, lane, ldsk);
+    sm.stage_k(Kh, b, lane, ldsk);
     for (int k = k0; k < k1; ++k) {
       const bool more = k + 1 < k1;      // wave-uniform
+      src.resolve(b1);
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-      stage_v(Vh, b, lane, ldsv);
+      sm.stage_v(Vh, b, lane, ldsv);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
       wait_loads_except<4>();            // K block k is older than the 4 V copies just issued
@@ -450,30 +556,11 @@ struct CoreF16 {
       read_k(ldsk, n, h, kf);
       wait_lds_reads();                  // the K buffer may be overwritten now
       __builtin_amdgcn_wave_barrier();
-      if (more) stage_k(Kh, b1, lane, ldsk);
-      floatx16 sacc = {0};
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
-      float p[16];
-      softmax_block(sacc, c, b, h, st, p);
+      if (more) sm.stage_k(Kh, b1, lane, ldsk);
       // V block k is older than the 4 K copies issued above (if any)
-      if (more) wait_loads_except<4>(); else wait_loads_except<0>();
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        half8 pb;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[8 * u + e];
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          // A operand: V^T[channel cb*32+n][slot (u,h,e)], slot key = 16u + 8(e/4) + 4h + e%4
-          const half4 lo = read_vt(ldsv, 16 * u + 4 * h, cb, lane);
-          const half4 hi = read_vt(ldsv, 16 * u + 8 + 4 * h, cb, lane);
-          const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
-        }
-      }
+      block_math(kf, b, c, lane, h, st, ldsv, [more] {
+        if (more) wait_loads_except<4>(); else wait_loads_except<0>();
+      });
       b = b1;
       b1 = b2;
     }
@@ -485,49 +572,30 @@ struct CoreF16 {
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
     if (k0 >= k1) return;
     const int n = lane & 31, h = lane >> 5;
+    Stage sm;
+    sm.init(src.key_stride(), lane);
+    const uint32_t klane = (uint32_t)(n * sm.stride_bytes) + h * 64;
     BlockInfo b = src.get(k0, n);
     BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    src.resolve(b);
     half8 kf_next[4];
-    load_k(Kh, b, n, h, kf_next);
+    load_k(Kh, b, sm.stride_bytes, klane, n, h, kf_next);
     for (int k = k0; k < k1; ++k) {
+      src.resolve(b1);
       half8 kf[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) kf[s] = kf_next[s];
-      if (k + 1 < k1) load_k(Kh, b1, n, h, kf_next);
+      if (k + 1 < k1) load_k(Kh, b1, sm.stride_bytes, klane, n, h, kf_next);
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-      stage_v(Vh, b, lane, lds);
+      sm.stage_v(Vh, b, lane, lds);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
-      floatx16 sacc = {0};
-#pragma unroll
-      for (int s = 0; s < 4; ++s)
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
-      float p[16];
-      softmax_block(sacc, c, b, h, st, p);
-      wait_loads_except<0>();
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        half8 pb;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[8 * u + e];
-#pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          // A operand: V^T[channel cb*32+n][slot (u,h,e)], slot key = 16u + 8(e/4) + 4h + e%4
-          const half4 lo = read_vt(lds, 16 * u + 4 * h, cb, lane);
-          const half4 hi = read_vt(lds, 16 * u + 8 + 4 * h, cb, lane);
-          const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
-        }
-      }
+      block_math(kf, b, c, lane, h, st, lds, [] { wait_loads_except<0>(); });
       b = b1;
       b1 = b2;
     }
   }
 
-  // kLdsK selects the pipeline: K block staged in LDS (coalesced whole-row copies; best with many
-  // blocks per tile) or K fragment loaded straight into registers (no LDS round trip before the
-  // first product; best with two or three blocks per tile).
   template <bool kLdsK>
   static constexpr int lds_bytes() { return kLdsK ? 2 * kBlockBytes : kBlockBytes; }
 
@@ -796,10 +864,14 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
   const int32_t H = (int32_t)gridDim.x;   // head-major grid: the long work items of every head are dispatched first
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
   if (pl.total_bytes > ws_bytes) return;
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int n = lane & 31, h = lane >> 5;
   char* lds = lds_all + wave * kLds;
   char* base_ws = static_cast<char*>(ws);
+  // a negative scale is applied as a sign flip of Q (exact), so the kernels see c >= 0
+  const bool negate = scale < 0.f;
+  const float c = softmax_factor(scale);
   const int32_t* seg_tile = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_tile);
   const int2* seg_meta = reinterpret_cast<const int2*>(base_ws + pl.off_seg_meta);
   const int32_t* seg_count = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_count);
@@ -840,10 +912,10 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     const int64_t qrow = row_first + n;
     const bool exists = qrow < L;
     typename CoreOf<T>::type core;
-    core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h);
+    core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h, negate);
     TileState st;
     st.init();
-    core.template run<kLdsK>(K + hoff, V + hoff, src, 0, seg_count[w_cur], scale * kLog2e, lane, st, lds);
+    core.template run<kLdsK>(K + hoff, V + hoff, src, 0, seg_count[w_cur], c, lane, st, lds);
     if (meta.y > 1) {
       float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
                     (((int64_t)tile_pbase[t] + meta.x) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
@@ -935,7 +1007,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
                                                           int64_t s, int64_t n_groups, float scale) {
   constexpr int kLds = CoreOf<T>::type::template lds_bytes<kLdsK>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
-  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int n = lane & 31, h = lane >> 5;
   char* lds = lds_all + wave * kLds;
   // gridDim.x is a multiple of 8: XCD x handles the workgroups [x*chunk, (x+1)*chunk)
@@ -957,10 +1030,10 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   const bool exists = u < Lc;
   const int64_t qrow = s * (exists ? u : Lc - 1) + p;
   typename CoreOf<T>::type core;
-  core.load_q(Q + hoff + qrow * kHeadDim, h);
+  core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
   TileState st;
   st.init();
-  core.template run<kLdsK>(K + hoff, V + hoff, src, 0, nblk, scale * kLog2e, lane, st, lds);
+  core.template run<kLdsK>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st, lds);
   finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h);
 }
 

@@ -185,3 +185,29 @@ def test_explicit_and_implicit_paths_agree():
         O1, _ = _run_explicit(wl, Q, K, V, path)
         O2, _ = _run_implicit(wl, Q, K, V, path)
         assert max_err(O1, O2) <= 2 * TOL[wl.dtype]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+@pytest.mark.parametrize("scale", [-0.125, 0.0, 0.37])
+def test_scale_sign_zero_and_non_power_of_two(scale, dtype, path):
+    """The scale multiplies the dot product (Eq. 1): a negative one reverses the ranking of the
+    neighbours, zero gives uniform weights, and a value that is no power of two is not exact in
+    fp16 (the scale must not be folded into the stored inputs)."""
+    print("case scale", scale, dtype, path, flush=True)
+    for spec, implicit in [(MaskSpec(KIND_GLOBAL_LOCAL, 333, window=20, n_global=3), False),
+                           (MaskSpec(KIND_DILATED, 333, window=9, stride=2), True)]:
+        wl = Workload("t", H=2, L=spec.L, d=64, dtype=dtype, sigma=1.0, mask=spec, explicit=True, seed=5)
+        Q, K, V = small_inputs(wl)
+        dQ, dK, dV = to_device(Q, K, V)
+        O_ref, lse_ref = R.attention_masked(Q, K, V, spec, scale)
+        rp, ci = sga.build_mask(spec)
+        ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, int(rp[-1]))
+        O, lse = sga.attention_forward(dQ, dK, dV, rp, ci, scale, workspace=ws, path=path, want_lse=True)
+        assert max_err(O.cpu().numpy(), O_ref) <= TOL[dtype]
+        assert max_err(lse.cpu().numpy(), lse_ref) <= 1e-4
+        if implicit:
+            O, lse = sga.attention_forward_implicit(dQ, dK, dV, spec, scale, workspace=ws, path=path,
+                                                    want_lse=True)
+            assert max_err(O.cpu().numpy(), O_ref) <= TOL[dtype]
+            assert max_err(lse.cpu().numpy(), lse_ref) <= 1e-4
