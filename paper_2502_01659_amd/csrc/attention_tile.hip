@@ -53,15 +53,19 @@ __device__ __forceinline__ void copy16_to_lds(const void* src, char* dst) {
 }
 
 // s_waitcnt vmcnt(N): all but the N most recently issued vector memory operations (global
-// loads, LDS copies included) have completed; N <= 15 here.
+// loads, LDS copies included) have completed.  The 6-bit count sits in bits 3:0 and 15:14.
 template <int N>
 __device__ __forceinline__ void wait_loads_except() {
-  static_assert(N >= 0 && N <= 15, "vmcnt immediate");
-  __builtin_amdgcn_s_waitcnt(0x0F70 | N);
+  static_assert(N >= 0 && N <= 63, "vmcnt immediate");
+  __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
 // s_waitcnt lgkmcnt(0): every LDS read issued so far has returned its data.
 __device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
+// K/V pipelines of the tile kernels (template parameter kPipe).
+constexpr int kPipeRegK = 0;   // K fragment prefetched into registers, V block staged in LDS
+constexpr int kPipeLdsK = 1;   // K and V blocks staged in LDS, one block ahead
 
 struct BlockInfo {
   int raw;          // explicit masks: block record as loaded (row0, nvalid, full follow from it)
@@ -423,13 +427,14 @@ struct CoreF32 {
   // kLdsK selects the pipeline: K block staged in LDS (coalesced whole-row copies; best with many
   // blocks per tile) or K fragment loaded straight into registers (no LDS round trip before the
   // first product; best with two or three blocks per tile).
-  template <bool kLdsK>
-  static constexpr int lds_bytes() { return kLdsK ? 2 * kBlockBytes : kBlockBytes; }
+  template <int kPipe>
+  static constexpr int lds_bytes() { return kPipe == kPipeRegK ? kBlockBytes : 2 * kBlockBytes; }
 
-  template <bool kLdsK, typename Src>
+  template <int kPipe, typename Src>
   __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
-    if (kLdsK) run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
+    static_assert(kPipe == kPipeRegK || kPipe == kPipeLdsK, "fp32 pipelines");
+    if (kPipe == kPipeLdsK) run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
     else run_regk(Kh, Vh, src, k0, k1, c, lane, st, lds);
   }
 
@@ -596,13 +601,13 @@ struct CoreF16 {
     }
   }
 
-  template <bool kLdsK>
-  static constexpr int lds_bytes() { return kLdsK ? 2 * kBlockBytes : kBlockBytes; }
+  template <int kPipe>
+  static constexpr int lds_bytes() { return kPipe == kPipeRegK ? kBlockBytes : 2 * kBlockBytes; }
 
-  template <bool kLdsK, typename Src>
+  template <int kPipe, typename Src>
   __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
-    if (kLdsK) run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
+    if (kPipe == kPipeLdsK) run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
     else run_regk(Kh, Vh, src, k0, k1, c, lane, st, lds);
   }
 
@@ -739,9 +744,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   char* base_ws = static_cast<char*>(ws);
-  int32_t* seg_tile = reinterpret_cast<int32_t*>(base_ws + pl.off_seg_tile);
-  int2* seg_meta = reinterpret_cast<int2*>(base_ws + pl.off_seg_meta);
-  int32_t* seg_count = reinterpret_cast<int32_t*>(base_ws + pl.off_seg_count);
+  TileItem* items = reinterpret_cast<TileItem*>(base_ws + pl.off_items_rec);
   int32_t* tile_bad = reinterpret_cast<int32_t*>(base_ws + pl.off_tile_bad);
   int32_t* tile_pbase = reinterpret_cast<int32_t*>(base_ws + pl.off_tile_pbase);
   int32_t* pair_blk = reinterpret_cast<int32_t*>(base_ws + pl.off_pair_blk);
@@ -751,7 +754,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
        w += (int64_t)gridDim.x * waves) {
     const WorkId id = locate_work(row_ptr, L, S, pl.n_tiles, pl.n_work, w);
     if (id.seg >= id.nseg) {          // spare item of a tile whose edge range crosses a multiple of S
-      if (lane == 0) seg_tile[w] = -1;
+      if (lane == 0) items[w].tile = -1;
       continue;
     }
     const int64_t t = id.tile;
@@ -828,9 +831,14 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
       ++nblk;
     }
     if (lane == 0) {
-      seg_tile[w] = (int32_t)t;
-      seg_meta[w] = make_int2(id.seg, id.nseg);
-      seg_count[w] = overflow ? -1 : nblk;
+      TileItem it;
+      it.tile = (int32_t)t;
+      it.nblk = overflow ? -1 : nblk;
+      it.seg = id.seg;
+      it.nseg = id.nseg;
+      it.slot0 = slot0;
+      it.pad = 0;
+      items[w] = it;
       if (overflow && atomicOr(&tile_bad[t], 1) == 0) atomicAdd(&ctr[kCtrTilesBad], 1u);
       if (id.seg == 0 && id.nseg > 1) {
         // reserve the tile's partial slots; if the call needs more than exist, every
@@ -854,12 +862,12 @@ __device__ __forceinline__ bool tile_parts_fit(const WorkspacePlan& pl, const vo
 // a device counter until none is left (items are ordered long segments first, so the greedy
 // order balances the load and no workgroup has to be re-launched between items).  A segment
 // of a multi-segment tile leaves a partial state.
-template <typename T, bool kLdsK>
+template <typename T, int kPipe>
 __global__ __launch_bounds__(256) void tile_attend_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
     size_t ws_bytes) {
-  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kLdsK>();
+  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int32_t H = (int32_t)gridDim.x;   // head-major grid: the long work items of every head are dispatched first
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
@@ -872,9 +880,7 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
   // a negative scale is applied as a sign flip of Q (exact), so the kernels see c >= 0
   const bool negate = scale < 0.f;
   const float c = softmax_factor(scale);
-  const int32_t* seg_tile = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_tile);
-  const int2* seg_meta = reinterpret_cast<const int2*>(base_ws + pl.off_seg_meta);
-  const int32_t* seg_count = reinterpret_cast<const int32_t*>(base_ws + pl.off_seg_count);
+  const TileItem* items = reinterpret_cast<const TileItem*>(base_ws + pl.off_items_rec);
   const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
   const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
   const bool parts_fit = tile_parts_fit(pl, ws);
@@ -893,20 +899,23 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
       uint32_t claimed = 0;
       if (lane == 0) claimed = atomicAdd(work_next, 1u);
       w_cur = __builtin_amdgcn_readfirstlane(claimed);
+      if (w_cur >= pl.n_work) break;
     } else {
       w_cur = w_static;
       w_static += (int64_t)gridDim.y * 4;
+      if (w_cur >= pl.n_work) break;
     }
-    if (w_cur >= pl.n_work) break;
-    const int64_t t = seg_tile[w_cur];
-    if (t < 0 || tile_bad[t]) continue;                     // idle item / tile left to the gather path
-    const int2 meta = seg_meta[w_cur];
-    if (meta.y > 1 && !parts_fit) continue;
-    const int64_t row_first = t * kTile;
-    const int64_t row_last = row_first + kTile < L ? row_first + kTile : L;
-    const int64_t slot_t = row_ptr[row_first] / kPairEdges;
-    const int64_t cap = (row_ptr[row_last] / kPairEdges - slot_t) / meta.y;
-    const int64_t slot0 = slot_t + (int64_t)meta.x * cap;
+    // the whole record in one uniform 32-byte read
+    const int4 r0 = reinterpret_cast<const int4*>(items + w_cur)[0];
+    const int64_t slot_raw = reinterpret_cast<const int64_t*>(items + w_cur)[2];
+    const int32_t t = __builtin_amdgcn_readfirstlane(r0.x);
+    const int32_t nblk = __builtin_amdgcn_readfirstlane(r0.y);
+    const int32_t seg = __builtin_amdgcn_readfirstlane(r0.z);
+    const int32_t nseg = __builtin_amdgcn_readfirstlane(r0.w);
+    const int64_t slot0 = uniform64(slot_raw);
+    if (t < 0 || nblk < 0) continue;         // idle item / list overflow: tile left to the gather path
+    if (nseg > 1 && (!parts_fit || tile_bad[t])) continue;
+    const int64_t row_first = (int64_t)t * kTile;
     ExplicitBlocks src{reinterpret_cast<const int32_t*>(base_ws + pl.off_pair_blk) + slot0,
                        reinterpret_cast<const uint32_t*>(base_ws + pl.off_pair_mask) + slot0 * kTile, L};
     const int64_t qrow = row_first + n;
@@ -915,10 +924,10 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h, negate);
     TileState st;
     st.init();
-    core.template run<kLdsK>(K + hoff, V + hoff, src, 0, seg_count[w_cur], c, lane, st, lds);
-    if (meta.y > 1) {
+    core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, c, lane, st, lds);
+    if (nseg > 1) {
       float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
-                    (((int64_t)tile_pbase[t] + meta.x) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
+                    (((int64_t)tile_pbase[t] + seg) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
       store_partial(part, st, n, h);
     } else {
       finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.x * L : nullptr, qrow, qrow, exists, st, h);
@@ -999,13 +1008,13 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
 // share most of their K/V rows, so the linear workgroup id is remapped to give every XCD one
 // contiguous range of the sequence; inside it consecutive workgroups alternate between the
 // residue classes, so that the interleaved rows of all classes are touched together.
-template <typename T, bool kLdsK>
+template <typename T, int kPipe>
 __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_kernel(const T* __restrict__ Q,
                                                           const T* __restrict__ K,
                                                           const T* __restrict__ V, T* __restrict__ O,
                                                           float* __restrict__ lse, int64_t L, int64_t W,
                                                           int64_t s, int64_t n_groups, float scale) {
-  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kLdsK>();
+  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -1033,7 +1042,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
   TileState st;
   st.init();
-  core.template run<kLdsK>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st, lds);
+  core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st, lds);
   finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h);
 }
 
@@ -1060,8 +1069,8 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   }
   profile_mark_begin(a.stream);
   // fp32 tiles keep the K fragment in registers; fp16 tiles stage K in LDS (measured best)
-  constexpr bool kLdsK = DtypeOf<T>::code == SGA_F16;
-  hipLaunchKernelGGL((tile_attend_kernel<T, kLdsK>), dim3((unsigned)a.H, (unsigned)per_head), dim3(256),
+  constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
+  hipLaunchKernelGGL((tile_attend_kernel<T, kPipe>), dim3((unsigned)a.H, (unsigned)per_head), dim3(256),
                      0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
   profile_mark_end(a.stream);
   hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
@@ -1083,11 +1092,11 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const bool lds_k = a.dtype == SGA_F16 && 2 * (int64_t)a.window + kTile > 3 * kTile;
   profile_mark_begin(a.stream);
   if (lds_k) {
-    hipLaunchKernelGGL((tile_window_kernel<T, true>), grid, dim3(256), 0, a.stream,
+    hipLaunchKernelGGL((tile_window_kernel<T, kPipeLdsK>), grid, dim3(256), 0, a.stream,
                        static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
                        static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
   } else {
-    hipLaunchKernelGGL((tile_window_kernel<T, false>), grid, dim3(256), 0, a.stream,
+    hipLaunchKernelGGL((tile_window_kernel<T, kPipeRegK>), grid, dim3(256), 0, a.stream,
                        static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
                        static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
   }
@@ -1106,7 +1115,8 @@ sga_status launch_tile_explicit(const AttnArgs& a) {
 }
 
 sga_status launch_tile_implicit(const AttnArgs& a) {
-  if (a.H > 65535) return launch_gather_implicit(a);
+  // (the tile kernels keep per-lane row offsets in 32 bits, which bounds the stride)
+  if (a.H > 65535 || a.stride > (1 << 20)) return launch_gather_implicit(a);
   return a.dtype == SGA_F32 ? run_tile_implicit<float>(a) : run_tile_implicit<__half>(a);
 }
 

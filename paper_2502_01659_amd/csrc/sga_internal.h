@@ -57,6 +57,17 @@ enum WsCounter : int {
   kNumCounters = 64
 };
 
+// One work item of the tile path, written by the CSR -> tile graph pass and read (one record,
+// one load) by the attention kernel.
+struct alignas(32) TileItem {
+  int32_t tile;     // tile index, or -1 for an idle item
+  int32_t nblk;     // key blocks in the item's list, or -1 if the list overflowed its slots
+  int32_t seg;      // segment of the tile's key-block span ...
+  int32_t nseg;     // ... out of this many
+  int64_t slot0;    // first (tile, key block) pair slot of the list
+  int64_t pad;
+};
+
 struct WorkspacePlan {
   // gather split
   int64_t cap_items;
@@ -66,8 +77,8 @@ struct WorkspacePlan {
   int64_t n_work;         // tile work items (segments)
   int64_t cap_pairs;      // capacity of the (tile, key block) pair arrays
   int64_t cap_tparts;     // capacity of tile partial states
-  size_t off_seg_tile, off_seg_meta, off_seg_count, off_tile_bad, off_tile_pbase, off_multi_tiles,
-      off_pair_blk, off_pair_mask, off_tpartials, off_work_next;
+  size_t off_items_rec, off_tile_bad, off_tile_pbase, off_multi_tiles, off_pair_blk, off_pair_mask,
+      off_tpartials, off_work_next;
   size_t total_bytes;
 };
 
@@ -99,12 +110,8 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   p.cap_pairs = tiles ? e / kPairEdges + 1 : 0;
   p.cap_tparts = tiles ? e / seg_edges(dtype) + 1 : 0;
   if (p.cap_tparts > kMaxTilePartials) p.cap_tparts = kMaxTilePartials;
-  p.off_seg_tile = off;
-  off = (off + (size_t)p.n_work * 4 + 255) & ~size_t(255);
-  p.off_seg_meta = off;
-  off = (off + (size_t)p.n_work * 8 + 255) & ~size_t(255);
-  p.off_seg_count = off;
-  off = (off + (size_t)p.n_work * 4 + 255) & ~size_t(255);
+  p.off_items_rec = off;
+  off = (off + (size_t)p.n_work * sizeof(TileItem) + 255) & ~size_t(255);
   p.off_tile_bad = off;
   off = (off + (size_t)p.n_tiles * 4 + 255) & ~size_t(255);
   p.off_tile_pbase = off;
