@@ -28,6 +28,14 @@ Readings of the paper fixed here (the paper is silent or ambiguous):
     initial state), not NaN;
   - global tokens are positions 0..g-1 and are symmetric: they attend to and
     are attended by every token;
+  - the "global (non-local)" mask is the global mask (i < g or j < g) minus the
+    local window |i - j| <= w, as Section IV-B states for the kernel that runs
+    after a local pass on the same (O, l, m) state;
+  - the 2-D dilated predicate is printed with the segment id floor(i / (L / b)) but
+    the in-block index i % b; the two agree only when L = b^2.  Here a block is b
+    consecutive tokens (segment id floor(i / b)), "dilation factor r" is carried as
+    the stride s = r + 1, and rows whose in-block index is not a multiple of s have
+    no neighbour (in LongNet other segment/dilation pairs cover them);
   - the block mask is defined at block level: global blocks 0..G-1 (symmetric),
     a window of +-wb blocks, and R distinct random key blocks per non-global
     query block, drawn without replacement from blocks not already attended,
@@ -42,7 +50,8 @@ import math
 import numpy as np
 
 from sga_inputs.masks import (MaskSpec, KIND_SLIDING, KIND_DILATED,
-                              KIND_GLOBAL_LOCAL, KIND_BIGBIRD)
+                              KIND_GLOBAL_LOCAL, KIND_BIGBIRD, KIND_NONLOCAL,
+                              KIND_DILATED_2D)
 
 _M64 = (1 << 64) - 1
 _GOLD = 0x9E3779B97F4A7C15
@@ -98,6 +107,16 @@ def mask_rows(spec: MaskSpec, rows) -> np.ndarray:
     if spec.kind == KIND_GLOBAL_LOCAL:
         g = spec.n_global
         return (np.abs(i - j) <= spec.window) | (i < g) | (j < g)
+    if spec.kind == KIND_NONLOCAL:
+        # the global mask with the local mask taken out of it (Section IV-B, "Global
+        # (non-local)"), so that a local pass and this pass never visit an edge twice
+        g = spec.n_global
+        return ((i < g) | (j < g)) & ~(np.abs(i - j) <= spec.window)
+    if spec.kind == KIND_DILATED_2D:
+        # blocks of b x b tokens on the diagonal; inside a block every stride-th row and
+        # every stride-th column, counted from the block's first token, is kept
+        b, s = spec.block, spec.stride
+        return (i // b == j // b) & ((i % b) % s == 0) & ((j % b) % s == 0)
     if spec.kind == KIND_BIGBIRD:
         B = spec.block
         if L % B != 0:
@@ -281,6 +300,17 @@ def nnz_dilated(L, W, s):
 def nnz_global_local(L, w, g):
     """|i-j| <= w or i < g or j < g, valid for g <= w+1 and L >= 2w+1+g."""
     return L * (2 * w + 1) - w * (w + 1) + 2 * g * L - g * g - g * (2 * w + 1)
+
+
+def nnz_nonlocal(L, w, g):
+    """(i < g or j < g) and |i-j| > w: the global+local count minus the window count."""
+    return nnz_global_local(L, w, g) - nnz_sliding(L, w)
+
+
+def nnz_dilated_2d(L, b, s):
+    """Blocks of b tokens, every s-th row and column: sum over blocks of ceil(len/s)^2."""
+    full, rest = divmod(L, b)
+    return full * (-(-b // s)) ** 2 + (-(-rest // s)) ** 2
 
 
 def nnz_bigbird_g2_w1(L, B, R):

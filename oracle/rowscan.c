@@ -28,7 +28,8 @@
 #endif
 
 typedef struct {
-    int32_t kind;            /* 0 sliding, 1 dilated, 2 global+local, 3 block mask */
+    int32_t kind;            /* 0 sliding, 1 dilated, 2 global+local, 3 block mask,
+                                4 global minus local, 5 2-D dilated blocks */
     int32_t window;
     int32_t stride;
     int32_t n_global;
@@ -75,7 +76,7 @@ static void orc_block_members(const orc_mask *mk, int64_t b, uint8_t *member)
     }
 }
 
-/* A[i][j] for the three element-level masks. */
+/* A[i][j] for the element-level masks. */
 static inline int orc_pred_elem(const orc_mask *mk, int64_t i, int64_t j)
 {
     int64_t diff = i - j;
@@ -87,6 +88,11 @@ static inline int orc_pred_elem(const orc_mask *mk, int64_t i, int64_t j)
         return ad <= (int64_t)mk->window * mk->stride && (ad % mk->stride) == 0;
     case 2:
         return ad <= mk->window || i < mk->n_global || j < mk->n_global;
+    case 4:
+        return (i < mk->n_global || j < mk->n_global) && !(ad <= mk->window);
+    case 5:
+        return i / mk->block == j / mk->block && (i % mk->block) % mk->stride == 0 &&
+               (j % mk->block) % mk->stride == 0;
     default:
         return 0;
     }

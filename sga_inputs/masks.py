@@ -10,12 +10,16 @@ KIND_SLIDING = 0        # local window, Section II-C "Local/Windowed Attention"
 KIND_DILATED = 1        # 1-D dilated window, Section II-C
 KIND_GLOBAL_LOCAL = 2   # local window plus leading global tokens
 KIND_BIGBIRD = 3        # block mask: window + global + random key blocks
+KIND_NONLOCAL = 4       # global tokens minus the local window (Section IV-B "Global (non-local)")
+KIND_DILATED_2D = 5     # 2-D dilated blocks on the diagonal, Section II-C
 
 KIND_NAMES = {
     KIND_SLIDING: "sliding",
     KIND_DILATED: "dilated",
     KIND_GLOBAL_LOCAL: "global_local",
     KIND_BIGBIRD: "bigbird",
+    KIND_NONLOCAL: "nonlocal",
+    KIND_DILATED_2D: "dilated_2d",
 }
 
 
@@ -25,11 +29,12 @@ class MaskSpec:
 
     kind             one of the KIND_* codes
     L                context length (rows = queries, columns = keys)
-    window           half-width in steps: sliding/global_local use |i-j| <= window,
+    window           half-width in steps: sliding/global_local/nonlocal use |i-j| <= window,
                      dilated uses |i-j| <= window*stride
-    stride           distance between attended keys (1 = contiguous, 2 = every other)
-    n_global         global tokens occupy positions 0..n_global-1 (global_local)
-    block            block edge in tokens (bigbird)
+    stride           distance between attended keys (1 = contiguous, 2 = every other);
+                     dilated_2d keeps every stride-th row and column of a block
+    n_global         global tokens occupy positions 0..n_global-1 (global_local, nonlocal)
+    block            block edge in tokens (bigbird, dilated_2d)
     window_blocks    neighbouring key blocks on each side (bigbird)
     n_global_blocks  global blocks occupy block indices 0..n_global_blocks-1 (bigbird)
     n_random_blocks  random key blocks per non-global query block (bigbird)

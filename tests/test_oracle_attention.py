@@ -29,7 +29,7 @@ import numpy as np
 import pytest
 import scipy.special
 
-from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
+from sga_inputs import (KIND_NONLOCAL, MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
                         KIND_BIGBIRD, numpy_qkv)
 from oracle import reference as R
 
@@ -217,6 +217,22 @@ def test_p8_merge_of_any_partition_equals_unsplit():
     s1 = R.algorithm1_row(Q[0][0], K[0], V[0], a, 0.4)
     s2 = R.algorithm1_row(Q[0][0], K[0], V[0], b, 0.4, state=s1)
     assert np.abs(s2[0] - O_def[0]).max() < 1e-13
+
+
+def test_sequential_composition_local_then_nonlocal():
+    """Section V-F runs a local kernel and then the global (non-local) kernel on one shared
+    (O, l, m) state; because the two masks partition the global+local mask, the result is
+    the single-mask result."""
+    L, d, w, g = 90, 8, 6, 4
+    Q, K, V = _qkv(L, d, seed=21)
+    loc = R.dense_mask(MaskSpec(KIND_SLIDING, L, window=w))
+    nl = R.dense_mask(MaskSpec(KIND_NONLOCAL, L, window=w, n_global=g))
+    O_def, lse = R.attention_masked(Q, K, V, MaskSpec(KIND_GLOBAL_LOCAL, L, window=w, n_global=g), 0.3)
+    for i in range(L):
+        st = R.algorithm1_row(Q[0][i], K[0], V[0], np.nonzero(loc[i])[0], 0.3)
+        st = R.algorithm1_row(Q[0][i], K[0], V[0], np.nonzero(nl[i])[0], 0.3, state=st)
+        assert np.abs(st[0] - O_def[0][i]).max() < 1e-13
+        assert abs(st[2] + math.log(st[1]) - lse[0][i]) < 1e-12
 
 
 def test_p13_neighbour_order_does_not_matter():

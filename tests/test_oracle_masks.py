@@ -16,7 +16,7 @@ import os
 import numpy as np
 import pytest
 
-from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
+from sga_inputs import (MaskSpec, KIND_NONLOCAL, KIND_DILATED_2D, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
                         KIND_BIGBIRD, WORKLOADS)
 from oracle import reference as R
 from oracle import rowscan as C
@@ -193,3 +193,55 @@ def test_rowscan_degrees_on_large_masks():
     deg = C.degrees(m4, rows)
     # block 2's window {1,2,3} overlaps global block 1: 2 global + {2,3} + 3 random = 7
     assert list(deg) == [1 << 20, 1 << 20, 7 * 64, 7 * 64, 8 * 64, 8 * 64, 7 * 64]
+
+
+@pytest.mark.parametrize("L,w,g", [(100, 8, 3), (300, 20, 16), (64, 5, 6), (41, 3, 0), (50, 60, 4)])
+def test_nonlocal_is_global_minus_local(L, w, g):
+    """Section IV-B, "Global (non-local)": the global mask with the local mask subtracted, so
+    that local and non-local passes partition the global+local mask."""
+    nl = R.dense_mask(MaskSpec(KIND_NONLOCAL, L, window=w, n_global=g))
+    loc = R.dense_mask(MaskSpec(KIND_SLIDING, L, window=w))
+    gl = R.dense_mask(MaskSpec(KIND_GLOBAL_LOCAL, L, window=w, n_global=g))
+    assert not (nl & loc).any()
+    assert ((nl | loc) == gl).all()
+    # written out pair by pair
+    for i in (0, g - 1 if g else 0, g, L // 2, L - 1):
+        for j in range(L):
+            assert nl[i, j] == ((i < g or j < g) and abs(i - j) > w)
+    if g <= w + 1 and L >= 2 * w + 1 + g:
+        assert int(nl.sum()) == R.nnz_nonlocal(L, w, g)
+    assert (nl == nl.T).all()
+
+
+@pytest.mark.parametrize("b,r", [(4, 0), (6, 1), (8, 2), (9, 3)])
+def test_dilated_2d_printed_predicate_where_it_is_unambiguous(b, r):
+    """The printed 2-D predicate (Section II-C) takes the segment id from i / (L / b) and the
+    in-block index from i % b; with L = b*b both describe blocks of b tokens, and the printed
+    text evaluated literally must equal the oracle's reading."""
+    L = b * b
+    m = R.dense_mask(MaskSpec(KIND_DILATED_2D, L, block=b, stride=r + 1))
+    for i in range(L):
+        for j in range(L):
+            printed = 0
+            if i // (L // b) == j // (L // b):
+                i_b, j_b = i % b, j % b
+                if i_b % (r + 1) == 0 and j_b % (r + 1) == 0:
+                    printed = 1
+            assert int(m[i, j]) == printed
+
+
+@pytest.mark.parametrize("L,b,s", [(64, 16, 2), (100, 16, 3), (333, 40, 3), (50, 64, 4), (96, 32, 1)])
+def test_dilated_2d_count_and_structure(L, b, s):
+    m = R.dense_mask(MaskSpec(KIND_DILATED_2D, L, block=b, stride=s))
+    assert int(m.sum()) == R.nnz_dilated_2d(L, b, s)
+    assert (m == m.T).all()
+    deg = m.sum(axis=1)
+    for i in range(L):
+        blk_len = min(b, L - (i // b) * b)
+        expect = -(-blk_len // s) if (i % b) % s == 0 else 0
+        assert deg[i] == expect
+        if expect:
+            cols = np.nonzero(m[i])[0]
+            assert cols[0] == (i // b) * b and (np.diff(cols) == s).all()
+    if s == 1:      # no dilation: dense blocks on the diagonal
+        assert int(m.sum()) == sum(min(b, L - k) ** 2 for k in range(0, L, b))

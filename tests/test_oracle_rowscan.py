@@ -13,7 +13,7 @@ import pytest
 import scipy.special
 
 from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
-                        KIND_BIGBIRD, numpy_qkv, small_variants)
+                        KIND_BIGBIRD, KIND_NONLOCAL, KIND_DILATED_2D, numpy_qkv, small_variants)
 from oracle import reference as R
 from oracle import rowscan as C
 
@@ -27,6 +27,8 @@ SPECS = [
              n_random_blocks=3, seed=77),
     MaskSpec(KIND_BIGBIRD, 240, block=8, window_blocks=2, n_global_blocks=1,
              n_random_blocks=2, seed=3),
+    MaskSpec(KIND_NONLOCAL, 333, window=10, n_global=5),
+    MaskSpec(KIND_DILATED_2D, 333, block=40, stride=3),
 ]
 
 
@@ -49,7 +51,9 @@ def test_rows_equal_dense_oracle(spec, dtype):
     O_d, lse_d = R.attention_masked(Q, K, V, spec, 0.25)
     assert edges == int(R.dense_mask(spec).sum())
     assert np.abs(O_c - O_d[0]).max() < 1e-12
-    assert np.abs(lse_c - lse_d[0]).max() < 1e-12
+    empty = np.isneginf(lse_d[0])                 # rows without neighbours: lse = -inf on both sides
+    assert (np.isneginf(lse_c) == empty).all()
+    assert np.abs(lse_c[~empty] - lse_d[0][~empty]).max() < 1e-12
 
 
 def test_small_workload_variants_agree():
