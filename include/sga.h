@@ -60,12 +60,20 @@ typedef enum {
                                 (the paper's dilation factor r is stride-1)               */
   SGA_MASK_GLOBAL_LOCAL = 2, /* local window plus global tokens 0..n_global-1, symmetric:
                                 |i-j| <= window  or  i < n_global  or  j < n_global       */
-  SGA_MASK_BIGBIRD = 3       /* block mask (block x block tiles, L % block == 0):
+  SGA_MASK_BIGBIRD = 3,      /* block mask (block x block tiles, L % block == 0):
                                 query blocks 0..n_global_blocks-1 attend every key block;
                                 every other query block b attends the global key blocks,
                                 key blocks b-window_blocks..b+window_blocks, and
                                 n_random_blocks further distinct key blocks chosen by the
                                 counter-based generator described at sga_build_mask      */
+  SGA_MASK_NONLOCAL = 4,     /* "global (non-local)" of Section IV-B: the global mask with the
+                                local window taken out, (i < n_global or j < n_global) and
+                                |i-j| > window; together with SGA_MASK_SLIDING it partitions
+                                SGA_MASK_GLOBAL_LOCAL (see sga_attention_accumulate)       */
+  SGA_MASK_DILATED_2D = 5    /* 2-D dilated blocks (Section II-C): i and j in the same block of
+                                `block` consecutive tokens, and both in-block indices
+                                multiples of stride (the paper's r is stride-1); rows whose
+                                in-block index is no multiple of stride have no neighbour  */
 } sga_mask_kind;
 
 /* Attention-specific parameters P_a of Algorithm 1.  Plain data, host memory. */
@@ -74,9 +82,9 @@ typedef struct {
   int32_t kind;              /* sga_mask_kind                                             */
   int64_t L;                 /* context length, 1 <= L < 2^31                             */
   int32_t window;            /* half-width in steps, >= 0                                 */
-  int32_t stride;            /* >= 1; only DILATED reads it (others behave as stride 1)   */
-  int32_t n_global;          /* GLOBAL_LOCAL: 0 <= n_global <= L                          */
-  int32_t block;             /* BIGBIRD: block edge in tokens, 1..1024                    */
+  int32_t stride;            /* >= 1; DILATED and DILATED_2D read it (others: stride 1)   */
+  int32_t n_global;          /* GLOBAL_LOCAL, NONLOCAL: 0 <= n_global <= L                */
+  int32_t block;             /* BIGBIRD: block edge in tokens, 1..1024; DILATED_2D: >= 1  */
   int32_t window_blocks;     /* BIGBIRD                                                   */
   int32_t n_global_blocks;   /* BIGBIRD                                                   */
   int32_t n_random_blocks;   /* BIGBIRD: 0..16; needs L/block >= 2*window_blocks+1
@@ -158,7 +166,10 @@ sga_status sga_attention_forward(const void* Q, const void* K, const void* V,
  * Algorithm 1 with an implicit mask (Section IV-B "Local", "1D Dilation"): the
  * neighbours of row i are computed from desc inside the kernel (index
  * arithmetic, no stored graph), so memory stays O(L) and L is bounded only by
- * Q, K, V, O themselves.  Supports SGA_MASK_SLIDING and SGA_MASK_DILATED;
+ * Q, K, V, O themselves.  Supports SGA_MASK_SLIDING and SGA_MASK_DILATED (tile and
+ * gather kernels), SGA_MASK_DILATED_2D ("2D Dilation") and SGA_MASK_NONLOCAL ("Global
+ * (non-local)"; n_global <= 64 and a workspace of sga_workspace_bytes(..., nnz = -1) are
+ * required: the global rows are split over the key range) through the per-row kernels;
  * other kinds return SGA_ERR_UNSUPPORTED (build their CSR instead).
  * Arguments as in sga_attention_forward; desc: host; desc->L must equal L.
  * Element offsets are 64-bit (L*d may pass 2^31).
@@ -168,6 +179,33 @@ sga_status sga_attention_forward_implicit(const void* Q, const void* K, const vo
                                           int32_t H, int32_t d, float scale, void* stream,
                                           int32_t dtype, float* lse, void* workspace,
                                           size_t workspace_bytes, int32_t path);
+
+/*
+ * Sequential composition on one shared state (Section V-F: a local, a global and a CSR kernel run
+ * one after another on the same O, l, m of Algorithm 1).  These two entry points visit the
+ * edges of their mask like the forward calls, but start from the state already held in O and
+ * lse instead of Algorithm 1's initial state, and leave the continued state there:
+ *   O    device, [H][L][d], read and written: the normalised output over the edges visited so far
+ *   lse  device, float [H][L], required, read and written: m_i + ln l_i over those edges (the
+ *        two statistics vectors of Algorithm 1 enter the recurrence only through this sum);
+ *        -inf with O_i = 0 is the initial state, which sga_attention_forward* also leaves for
+ *        rows without neighbours.
+ * A sequence  forward(mask_1), accumulate(mask_2), ...  over pairwise disjoint masks equals one
+ * forward over their union (an edge present in two of the masks would be counted twice: this
+ * is why the global kernel of Section IV-B subtracts the local window, SGA_MASK_NONLOCAL).
+ * With fp16 storage O is rounded to fp16 after every call.  All other arguments, errors and
+ * the supported implicit kinds are those of the forward calls.
+ */
+sga_status sga_attention_accumulate(const void* Q, const void* K, const void* V,
+                                    const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                    int64_t L, int32_t H, int32_t d, float scale, void* stream,
+                                    int32_t dtype, float* lse, void* workspace,
+                                    size_t workspace_bytes, int32_t path);
+sga_status sga_attention_accumulate_implicit(const void* Q, const void* K, const void* V,
+                                             const sga_mask_desc* desc, void* O, int64_t L,
+                                             int32_t H, int32_t d, float scale, void* stream,
+                                             int32_t dtype, float* lse, void* workspace,
+                                             size_t workspace_bytes, int32_t path);
 
 /*
  * Benchmark hook: timing of the dominant attention kernel of each forward call.

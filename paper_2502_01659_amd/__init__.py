@@ -7,6 +7,8 @@ PyTorch only provides device memory and streams.
 from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, load, lib_path,
                       mask_nnz, build_mask, workspace_bytes, alloc_workspace,
                       attention_forward, attention_forward_implicit,
+                      attention_accumulate, attention_accumulate_implicit,
+                      sga_attention_accumulate, sga_attention_accumulate_implicit,
                       sga_mask_nnz, sga_build_mask, sga_workspace_bytes,
                       sga_attention_forward, sga_attention_forward_implicit,
                       sga_status_string, sga_profile_enable, sga_profile_collect)
@@ -15,6 +17,8 @@ __all__ = [
     "SgaError", "PATH_AUTO", "PATH_GATHER", "PATH_TILE", "load", "lib_path",
     "mask_nnz", "build_mask", "workspace_bytes", "alloc_workspace",
     "attention_forward", "attention_forward_implicit",
+    "attention_accumulate", "attention_accumulate_implicit",
+    "sga_attention_accumulate", "sga_attention_accumulate_implicit",
     "sga_mask_nnz", "sga_build_mask", "sga_workspace_bytes",
     "sga_attention_forward", "sga_attention_forward_implicit", "sga_status_string",
     "sga_profile_enable", "sga_profile_collect",

@@ -63,6 +63,10 @@ def load():
     lib.sga_attention_forward_implicit.restype = ctypes.c_int
     lib.sga_attention_forward_implicit.argtypes = [vp, vp, vp, P(_MaskDesc), vp, i64, i32, i32,
                                                    f32, vp, i32, vp, vp, ctypes.c_size_t, i32]
+    lib.sga_attention_accumulate.restype = ctypes.c_int
+    lib.sga_attention_accumulate.argtypes = lib.sga_attention_forward.argtypes
+    lib.sga_attention_accumulate_implicit.restype = ctypes.c_int
+    lib.sga_attention_accumulate_implicit.argtypes = lib.sga_attention_forward_implicit.argtypes
     lib.sga_profile_enable.restype = ctypes.c_int
     lib.sga_profile_enable.argtypes = [i32]
     lib.sga_profile_collect.restype = ctypes.c_int
@@ -114,6 +118,20 @@ def sga_attention_forward_implicit(Q, K, V, spec, O, L, H, d, scale, stream, dty
     return load().sga_attention_forward_implicit(Q, K, V, ctypes.byref(dsc), O, L, H, d, scale,
                                                  stream, dtype_code, lse, workspace,
                                                  workspace_bytes_, path)
+
+
+def sga_attention_accumulate(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype_code,
+                             lse, workspace, workspace_bytes_, path):
+    return load().sga_attention_accumulate(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream,
+                                           dtype_code, lse, workspace, workspace_bytes_, path)
+
+
+def sga_attention_accumulate_implicit(Q, K, V, spec, O, L, H, d, scale, stream, dtype_code, lse,
+                                      workspace, workspace_bytes_, path):
+    dsc = _desc(spec)
+    return load().sga_attention_accumulate_implicit(Q, K, V, ctypes.byref(dsc), O, L, H, d, scale,
+                                                    stream, dtype_code, lse, workspace,
+                                                    workspace_bytes_, path)
 
 
 def sga_profile_enable(on):
@@ -187,6 +205,12 @@ def _check_qkv(Q, K, V):
         raise ValueError("Q, K, V must share a dtype")
 
 
+def _col_ptr(row_ptr, col_idx):
+    # a mask without edges has an empty col_idx, whose address is null; the entry points want a
+    # device address even though they will not read through it
+    return col_idx.data_ptr() if col_idx.numel() > 0 else row_ptr.data_ptr()
+
+
 def attention_forward(Q, K, V, row_ptr, col_idx, scale, O=None, lse=None, workspace=None,
                       path=PATH_AUTO, want_lse=False):
     """Masked attention over an explicit CSR mask.  Returns O (and lse if requested)."""
@@ -205,7 +229,7 @@ def attention_forward(Q, K, V, row_ptr, col_idx, scale, O=None, lse=None, worksp
     ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(Q.device):
         st = sga_attention_forward(Q.data_ptr(), K.data_ptr(), V.data_ptr(), row_ptr.data_ptr(),
-                                   col_idx.data_ptr(), O.data_ptr(), L, H, d, float(scale),
+                                   _col_ptr(row_ptr, col_idx), O.data_ptr(), L, H, d, float(scale),
                                    _stream(), _dtype_code(Q),
                                    lse.data_ptr() if lse is not None else None, ws_ptr, ws_n, path)
     if st != 0:
@@ -234,3 +258,52 @@ def attention_forward_implicit(Q, K, V, spec: MaskSpec, scale, O=None, lse=None,
     if st != 0:
         raise SgaError(st, "sga_attention_forward_implicit")
     return (O, lse) if (want_lse or lse is not None) else O
+
+
+def _check_state(Q, O, lse):
+    import torch
+    H, L, d = Q.shape
+    if O.shape != Q.shape or O.dtype != Q.dtype or not O.is_contiguous() or O.device != Q.device:
+        raise ValueError("O must match Q in shape, dtype and device")
+    if (lse.shape != (H, L) or lse.dtype != torch.float32 or not lse.is_contiguous()
+            or lse.device != Q.device):
+        raise ValueError("lse must be contiguous float32 [H, L] on Q's device")
+
+
+def attention_accumulate(Q, K, V, row_ptr, col_idx, scale, O, lse, workspace=None, path=PATH_AUTO):
+    """Continue the (O, lse) state over the edges of an explicit CSR mask, in place."""
+    import torch
+    _check_qkv(Q, K, V)
+    _check_state(Q, O, lse)
+    H, L, d = Q.shape
+    if row_ptr.dtype != torch.int64 or row_ptr.numel() != L + 1 or not row_ptr.is_contiguous():
+        raise ValueError("row_ptr must be contiguous int64 [L+1]")
+    if col_idx.dtype != torch.int32 or not col_idx.is_contiguous():
+        raise ValueError("col_idx must be contiguous int32")
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(Q.device):
+        st = sga_attention_accumulate(Q.data_ptr(), K.data_ptr(), V.data_ptr(), row_ptr.data_ptr(),
+                                      _col_ptr(row_ptr, col_idx), O.data_ptr(), L, H, d, float(scale),
+                                      _stream(), _dtype_code(Q), lse.data_ptr(), ws_ptr, ws_n, path)
+    if st != 0:
+        raise SgaError(st, "sga_attention_accumulate")
+    return O, lse
+
+
+def attention_accumulate_implicit(Q, K, V, spec: MaskSpec, scale, O, lse, workspace=None,
+                                  path=PATH_AUTO):
+    """Continue the (O, lse) state over the edges of an implicit mask, in place."""
+    import torch
+    _check_qkv(Q, K, V)
+    _check_state(Q, O, lse)
+    H, L, d = Q.shape
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    with torch.cuda.device(Q.device):
+        st = sga_attention_accumulate_implicit(Q.data_ptr(), K.data_ptr(), V.data_ptr(), spec,
+                                               O.data_ptr(), L, H, d, float(scale), _stream(),
+                                               _dtype_code(Q), lse.data_ptr(), ws_ptr, ws_n, path)
+    if st != 0:
+        raise SgaError(st, "sga_attention_accumulate_implicit")
+    return O, lse

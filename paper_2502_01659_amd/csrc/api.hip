@@ -122,19 +122,25 @@ sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, i
   return SGA_OK;
 }
 
-sga_status sga_attention_forward(const void* Q, const void* K, const void* V, const int64_t* row_ptr,
-                                 const int32_t* col_idx, void* O, int64_t L, int32_t H, int32_t d,
-                                 float scale, void* stream, int32_t dtype, float* lse,
-                                 void* workspace, size_t workspace_bytes, int32_t path) {
+}  // extern "C"
+
+namespace {
+
+sga_status run_explicit_call(const void* Q, const void* K, const void* V, const int64_t* row_ptr,
+                             const int32_t* col_idx, void* O, int64_t L, int32_t H, int32_t d,
+                             float scale, void* stream, int32_t dtype, float* lse, void* workspace,
+                             size_t workspace_bytes, int32_t path, bool accumulate) {
   const sga_status st = check_common(Q, K, V, O, L, H, d, dtype, path, workspace, workspace_bytes);
   if (st != SGA_OK) return st;
   if (!row_ptr || !col_idx) return SGA_ERR_INVALID_ARG;
+  if (accumulate && !lse) return SGA_ERR_INVALID_ARG;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
   a.L = L; a.H = H; a.scale = scale; a.dtype = dtype;
   a.stream = static_cast<hipStream_t>(stream);
   a.row_ptr = row_ptr; a.col_idx = col_idx;
   a.ws = workspace; a.ws_bytes = workspace_bytes;
+  a.accumulate = accumulate;
   if (path == SGA_PATH_TILE && (!workspace || workspace_bytes < 256)) return SGA_ERR_WORKSPACE;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   if (workspace && workspace_bytes >= 256) clear_workspace(a, path != SGA_PATH_GATHER);
@@ -142,28 +148,80 @@ sga_status sga_attention_forward(const void* Q, const void* K, const void* V, co
   return launch_tile_explicit(a);
 }
 
-sga_status sga_attention_forward_implicit(const void* Q, const void* K, const void* V,
-                                          const sga_mask_desc* desc, void* O, int64_t L, int32_t H,
-                                          int32_t d, float scale, void* stream, int32_t dtype,
-                                          float* lse, void* workspace, size_t workspace_bytes,
-                                          int32_t path) {
+sga_status run_implicit_call(const void* Q, const void* K, const void* V, const sga_mask_desc* desc,
+                             void* O, int64_t L, int32_t H, int32_t d, float scale, void* stream,
+                             int32_t dtype, float* lse, void* workspace, size_t workspace_bytes,
+                             int32_t path, bool accumulate) {
   sga_status st = check_common(Q, K, V, O, L, H, d, dtype, path, workspace, workspace_bytes);
   if (st != SGA_OK) return st;
   st = mask_validate(desc);
   if (st != SGA_OK) return st;
   if (desc->L != L) return SGA_ERR_INVALID_ARG;
-  if (desc->kind != SGA_MASK_SLIDING && desc->kind != SGA_MASK_DILATED) return SGA_ERR_UNSUPPORTED;
+  if (accumulate && !lse) return SGA_ERR_INVALID_ARG;
+  const int32_t kind = desc->kind;
+  if (kind != SGA_MASK_SLIDING && kind != SGA_MASK_DILATED && kind != SGA_MASK_NONLOCAL &&
+      kind != SGA_MASK_DILATED_2D)
+    return SGA_ERR_UNSUPPORTED;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
   a.L = L; a.H = H; a.scale = scale; a.dtype = dtype;
   a.stream = static_cast<hipStream_t>(stream);
-  a.stride = desc->kind == SGA_MASK_DILATED ? desc->stride : 1;
+  a.mask_kind = kind;
+  a.stride = (kind == SGA_MASK_DILATED || kind == SGA_MASK_DILATED_2D) ? desc->stride : 1;
   const int64_t wmax = (L - 1) / a.stride;
   a.window = (int32_t)(desc->window < wmax ? desc->window : wmax);
+  a.n_global = desc->n_global;
+  a.block = desc->block;
   a.ws = workspace; a.ws_bytes = workspace_bytes;
+  a.accumulate = accumulate;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
-  if (path == SGA_PATH_GATHER) return launch_gather_implicit(a);
+  if (kind == SGA_MASK_NONLOCAL) {
+    const int64_t g = desc->n_global < L ? desc->n_global : L;
+    if (g > kMaxImplicitGlobal) return SGA_ERR_UNSUPPORTED;
+    if (g > 0 && (!workspace || workspace_bytes < plan_workspace(L, H, -1, dtype).total_bytes))
+      return SGA_ERR_WORKSPACE;
+    return launch_gather_implicit(a);
+  }
+  if (kind == SGA_MASK_DILATED_2D || path == SGA_PATH_GATHER) return launch_gather_implicit(a);
   return launch_tile_implicit(a);
+}
+
+}  // namespace
+
+extern "C" {
+
+sga_status sga_attention_forward(const void* Q, const void* K, const void* V, const int64_t* row_ptr,
+                                 const int32_t* col_idx, void* O, int64_t L, int32_t H, int32_t d,
+                                 float scale, void* stream, int32_t dtype, float* lse,
+                                 void* workspace, size_t workspace_bytes, int32_t path) {
+  return run_explicit_call(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype, lse, workspace,
+                           workspace_bytes, path, false);
+}
+
+sga_status sga_attention_forward_implicit(const void* Q, const void* K, const void* V,
+                                          const sga_mask_desc* desc, void* O, int64_t L, int32_t H,
+                                          int32_t d, float scale, void* stream, int32_t dtype,
+                                          float* lse, void* workspace, size_t workspace_bytes,
+                                          int32_t path) {
+  return run_implicit_call(Q, K, V, desc, O, L, H, d, scale, stream, dtype, lse, workspace,
+                           workspace_bytes, path, false);
+}
+
+sga_status sga_attention_accumulate(const void* Q, const void* K, const void* V, const int64_t* row_ptr,
+                                    const int32_t* col_idx, void* O, int64_t L, int32_t H, int32_t d,
+                                    float scale, void* stream, int32_t dtype, float* lse,
+                                    void* workspace, size_t workspace_bytes, int32_t path) {
+  return run_explicit_call(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype, lse, workspace,
+                           workspace_bytes, path, true);
+}
+
+sga_status sga_attention_accumulate_implicit(const void* Q, const void* K, const void* V,
+                                             const sga_mask_desc* desc, void* O, int64_t L, int32_t H,
+                                             int32_t d, float scale, void* stream, int32_t dtype,
+                                             float* lse, void* workspace, size_t workspace_bytes,
+                                             int32_t path) {
+  return run_implicit_call(Q, K, V, desc, O, L, H, d, scale, stream, dtype, lse, workspace,
+                           workspace_bytes, path, true);
 }
 
 }  // extern "C"

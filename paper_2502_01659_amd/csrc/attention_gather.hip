@@ -76,6 +76,8 @@ struct Row<__half> {
   }
 };
 
+__device__ __forceinline__ float load_scalar(const float* p) { return *p; }
+__device__ __forceinline__ float load_scalar(const __half* p) { return __half2float(*p); }
 __device__ __forceinline__ void store_scalar(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_scalar(__half* p, float v) { *p = __float2half_rn(v); }
 
@@ -176,19 +178,36 @@ __device__ __forceinline__ void load_query(const T* Qrow, float scale, int lane,
   for (int k = 0; k < Row<T>::VEC; ++k) q[k] *= c;
 }
 
+// Normalise and store a row; with `accumulate` the row continues the (O, lse) state already
+// in the output buffers (sequential composition on one state, Section V-F).
 template <typename T>
 __device__ __forceinline__ void finish_row(T* Orow, float* lse_i, int lane,
-                                           State<Row<T>::VEC>& st) {
+                                           State<Row<T>::VEC>& st, bool accumulate) {
   constexpr int LPK = Row<T>::LPK, VEC = Row<T>::VEC;
   merge_groups<LPK, VEC>(st);
   const bool empty = !(st.l > 0.f);
-  const float inv = empty ? 0.f : 1.0f / st.l;
+  float inv = empty ? 0.f : 1.0f / st.l;
+  float lse_row = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(st.l)) * kLn2;
+  float w_prev = 0.f;
+  if (accumulate) {     // every lane reads the earlier lse before lane 0 replaces it
+    const CarryWeights cw = carry_weights(*lse_i, lse_row);
+    inv *= cw.w_now;
+    w_prev = cw.w_prev;
+    lse_row = cw.lse;
+  }
   float o[VEC];
 #pragma unroll
   for (int c = 0; c < VEC; ++c) o[c] = st.acc[c] * inv;
-  if (lane < LPK) Row<T>::store(Orow + lane * VEC, o);
-  if (lse_i && lane == 0)
-    *lse_i = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(st.l)) * kLn2;
+  if (lane < LPK) {
+    if (accumulate) {
+      float old[VEC];
+      Row<T>::load(Orow + lane * VEC, old);
+#pragma unroll
+      for (int c = 0; c < VEC; ++c) o[c] = __builtin_fmaf(w_prev, old[c], o[c]);
+    }
+    Row<T>::store(Orow + lane * VEC, o);
+  }
+  if (lse_i && lane == 0) *lse_i = lse_row;
 }
 
 __host__ __device__ inline void split_shape(int64_t deg, int32_t& nchunks, int32_t& len) {
@@ -271,7 +290,8 @@ template <typename T>
 __global__ __launch_bounds__(256) void gather_csr_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-    int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split, int skip_tiled) {
+    int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split, int skip_tiled,
+    int accumulate) {
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
@@ -293,14 +313,14 @@ __global__ __launch_bounds__(256) void gather_csr_kernel(
     st.init();
     CsrNeighbours nbr{col_idx + r0};
     attend_range<T>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
-    finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st);
+    finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
   }
 }
 
 template <typename T>
 __global__ __launch_bounds__(256) void gather_window_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
-    float* __restrict__ lse, int64_t L, int64_t W, int64_t s, float scale) {
+    float* __restrict__ lse, int64_t L, int64_t W, int64_t s, float scale, int accumulate) {
   const int lane = threadIdx.x & (kWave - 1);
   const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
   if (i >= L) return;
@@ -313,7 +333,120 @@ __global__ __launch_bounds__(256) void gather_window_kernel(
   st.init();
   WindowNeighbours nbr{i - kl * s, s};
   attend_range<T>(K + hoff, V + hoff, q, nbr, 0, kl + kr + 1, lane, st);
-  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st);
+  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
+}
+
+// Implicit Get_Neighbors for the masks whose rows are one arithmetic run of keys that is not a
+// centred window: the 2-D dilated blocks of Section II-C, and the rows below the global rows
+// of the "global (non-local)" mask of Section IV-B.  One wavefront per row; a row without
+// neighbours is written as the initial state (or left as it is when accumulating).
+struct RowRun {
+  int64_t first, step, count;
+};
+
+__device__ __forceinline__ RowRun row_run(int32_t kind, int64_t i, int64_t L, int64_t W, int64_t s,
+                                          int64_t g, int64_t B) {
+  if (kind == SGA_MASK_DILATED_2D) {
+    const int64_t blk = i / B, r = i - blk * B;
+    if (r % s != 0) return {0, 1, 0};
+    const int64_t len = min(B, L - blk * B);
+    return {blk * B, s, (len + s - 1) / s};
+  }
+  // non-local, row i >= g: global columns 0..g-1 that lie left of the window
+  const int64_t n = min(g, i - W);
+  return {0, 1, n > 0 ? n : 0};
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void gather_runs_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, int64_t L, int32_t kind, int64_t W, int64_t s, int64_t g, int64_t B,
+    int64_t row0, float scale, int accumulate) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int64_t i = row0 + (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
+  if (i >= L) return;
+  const int64_t h = blockIdx.y;
+  const int64_t hoff = h * L * kHeadDim;
+  const RowRun run = row_run(kind, i, L, W, s, g, B);
+  float q[Row<T>::VEC];
+  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
+  State<Row<T>::VEC> st;
+  st.init();
+  if (run.count > 0) {
+    WindowNeighbours nbr{run.first, run.step};
+    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, run.count, lane, st);
+  }
+  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
+}
+
+// Global rows i < g of the non-local mask attend every key outside their window: about L
+// neighbours each.  grid = (chunks, g, H): a wavefront reduces the keys of one chunk of the
+// key range (the window cut out) to a partial (m, l, acc) state ...
+template <typename T>
+__global__ __launch_bounds__(64) void nonlocal_chunk_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, int64_t L, int64_t W,
+    int64_t chunk_len, float scale, float* __restrict__ partials) {
+  const int lane = threadIdx.x;
+  const int64_t c = blockIdx.x, i = blockIdx.y, h = blockIdx.z;
+  const int64_t H = gridDim.z, n_chunks = gridDim.x;
+  const int64_t hoff = h * L * kHeadDim;
+  const int64_t lo = c * chunk_len, hi = min(L, lo + chunk_len);      // keys [lo, hi)
+  float q[Row<T>::VEC];
+  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
+  State<Row<T>::VEC> st;
+  st.init();
+  const int64_t a1 = min(hi, i - W);             // keys [lo, a1) lie left of the window
+  if (a1 > lo) {
+    WindowNeighbours nbr{lo, 1};
+    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, a1 - lo, lane, st);
+  }
+  const int64_t b0 = max(lo, i + W + 1);         // keys [b0, hi) lie right of it
+  if (hi > b0) {
+    WindowNeighbours nbr{b0, 1};
+    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, hi - b0, lane, st);
+  }
+  merge_groups<Row<T>::LPK, Row<T>::VEC>(st);
+  float* p = partials + ((i * n_chunks + c) * H + h) * kPartialStride;
+  if (lane < Row<T>::LPK) {
+#pragma unroll
+    for (int k = 0; k < Row<T>::VEC; ++k) p[lane * Row<T>::VEC + k] = st.acc[k];
+  }
+  if (lane == 0) {
+    p[kHeadDim] = st.m;
+    p[kHeadDim + 1] = st.l;
+  }
+}
+
+// ... and one wavefront per (global row, head) combines the row's partials in chunk order
+// (deterministic).  lane = channel.
+template <typename T>
+__global__ __launch_bounds__(64) void nonlocal_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
+                                                            int64_t L, int32_t n_chunks,
+                                                            const float* __restrict__ partials,
+                                                            int accumulate) {
+  const int lane = threadIdx.x;
+  const int64_t i = blockIdx.x, h = blockIdx.y, H = gridDim.y;
+  const float* p0 = partials + ((i * n_chunks) * H + h) * kPartialStride;
+  const int64_t step = H * kPartialStride;
+  float M = kMinusHuge;
+  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, p0[c * step + kHeadDim]);
+  float l = 0.f, acc = 0.f;
+  for (int c = 0; c < n_chunks; ++c) {
+    const float w = __builtin_amdgcn_exp2f(p0[c * step + kHeadDim] - M);
+    l = __builtin_fmaf(p0[c * step + kHeadDim + 1], w, l);
+    acc = __builtin_fmaf(p0[c * step + lane], w, acc);
+  }
+  const bool empty = !(l > 0.f);
+  float o = empty ? 0.f : acc / l;
+  float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+  T* dst = O + h * L * kHeadDim + i * kHeadDim + lane;
+  if (accumulate) {
+    const CarryWeights cw = carry_weights(lse[h * L + i], lse_row);
+    o = cw.w_prev * load_scalar(dst) + cw.w_now * o;
+    lse_row = cw.lse;
+  }
+  store_scalar(dst, o);
+  if (lse && lane == 0) lse[h * L + i] = lse_row;
 }
 
 // One wavefront per (chunk item, head): partial state of a slice of a long row.
@@ -365,7 +498,8 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                            const int64_t* __restrict__ row_ptr,
-                                                           int64_t L, void* ws, size_t ws_bytes) {
+                                                           int64_t L, void* ws, size_t ws_bytes,
+                                                           int accumulate) {
   const int32_t H = (int32_t)gridDim.y;
   constexpr int32_t dtype = DtypeOf<T>::code;
   if (!split_active(row_ptr, L, H, dtype, ws, ws_bytes)) return;
@@ -390,10 +524,16 @@ __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, fl
       acc = __builtin_fmaf(p0[c * step + lane], w, acc);
     }
     const bool empty = !(l > 0.f);
-    const float o = empty ? 0.f : acc / l;
-    store_scalar(O + h * L * kHeadDim + i * kHeadDim + lane, o);
-    if (lse && lane == 0)
-      lse[h * L + i] = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+    float o = empty ? 0.f : acc / l;
+    float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+    T* dst = O + h * L * kHeadDim + i * kHeadDim + lane;
+    if (accumulate) {
+      const CarryWeights cw = carry_weights(lse[h * L + i], lse_row);
+      o = cw.w_prev * load_scalar(dst) + cw.w_now * o;
+      lse_row = cw.lse;
+    }
+    store_scalar(dst, o);
+    if (lse && lane == 0) lse[h * L + i] = lse_row;
   }
 }
 
@@ -415,13 +555,13 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   if (!skip_tiled) profile_mark_begin(a.stream);
   hipLaunchKernelGGL(gather_csr_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
                      a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
-                     skip_tiled ? 1 : 0);
+                     skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
   if (!skip_tiled) profile_mark_end(a.stream);
   if (split) {
     hipLaunchKernelGGL(gather_chunk_kernel<T>, dim3(1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
     hipLaunchKernelGGL(gather_merge_kernel<T>, dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
-                       a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);
+                       a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   }
   return hip_status(hipGetLastError());
 }
@@ -443,13 +583,42 @@ sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, bool skip
 
 template <typename T>
 static sga_status run_implicit(const AttnArgs& a) {
-  const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
-  profile_mark_begin(a.stream);
-  hipLaunchKernelGGL(gather_window_kernel<T>, grid, dim3(256), 0, a.stream,
-                     static_cast<const T*>(a.Q), static_cast<const T*>(a.K),
-                     static_cast<const T*>(a.V), static_cast<T*>(a.O), a.lse, a.L,
-                     (int64_t)a.window, (int64_t)a.stride, a.scale);
-  profile_mark_end(a.stream);
+  const T* Q = static_cast<const T*>(a.Q);
+  const T* K = static_cast<const T*>(a.K);
+  const T* V = static_cast<const T*>(a.V);
+  T* O = static_cast<T*>(a.O);
+  const int acc = a.accumulate ? 1 : 0;
+  if (a.mask_kind == SGA_MASK_SLIDING || a.mask_kind == SGA_MASK_DILATED) {
+    const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
+    profile_mark_begin(a.stream);
+    hipLaunchKernelGGL(gather_window_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
+                       (int64_t)a.window, (int64_t)a.stride, a.scale, acc);
+    profile_mark_end(a.stream);
+    return hip_status(hipGetLastError());
+  }
+  // rows that are one arithmetic run: all rows of the 2-D dilated mask, rows >= g of the
+  // non-local mask
+  const int64_t g = a.mask_kind == SGA_MASK_NONLOCAL ? (a.n_global < a.L ? a.n_global : a.L) : 0;
+  if (a.L > g) {
+    const dim3 grid((unsigned)((a.L - g + 3) / 4), (unsigned)a.H);
+    profile_mark_begin(a.stream);
+    hipLaunchKernelGGL(gather_runs_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
+                       a.mask_kind, (int64_t)a.window, (int64_t)a.stride, g, (int64_t)a.block, g, a.scale,
+                       acc);
+    profile_mark_end(a.stream);
+  }
+  if (g > 0) {
+    // the g global rows: split over the key range, partial states in the workspace
+    int32_t n_chunks, len;
+    split_shape(a.L, n_chunks, len);
+    float* partials = reinterpret_cast<float*>(static_cast<char*>(a.ws) +
+                                               plan_workspace(a.L, a.H, -1, a.dtype).off_partials);
+    hipLaunchKernelGGL(nonlocal_chunk_kernel<T>, dim3((unsigned)n_chunks, (unsigned)g, (unsigned)a.H),
+                       dim3(64), 0, a.stream, Q, K, V, a.L, (int64_t)a.window, (int64_t)len, a.scale,
+                       partials);
+    hipLaunchKernelGGL(nonlocal_merge_kernel<T>, dim3((unsigned)g, (unsigned)a.H), dim3(64), 0, a.stream,
+                       O, a.lse, a.L, n_chunks, partials, acc);
+  }
   return hip_status(hipGetLastError());
 }
 

@@ -438,14 +438,24 @@ struct CoreF32 {
     else run_regk(Kh, Vh, src, k0, k1, c, lane, st, lds);
   }
 
-  __device__ static void store_row(float* Orow, const TileState& st, float inv, int h) {
+  // Orow = acc * inv, or w_prev * Orow + acc * inv when the call continues an earlier state.
+  __device__ static void store_row(float* Orow, const TileState& st, float inv, float w_prev,
+                                   bool accumulate, int h) {
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const float4 v = make_float4(st.o[cb][4 * g] * inv, st.o[cb][4 * g + 1] * inv,
-                                     st.o[cb][4 * g + 2] * inv, st.o[cb][4 * g + 3] * inv);
-        *reinterpret_cast<float4*>(Orow + cb * 32 + 8 * g + 4 * h) = v;
+        float4* dst = reinterpret_cast<float4*>(Orow + cb * 32 + 8 * g + 4 * h);
+        float4 v = make_float4(st.o[cb][4 * g] * inv, st.o[cb][4 * g + 1] * inv,
+                               st.o[cb][4 * g + 2] * inv, st.o[cb][4 * g + 3] * inv);
+        if (accumulate) {
+          const float4 old = *dst;
+          v.x = __builtin_fmaf(w_prev, old.x, v.x);
+          v.y = __builtin_fmaf(w_prev, old.y, v.y);
+          v.z = __builtin_fmaf(w_prev, old.z, v.z);
+          v.w = __builtin_fmaf(w_prev, old.w, v.w);
+        }
+        *dst = v;
       }
   }
 };
@@ -611,17 +621,27 @@ struct CoreF16 {
     else run_regk(Kh, Vh, src, k0, k1, c, lane, st, lds);
   }
 
-  __device__ static void store_row(__half* Orow, const TileState& st, float inv, int h) {
+  __device__ static void store_row(__half* Orow, const TileState& st, float inv, float w_prev,
+                                   bool accumulate, int h) {
 #pragma unroll
     for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const __half2 a = __floats2half2_rn(st.o[cb][4 * g] * inv, st.o[cb][4 * g + 1] * inv);
-        const __half2 bq = __floats2half2_rn(st.o[cb][4 * g + 2] * inv, st.o[cb][4 * g + 3] * inv);
+        uint2* dst = reinterpret_cast<uint2*>(Orow + cb * 32 + 8 * g + 4 * h);
+        float v[4] = {st.o[cb][4 * g] * inv, st.o[cb][4 * g + 1] * inv, st.o[cb][4 * g + 2] * inv,
+                      st.o[cb][4 * g + 3] * inv};
+        if (accumulate) {
+          const uint2 old = *dst;
+          const __half2 o01 = __builtin_bit_cast(__half2, old.x), o23 = __builtin_bit_cast(__half2, old.y);
+          v[0] = __builtin_fmaf(w_prev, __low2float(o01), v[0]);
+          v[1] = __builtin_fmaf(w_prev, __high2float(o01), v[1]);
+          v[2] = __builtin_fmaf(w_prev, __low2float(o23), v[2]);
+          v[3] = __builtin_fmaf(w_prev, __high2float(o23), v[3]);
+        }
         uint2 w;
-        w.x = __builtin_bit_cast(uint32_t, a);
-        w.y = __builtin_bit_cast(uint32_t, bq);
-        *reinterpret_cast<uint2*>(Orow + cb * 32 + 8 * g + 4 * h) = w;
+        w.x = __builtin_bit_cast(uint32_t, __floats2half2_rn(v[0], v[1]));
+        w.y = __builtin_bit_cast(uint32_t, __floats2half2_rn(v[2], v[3]));
+        *dst = w;
       }
   }
 };
@@ -633,13 +653,21 @@ template <> struct CoreOf<__half> { using type = CoreF16; };
 // Normalise and store the tile's rows (row(n) = tensor row of query n, < 0 if it does not exist).
 template <typename T>
 __device__ __forceinline__ void finish_tile(T* Oh, float* lse_h, int64_t row, int64_t lse_idx,
-                                            bool exists, TileState& st, int h) {
+                                            bool exists, TileState& st, int h, bool accumulate) {
   const float l = st.l + __shfl_xor(st.l, 32, kWave);
   if (!exists) return;
   const bool empty = !(l > 0.f);
-  const float inv = empty ? 0.f : 1.0f / l;
-  CoreOf<T>::type::store_row(Oh + row * kHeadDim, st, inv, h);
-  if (lse_h && h == 0) lse_h[lse_idx] = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(l)) * kLn2;
+  float inv = empty ? 0.f : 1.0f / l;
+  float lse_row = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(l)) * kLn2;
+  float w_prev = 0.f;
+  if (accumulate) {    // both half-waves read the earlier lse before half-wave 0 replaces it
+    const CarryWeights cw = carry_weights(lse_h[lse_idx], lse_row);
+    inv *= cw.w_now;
+    w_prev = cw.w_prev;
+    lse_row = cw.lse;
+  }
+  CoreOf<T>::type::store_row(Oh + row * kHeadDim, st, inv, w_prev, accumulate, h);
+  if (lse_h && h == 0) lse_h[lse_idx] = lse_row;
 }
 
 // Un-normalised partial of a chunk: o[32][64], m[32], l[32].
@@ -866,7 +894,7 @@ template <typename T, int kPipe>
 __global__ __launch_bounds__(256) void tile_attend_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
-    size_t ws_bytes) {
+    size_t ws_bytes, int accumulate) {
   constexpr int kLds = CoreOf<T>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int32_t H = (int32_t)gridDim.x;   // head-major grid: the long work items of every head are dispatched first
@@ -930,11 +958,14 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
                     (((int64_t)tile_pbase[t] + seg) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
       store_partial(part, st, n, h);
     } else {
-      finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.x * L : nullptr, qrow, qrow, exists, st, h);
+      finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.x * L : nullptr, qrow, qrow, exists, st, h,
+                     accumulate != 0);
     }
   }
 }
 
+__device__ __forceinline__ float load_out(const float* p) { return *p; }
+__device__ __forceinline__ float load_out(const __half* p) { return __half2float(*p); }
 __device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(__half* p, float v) { *p = __float2half_rn(v); }
 
@@ -945,7 +976,7 @@ __device__ __forceinline__ void store_out(__half* p, float v) { *p = __float2hal
 template <typename T>
 __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                          const int64_t* __restrict__ row_ptr, int64_t L,
-                                                         void* ws, size_t ws_bytes) {
+                                                         void* ws, size_t ws_bytes, int accumulate) {
   __shared__ float sm_acc[4][kHeadDim];
   __shared__ float sm_m[4], sm_l[4];
   const int32_t H = (int32_t)gridDim.y;
@@ -995,9 +1026,16 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
           at = __builtin_fmaf(sm_acc[v][lane], wgt, at);
         }
         const bool empty = !(lt > 0.f);
-        store_out(O + hd * L * kHeadDim + row * kHeadDim + lane, empty ? 0.f : at / lt);
-        if (lse && lane == 0)
-          lse[hd * L + row] = empty ? -INFINITY : (Mt + __builtin_amdgcn_logf(lt)) * kLn2;
+        T* dst = O + hd * L * kHeadDim + row * kHeadDim + lane;
+        float o = empty ? 0.f : at / lt;
+        float lse_row = empty ? -INFINITY : (Mt + __builtin_amdgcn_logf(lt)) * kLn2;
+        if (accumulate) {
+          const CarryWeights cw = carry_weights(lse[hd * L + row], lse_row);
+          o = cw.w_prev * load_out(dst) + cw.w_now * o;
+          lse_row = cw.lse;
+        }
+        store_out(dst, o);
+        if (lse && lane == 0) lse[hd * L + row] = lse_row;
       }
     }
   }
@@ -1013,7 +1051,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
                                                           const T* __restrict__ K,
                                                           const T* __restrict__ V, T* __restrict__ O,
                                                           float* __restrict__ lse, int64_t L, int64_t W,
-                                                          int64_t s, int64_t n_groups, float scale) {
+                                                          int64_t s, int64_t n_groups, float scale,
+                                                          int accumulate) {
   constexpr int kLds = CoreOf<T>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int lane = threadIdx.x & (kWave - 1);
@@ -1043,7 +1082,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   TileState st;
   st.init();
   core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st, lds);
-  finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h);
+  finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h, accumulate != 0);
 }
 
 template <typename T>
@@ -1071,10 +1110,11 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   // fp32 tiles keep the K fragment in registers; fp16 tiles stage K in LDS (measured best)
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
   hipLaunchKernelGGL((tile_attend_kernel<T, kPipe>), dim3((unsigned)a.H, (unsigned)per_head), dim3(256),
-                     0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes);
+                     0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes,
+                     a.accumulate ? 1 : 0);
   profile_mark_end(a.stream);
   hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
-                     O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes);
+                     O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   return hip_status(hipGetLastError());
 }
 
@@ -1094,11 +1134,13 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   if (lds_k) {
     hipLaunchKernelGGL((tile_window_kernel<T, kPipeLdsK>), grid, dim3(256), 0, a.stream,
                        static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
-                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
+                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale,
+                       a.accumulate ? 1 : 0);
   } else {
     hipLaunchKernelGGL((tile_window_kernel<T, kPipeRegK>), grid, dim3(256), 0, a.stream,
                        static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
-                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale);
+                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale,
+                       a.accumulate ? 1 : 0);
   }
   profile_mark_end(a.stream);
   return hip_status(hipGetLastError());

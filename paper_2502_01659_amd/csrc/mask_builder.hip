@@ -1,5 +1,6 @@
 // Mask -> graph: CSR row offsets and sorted column indices of the mask families of
-// Section II-C (explicit form of Get_Neighbors, Section IV-B "CSR").
+// Section II-C and of the "global (non-local)" mask of Section IV-B (explicit form of
+// Get_Neighbors, Section IV-B "CSR").
 //
 // Every row of every family is a short ordered list of arithmetic column runs
 // ("segments": start, length, step), so
@@ -79,6 +80,17 @@ __host__ __device__ inline int64_t row_offset(const MaskParams& p, int64_t i) {
       return window_prefix(i, p.L, p.W, p.s);
     case SGA_MASK_GLOBAL_LOCAL:
       return global_local_prefix(i, p.L, p.W, p.g, 0);
+    case SGA_MASK_NONLOCAL:   // the global+local mask without its window
+      return global_local_prefix(i, p.L, p.W, p.g, 0) - window_prefix(i, p.L, p.W, 1);
+    case SGA_MASK_DILATED_2D: {
+      // blocks before row i's block are whole: ceil(B/s)^2 edges each; inside the block the
+      // selected rows (every s-th) before row i have one edge per selected column
+      const int64_t blk = i / p.B, r = i - blk * p.B;
+      const int64_t per_full = (p.B + p.s - 1) / p.s;
+      const int64_t len = imin(p.B, p.L - blk * p.B);
+      const int64_t n_sel = (len + p.s - 1) / p.s;
+      return blk * per_full * per_full + ((r + p.s - 1) / p.s) * n_sel;
+    }
     default: {  // block mask: all rows of a query block have the same degree
       const int64_t b = i / p.B;
       const int64_t before = global_local_prefix(b, p.nb, p.wb, p.G, p.R);
@@ -92,7 +104,7 @@ MaskParams make_params(const sga_mask_desc& d) {
   MaskParams p{};
   p.kind = d.kind;
   p.L = d.L;
-  p.s = (d.kind == SGA_MASK_DILATED) ? d.stride : 1;
+  p.s = (d.kind == SGA_MASK_DILATED || d.kind == SGA_MASK_DILATED_2D) ? d.stride : 1;
   p.W = imin(d.window, (d.L - 1) / p.s);
   p.g = imin(d.n_global, d.L);
   p.B = d.block > 0 ? d.block : 1;
@@ -152,6 +164,20 @@ __global__ __launch_bounds__(256) void fill_kernel(MaskParams p, const int64_t* 
       } else {
         if (p.g > 0) seg[n++] = {0, (int32_t)p.g, 1};
         seg[n++] = {(int32_t)lo, (int32_t)(hi - lo + 1), 1};
+      }
+    } else if (p.kind == SGA_MASK_NONLOCAL) {
+      if (i < p.g) {
+        if (i - p.W - 1 >= 0) seg[n++] = {0, (int32_t)(i - p.W), 1};
+        if (i + p.W + 1 <= p.L - 1) seg[n++] = {(int32_t)(i + p.W + 1), (int32_t)(p.L - 1 - i - p.W), 1};
+      } else {
+        const int64_t hi = imin(p.g - 1, i - p.W - 1);
+        if (hi >= 0) seg[n++] = {0, (int32_t)(hi + 1), 1};
+      }
+    } else if (p.kind == SGA_MASK_DILATED_2D) {
+      const int64_t blk = i / p.B, r = i - blk * p.B;
+      if (r % p.s == 0) {
+        const int64_t len = imin(p.B, p.L - blk * p.B);
+        seg[n++] = {(int32_t)(blk * p.B), (int32_t)((len + p.s - 1) / p.s), (int32_t)p.s};
       }
     } else {
       const int64_t b = group;
@@ -232,7 +258,10 @@ sga_status mask_validate(const sga_mask_desc* d) {
     case SGA_MASK_DILATED:
       return d->stride >= 1 ? SGA_OK : SGA_ERR_INVALID_ARG;
     case SGA_MASK_GLOBAL_LOCAL:
+    case SGA_MASK_NONLOCAL:
       return d->n_global >= 0 ? SGA_OK : SGA_ERR_INVALID_ARG;
+    case SGA_MASK_DILATED_2D:
+      return d->block >= 1 && d->stride >= 1 ? SGA_OK : SGA_ERR_INVALID_ARG;
     case SGA_MASK_BIGBIRD: {
       if (d->block < 1 || d->block > 1024 || d->L % d->block != 0) return SGA_ERR_INVALID_ARG;
       if (d->window_blocks < 0 || d->n_global_blocks < 0) return SGA_ERR_INVALID_ARG;

@@ -16,6 +16,7 @@ constexpr int kWave = 64;             // CDNA wavefront width
 constexpr int kSplitThreshold = 8192; // rows with more neighbours are split
 constexpr int kSplitChunk = 2048;     // target edges per chunk
 constexpr int kMaxSplit = 64;         // at most this many chunks per row
+constexpr int kMaxImplicitGlobal = 64;  // global rows the implicit non-local kernels can split
 
 // ---- tile path parameters -----------------------------------------------------
 constexpr int kTile = 32;                 // query rows per tile = keys per block
@@ -35,9 +36,8 @@ __host__ __device__ inline int64_t seg_edges(int32_t dtype) { return dtype == SG
 // items               cap_items x int2 {row, chunk}                    (gather split)
 // long_rows           cap_items x int4 {row, base, nchunks, chunk_len}
 // partials            cap_items x H x kPartialStride floats {acc[d], m, l}
-// seg_tile/meta/count n_work entries: tile id (-1: idle item), {segment, segments of the tile},
-//                     key blocks found
-//                     (-1: the segment overflowed its slots)
+//                     (implicit non-local mask: kMaxImplicitGlobal rows x kMaxSplit chunks)
+// items_rec           n_work x TileItem: the work items of the tile path
 // tile_bad            n_tiles x int32: != 0 -> tile is left to the gather path
 // tile_pbase          n_tiles x int32: first partial slot of a multi-segment tile
 // multi_tiles         cap_tparts x int32: ids of the multi-segment tiles (merge list, any order)
@@ -96,6 +96,8 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   if (n_long > L) n_long = L;
   int64_t cap = e / kSplitChunk + n_long;
   if (cap > (int64_t)kMaxSplit * n_long) cap = (int64_t)kMaxSplit * n_long;
+  // implicit masks: only the dense rows of the global (non-local) mask are split
+  if (nnz < 0) cap = (int64_t)kMaxImplicitGlobal * kMaxSplit;
   p.cap_items = cap;
   p.off_items = off;
   off = (off + (size_t)cap * 8 + 255) & ~size_t(255);
@@ -184,6 +186,11 @@ struct AttnArgs {
   // implicit (window family): neighbours j = i + stride*k, |k| <= window
   int32_t window;
   int32_t stride;
+  int32_t mask_kind;   // implicit: sga_mask_kind
+  int32_t n_global;    // implicit non-local mask
+  int32_t block;       // implicit 2-D dilated mask
+  // continue from the (O, lse) state already in the output buffers instead of overwriting it
+  bool accumulate;
   // workspace
   void* ws;
   size_t ws_bytes;
@@ -211,6 +218,25 @@ sga_status launch_build_mask(const sga_mask_desc& d, int64_t* row_ptr, int32_t* 
 // call with a pair of events on the call's stream.
 void profile_mark_begin(hipStream_t stream);
 void profile_mark_end(hipStream_t stream);
+
+// Sequential composition on one shared state (Section V-F runs a local, a global and a CSR
+// kernel one after another on the same O, l, m of Algorithm 1).  The state handed from call to
+// call is the normalised O_i and lse_i = m_i + ln l_i of the edges visited so far (the two
+// statistics only ever enter the recurrence through this sum).  Given the earlier state and the
+// (O, lse) of the edges this call visited, the continued state is
+//   lse' = ln(e^lse_prev + e^lse_now),  O' = w_prev O_prev + w_now O_now,  w_x = e^(lse_x - lse').
+struct CarryWeights {
+  float w_prev, w_now, lse;
+};
+__device__ __forceinline__ CarryWeights carry_weights(float lse_prev, float lse_now) {
+  const float M = fmaxf(lse_prev, lse_now);
+  if (!(M > -INFINITY)) return {0.f, 0.f, -INFINITY};     // no edge visited so far
+  constexpr float kLog2eC = 1.4426950408889634f, kLn2C = 0.6931471805599453f;
+  const float a = __builtin_amdgcn_exp2f((lse_prev - M) * kLog2eC);
+  const float b = __builtin_amdgcn_exp2f((lse_now - M) * kLog2eC);
+  const float inv = 1.0f / (a + b);
+  return {a * inv, b * inv, M + __builtin_amdgcn_logf(a + b) * kLn2C};
+}
 
 inline sga_status hip_status(hipError_t e) { return e == hipSuccess ? SGA_OK : SGA_ERR_HIP; }
 

@@ -12,6 +12,7 @@ import pytest
 
 import paper_2502_01659_amd as sga
 from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD,
+                        KIND_NONLOCAL, KIND_DILATED_2D,
                         numpy_qkv, small_variants, Workload)
 from oracle import reference as R
 from gpu_util import TOL, to_device, small_inputs, oracle_full, max_err
@@ -211,3 +212,87 @@ def test_scale_sign_zero_and_non_power_of_two(scale, dtype, path):
                                                     want_lse=True)
             assert max_err(O.cpu().numpy(), O_ref) <= TOL[dtype]
             assert max_err(lse.cpu().numpy(), lse_ref) <= 1e-4
+
+
+def _close(O, lse, O_ref, lse_ref, dtype, factor=1.0):
+    assert max_err(O, O_ref) <= factor * TOL[dtype]
+    empty = np.isneginf(lse_ref)
+    assert (np.isneginf(lse) == empty).all()
+    if (~empty).any():
+        assert max_err(lse[~empty], lse_ref[~empty]) <= 1e-4
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("spec", [
+    MaskSpec(KIND_NONLOCAL, 700, window=20, n_global=5),
+    MaskSpec(KIND_NONLOCAL, 9000, window=128, n_global=16),       # global rows pass the split threshold
+    MaskSpec(KIND_NONLOCAL, 100, window=200, n_global=3),          # window covers everything: no edge at all
+    MaskSpec(KIND_NONLOCAL, 300, window=2, n_global=64),
+    MaskSpec(KIND_DILATED_2D, 640, block=64, stride=2),
+    MaskSpec(KIND_DILATED_2D, 1000, block=96, stride=3),
+    MaskSpec(KIND_DILATED_2D, 333, block=40, stride=1),
+], ids=lambda s: f"{s.name}-L{s.L}")
+def test_nonlocal_and_dilated_2d_masks(spec, dtype):
+    """Explicit CSR (every path) and the implicit generators of the global (non-local) and
+    2-D dilated masks against the dense oracle; rows without neighbours are the initial state."""
+    print("case", spec, dtype, flush=True)
+    wl = Workload("t", H=2, L=spec.L, d=64, dtype=dtype, sigma=0.9, mask=spec, explicit=True, seed=31)
+    Q, K, V = small_inputs(wl)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    for path in PATHS:
+        O, lse = _run_explicit(wl, Q, K, V, path)
+        _close(O, lse, O_ref, lse_ref, dtype)
+    O, lse = _run_implicit(wl, Q, K, V, sga.PATH_AUTO)
+    _close(O, lse, O_ref, lse_ref, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
+def test_sequential_composition_equals_single_mask(dtype, path):
+    """Section V-F: local kernel, then the global (non-local) kernel, on one shared state,
+    against one call on the combined mask -- with explicit CSR masks, with implicit masks,
+    and mixed; and a three-part BigBird-like composition local -> non-local -> CSR(random)."""
+    L, w, g = 2500, 24, 7
+    wl = Workload("t", H=3, L=L, d=64, dtype=dtype, sigma=1.0,
+                  mask=MaskSpec(KIND_GLOBAL_LOCAL, L, window=w, n_global=g), explicit=True, seed=41)
+    Q, K, V = small_inputs(wl)
+    dQ, dK, dV = to_device(Q, K, V)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    loc = MaskSpec(KIND_SLIDING, L, window=w)
+    nl = MaskSpec(KIND_NONLOCAL, L, window=w, n_global=g)
+    ws_i = sga.alloc_workspace(L, wl.H, 64, dtype, -1)
+    # implicit local -> implicit non-local
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=ws_i, path=path,
+                                            want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O, lse, workspace=ws_i, path=path)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    # explicit local -> explicit non-local
+    rp1, ci1 = sga.build_mask(loc)
+    rp2, ci2 = sga.build_mask(nl)
+    ws1 = sga.alloc_workspace(L, wl.H, 64, dtype, int(rp1[-1]))
+    ws2 = sga.alloc_workspace(L, wl.H, 64, dtype, int(rp2[-1]))
+    O, lse = sga.attention_forward(dQ, dK, dV, rp1, ci1, wl.scale, workspace=ws1, path=path,
+                                   want_lse=True)
+    sga.attention_accumulate(dQ, dK, dV, rp2, ci2, wl.scale, O, lse, workspace=ws2, path=path)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    # non-local first (rows >= g with no global column in reach start empty), then local
+    O, lse = sga.attention_forward(dQ, dK, dV, rp2, ci2, wl.scale, workspace=ws2, path=path,
+                                   want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, loc, wl.scale, O, lse, workspace=ws_i, path=path)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    # three parts: local, non-local, then a random CSR with the first two removed
+    rng = np.random.default_rng(5)
+    extra = rng.random((L, L)) < 0.002
+    covered = R.dense_mask(wl.mask)
+    extra &= ~covered
+    rp3, ci3 = R.csr_from_dense(extra)
+    import torch
+    rp3 = torch.from_numpy(rp3).cuda()
+    ci3 = torch.from_numpy(ci3).cuda()
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=ws_i, path=path,
+                                            want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O, lse, workspace=ws_i, path=path)
+    ws3 = sga.alloc_workspace(L, wl.H, 64, dtype, int(rp3[-1]))
+    sga.attention_accumulate(dQ, dK, dV, rp3, ci3, wl.scale, O, lse, workspace=ws3, path=path)
+    O3_ref, lse3_ref = R.attention_dense(Q[0], K[0], V[0], covered | extra, wl.scale)
+    _close(O[0].cpu().numpy(), lse[0].cpu().numpy(), O3_ref, lse3_ref, dtype, factor=3.0)

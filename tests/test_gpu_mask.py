@@ -5,6 +5,7 @@ import pytest
 
 import paper_2502_01659_amd as sga
 from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD,
+                        KIND_NONLOCAL, KIND_DILATED_2D,
                         WORKLOADS, small_variants)
 from oracle import reference as R
 from oracle import rowscan as C
@@ -39,6 +40,18 @@ SPECS = [
              n_random_blocks=3, seed=3),
     MaskSpec(KIND_BIGBIRD, 5 * 12, block=5, window_blocks=3, n_global_blocks=2,
              n_random_blocks=0, seed=4),
+    MaskSpec(KIND_NONLOCAL, 900, window=128, n_global=16),
+    MaskSpec(KIND_NONLOCAL, 300, window=4, n_global=0),
+    MaskSpec(KIND_NONLOCAL, 300, window=4, n_global=40),
+    MaskSpec(KIND_NONLOCAL, 40, window=3, n_global=99),
+    MaskSpec(KIND_NONLOCAL, 40, window=60, n_global=2),
+    MaskSpec(KIND_NONLOCAL, 777, window=0, n_global=3),
+    MaskSpec(KIND_DILATED_2D, 64, block=16, stride=2),
+    MaskSpec(KIND_DILATED_2D, 1000, block=64, stride=3),
+    MaskSpec(KIND_DILATED_2D, 333, block=40, stride=1),
+    MaskSpec(KIND_DILATED_2D, 50, block=64, stride=4),
+    MaskSpec(KIND_DILATED_2D, 129, block=1, stride=1),
+    MaskSpec(KIND_DILATED_2D, 500, block=7, stride=9),
 ]
 
 
