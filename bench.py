@@ -199,6 +199,54 @@ def cpu_baseline(wl, runner, budget_s=12.0):
             "extrapolated_full_workload_s": t / n * wl.L * wl.H}
 
 
+def composition_times(wl, path, steps=5, warmup=2):
+    """Section V-F's comparison on the headline mask: one CSR call on the global+local mask
+    against a local call followed by a global (non-local) call on the same (O, lse) state."""
+    import torch
+    import paper_2502_01659_amd as sga
+    from sga_inputs import MaskSpec, KIND_SLIDING, KIND_NONLOCAL, torch_qkv
+    m = wl.mask
+    loc = MaskSpec(KIND_SLIDING, wl.L, window=m.window)
+    nl = MaskSpec(KIND_NONLOCAL, wl.L, window=m.window, n_global=m.n_global)
+    Q, K, V = torch_qkv(wl.H, wl.L, wl.d, wl.dtype, wl.sigma, wl.seed, "cuda:0")
+    O = torch.empty_like(Q)
+    lse = torch.empty((wl.H, wl.L), dtype=torch.float32, device="cuda:0")
+    rp, ci = sga.build_mask(m)
+    rp1, ci1 = sga.build_mask(loc)
+    rp2, ci2 = sga.build_mask(nl)
+    ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, int(rp[-1]))
+    ws1 = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, int(rp1[-1]))
+    ws2 = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, int(rp2[-1]))
+    wsi = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, -1)
+
+    def single():
+        sga.attention_forward(Q, K, V, rp, ci, wl.scale, O=O, lse=lse, workspace=ws, path=path)
+
+    def implicit_pair():
+        sga.attention_forward_implicit(Q, K, V, loc, wl.scale, O=O, lse=lse, workspace=wsi, path=path)
+        sga.attention_accumulate_implicit(Q, K, V, nl, wl.scale, O, lse, workspace=wsi, path=path)
+
+    def csr_pair():
+        sga.attention_forward(Q, K, V, rp1, ci1, wl.scale, O=O, lse=lse, workspace=ws1, path=path)
+        sga.attention_accumulate(Q, K, V, rp2, ci2, wl.scale, O, lse, workspace=ws2, path=path)
+
+    out = {}
+    for name, fn in (("single_csr_ms", single), ("local_then_nonlocal_implicit_ms", implicit_pair),
+                     ("local_then_nonlocal_csr_ms", csr_pair)):
+        for _ in range(warmup):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1) / steps
+    out["mask"] = f"window {m.window} + {m.n_global} global tokens, L={wl.L}, H={wl.H}, {wl.dtype}"
+    return out
+
+
 def path_name(path, wl):
     return {0: "auto", 1: "gather", 2: "tile"}[path]
 
@@ -281,6 +329,11 @@ def main():
                 sweep.append({"workload": name, "error": repr(ex)})
             torch.cuda.empty_cache()
         out["sweep"] = sweep
+        if wl.mask.name == "global_local":
+            try:
+                out["composition"] = composition_times(wl, path)
+            except Exception as ex:
+                out["composition"] = {"error": repr(ex)}
     print(json.dumps(out))
 
 
