@@ -247,6 +247,108 @@ def composition_times(wl, path, steps=5, warmup=2):
     return out
 
 
+def _time_calls(fn, steps, warmup):
+    import torch
+    for _ in range(warmup):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / steps
+
+
+def suite_table3(path):
+    """The long-context shapes of the paper's Table III (Section V-E): local attention, fp16,
+    one head, window sized to S_f = 2730/L (S_f = 1e-5 at 160M tokens).  The paper's A100
+    seconds are quoted beside ours as context (another machine, another implementation)."""
+    import torch
+    import paper_2502_01659_amd as sga
+    from sga_inputs import MaskSpec, KIND_SLIDING, torch_qkv, BASE_SEED
+    shapes = [(1_600_000, 0.0017, 12.46), (8_000_000, 0.00034, 62.32), (16_000_000, 0.00017, 124.67),
+              (160_000_000, 0.00001, 733.93)]
+    rows = []
+    for L, sf, paper_s in shapes:
+        w = max(0, (int(round(sf * L)) - 1) // 2)
+        spec = MaskSpec(KIND_SLIDING, L, window=w)
+        Q, K, V = torch_qkv(1, L, 64, "f16", 0.5, BASE_SEED, "cuda:0")
+        O = torch.empty_like(Q)
+        ms = _time_calls(lambda: sga.attention_forward_implicit(Q, K, V, spec, 0.125, O=O, path=path),
+                         steps=3, warmup=1)
+        edges = sga.mask_nnz(spec)
+        rows.append({"L": L, "window": w, "S_f": edges / (L * L), "edges": edges, "dtype": "f16", "d": 64,
+                     "ms": ms, "edges_per_s": edges / (ms * 1e-3),
+                     "hbm_algorithmic_GBps": 4 * L * 64 * 2 / (ms * 1e-3) / 1e9,
+                     "mfma_f16_TFLOPs": FLOPS_PER_EDGE * edges / (ms * 1e-3) / 1e12,
+                     "paper_a100_seconds": paper_s, "paper_over_ours": paper_s * 1e3 / ms})
+        del Q, K, V, O
+        torch.cuda.empty_cache()
+    return {"suite": "table3", "unit": "ms per forward (sga_attention_forward_implicit)", "rows": rows}
+
+
+def suite_e2(path, dims=(64,)):
+    """The shapes of the paper's microbenchmark (Section V-C): L in {8192, 16384, 24576}, one
+    head, fp32, sparsity factors across (0, 1], masks sized to the sparsity factor: local,
+    1-D dilated (r = 1), 2-D dilated (r = 1), global with the smallest local window, and a
+    uniformly random CSR mask."""
+    import torch
+    import paper_2502_01659_amd as sga
+    from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_DILATED_2D, KIND_GLOBAL_LOCAL,
+                            torch_qkv, BASE_SEED)
+    rows = []
+    for d in dims:
+        for L in (8192, 16384, 24576):
+            Q, K, V = torch_qkv(1, L, d, "f32", 1.0, BASE_SEED, "cuda:0")
+            O = torch.empty_like(Q)
+            for sf in (0.001, 0.01, 0.1, 0.5, 1.0):
+                span = max(1, int(round(sf * L)))
+                specs = {
+                    "local": MaskSpec(KIND_SLIDING, L, window=(span - 1) // 2),
+                    "dilated_1d": MaskSpec(KIND_DILATED, L, window=(span - 1) // 2, stride=2),
+                    "dilated_2d": MaskSpec(KIND_DILATED_2D, L, block=min(L, max(2, 4 * span)), stride=2),
+                    "global": MaskSpec(KIND_GLOBAL_LOCAL, L, window=0, n_global=min(L, max(1, span // 2))),
+                }
+                for name, spec in specs.items():
+                    implicit = name != "global"
+                    if implicit:
+                        wsi = sga.alloc_workspace(L, 1, d, "f32", -1)
+                        fn = lambda: sga.attention_forward_implicit(Q, K, V, spec, d ** -0.5, O=O,
+                                                                    workspace=wsi, path=path)
+                        edges = sga.mask_nnz(spec)
+                    else:
+                        rp, ci = sga.build_mask(spec)
+                        edges = int(rp[-1])
+                        ws = sga.alloc_workspace(L, 1, d, "f32", edges)
+                        fn = lambda: sga.attention_forward(Q, K, V, rp, ci, d ** -0.5, O=O, workspace=ws,
+                                                           path=path)
+                    ms = _time_calls(fn, steps=5, warmup=2)
+                    rows.append({"mask": name, "entry": "implicit" if implicit else "csr", "L": L, "d": d,
+                                 "S_f_target": sf, "S_f": edges / (L * L), "edges": edges, "ms": ms,
+                                 "edges_per_s": edges / (ms * 1e-3)})
+                # uniformly random explicit mask
+                g = torch.Generator(device="cuda:0")
+                g.manual_seed(BASE_SEED + 7)
+                dense = torch.rand((L, L), generator=g, device="cuda:0") < sf
+                rp = torch.zeros(L + 1, dtype=torch.int64, device="cuda:0")
+                rp[1:] = dense.sum(dim=1).cumsum(0)
+                ci = dense.nonzero()[:, 1].to(torch.int32).contiguous()
+                del dense
+                edges = int(rp[-1])
+                ws = sga.alloc_workspace(L, 1, d, "f32", edges)
+                ms = _time_calls(lambda: sga.attention_forward(Q, K, V, rp, ci, d ** -0.5, O=O,
+                                                               workspace=ws, path=path), steps=5, warmup=2)
+                rows.append({"mask": "random_csr", "entry": "csr", "L": L, "d": d, "S_f_target": sf,
+                             "S_f": edges / (L * L), "edges": edges, "ms": ms,
+                             "edges_per_s": edges / (ms * 1e-3)})
+                del rp, ci, ws
+                torch.cuda.empty_cache()
+            del Q, K, V, O
+    return {"suite": "e2", "unit": "ms per forward, one head, fp32", "rows": rows}
+
+
 def path_name(path, wl):
     return {0: "auto", 1: "gather", 2: "tile"}[path]
 
@@ -260,6 +362,9 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "gather", "tile"])
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--suite", default=None, choices=["table3", "e2"],
+                    help="instead of the benchmark line, time the shapes of the paper's Table III "
+                         "or of its microbenchmark grid and print one JSON object")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of known size (1 GiB read + 1 GiB written) and "
                          "exit: the reference against which rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -283,6 +388,9 @@ def main():
                           "bytes_written_per_copy": n, "copies": 5}))
         return
     path = {"auto": 0, "gather": 1, "tile": 2}[args.path]
+    if args.suite:
+        print(json.dumps(suite_table3(path) if args.suite == "table3" else suite_e2(path)))
+        return
     wl = WORKLOADS[args.workload]
     run = Runner(wl, path)
     ms_step, fwd_ms, bld_ms, kern_ms = run.timed(args.steps, args.warmup)

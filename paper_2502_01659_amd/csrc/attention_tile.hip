@@ -844,7 +844,23 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
             word = ~0u;   // 32 consecutive columns: the whole block row
             pos += 32;
           } else {
-            while (pos < end) {
+            // the row's columns inside block b are the next entries of its sorted list: take
+            // them four per load while four remain, then one by one
+            bool more = true;
+            while (more && pos + 4 <= end) {
+              int cc[4];
+              __builtin_memcpy(cc, col_idx + pos, 16);
+#pragma unroll
+              for (int t = 0; t < 4; ++t) {
+                if (more && (cc[t] >> 5) == b) {
+                  word |= 1u << (cc[t] & 31);
+                  ++pos;
+                } else {
+                  more = false;
+                }
+              }
+            }
+            while (more && pos < end) {
               const int cc = col_idx[pos];
               if ((cc >> 5) != b) break;
               word |= 1u << (cc & 31);

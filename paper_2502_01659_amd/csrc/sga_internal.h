@@ -13,7 +13,7 @@ constexpr int kHeadDim = 64;          // the only supported d
 constexpr int kWave = 64;             // CDNA wavefront width
 
 // ---- split-row parameters (gather path) -----------------------------------
-constexpr int kSplitThreshold = 8192; // rows with more neighbours are split
+constexpr int kSplitThreshold = 2048; // rows with more neighbours are split
 constexpr int kSplitChunk = 2048;     // target edges per chunk
 constexpr int kMaxSplit = 64;         // at most this many chunks per row
 constexpr int kMaxImplicitGlobal = 64;  // global rows the implicit non-local kernels can split
@@ -21,7 +21,7 @@ constexpr int kMaxImplicitGlobal = 64;  // global rows the implicit non-local ke
 // ---- tile path parameters -----------------------------------------------------
 constexpr int kTile = 32;                 // query rows per tile = keys per block
 constexpr int kPairEdges = 128;           // a tile qualifies if it averages >= this many edges per block
-constexpr int kMaxTilePartials = 4096;    // partial states of split tiles per call
+constexpr int kMaxTilePartials = 32768;   // partial states of split tiles per call
 constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32], l[32]
 
 // Edges per unit of tile work.  Tile t owns the work items [f(t), f(t+1)) with
