@@ -29,7 +29,9 @@
  *     undefined behaviour of the forward.
  *   - A row with no neighbour yields O_i = 0 and lse_i = -inf (the initial state
  *     of Algorithm 1: O = 0, l = 0, m = -inf).
- *   - Supported head dimension: d = 64.
+ *   - Supported head dimensions: d = 64 on every path; d = 32, 128 and 256 (the other sizes of
+ *     the paper's verification and microbenchmark runs, Section V-A and V-C) on the per-row
+ *     kernels only (SGA_PATH_AUTO selects them; SGA_PATH_TILE returns SGA_ERR_UNSUPPORTED).
  */
 #ifndef SGA_H_
 #define SGA_H_
@@ -153,7 +155,8 @@ sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, i
  *             preserved between calls; concurrent calls need separate workspaces.
  *   path      sga_path
  * Errors: SGA_ERR_INVALID_ARG (null pointer, L < 1 or >= 2^31, H < 1, unknown
- * dtype/path, misaligned pointers), SGA_ERR_UNSUPPORTED (d != 64),
+ * dtype/path, misaligned pointers), SGA_ERR_UNSUPPORTED (d not in {32, 64, 128, 256}, or
+ * SGA_PATH_TILE with d != 64),
  * SGA_ERR_WORKSPACE (path = SGA_PATH_TILE without a sufficient workspace).
  */
 sga_status sga_attention_forward(const void* Q, const void* K, const void* V,

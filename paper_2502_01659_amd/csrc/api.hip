@@ -26,7 +26,8 @@ sga_status check_common(const void* Q, const void* K, const void* V, const void*
   if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
   if (path != SGA_PATH_AUTO && path != SGA_PATH_GATHER && path != SGA_PATH_TILE)
     return SGA_ERR_INVALID_ARG;
-  if (d != kHeadDim) return SGA_ERR_UNSUPPORTED;
+  if (d != 32 && d != 64 && d != 128 && d != 256) return SGA_ERR_UNSUPPORTED;
+  if (path == SGA_PATH_TILE && d != kHeadDim) return SGA_ERR_UNSUPPORTED;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return SGA_ERR_INVALID_ARG;
   if (ws && (reinterpret_cast<uintptr_t>(ws) & 255u)) return SGA_ERR_INVALID_ARG;
   if (!ws && ws_bytes != 0) return SGA_ERR_INVALID_ARG;
@@ -116,9 +117,9 @@ sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, i
   if (!bytes_out) return SGA_ERR_INVALID_ARG;
   if (L < 1 || L >= (int64_t(1) << 31) || H < 1 || H > 65535) return SGA_ERR_INVALID_ARG;
   if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
-  if (d != kHeadDim) return SGA_ERR_UNSUPPORTED;
+  if (d != 32 && d != 64 && d != 128 && d != 256) return SGA_ERR_UNSUPPORTED;
   if (nnz < -1 || nnz > L * L) return SGA_ERR_INVALID_ARG;
-  *bytes_out = plan_workspace(L, H, nnz, dtype).total_bytes;
+  *bytes_out = plan_workspace(L, H, nnz, dtype, d).total_bytes;
   return SGA_OK;
 }
 
@@ -136,15 +137,17 @@ sga_status run_explicit_call(const void* Q, const void* K, const void* V, const 
   if (accumulate && !lse) return SGA_ERR_INVALID_ARG;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
-  a.L = L; a.H = H; a.scale = scale; a.dtype = dtype;
+  a.L = L; a.H = H; a.scale = scale; a.dtype = dtype; a.d = d;
   a.stream = static_cast<hipStream_t>(stream);
   a.row_ptr = row_ptr; a.col_idx = col_idx;
   a.ws = workspace; a.ws_bytes = workspace_bytes;
   a.accumulate = accumulate;
   if (path == SGA_PATH_TILE && (!workspace || workspace_bytes < 256)) return SGA_ERR_WORKSPACE;
+  // the MFMA tile kernels exist for d = 64; other head dimensions run on the per-row kernels
+  const bool gather_only = path == SGA_PATH_GATHER || d != kHeadDim;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
-  if (workspace && workspace_bytes >= 256) clear_workspace(a, path != SGA_PATH_GATHER);
-  if (path == SGA_PATH_GATHER) return launch_gather_explicit(a, true, false);
+  if (workspace && workspace_bytes >= 256) clear_workspace(a, !gather_only);
+  if (gather_only) return launch_gather_explicit(a, true, false);
   return launch_tile_explicit(a);
 }
 
@@ -164,7 +167,7 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
     return SGA_ERR_UNSUPPORTED;
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
-  a.L = L; a.H = H; a.scale = scale; a.dtype = dtype;
+  a.L = L; a.H = H; a.scale = scale; a.dtype = dtype; a.d = d;
   a.stream = static_cast<hipStream_t>(stream);
   a.mask_kind = kind;
   a.stride = (kind == SGA_MASK_DILATED || kind == SGA_MASK_DILATED_2D) ? desc->stride : 1;
@@ -178,11 +181,12 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
   if (kind == SGA_MASK_NONLOCAL) {
     const int64_t g = desc->n_global < L ? desc->n_global : L;
     if (g > kMaxImplicitGlobal) return SGA_ERR_UNSUPPORTED;
-    if (g > 0 && (!workspace || workspace_bytes < plan_workspace(L, H, -1, dtype).total_bytes))
+    if (g > 0 && (!workspace || workspace_bytes < plan_workspace(L, H, -1, dtype, d).total_bytes))
       return SGA_ERR_WORKSPACE;
     return launch_gather_implicit(a);
   }
-  if (kind == SGA_MASK_DILATED_2D || path == SGA_PATH_GATHER) return launch_gather_implicit(a);
+  if (kind == SGA_MASK_DILATED_2D || path == SGA_PATH_GATHER || d != kHeadDim)
+    return launch_gather_implicit(a);
   return launch_tile_implicit(a);
 }
 

@@ -1,9 +1,9 @@
 // Gather path of Algorithm 1: one wavefront per query row, per-edge K/V row gathers.
 //
-// Lane layout (d = 64).  A K or V row is 256 B (fp32) or 128 B (fp16); a group of
-// LPK lanes reads one row with one 16-byte load per lane (LPK = 16 for fp32, 8 for fp16),
-// so a wavefront pulls G = 64/LPK rows per load instruction and every row is a fully
-// coalesced 128/256-byte gather.  The dot product Q_i.K_j is reduced inside the lane
+// Lane layout.  A K or V row is d*4 B (fp32) or d*2 B (fp16), d in {32, 64, 128, 256}; a
+// group of LPK lanes reads one row with one 16-byte load per lane (LPK = d/4 for fp32, d/8
+// for fp16: 16 and 8 at d = 64), so a wavefront pulls G = 64/LPK rows per load instruction
+// and every row is a fully coalesced gather.  The dot product Q_i.K_j is reduced inside the lane
 // group with DPP adds (no LDS); each group keeps its own running (m, l, acc) state of
 // the recurrence in Algorithm 1 for the keys it has seen, and the G group states are
 // merged with wavefront shuffles once per row.  The accumulator is kept un-normalised
@@ -32,19 +32,22 @@ __device__ __forceinline__ float dpp(float x) {
 // Sum over the LPK consecutive lanes of a group; every lane of the group gets the total.
 template <int LPK>
 __device__ __forceinline__ float group_sum(float x) {
+  static_assert(LPK == 4 || LPK == 8 || LPK == 16 || LPK == 32 || LPK == 64, "lanes per row");
   x += dpp<0xB1>(x);    // quad_perm [1,0,3,2]
   x += dpp<0x4E>(x);    // quad_perm [2,3,0,1]
-  x += dpp<0x141>(x);   // row_half_mirror: lane k <-> 7-k of each 8
-  if (LPK == 16) x += dpp<0x140>(x);  // row_mirror: lane k <-> 15-k of each 16
+  if (LPK >= 8) x += dpp<0x141>(x);    // row_half_mirror: lane k <-> 7-k of each 8
+  if (LPK >= 16) x += dpp<0x140>(x);   // row_mirror: lane k <-> 15-k of each 16
+  if (LPK >= 32) x += __shfl_xor(x, 16, kWave);
+  if (LPK >= 64) x += __shfl_xor(x, 32, kWave);
   return x;
 }
 
-template <typename T>
+template <typename T, int D>
 struct Row;
 
-template <>
-struct Row<float> {
-  static constexpr int LPK = 16, VEC = 4;
+template <int D>
+struct Row<float, D> {
+  static constexpr int VEC = 4, LPK = D / VEC;
   __device__ static void load(const float* p, float (&v)[4]) {
     const float4 t = *reinterpret_cast<const float4*>(p);
     v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
@@ -54,9 +57,9 @@ struct Row<float> {
   }
 };
 
-template <>
-struct Row<__half> {
-  static constexpr int LPK = 8, VEC = 8;
+template <int D>
+struct Row<__half, D> {
+  static constexpr int VEC = 8, LPK = D / VEC;
   __device__ static void load(const __half* p, float (&v)[8]) {
     const uint4 t = *reinterpret_cast<const uint4*>(p);
     const uint32_t w[4] = {t.x, t.y, t.z, t.w};
@@ -104,12 +107,12 @@ struct State {
 };
 
 // Visit edges [e0, e1) of one row.  q holds this lane's channels of Q_i * scale * log2(e).
-template <typename T, typename Nbr>
+template <typename T, int D, typename Nbr>
 __device__ __forceinline__ void attend_range(const T* __restrict__ Kh, const T* __restrict__ Vh,
-                                             const float (&q)[Row<T>::VEC], const Nbr& nbr,
+                                             const float (&q)[Row<T, D>::VEC], const Nbr& nbr,
                                              int64_t e0, int64_t e1, int lane,
-                                             State<Row<T>::VEC>& st) {
-  constexpr int LPK = Row<T>::LPK, VEC = Row<T>::VEC, G = kWave / LPK;
+                                             State<Row<T, D>::VEC>& st) {
+  constexpr int LPK = Row<T, D>::LPK, VEC = Row<T, D>::VEC, G = kWave / LPK;
   const int grp = lane / LPK;
   const int cofs = (lane % LPK) * VEC;
   for (int64_t base = e0; base < e1; base += G * kUnroll) {
@@ -120,8 +123,8 @@ __device__ __forceinline__ void attend_range(const T* __restrict__ Kh, const T* 
       const int64_t e = base + u * G + grp;
       valid[u] = e < e1;
       const int64_t j = nbr(valid[u] ? e : e1 - 1);   // out-of-range lanes re-read a real neighbour
-      Row<T>::load(Kh + j * kHeadDim + cofs, kf[u]);
-      Row<T>::load(Vh + j * kHeadDim + cofs, vf[u]);
+      Row<T, D>::load(Kh + j * D + cofs, kf[u]);
+      Row<T, D>::load(Vh + j * D + cofs, vf[u]);
     }
     float s[kUnroll];
     float smax = st.m;
@@ -169,21 +172,21 @@ __device__ __forceinline__ void merge_groups(State<VEC>& st) {
   }
 }
 
-template <typename T>
+template <typename T, int D>
 __device__ __forceinline__ void load_query(const T* Qrow, float scale, int lane,
-                                           float (&q)[Row<T>::VEC]) {
-  Row<T>::load(Qrow + (lane % Row<T>::LPK) * Row<T>::VEC, q);
+                                           float (&q)[Row<T, D>::VEC]) {
+  Row<T, D>::load(Qrow + (lane % Row<T, D>::LPK) * Row<T, D>::VEC, q);
   const float c = scale * kLog2e;
 #pragma unroll
-  for (int k = 0; k < Row<T>::VEC; ++k) q[k] *= c;
+  for (int k = 0; k < Row<T, D>::VEC; ++k) q[k] *= c;
 }
 
 // Normalise and store a row; with `accumulate` the row continues the (O, lse) state already
 // in the output buffers (sequential composition on one state, Section V-F).
-template <typename T>
+template <typename T, int D>
 __device__ __forceinline__ void finish_row(T* Orow, float* lse_i, int lane,
-                                           State<Row<T>::VEC>& st, bool accumulate) {
-  constexpr int LPK = Row<T>::LPK, VEC = Row<T>::VEC;
+                                           State<Row<T, D>::VEC>& st, bool accumulate) {
+  constexpr int LPK = Row<T, D>::LPK, VEC = Row<T, D>::VEC;
   merge_groups<LPK, VEC>(st);
   const bool empty = !(st.l > 0.f);
   float inv = empty ? 0.f : 1.0f / st.l;
@@ -201,11 +204,11 @@ __device__ __forceinline__ void finish_row(T* Orow, float* lse_i, int lane,
   if (lane < LPK) {
     if (accumulate) {
       float old[VEC];
-      Row<T>::load(Orow + lane * VEC, old);
+      Row<T, D>::load(Orow + lane * VEC, old);
 #pragma unroll
       for (int c = 0; c < VEC; ++c) o[c] = __builtin_fmaf(w_prev, old[c], o[c]);
     }
-    Row<T>::store(Orow + lane * VEC, o);
+    Row<T, D>::store(Orow + lane * VEC, o);
   }
   if (lse_i && lane == 0) *lse_i = lse_row;
 }
@@ -224,12 +227,12 @@ __host__ __device__ inline void split_shape(int64_t deg, int32_t& nchunks, int32
 // Zeroes the counters and (tile_flags != 0) the per-tile flags of the tile path.
 __global__ __launch_bounds__(256) void clear_workspace_kernel(void* ws, size_t ws_bytes,
                                                               const int64_t* row_ptr, int64_t L,
-                                                              int32_t H, int32_t dtype,
+                                                              int32_t H, int32_t dtype, int32_t d,
                                                               int tile_flags) {
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   if (blockIdx.x == 0 && threadIdx.x < kNumCounters) ctr[threadIdx.x] = 0;
   if (!tile_flags) return;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
   if (pl.total_bytes > ws_bytes) return;
   int32_t* bad = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + pl.off_tile_bad);
   for (int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; t < pl.n_tiles;
@@ -244,13 +247,13 @@ __global__ __launch_bounds__(256) void clear_workspace_kernel(void* ws, size_t w
 // One thread per row: rows over the split threshold reserve chunk work items.
 __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __restrict__ row_ptr,
                                                             int64_t L, int32_t H, int32_t dtype,
-                                                            void* ws, size_t ws_bytes,
+                                                            int32_t d, void* ws, size_t ws_bytes,
                                                             int skip_tiled) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= L) return;
   const int64_t deg = row_ptr[i + 1] - row_ptr[i];
   if (deg <= kSplitThreshold) return;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
   if (pl.total_bytes > ws_bytes) return;
   if (skip_tiled && (tiles_cover_everything(pl, ws) || tile_handled(pl, ws, row_ptr, L, dtype, i / kTile)))
     return;
@@ -269,9 +272,10 @@ __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __res
 
 // True when the long rows of this call are handled by the chunk kernels.
 __device__ __forceinline__ bool split_active(const int64_t* row_ptr, int64_t L, int32_t H,
-                                             int32_t dtype, const void* ws, size_t ws_bytes) {
+                                             int32_t dtype, int32_t d, const void* ws,
+                                             size_t ws_bytes) {
   if (!ws) return false;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
   if (pl.total_bytes > ws_bytes) return false;
   const uint32_t need = reinterpret_cast<const uint32_t*>(ws)[kCtrChunksNeeded];
   return (int64_t)need <= pl.cap_items;
@@ -279,14 +283,14 @@ __device__ __forceinline__ bool split_active(const int64_t* row_ptr, int64_t L, 
 
 // True when this call's tile path produced row i (its 32-row tile has a block list).
 __device__ __forceinline__ bool row_done_by_tiles(const int64_t* row_ptr, int64_t L, int32_t H,
-                                                  int32_t dtype, const void* ws, size_t ws_bytes,
-                                                  int64_t i) {
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+                                                  int32_t dtype, int32_t d, const void* ws,
+                                                  size_t ws_bytes, int64_t i) {
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
   if (pl.total_bytes > ws_bytes) return false;
   return tile_handled(pl, ws, row_ptr, L, dtype, i / kTile);
 }
 
-template <typename T>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_csr_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
@@ -296,28 +300,28 @@ __global__ __launch_bounds__(256) void gather_csr_kernel(
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
   const int32_t H = (int32_t)gridDim.y;
-  const int64_t hoff = h * L * kHeadDim;
+  const int64_t hoff = h * L * D;
   if (skip_tiled) {
-    const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
+    const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code, D);
     if (pl.total_bytes <= ws_bytes && tiles_cover_everything(pl, ws)) return;
   }
   for (int64_t i = (int64_t)blockIdx.x * waves + (threadIdx.x / kWave); i < L;
        i += (int64_t)gridDim.x * waves) {
-    if (skip_tiled && row_done_by_tiles(row_ptr, L, H, DtypeOf<T>::code, ws, ws_bytes, i)) continue;
+    if (skip_tiled && row_done_by_tiles(row_ptr, L, H, DtypeOf<T>::code, D, ws, ws_bytes, i)) continue;
     const int64_t r0 = row_ptr[i], r1 = row_ptr[i + 1];
-    if (use_split && r1 - r0 > kSplitThreshold && split_active(row_ptr, L, H, DtypeOf<T>::code, ws, ws_bytes))
+    if (use_split && r1 - r0 > kSplitThreshold && split_active(row_ptr, L, H, DtypeOf<T>::code, D, ws, ws_bytes))
       continue;
-    float q[Row<T>::VEC];
-    load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
-    State<Row<T>::VEC> st;
+    float q[Row<T, D>::VEC];
+    load_query<T, D>(Q + hoff + i * D, scale, lane, q);
+    State<Row<T, D>::VEC> st;
     st.init();
     CsrNeighbours nbr{col_idx + r0};
-    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
-    finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
+    attend_range<T, D>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
+    finish_row<T, D>(O + hoff + i * D, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
   }
 }
 
-template <typename T>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_window_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, int64_t L, int64_t W, int64_t s, float scale, int accumulate) {
@@ -325,15 +329,15 @@ __global__ __launch_bounds__(256) void gather_window_kernel(
   const int64_t i = (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
   if (i >= L) return;
   const int64_t h = blockIdx.y;
-  const int64_t hoff = h * L * kHeadDim;
+  const int64_t hoff = h * L * D;
   const int64_t kl = min(W, i / s), kr = min(W, (L - 1 - i) / s);
-  float q[Row<T>::VEC];
-  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
-  State<Row<T>::VEC> st;
+  float q[Row<T, D>::VEC];
+  load_query<T, D>(Q + hoff + i * D, scale, lane, q);
+  State<Row<T, D>::VEC> st;
   st.init();
   WindowNeighbours nbr{i - kl * s, s};
-  attend_range<T>(K + hoff, V + hoff, q, nbr, 0, kl + kr + 1, lane, st);
-  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
+  attend_range<T, D>(K + hoff, V + hoff, q, nbr, 0, kl + kr + 1, lane, st);
+  finish_row<T, D>(O + hoff + i * D, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
 }
 
 // Implicit Get_Neighbors for the masks whose rows are one arithmetic run of keys that is not a
@@ -357,7 +361,7 @@ __device__ __forceinline__ RowRun row_run(int32_t kind, int64_t i, int64_t L, in
   return {0, 1, n > 0 ? n : 0};
 }
 
-template <typename T>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_runs_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, int64_t L, int32_t kind, int64_t W, int64_t s, int64_t g, int64_t B,
@@ -366,106 +370,126 @@ __global__ __launch_bounds__(256) void gather_runs_kernel(
   const int64_t i = row0 + (int64_t)blockIdx.x * (blockDim.x / kWave) + (threadIdx.x / kWave);
   if (i >= L) return;
   const int64_t h = blockIdx.y;
-  const int64_t hoff = h * L * kHeadDim;
+  const int64_t hoff = h * L * D;
   const RowRun run = row_run(kind, i, L, W, s, g, B);
-  float q[Row<T>::VEC];
-  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
-  State<Row<T>::VEC> st;
+  float q[Row<T, D>::VEC];
+  load_query<T, D>(Q + hoff + i * D, scale, lane, q);
+  State<Row<T, D>::VEC> st;
   st.init();
   if (run.count > 0) {
     WindowNeighbours nbr{run.first, run.step};
-    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, run.count, lane, st);
+    attend_range<T, D>(K + hoff, V + hoff, q, nbr, 0, run.count, lane, st);
   }
-  finish_row<T>(O + hoff + i * kHeadDim, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
+  finish_row<T, D>(O + hoff + i * D, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
+}
+
+// Combine the n partial (m, l, acc) states of one row in their stored order (deterministic) and
+// write the row: one wavefront, lane c owns channels c, c + 64, ...
+template <typename T, int D>
+__device__ __forceinline__ void merge_row_partials(const float* p0, int64_t step, int n, T* Orow,
+                                                   float* lse_i, int lane, bool accumulate) {
+  constexpr int kCh = (D + kWave - 1) / kWave;
+  float M = kMinusHuge;
+  for (int c = 0; c < n; ++c) M = fmaxf(M, p0[c * step + D]);
+  float l = 0.f, acc[kCh];
+#pragma unroll
+  for (int k = 0; k < kCh; ++k) acc[k] = 0.f;
+  for (int c = 0; c < n; ++c) {
+    const float w = __builtin_amdgcn_exp2f(p0[c * step + D] - M);
+    l = __builtin_fmaf(p0[c * step + D + 1], w, l);
+#pragma unroll
+    for (int k = 0; k < kCh; ++k)
+      if (lane + k * kWave < D) acc[k] = __builtin_fmaf(p0[c * step + lane + k * kWave], w, acc[k]);
+  }
+  const bool empty = !(l > 0.f);
+  const float inv = empty ? 0.f : 1.0f / l;
+  float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+  CarryWeights cw{0.f, 1.f, lse_row};
+  if (accumulate) {      // every lane reads the earlier lse before lane 0 replaces it
+    cw = carry_weights(*lse_i, lse_row);
+    lse_row = cw.lse;
+  }
+#pragma unroll
+  for (int k = 0; k < kCh; ++k) {
+    const int ch = lane + k * kWave;
+    if (ch < D) {
+      float o = acc[k] * inv * cw.w_now;
+      if (accumulate) o = __builtin_fmaf(cw.w_prev, load_scalar(Orow + ch), o);
+      store_scalar(Orow + ch, o);
+    }
+  }
+  if (lse_i && lane == 0) *lse_i = lse_row;
 }
 
 // Global rows i < g of the non-local mask attend every key outside their window: about L
 // neighbours each.  grid = (chunks, g, H): a wavefront reduces the keys of one chunk of the
 // key range (the window cut out) to a partial (m, l, acc) state ...
-template <typename T>
+template <typename T, int D>
 __global__ __launch_bounds__(64) void nonlocal_chunk_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, int64_t L, int64_t W,
     int64_t chunk_len, float scale, float* __restrict__ partials) {
   const int lane = threadIdx.x;
   const int64_t c = blockIdx.x, i = blockIdx.y, h = blockIdx.z;
   const int64_t H = gridDim.z, n_chunks = gridDim.x;
-  const int64_t hoff = h * L * kHeadDim;
+  const int64_t hoff = h * L * D;
   const int64_t lo = c * chunk_len, hi = min(L, lo + chunk_len);      // keys [lo, hi)
-  float q[Row<T>::VEC];
-  load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
-  State<Row<T>::VEC> st;
+  float q[Row<T, D>::VEC];
+  load_query<T, D>(Q + hoff + i * D, scale, lane, q);
+  State<Row<T, D>::VEC> st;
   st.init();
   const int64_t a1 = min(hi, i - W);             // keys [lo, a1) lie left of the window
   if (a1 > lo) {
     WindowNeighbours nbr{lo, 1};
-    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, a1 - lo, lane, st);
+    attend_range<T, D>(K + hoff, V + hoff, q, nbr, 0, a1 - lo, lane, st);
   }
   const int64_t b0 = max(lo, i + W + 1);         // keys [b0, hi) lie right of it
   if (hi > b0) {
     WindowNeighbours nbr{b0, 1};
-    attend_range<T>(K + hoff, V + hoff, q, nbr, 0, hi - b0, lane, st);
+    attend_range<T, D>(K + hoff, V + hoff, q, nbr, 0, hi - b0, lane, st);
   }
-  merge_groups<Row<T>::LPK, Row<T>::VEC>(st);
-  float* p = partials + ((i * n_chunks + c) * H + h) * kPartialStride;
-  if (lane < Row<T>::LPK) {
+  merge_groups<Row<T, D>::LPK, Row<T, D>::VEC>(st);
+  float* p = partials + ((i * n_chunks + c) * H + h) * (D + 4);
+  if (lane < Row<T, D>::LPK) {
 #pragma unroll
-    for (int k = 0; k < Row<T>::VEC; ++k) p[lane * Row<T>::VEC + k] = st.acc[k];
+    for (int k = 0; k < Row<T, D>::VEC; ++k) p[lane * Row<T, D>::VEC + k] = st.acc[k];
   }
   if (lane == 0) {
-    p[kHeadDim] = st.m;
-    p[kHeadDim + 1] = st.l;
+    p[D] = st.m;
+    p[D + 1] = st.l;
   }
 }
 
 // ... and one wavefront per (global row, head) combines the row's partials in chunk order
-// (deterministic).  lane = channel.
-template <typename T>
+// (deterministic).
+template <typename T, int D>
 __global__ __launch_bounds__(64) void nonlocal_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                             int64_t L, int32_t n_chunks,
                                                             const float* __restrict__ partials,
                                                             int accumulate) {
   const int lane = threadIdx.x;
   const int64_t i = blockIdx.x, h = blockIdx.y, H = gridDim.y;
-  const float* p0 = partials + ((i * n_chunks) * H + h) * kPartialStride;
-  const int64_t step = H * kPartialStride;
-  float M = kMinusHuge;
-  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, p0[c * step + kHeadDim]);
-  float l = 0.f, acc = 0.f;
-  for (int c = 0; c < n_chunks; ++c) {
-    const float w = __builtin_amdgcn_exp2f(p0[c * step + kHeadDim] - M);
-    l = __builtin_fmaf(p0[c * step + kHeadDim + 1], w, l);
-    acc = __builtin_fmaf(p0[c * step + lane], w, acc);
-  }
-  const bool empty = !(l > 0.f);
-  float o = empty ? 0.f : acc / l;
-  float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
-  T* dst = O + h * L * kHeadDim + i * kHeadDim + lane;
-  if (accumulate) {
-    const CarryWeights cw = carry_weights(lse[h * L + i], lse_row);
-    o = cw.w_prev * load_scalar(dst) + cw.w_now * o;
-    lse_row = cw.lse;
-  }
-  store_scalar(dst, o);
-  if (lse && lane == 0) lse[h * L + i] = lse_row;
+  const float* p0 = partials + ((i * n_chunks) * H + h) * (D + 4);
+  merge_row_partials<T, D>(p0, H * (D + 4), n_chunks, O + h * L * D + i * D,
+                           lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
 }
 
 // One wavefront per (chunk item, head): partial state of a slice of a long row.
-template <typename T>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_chunk_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t L, float scale,
     void* ws, size_t ws_bytes) {
   const int32_t H = (int32_t)gridDim.y;
   constexpr int32_t dtype = DtypeOf<T>::code;
-  if (!split_active(row_ptr, L, H, dtype, ws, ws_bytes)) return;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, D);
   const uint32_t n_items = reinterpret_cast<const uint32_t*>(ws)[kCtrItemsAlloc];
   const int2* items = reinterpret_cast<const int2*>(static_cast<char*>(ws) + pl.off_items);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_partials);
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
-  const int64_t hoff = h * L * kHeadDim;
+  const int64_t hoff = h * L * D;
   for (uint32_t it = blockIdx.x * waves + threadIdx.x / kWave; it < n_items;
        it += gridDim.x * waves) {
     const int2 item = items[it];
@@ -475,35 +499,35 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
     split_shape(deg, n, len);
     const int64_t e0 = (int64_t)item.y * len;
     const int64_t e1 = min(deg, e0 + len);
-    float q[Row<T>::VEC];
-    load_query<T>(Q + hoff + i * kHeadDim, scale, lane, q);
-    State<Row<T>::VEC> st;
+    float q[Row<T, D>::VEC];
+    load_query<T, D>(Q + hoff + i * D, scale, lane, q);
+    State<Row<T, D>::VEC> st;
     st.init();
     CsrNeighbours nbr{col_idx + r0};
-    attend_range<T>(K + hoff, V + hoff, q, nbr, e0, e1, lane, st);
-    merge_groups<Row<T>::LPK, Row<T>::VEC>(st);
-    float* p = partials + ((int64_t)it * H + h) * kPartialStride;
-    if (lane < Row<T>::LPK) {
+    attend_range<T, D>(K + hoff, V + hoff, q, nbr, e0, e1, lane, st);
+    merge_groups<Row<T, D>::LPK, Row<T, D>::VEC>(st);
+    float* p = partials + ((int64_t)it * H + h) * (D + 4);
+    if (lane < Row<T, D>::LPK) {
 #pragma unroll
-      for (int c = 0; c < Row<T>::VEC; ++c) p[lane * Row<T>::VEC + c] = st.acc[c];
+      for (int c = 0; c < Row<T, D>::VEC; ++c) p[lane * Row<T, D>::VEC + c] = st.acc[c];
     }
     if (lane == 0) {
-      p[kHeadDim] = st.m;
-      p[kHeadDim + 1] = st.l;
+      p[D] = st.m;
+      p[D + 1] = st.l;
     }
   }
 }
 
 // One wavefront per (long row, head): combine the row's partials in chunk order.
-template <typename T>
+template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                            const int64_t* __restrict__ row_ptr,
                                                            int64_t L, void* ws, size_t ws_bytes,
                                                            int accumulate) {
   const int32_t H = (int32_t)gridDim.y;
   constexpr int32_t dtype = DtypeOf<T>::code;
-  if (!split_active(row_ptr, L, H, dtype, ws, ws_bytes)) return;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, D);
   const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrLongRows];
   const int4* lr = reinterpret_cast<const int4*>(static_cast<char*>(ws) + pl.off_long);
   const float* partials = reinterpret_cast<const float*>(static_cast<char*>(ws) + pl.off_partials);
@@ -513,31 +537,13 @@ __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, fl
   for (uint32_t r = blockIdx.x * waves + threadIdx.x / kWave; r < n_long; r += gridDim.x * waves) {
     const int4 rec = lr[r];
     const int64_t i = rec.x;
-    const float* p0 = partials + ((int64_t)rec.y * H + h) * kPartialStride;
-    const int64_t step = (int64_t)H * kPartialStride;
-    float M = kMinusHuge;
-    for (int c = 0; c < rec.z; ++c) M = fmaxf(M, p0[c * step + kHeadDim]);
-    float l = 0.f, acc = 0.f;
-    for (int c = 0; c < rec.z; ++c) {
-      const float w = __builtin_amdgcn_exp2f(p0[c * step + kHeadDim] - M);
-      l = __builtin_fmaf(p0[c * step + kHeadDim + 1], w, l);
-      acc = __builtin_fmaf(p0[c * step + lane], w, acc);
-    }
-    const bool empty = !(l > 0.f);
-    float o = empty ? 0.f : acc / l;
-    float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
-    T* dst = O + h * L * kHeadDim + i * kHeadDim + lane;
-    if (accumulate) {
-      const CarryWeights cw = carry_weights(lse[h * L + i], lse_row);
-      o = cw.w_prev * load_scalar(dst) + cw.w_now * o;
-      lse_row = cw.lse;
-    }
-    store_scalar(dst, o);
-    if (lse && lane == 0) lse[h * L + i] = lse_row;
+    const float* p0 = partials + ((int64_t)rec.y * H + h) * (D + 4);
+    merge_row_partials<T, D>(p0, (int64_t)H * (D + 4), rec.z, O + h * L * D + i * D,
+                             lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
   }
 }
 
-template <typename T>
+template <typename T, int D>
 sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   const T* Q = static_cast<const T*>(a.Q);
   const T* K = static_cast<const T*>(a.K);
@@ -546,21 +552,21 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   const bool split = allow_split && a.ws && a.ws_bytes >= 256 && a.L > kSplitThreshold;
   if (split) {
     hipLaunchKernelGGL(split_prepass_kernel, dim3((unsigned)((a.L + 255) / 256)), dim3(256), 0,
-                       a.stream, a.row_ptr, a.L, a.H, a.dtype, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
+                       a.stream, a.row_ptr, a.L, a.H, a.dtype, D, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
   }
   // after the tile path only leftover rows remain: a small grid strides over the rows
   int64_t nwg = (a.L + 3) / 4;
   if (skip_tiled && nwg > 2048) nwg = 2048;
   const dim3 grid((unsigned)nwg, (unsigned)a.H);
   if (!skip_tiled) profile_mark_begin(a.stream);
-  hipLaunchKernelGGL(gather_csr_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
+  hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
                      a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
                      skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
   if (!skip_tiled) profile_mark_end(a.stream);
   if (split) {
-    hipLaunchKernelGGL(gather_chunk_kernel<T>, dim3(1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
+    hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
-    hipLaunchKernelGGL(gather_merge_kernel<T>, dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
+    hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
                        a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   }
   return hip_status(hipGetLastError());
@@ -573,15 +579,29 @@ void clear_workspace(const AttnArgs& a, bool tile_flags) {
   int64_t nwg = tile_flags ? (n_tiles + 255) / 256 : 1;
   if (nwg > 1024) nwg = 1024;
   hipLaunchKernelGGL(clear_workspace_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.ws,
-                     a.ws_bytes, a.row_ptr, a.L, a.H, a.dtype, tile_flags ? 1 : 0);
+                     a.ws_bytes, a.row_ptr, a.L, a.H, a.dtype, a.d, tile_flags ? 1 : 0);
 }
 
 sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
-  return a.dtype == SGA_F32 ? run_explicit<float>(a, allow_split, skip_tiled)
-                            : run_explicit<__half>(a, allow_split, skip_tiled);
+  switch (a.d) {
+    case 32:
+      return a.dtype == SGA_F32 ? run_explicit<float, 32>(a, allow_split, skip_tiled)
+                                : run_explicit<__half, 32>(a, allow_split, skip_tiled);
+    case 64:
+      return a.dtype == SGA_F32 ? run_explicit<float, 64>(a, allow_split, skip_tiled)
+                                : run_explicit<__half, 64>(a, allow_split, skip_tiled);
+    case 128:
+      return a.dtype == SGA_F32 ? run_explicit<float, 128>(a, allow_split, skip_tiled)
+                                : run_explicit<__half, 128>(a, allow_split, skip_tiled);
+    case 256:
+      return a.dtype == SGA_F32 ? run_explicit<float, 256>(a, allow_split, skip_tiled)
+                                : run_explicit<__half, 256>(a, allow_split, skip_tiled);
+    default:
+      return SGA_ERR_UNSUPPORTED;
+  }
 }
 
-template <typename T>
+template <typename T, int D>
 static sga_status run_implicit(const AttnArgs& a) {
   const T* Q = static_cast<const T*>(a.Q);
   const T* K = static_cast<const T*>(a.K);
@@ -591,7 +611,7 @@ static sga_status run_implicit(const AttnArgs& a) {
   if (a.mask_kind == SGA_MASK_SLIDING || a.mask_kind == SGA_MASK_DILATED) {
     const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
     profile_mark_begin(a.stream);
-    hipLaunchKernelGGL(gather_window_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
+    hipLaunchKernelGGL((gather_window_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
                        (int64_t)a.window, (int64_t)a.stride, a.scale, acc);
     profile_mark_end(a.stream);
     return hip_status(hipGetLastError());
@@ -602,7 +622,7 @@ static sga_status run_implicit(const AttnArgs& a) {
   if (a.L > g) {
     const dim3 grid((unsigned)((a.L - g + 3) / 4), (unsigned)a.H);
     profile_mark_begin(a.stream);
-    hipLaunchKernelGGL(gather_runs_kernel<T>, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
+    hipLaunchKernelGGL((gather_runs_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
                        a.mask_kind, (int64_t)a.window, (int64_t)a.stride, g, (int64_t)a.block, g, a.scale,
                        acc);
     profile_mark_end(a.stream);
@@ -612,18 +632,24 @@ static sga_status run_implicit(const AttnArgs& a) {
     int32_t n_chunks, len;
     split_shape(a.L, n_chunks, len);
     float* partials = reinterpret_cast<float*>(static_cast<char*>(a.ws) +
-                                               plan_workspace(a.L, a.H, -1, a.dtype).off_partials);
-    hipLaunchKernelGGL(nonlocal_chunk_kernel<T>, dim3((unsigned)n_chunks, (unsigned)g, (unsigned)a.H),
+                                               plan_workspace(a.L, a.H, -1, a.dtype, D).off_partials);
+    hipLaunchKernelGGL((nonlocal_chunk_kernel<T, D>), dim3((unsigned)n_chunks, (unsigned)g, (unsigned)a.H),
                        dim3(64), 0, a.stream, Q, K, V, a.L, (int64_t)a.window, (int64_t)len, a.scale,
                        partials);
-    hipLaunchKernelGGL(nonlocal_merge_kernel<T>, dim3((unsigned)g, (unsigned)a.H), dim3(64), 0, a.stream,
+    hipLaunchKernelGGL((nonlocal_merge_kernel<T, D>), dim3((unsigned)g, (unsigned)a.H), dim3(64), 0, a.stream,
                        O, a.lse, a.L, n_chunks, partials, acc);
   }
   return hip_status(hipGetLastError());
 }
 
 sga_status launch_gather_implicit(const AttnArgs& a) {
-  return a.dtype == SGA_F32 ? run_implicit<float>(a) : run_implicit<__half>(a);
+  switch (a.d) {
+    case 32: return a.dtype == SGA_F32 ? run_implicit<float, 32>(a) : run_implicit<__half, 32>(a);
+    case 64: return a.dtype == SGA_F32 ? run_implicit<float, 64>(a) : run_implicit<__half, 64>(a);
+    case 128: return a.dtype == SGA_F32 ? run_implicit<float, 128>(a) : run_implicit<__half, 128>(a);
+    case 256: return a.dtype == SGA_F32 ? run_implicit<float, 256>(a) : run_implicit<__half, 256>(a);
+    default: return SGA_ERR_UNSUPPORTED;
+  }
 }
 
 }  // namespace sga

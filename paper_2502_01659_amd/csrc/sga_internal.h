@@ -9,7 +9,8 @@
 
 namespace sga {
 
-constexpr int kHeadDim = 64;          // the only supported d
+constexpr int kHeadDim = 64;          // head dimension of the tile (MFMA) kernels; the per-row
+                                      // kernels also take 32, 128 and 256
 constexpr int kWave = 64;             // CDNA wavefront width
 
 // ---- split-row parameters (gather path) -----------------------------------
@@ -82,13 +83,13 @@ struct WorkspacePlan {
   size_t total_bytes;
 };
 
-constexpr int kPartialStride = 68;    // floats per row partial: acc[64], m, l, 2 pad
+// A row partial of the split-row path is d + 4 floats: acc[d], m, l, 2 pad.
 
 // Sizes every region for (L, H, nnz, dtype); nnz < 0 means implicit mask (no tile lists).
 // Evaluated identically on the host (sga_workspace_bytes) and inside the kernels
 // (with nnz = row_ptr[L]), so no layout has to be passed around.
 __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, int64_t nnz,
-                                                        int32_t dtype) {
+                                                        int32_t dtype, int32_t d = kHeadDim) {
   WorkspacePlan p{};
   size_t off = 256;   // counters
   const int64_t e = nnz < 0 ? 0 : nnz;
@@ -104,7 +105,7 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   p.off_long = off;
   off = (off + (size_t)cap * 16 + 255) & ~size_t(255);
   p.off_partials = off;
-  off = (off + (size_t)cap * H * kPartialStride * sizeof(float) + 255) & ~size_t(255);
+  off = (off + (size_t)cap * H * (d + 4) * sizeof(float) + 255) & ~size_t(255);
   // tile path
   const bool tiles = nnz >= 0;
   p.n_tiles = tiles ? (L + kTile - 1) / kTile : 0;
@@ -179,6 +180,7 @@ struct AttnArgs {
   int32_t H;
   float scale;
   int32_t dtype;
+  int32_t d;           // head dimension
   hipStream_t stream;
   // explicit
   const int64_t* row_ptr;

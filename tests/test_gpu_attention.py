@@ -296,3 +296,53 @@ def test_sequential_composition_equals_single_mask(dtype, path):
     sga.attention_accumulate(dQ, dK, dV, rp3, ci3, wl.scale, O, lse, workspace=ws3, path=path)
     O3_ref, lse3_ref = R.attention_dense(Q[0], K[0], V[0], covered | extra, wl.scale)
     _close(O[0].cpu().numpy(), lse[0].cpu().numpy(), O3_ref, lse3_ref, dtype, factor=3.0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("d", [32, 128, 256])
+def test_other_head_dimensions(d, dtype):
+    """Head dimensions of the paper's verification (d_k = 32, Section V-A) and microbenchmark
+    runs (128, 256, Section V-C): explicit CSR incl. split rows and empty rows, implicit window,
+    dilated, 2-D dilated and non-local masks, and a composed local + non-local pass."""
+    print("case d", d, dtype, flush=True)
+    for spec, implicit in [(MaskSpec(KIND_GLOBAL_LOCAL, 2600, window=9, n_global=3), False),
+                           (MaskSpec(KIND_SLIDING, 700, window=20), True),
+                           (MaskSpec(KIND_DILATED, 700, window=11, stride=3), True),
+                           (MaskSpec(KIND_DILATED_2D, 700, block=50, stride=2), True),
+                           (MaskSpec(KIND_NONLOCAL, 2600, window=9, n_global=3), True)]:
+        wl = Workload("t", H=2, L=spec.L, d=d, dtype=dtype, sigma=0.8, mask=spec, explicit=True, seed=61)
+        Q, K, V = small_inputs(wl)
+        O_ref, lse_ref = oracle_full(wl, Q, K, V)
+        O, lse = _run_explicit(wl, Q, K, V, sga.PATH_AUTO)
+        _close(O, lse, O_ref, lse_ref, dtype)
+        O, lse = _run_explicit(wl, Q, K, V, sga.PATH_GATHER, with_ws=False)
+        _close(O, lse, O_ref, lse_ref, dtype)
+        if implicit:
+            O, lse = _run_implicit(wl, Q, K, V, sga.PATH_AUTO)
+            _close(O, lse, O_ref, lse_ref, dtype)
+    # Bernoulli mask with empty rows (the verification protocol's kind of mask)
+    L = 300
+    rng = np.random.default_rng(8)
+    dense = rng.random((L, L)) < 0.02
+    wl = Workload("t", H=1, L=L, d=d, dtype=dtype, sigma=1.0, mask=MaskSpec(KIND_SLIDING, L), explicit=True,
+                  seed=62)
+    Q, K, V = small_inputs(wl)
+    dQ, dK, dV = to_device(Q, K, V)
+    rp, ci = R.csr_from_dense(dense)
+    import torch
+    rp = torch.from_numpy(rp).cuda()
+    ci_t = torch.from_numpy(ci).cuda() if len(ci) else torch.empty(0, dtype=torch.int32, device="cuda")
+    ws = sga.alloc_workspace(L, 1, d, dtype, int(rp[-1]))
+    O, lse = sga.attention_forward(dQ, dK, dV, rp, ci_t, wl.scale, workspace=ws, want_lse=True)
+    O_ref, lse_ref = R.attention_dense(Q[0], K[0], V[0], dense, wl.scale)
+    _close(O[0].cpu().numpy(), lse[0].cpu().numpy(), O_ref, lse_ref, dtype)
+    # composition on one state
+    loc, nl = MaskSpec(KIND_SLIDING, L, window=5), MaskSpec(KIND_NONLOCAL, L, window=5, n_global=2)
+    wsi = sga.alloc_workspace(L, 1, d, dtype, -1)
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O, lse, workspace=wsi)
+    O_ref, lse_ref = R.attention_masked(Q, K, V, MaskSpec(KIND_GLOBAL_LOCAL, L, window=5, n_global=2), wl.scale)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    # the tile kernels exist for d = 64 only
+    with pytest.raises(sga.SgaError):
+        sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, path=sga.PATH_TILE)
