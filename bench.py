@@ -289,7 +289,7 @@ def suite_table3(path):
     return {"suite": "table3", "unit": "ms per forward (sga_attention_forward_implicit)", "rows": rows}
 
 
-def suite_e2(path, dims=(64,)):
+def suite_e2(path, dims=(64, 128, 256)):
     """The shapes of the paper's microbenchmark (Section V-C): L in {8192, 16384, 24576}, one
     head, fp32, sparsity factors across (0, 1], masks sized to the sparsity factor: local,
     1-D dilated (r = 1), 2-D dilated (r = 1), global with the smallest local window, and a
