@@ -488,20 +488,6 @@ struct CoreF16 {
     }
   }
 
-  __device__ static void load_k(const __half* __restrict__ Kh, const BlockInfo& b, int64_t stride_bytes,
-                                uint32_t lane_off, int n, int h, half8 (&kf)[4]) {
-    const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * Stage::kRowBytes;
-    const half8* kp;
-    if (b.nvalid == kTile) {
-      kp = reinterpret_cast<const half8*>(base + lane_off);
-    } else {
-      const int krow = n < b.nvalid ? n : b.nvalid - 1;
-      kp = reinterpret_cast<const half8*>(base + krow * stride_bytes + h * 64);
-    }
-#pragma unroll
-    for (int s = 0; s < 4; ++s) kf[s] = kp[s];
-  }
-
   // 4 keys x 1 channel per lane out of the row-major staged V block, using the LDS transpose
   // read of gfx950: inside a 16-lane group, lane i receives element (i % 4) of the 8 bytes
   // addressed by lanes i/4, 4 + i/4, 8 + i/4 and 12 + i/4.  Lane i therefore addresses key
@@ -581,44 +567,87 @@ struct CoreF16 {
     }
   }
 
-  // Same pipeline as CoreF32::run_regk.
+  // Two neighbouring 32-query sub-tiles in one wavefront (this->qf holds the first, qb the
+  // second): every staged K and V block, the K fragment read and the V^T operand reads serve
+  // both, and the two chains of products are independent of each other.  The block lists of
+  // the two sub-tiles (sa, sb) must start at the same key; a block outside a sub-tile's window
+  // (mask words all zero) is skipped for that sub-tile.  Pipeline as in run_ldsk.
   template <typename Src>
-  __device__ void run_regk(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
-                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
-    if (k0 >= k1) return;
+  __device__ void run_pair(const half8 (&qb)[4], const __half* __restrict__ Kh,
+                           const __half* __restrict__ Vh, const Src& sa, const Src& sb, int k1, float c,
+                           int lane, TileState& sta, TileState& stb, char* lds) {
+    if (k1 <= 0) return;
     const int n = lane & 31, h = lane >> 5;
     Stage sm;
-    sm.init(src.key_stride(), lane);
-    const uint32_t klane = (uint32_t)(n * sm.stride_bytes) + h * 64;
-    BlockInfo b = src.get(k0, n);
-    BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
-    src.resolve(b);
-    half8 kf_next[4];
-    load_k(Kh, b, sm.stride_bytes, klane, n, h, kf_next);
-    for (int k = k0; k < k1; ++k) {
-      src.resolve(b1);
-      half8 kf[4];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) kf[s] = kf_next[s];
-      if (k + 1 < k1) load_k(Kh, b1, sm.stride_bytes, klane, n, h, kf_next);
+    sm.init(sa.key_stride(), lane);
+    char* ldsk = lds;
+    char* ldsv = lds + kBlockBytes;
+    BlockInfo ba = sa.get(0, n), bb = sb.get(0, n);
+    __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
+    sm.stage_k(Kh, ba, lane, ldsk);
+    const int i16 = lane & 15, grp16 = (lane >> 4) & 1;
+    const char* vt = ldsv + (4 * h + (i16 >> 2)) * (kHeadDim * 2) + (grp16 * 16 + 4 * (i16 & 3)) * 2;
+    for (int k = 0; k < k1; ++k) {
+      const bool more = k + 1 < k1;      // wave-uniform
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-      sm.stage_v(Vh, b, lane, lds);
-      BlockInfo b2 = b1;
-      if (k + 2 < k1) b2 = src.get(k + 2, n);
-      block_math(kf, b, c, lane, h, st, lds, [] { wait_loads_except<0>(); });
-      b = b1;
-      b1 = b2;
+      sm.stage_v(Vh, ba, lane, ldsv);
+      const BlockInfo na = sa.get(more ? k + 1 : k, n), nb = sb.get(more ? k + 1 : k, n);
+      wait_loads_except<4>();            // K block k is older than the 4 V copies just issued
+      __builtin_amdgcn_wave_barrier();
+      half8 kf[4];
+      read_k(ldsk, n, h, kf);
+      wait_lds_reads();                  // the K buffer may be overwritten now
+      __builtin_amdgcn_wave_barrier();
+      if (more) sm.stage_k(Kh, na, lane, ldsk);
+      const bool act_a = __builtin_amdgcn_ballot_w64(ba.word != 0) != 0;
+      const bool act_b = __builtin_amdgcn_ballot_w64(bb.word != 0) != 0;
+      floatx16 sacc_a = {0}, sacc_b = {0};
+      if (act_a) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          sacc_a = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qf[t], sacc_a, 0, 0, 0);
+      }
+      if (act_b) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+          sacc_b = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qb[t], sacc_b, 0, 0, 0);
+      }
+      float pa[16], pb[16];
+      if (act_a) softmax_block(sacc_a, c, ba, h, sta, pa);
+      if (act_b) softmax_block(sacc_b, c, bb, h, stb, pb);
+      // V block k is older than the 4 K copies issued above (if any)
+      if (more) wait_loads_except<4>(); else wait_loads_except<0>();
+      __builtin_amdgcn_wave_barrier();
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        half8 pha, phb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          pha[e] = act_a ? (_Float16)pa[8 * u + e] : (_Float16)0;
+          phb[e] = act_b ? (_Float16)pb[8 * u + e] : (_Float16)0;
+        }
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          const half4 lo = read_vt(vt + (16 * u) * (kHeadDim * 2) + cb * 64);
+          const half4 hi = read_vt(vt + (16 * u + 8) * (kHeadDim * 2) + cb * 64);
+          const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+          if (act_a) sta.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pha, sta.o[cb], 0, 0, 0);
+          if (act_b) stb.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, phb, stb.o[cb], 0, 0, 0);
+        }
+      }
+      ba = na;
+      bb = nb;
     }
   }
 
   template <int kPipe>
-  static constexpr int lds_bytes() { return kPipe == kPipeRegK ? kBlockBytes : 2 * kBlockBytes; }
+  static constexpr int lds_bytes() { return 2 * kBlockBytes; }
 
   template <int kPipe, typename Src>
   __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
                       int k0, int k1, float c, int lane, TileState& st, char* lds) {
-    if (kPipe == kPipeLdsK) run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
-    else run_regk(Kh, Vh, src, k0, k1, c, lane, st, lds);
+    static_assert(kPipe == kPipeLdsK, "fp16 pipeline");
+    run_ldsk(Kh, Vh, src, k0, k1, c, lane, st, lds);
   }
 
   __device__ static void store_row(__half* Orow, const TileState& st, float inv, float w_prev,
@@ -1101,6 +1130,123 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h, accumulate != 0);
 }
 
+// fp16 window masks, 64 queries per wavefront: two neighbouring 32-query sub-tiles share every
+// K and V block they both need (CoreF16::run_pair), which roughly halves the staging, the LDS
+// operand reads and the per-tile set-up per query.  Same grid mapping as tile_window_kernel
+// with 256 queries per workgroup.
+__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_pair_kernel(
+    const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
+    __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
+    float scale, int accumulate) {
+  constexpr int kLds = 2 * CoreF16::kBlockBytes;
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  char* lds = lds_all + wave * kLds;
+  const int64_t chunk = gridDim.x / 8;
+  const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  if (bid >= n_groups * s) return;
+  const int64_t p = bid % s;                       // residue class
+  if (p >= L) return;
+  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
+  const int64_t u0 = ((bid / s) * 4 + wave) * (2 * kTile);
+  if (u0 >= Lc) return;
+  const int64_t hd = blockIdx.y;
+  const int64_t hoff = hd * L * kHeadDim;
+  const int64_t vlo = u0 - W > 0 ? u0 - W : 0;
+  const int64_t vhi = u0 + 2 * kTile - 1 + W < Lc - 1 ? u0 + 2 * kTile - 1 + W : Lc - 1;
+  const WindowBlocks sa{vlo, Lc, s, p, u0, W}, sb{vlo, Lc, s, p, u0 + kTile, W};
+  const int nblk = (int)((vhi - vlo) / kTile + 1);
+  const int64_t ua = u0 + n, ub = u0 + kTile + n;
+  const bool exists_a = ua < Lc, exists_b = ub < Lc;
+  const int64_t qrow_a = s * (exists_a ? ua : Lc - 1) + p, qrow_b = s * (exists_b ? ub : Lc - 1) + p;
+  CoreF16 core, core_b;
+  core.load_q(Q + hoff + qrow_a * kHeadDim, h, scale < 0.f);
+  core_b.load_q(Q + hoff + qrow_b * kHeadDim, h, scale < 0.f);
+  TileState sta, stb;
+  sta.init();
+  stb.init();
+  core.run_pair(core_b.qf, K + hoff, V + hoff, sa, sb, nblk, softmax_factor(scale), lane, sta, stb, lds);
+  float* lse_h = lse ? lse + hd * L : nullptr;
+  finish_tile<__half>(O + hoff, lse_h, qrow_a, qrow_a, exists_a, sta, h, accumulate != 0);
+  finish_tile<__half>(O + hoff, lse_h, qrow_b, qrow_b, exists_b, stb, h, accumulate != 0);
+}
+
+// fp16 window masks narrow enough that the keys of 128 consecutive queries fit the LDS
+// (128 + 2W <= 256 keys: K and V blocks of 8 x 32 keys, 64 KB).  A workgroup owns 128 queries
+// of one residue class: its four wavefronts first copy every K and V block the workgroup
+// needs global -> LDS, once (wavefront w copies blocks w, w+4), and after one barrier each
+// wavefront runs its own 32-query sub-tile entirely out of LDS.  Compared with one wavefront
+// staging its own blocks, neighbouring sub-tiles no longer fetch the blocks they share four
+// times, and the block loop holds no memory instruction and no wait.  Grid mapping as in
+// tile_window_kernel.
+constexpr int kWgBlocks = 8;
+
+__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_wg_kernel(
+    const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
+    __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
+    float scale, int accumulate) {
+  __shared__ __attribute__((aligned(16))) char lds_k[kWgBlocks * CoreF16::kBlockBytes];
+  __shared__ __attribute__((aligned(16))) char lds_v[kWgBlocks * CoreF16::kBlockBytes];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  // (workgroup indices fit 32 bits: the host checks the grid size; 32-bit division by the
+  // stride is several times shorter than the 64-bit one)
+  const uint32_t chunk = gridDim.x / 8;
+  const uint32_t bid = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  const uint32_t s32 = (uint32_t)s;
+  if ((int64_t)bid >= n_groups * s) return;
+  const uint32_t grp = bid / s32;
+  const int64_t p = bid - grp * s32;               // residue class
+  if (p >= L) return;
+  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
+  const int64_t q0 = (int64_t)grp * (4 * kTile);   // first query of the workgroup
+  if (q0 >= Lc) return;                            // (the whole workgroup leaves: no barrier is missed)
+  const int64_t hd = blockIdx.y;
+  const int64_t hoff = hd * L * kHeadDim;
+  const int64_t vfirst = q0 - W > 0 ? q0 - W : 0;
+  const int64_t vlast = q0 + 4 * kTile - 1 + W < Lc - 1 ? q0 + 4 * kTile - 1 + W : Lc - 1;
+  const int nb = (int)((vlast - vfirst) / kTile + 1);          // <= kWgBlocks
+  CoreF16::Stage sm;
+  sm.init(s, lane);
+  for (int j = wave; j < nb; j += 4) {
+    BlockInfo b;
+    const int64_t v0 = vfirst + (int64_t)j * kTile;
+    b.raw = 0;
+    b.row0 = s * v0 + p;
+    b.nvalid = Lc - v0 < kTile ? (int)(Lc - v0) : kTile;
+    b.word = 0;
+    b.full = false;
+    sm.stage_k(K + hoff, b, lane, lds_k + j * CoreF16::kBlockBytes);
+    sm.stage_v(V + hoff, b, lane, lds_v + j * CoreF16::kBlockBytes);
+  }
+  const int64_t u0 = q0 + (int64_t)wave * kTile;
+  const int64_t u = u0 + n;
+  const bool exists = u < Lc;
+  const int64_t qrow = s * (exists ? u : Lc - 1) + p;
+  CoreF16 core;
+  core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
+  wait_loads_except<0>();
+  __syncthreads();
+  if (u0 >= Lc) return;
+  const WindowBlocks src{vfirst, Lc, s, p, u0, W};
+  const int64_t lo_key = u0 - W > vfirst ? u0 - W : vfirst;
+  const int64_t hi_key = u0 + kTile - 1 + W < vlast ? u0 + kTile - 1 + W : vlast;
+  const int k_lo = (int)((lo_key - vfirst) / kTile), k_hi = (int)((hi_key - vfirst) / kTile);
+  const float c = softmax_factor(scale);
+  TileState st;
+  st.init();
+  for (int k = k_lo; k <= k_hi; ++k) {
+    const BlockInfo b = src.get(k, n);
+    half8 kf[4];
+    CoreF16::read_k(lds_k + k * CoreF16::kBlockBytes, n, h, kf);
+    core.block_math(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, [] {});
+  }
+  finish_tile<__half>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h, accumulate != 0);
+}
+
 template <typename T>
 sga_status run_tile_explicit(const AttnArgs& a) {
   const T* Q = static_cast<const T*>(a.Q);
@@ -1134,29 +1280,31 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   return hip_status(hipGetLastError());
 }
 
-template <typename T>
 sga_status run_tile_implicit(const AttnArgs& a) {
   const int64_t s = a.stride;
   const int64_t Lc = (a.L + s - 1) / s;                 // tokens of the largest residue class
-  const int64_t n_tiles = (Lc + kTile - 1) / kTile;
+  // fp16, 128 queries' key range fits the LDS: one workgroup stages it once (128 queries per
+  // workgroup, as in the fp32 kernel); wider fp16 windows: 64 queries per wavefront
+  const bool wg = a.dtype == SGA_F16 && 4 * kTile + 2 * (int64_t)a.window <= kWgBlocks * kTile;
+  const bool pair = a.dtype == SGA_F16 && !wg;
+  const int64_t per_wave = pair ? 2 * kTile : kTile;
+  const int64_t n_tiles = (Lc + per_wave - 1) / per_wave;
   const int64_t n_groups = (n_tiles + 3) / 4;           // workgroups per class
   const int64_t n_wg = (n_groups * s + 7) / 8 * 8;
   if (n_wg >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;
   const dim3 grid((unsigned)n_wg, (unsigned)a.H);
-  // fp16 windows of four or more key blocks per tile stage K in LDS; narrow windows and fp32 load
-  // the K fragment straight into registers (measured best)
-  const bool lds_k = a.dtype == SGA_F16 && 2 * (int64_t)a.window + kTile > 3 * kTile;
+  const int acc = a.accumulate ? 1 : 0;
   profile_mark_begin(a.stream);
-  if (lds_k) {
-    hipLaunchKernelGGL((tile_window_kernel<T, kPipeLdsK>), grid, dim3(256), 0, a.stream,
-                       static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
-                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale,
-                       a.accumulate ? 1 : 0);
+  if (a.dtype == SGA_F16) {
+    auto kernel = wg ? tile_window_wg_kernel : tile_window_pair_kernel;
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, a.stream, static_cast<const __half*>(a.Q),
+                       static_cast<const __half*>(a.K), static_cast<const __half*>(a.V),
+                       static_cast<__half*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale, acc);
   } else {
-    hipLaunchKernelGGL((tile_window_kernel<T, kPipeRegK>), grid, dim3(256), 0, a.stream,
-                       static_cast<const T*>(a.Q), static_cast<const T*>(a.K), static_cast<const T*>(a.V),
-                       static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale,
-                       a.accumulate ? 1 : 0);
+    hipLaunchKernelGGL((tile_window_kernel<float, kPipeRegK>), grid, dim3(256), 0, a.stream,
+                       static_cast<const float*>(a.Q), static_cast<const float*>(a.K),
+                       static_cast<const float*>(a.V), static_cast<float*>(a.O), a.lse, a.L,
+                       (int64_t)a.window, s, n_groups, a.scale, acc);
   }
   profile_mark_end(a.stream);
   return hip_status(hipGetLastError());
@@ -1175,7 +1323,7 @@ sga_status launch_tile_explicit(const AttnArgs& a) {
 sga_status launch_tile_implicit(const AttnArgs& a) {
   // (the tile kernels keep per-lane row offsets in 32 bits, which bounds the stride)
   if (a.H > 65535 || a.stride > (1 << 20)) return launch_gather_implicit(a);
-  return a.dtype == SGA_F32 ? run_tile_implicit<float>(a) : run_tile_implicit<__half>(a);
+  return run_tile_implicit(a);
 }
 
 }  // namespace sga
