@@ -60,6 +60,15 @@ __device__ __forceinline__ void wait_loads_except() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// The value held by the lane 32 positions away (the same query in the other half-wave), by the
+// gfx950 half-wave swap: one vector instruction instead of a round trip through the LDS
+// permute network.  h = lane / 32.
+__device__ __forceinline__ float other_half(float x, int h) {
+  const unsigned xi = __builtin_bit_cast(unsigned, x);
+  const auto r = __builtin_amdgcn_permlane32_swap(xi, xi, false, false);
+  return __builtin_bit_cast(float, h ? r[0] : r[1]);
+}
+
 // s_waitcnt lgkmcnt(0): every LDS read issued so far has returned its data.
 __device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
 
@@ -181,7 +190,7 @@ __device__ __forceinline__ void softmax_block(floatx16 sv, float c, const BlockI
   }
 #pragma unroll
   for (int r = 0; r < 16; ++r) bm = fmaxf(bm, sv[r]);
-  bm = fmaxf(bm, __shfl_xor(bm, 32, kWave)) * c;
+  bm = fmaxf(bm, other_half(bm, h)) * c;
   if (__any(bm > st.m + kRescaleSlack)) {
     const float m_new = bm > st.m + kRescaleSlack ? bm : st.m;
     const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
@@ -683,7 +692,7 @@ template <> struct CoreOf<__half> { using type = CoreF16; };
 template <typename T>
 __device__ __forceinline__ void finish_tile(T* Oh, float* lse_h, int64_t row, int64_t lse_idx,
                                             bool exists, TileState& st, int h, bool accumulate) {
-  const float l = st.l + __shfl_xor(st.l, 32, kWave);
+  const float l = st.l + other_half(st.l, h);
   if (!exists) return;
   const bool empty = !(l > 0.f);
   float inv = empty ? 0.f : 1.0f / l;
@@ -701,7 +710,7 @@ __device__ __forceinline__ void finish_tile(T* Oh, float* lse_h, int64_t row, in
 
 // Un-normalised partial of a chunk: o[32][64], m[32], l[32].
 __device__ __forceinline__ void store_partial(float* part, TileState& st, int n, int h) {
-  const float l = st.l + __shfl_xor(st.l, 32, kWave);
+  const float l = st.l + other_half(st.l, h);
 #pragma unroll
   for (int cb = 0; cb < 2; ++cb)
 #pragma unroll
@@ -1179,16 +1188,19 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
 // needs global -> LDS, once (wavefront w copies blocks w, w+4), and after one barrier each
 // wavefront runs its own 32-query sub-tile entirely out of LDS.  Compared with one wavefront
 // staging its own blocks, neighbouring sub-tiles no longer fetch the blocks they share four
-// times, and the block loop holds no memory instruction and no wait.  Grid mapping as in
+// times, and the block loop holds no memory instruction and no wait.  The LDS is sized to the
+// window at launch, so narrow windows run up to four workgroups per CU.  Grid mapping as in
 // tile_window_kernel.
 constexpr int kWgBlocks = 8;
 
-__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_wg_kernel(
+__global__ __launch_bounds__(256) void tile_window_wg_kernel(
     const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
     __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
-    float scale, int accumulate) {
-  __shared__ __attribute__((aligned(16))) char lds_k[kWgBlocks * CoreF16::kBlockBytes];
-  __shared__ __attribute__((aligned(16))) char lds_v[kWgBlocks * CoreF16::kBlockBytes];
+    float scale, int accumulate, int nb_max) {
+  // nb_max K blocks, then nb_max V blocks (dynamic: narrow windows leave room for more workgroups)
+  extern __shared__ __attribute__((aligned(16))) char lds_wg[];
+  char* lds_k = lds_wg;
+  char* lds_v = lds_wg + nb_max * CoreF16::kBlockBytes;
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int n = lane & 31, h = lane >> 5;
@@ -1295,11 +1307,17 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const dim3 grid((unsigned)n_wg, (unsigned)a.H);
   const int acc = a.accumulate ? 1 : 0;
   profile_mark_begin(a.stream);
-  if (a.dtype == SGA_F16) {
-    auto kernel = wg ? tile_window_wg_kernel : tile_window_pair_kernel;
-    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, a.stream, static_cast<const __half*>(a.Q),
-                       static_cast<const __half*>(a.K), static_cast<const __half*>(a.V),
-                       static_cast<__half*>(a.O), a.lse, a.L, (int64_t)a.window, s, n_groups, a.scale, acc);
+  if (wg) {
+    const int nb_max = (int)((4 * kTile - 1 + 2 * (int64_t)a.window) / kTile + 1);
+    hipLaunchKernelGGL(tile_window_wg_kernel, grid, dim3(256), (size_t)nb_max * 2 * CoreF16::kBlockBytes,
+                       a.stream, static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
+                       static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
+                       (int64_t)a.window, s, n_groups, a.scale, acc, nb_max);
+  } else if (pair) {
+    hipLaunchKernelGGL(tile_window_pair_kernel, grid, dim3(256), 0, a.stream,
+                       static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
+                       static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
+                       (int64_t)a.window, s, n_groups, a.scale, acc);
   } else {
     hipLaunchKernelGGL((tile_window_kernel<float, kPipeRegK>), grid, dim3(256), 0, a.stream,
                        static_cast<const float*>(a.Q), static_cast<const float*>(a.K),
