@@ -98,8 +98,15 @@ typedef struct {
 typedef enum {
   SGA_PATH_AUTO = 0,    /* tile path where the mask is block-dense enough, gather elsewhere */
   SGA_PATH_GATHER = 1,  /* one wavefront per query row, per-edge K/V row gathers           */
-  SGA_PATH_TILE = 2     /* 32x32 MFMA tiles with per-tile bit masks; rows whose tile does
+  SGA_PATH_TILE = 2,    /* 32x32 MFMA tiles with per-tile bit masks; rows whose tile does
                            not qualify still go through the gather kernels                */
+  SGA_PATH_TILE_SPLIT = 3 /* SGA_PATH_TILE for fp32 storage with the products evaluated on the
+                           fp16 matrix cores: every fp32 operand x is split into fp16(x) and an
+                           fp16 remainder, and a.b becomes three fp16 products accumulated in
+                           fp32 (the "tensor cores" direction named under Limitations and Future Directions, kept
+                           at fp32 accuracy: the dropped terms are below 2^-23 |a.b|).  Opt-in:
+                           inputs must lie inside the fp16 range, |x| < 65504; SGA_F32 and
+                           d = 64 only (else SGA_ERR_UNSUPPORTED)                          */
 } sga_path;
 
 const char* sga_status_string(sga_status s);

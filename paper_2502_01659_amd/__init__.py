@@ -4,7 +4,7 @@ Thin Python binding over the C ABI of libsga.so (include/sga.h).  Every step of
 the attention path runs in the HIP kernels; Python only marshals arguments, and
 PyTorch only provides device memory and streams.
 """
-from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, load, lib_path,
+from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, PATH_TILE_SPLIT, load, lib_path,
                       mask_nnz, build_mask, workspace_bytes, alloc_workspace,
                       attention_forward, attention_forward_implicit,
                       attention_accumulate, attention_accumulate_implicit,
@@ -14,7 +14,7 @@ from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, load, lib_pat
                       sga_status_string, sga_profile_enable, sga_profile_collect)
 
 __all__ = [
-    "SgaError", "PATH_AUTO", "PATH_GATHER", "PATH_TILE", "load", "lib_path",
+    "SgaError", "PATH_AUTO", "PATH_GATHER", "PATH_TILE", "PATH_TILE_SPLIT", "load", "lib_path",
     "mask_nnz", "build_mask", "workspace_bytes", "alloc_workspace",
     "attention_forward", "attention_forward_implicit",
     "attention_accumulate", "attention_accumulate_implicit",

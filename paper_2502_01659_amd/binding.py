@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.environ.get("SGA_LIB", os.path.join(_HERE, "libsga.so"))
 _lib = None
 
-PATH_AUTO, PATH_GATHER, PATH_TILE = 0, 1, 2
+PATH_AUTO, PATH_GATHER, PATH_TILE, PATH_TILE_SPLIT = 0, 1, 2, 3
 _DTYPE_CODE = {"f32": 0, "f16": 1}
 
 

@@ -24,8 +24,10 @@ sga_status check_common(const void* Q, const void* K, const void* V, const void*
   if (!Q || !K || !V || !O) return SGA_ERR_INVALID_ARG;
   if (L < 1 || L >= (int64_t(1) << 31) || H < 1 || H > 65535) return SGA_ERR_INVALID_ARG;
   if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
-  if (path != SGA_PATH_AUTO && path != SGA_PATH_GATHER && path != SGA_PATH_TILE)
+  if (path != SGA_PATH_AUTO && path != SGA_PATH_GATHER && path != SGA_PATH_TILE &&
+      path != SGA_PATH_TILE_SPLIT)
     return SGA_ERR_INVALID_ARG;
+  if (path == SGA_PATH_TILE_SPLIT && (dtype != SGA_F32 || d != kHeadDim)) return SGA_ERR_UNSUPPORTED;
   if (d != 32 && d != 64 && d != 128 && d != 256) return SGA_ERR_UNSUPPORTED;
   if (path == SGA_PATH_TILE && d != kHeadDim) return SGA_ERR_UNSUPPORTED;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return SGA_ERR_INVALID_ARG;
@@ -142,7 +144,9 @@ sga_status run_explicit_call(const void* Q, const void* K, const void* V, const 
   a.row_ptr = row_ptr; a.col_idx = col_idx;
   a.ws = workspace; a.ws_bytes = workspace_bytes;
   a.accumulate = accumulate;
-  if (path == SGA_PATH_TILE && (!workspace || workspace_bytes < 256)) return SGA_ERR_WORKSPACE;
+  a.split = path == SGA_PATH_TILE_SPLIT;
+  if ((path == SGA_PATH_TILE || path == SGA_PATH_TILE_SPLIT) && (!workspace || workspace_bytes < 256))
+    return SGA_ERR_WORKSPACE;
   // the MFMA tile kernels exist for d = 64; other head dimensions run on the per-row kernels
   const bool gather_only = path == SGA_PATH_GATHER || d != kHeadDim;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
@@ -177,6 +181,7 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
   a.block = desc->block;
   a.ws = workspace; a.ws_bytes = workspace_bytes;
   a.accumulate = accumulate;
+  a.split = path == SGA_PATH_TILE_SPLIT;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   if (kind == SGA_MASK_NONLOCAL) {
     const int64_t g = desc->n_global < L ? desc->n_global : L;

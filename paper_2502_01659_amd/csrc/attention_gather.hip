@@ -556,7 +556,7 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   }
   // after the tile path only leftover rows remain: a small grid strides over the rows
   int64_t nwg = (a.L + 3) / 4;
-  if (skip_tiled && nwg > 2048) nwg = 2048;
+  if (skip_tiled && nwg > 256) nwg = 256;
   const dim3 grid((unsigned)nwg, (unsigned)a.H);
   if (!skip_tiled) profile_mark_begin(a.stream);
   hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
@@ -564,7 +564,7 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
                      skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
   if (!skip_tiled) profile_mark_end(a.stream);
   if (split) {
-    hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
+    hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
     hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
                        a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);

@@ -75,6 +75,7 @@ __device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0x
 // K/V pipelines of the tile kernels (template parameter kPipe).
 constexpr int kPipeRegK = 0;   // K fragment prefetched into registers, V block staged in LDS
 constexpr int kPipeLdsK = 1;   // K and V blocks staged in LDS, one block ahead
+constexpr int kPipeSplit = 2;  // fp32 storage, products as three fp16 matrix-core terms (CoreSplit)
 
 struct BlockInfo {
   int raw;          // explicit masks: block record as loaded (row0, nvalid, full follow from it)
@@ -175,7 +176,8 @@ __device__ __forceinline__ float softmax_factor(float scale) {
 // into the sign of Q by the caller), so the block maximum can be taken over the raw products
 // and the scaling fused into the exponent: p = 2^(c*s - m).
 __device__ __forceinline__ void softmax_block(floatx16 sv, float c, const BlockInfo& b, int h,
-                                              TileState& st, float (&p)[16]) {
+                                              TileState& st, float (&p)[16],
+                                              floatx16* o_low = nullptr) {
   float bm = -INFINITY;
   if (!b.full) {
     const uint32_t wh = b.word >> (4 * h);
@@ -200,6 +202,13 @@ __device__ __forceinline__ void softmax_block(floatx16 sv, float c, const BlockI
     for (int r = 0; r < 16; ++r) {
       st.o[0][r] *= alpha;
       st.o[1][r] *= alpha;
+    }
+    if (o_low) {       // low-order accumulators of the split-precision core
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        o_low[0][r] *= alpha;
+        o_low[1][r] *= alpha;
+      }
     }
   }
   float lsum = 0.f;
@@ -684,9 +693,163 @@ struct CoreF16 {
   }
 };
 
+// ---- fp32 storage, split-precision products -----------------------------------------------------
+// Every fp32 operand x is written as hi + lo with hi = fp16(x) and lo = fp16(x - hi) (x - hi is
+// exact in fp32), and a product a.b is evaluated as hi_a.hi_b + hi_a.lo_b + lo_a.hi_b on the
+// fp16 matrix cores, all three terms into the same fp32 accumulator.  The dropped term
+// lo_a.lo_b and the rounding of lo are below 2^-22 |a.b|, the size of an fp32 rounding error,
+// so results match the true-fp32 kernels to their tolerance while the matrix work drops from
+// 64 fp32 MFMAs (4096 cycles) to 24 fp16 MFMAs (768 cycles) per block.  lo is a subnormal fp16
+// number for |x| < 0.25 (the matrix cores do not flush them); below |x| ~ 2^-13 it loses bits,
+// an absolute error of at most 2^-25 per operand.  Inputs must lie inside the fp16 range
+// (|x| < 65504); the caller opts in (SGA_PATH_TILE_SPLIT).
+// K and V blocks travel global -> LDS as raw fp32 (as in CoreF32::run_ldsk); K is split when
+// its fragment is read, V is split in registers and written back over its own staged block as
+// two row-major fp16 blocks, which the PV products read with the LDS transpose read.
+struct CoreSplit {
+  using Stage = StageMap<float>;
+  static constexpr int kBlockBytes = kTile * kHeadDim * 4;
+  half8 qh[4], ql[4];   // Q[query n][h*32 + 8s .. +7], high and low parts
+
+  __device__ static void split8(const float* x, half8& hi, half8& lo) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const _Float16 hv = (_Float16)x[e];
+      hi[e] = hv;
+      lo[e] = (_Float16)(x[e] - (float)hv);
+    }
+  }
+
+  __device__ void load_q(const float* Qrow, int h, bool negate) {
+    float q[32];
+    const float4* src = reinterpret_cast<const float4*>(Qrow + h * 32);
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const float4 v = src[t];
+      q[4 * t] = v.x; q[4 * t + 1] = v.y; q[4 * t + 2] = v.z; q[4 * t + 3] = v.w;
+    }
+    if (negate) {
+#pragma unroll
+      for (int t = 0; t < 32; ++t) q[t] = -q[t];
+    }
+#pragma unroll
+    for (int s = 0; s < 4; ++s) split8(q + 8 * s, qh[s], ql[s]);
+  }
+
+  template <int kPipe>
+  static constexpr int lds_bytes() { return 2 * kBlockBytes; }
+
+  template <int kPipe, typename Src>
+  __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
+                      int k0, int k1, float c, int lane, TileState& st, char* lds) {
+    if (k0 >= k1) return;
+    const int n = lane & 31, h = lane >> 5;
+    Stage sm;
+    sm.init(src.key_stride(), lane);
+    char* ldsk = lds;
+    char* ldsv = lds + kBlockBytes;
+    BlockInfo b = src.get(k0, n);
+    BlockInfo b1 = src.get(k0 + 1 < k1 ? k0 + 1 : k0, n);
+    src.resolve(b);
+    __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
+    sm.stage_k(Kh, b, lane, ldsk);
+    // this lane's part of the row-major staged V block: copy i moved 16 bytes to dst + i*1024 + lane*16
+    const int lr = lane >> 4, lc = lane & 15;
+    const int i16 = lane & 15, grp16 = (lane >> 4) & 1;
+    const char* vt = ldsv + (4 * h + (i16 >> 2)) * (kHeadDim * 2) + (grp16 * 16 + 4 * (i16 & 3)) * 2;
+    for (int k = k0; k < k1; ++k) {
+      const bool more = k + 1 < k1;      // wave-uniform
+      src.resolve(b1);
+      __builtin_amdgcn_wave_barrier();   // the previous block's reads of the V buffer are done
+      sm.stage_v(Vh, b, lane, ldsv);
+      BlockInfo b2 = b1;
+      if (k + 2 < k1) b2 = src.get(k + 2, n);
+      wait_loads_except<8>();            // K block k is older than the 8 V copies just issued
+      __builtin_amdgcn_wave_barrier();
+      half8 kh[4], kl[4];
+      {
+        float kf[32];
+        CoreF32::read_k(ldsk, n, h, kf);
+        wait_lds_reads();                // the K buffer may be overwritten now
+        __builtin_amdgcn_wave_barrier();
+        if (more) sm.stage_k(Kh, b1, lane, ldsk);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) split8(kf + 8 * s, kh[s], kl[s]);
+      }
+      floatx16 sacc = {0};
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {     // smallest terms first
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kl[s], qh[s], sacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh[s], ql[s], sacc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int s = 0; s < 4; ++s)
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh[s], qh[s], sacc, 0, 0, 0);
+      float p[16];
+      softmax_block(sacc, c, b, h, st, p);
+      // V block k is older than the 8 K copies issued above (if any)
+      if (more) wait_loads_except<8>(); else wait_loads_except<0>();
+      __builtin_amdgcn_wave_barrier();
+      {
+        // split the staged fp32 V block in place: rows 4i + lr, channels 4*lc .. +3 per copy i
+        float vraw[32];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const float4 v = *reinterpret_cast<const float4*>(ldsv + i * 1024 + lane * 16);
+          vraw[4 * i] = v.x; vraw[4 * i + 1] = v.y; vraw[4 * i + 2] = v.z; vraw[4 * i + 3] = v.w;
+        }
+        wait_lds_reads();
+        __builtin_amdgcn_wave_barrier();   // every lane holds its part: the block may be overwritten
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          half4 vh, vl;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            const _Float16 hv = (_Float16)vraw[4 * i + e];
+            vh[e] = hv;
+            vl[e] = (_Float16)(vraw[4 * i + e] - (float)hv);
+          }
+          char* row = ldsv + (4 * i + lr) * (kHeadDim * 2) + lc * 8;
+          *reinterpret_cast<half4*>(row) = vh;
+          *reinterpret_cast<half4*>(row + kTile * kHeadDim * 2) = vl;
+        }
+        __builtin_amdgcn_s_waitcnt(0xC07F);   // LDS writes have landed
+        __builtin_amdgcn_wave_barrier();
+      }
+#pragma unroll
+      for (int u = 0; u < 2; ++u) {
+        half8 ph, pl;
+        split8(p + 8 * u, ph, pl);
+#pragma unroll
+        for (int cb = 0; cb < 2; ++cb) {
+          const char* a0 = vt + (16 * u) * (kHeadDim * 2) + cb * 64;
+          const half4 hlo = CoreF16::read_vt(a0), hhi = CoreF16::read_vt(a0 + 8 * (kHeadDim * 2));
+          const half4 llo = CoreF16::read_vt(a0 + kTile * kHeadDim * 2);
+          const half4 lhi = CoreF16::read_vt(a0 + kTile * kHeadDim * 2 + 8 * (kHeadDim * 2));
+          const half8 vh = {hlo[0], hlo[1], hlo[2], hlo[3], hhi[0], hhi[1], hhi[2], hhi[3]};
+          const half8 vl = {llo[0], llo[1], llo[2], llo[3], lhi[0], lhi[1], lhi[2], lhi[3]};
+          st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vl, ph, st.o[cb], 0, 0, 0);
+          st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vh, pl, st.o[cb], 0, 0, 0);
+          st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vh, ph, st.o[cb], 0, 0, 0);
+        }
+      }
+      b = b1;
+      b1 = b2;
+    }
+  }
+
+  __device__ static void store_row(float* Orow, const TileState& st, float inv, float w_prev,
+                                   bool accumulate, int h) {
+    CoreF32::store_row(Orow, st, inv, w_prev, accumulate, h);
+  }
+};
+
 template <typename T> struct CoreOf;
 template <> struct CoreOf<float> { using type = CoreF32; };
 template <> struct CoreOf<__half> { using type = CoreF16; };
+// the core that runs pipeline kPipe on storage type T
+template <typename T, int kPipe> struct CoreFor { using type = typename CoreOf<T>::type; };
+template <> struct CoreFor<float, kPipeSplit> { using type = CoreSplit; };
 
 // Normalise and store the tile's rows (row(n) = tensor row of query n, < 0 if it does not exist).
 template <typename T>
@@ -949,7 +1112,7 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
     size_t ws_bytes, int accumulate) {
-  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kPipe>();
+  constexpr int kLds = CoreFor<T, kPipe>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int32_t H = (int32_t)gridDim.x;   // head-major grid: the long work items of every head are dispatched first
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code);
@@ -1002,7 +1165,7 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
                        reinterpret_cast<const uint32_t*>(base_ws + pl.off_pair_mask) + slot0 * kTile, L};
     const int64_t qrow = row_first + n;
     const bool exists = qrow < L;
-    typename CoreOf<T>::type core;
+    typename CoreFor<T, kPipe>::type core;
     core.load_q(Q + hoff + (exists ? qrow : L - 1) * kHeadDim, h, negate);
     TileState st;
     st.init();
@@ -1107,7 +1270,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
                                                           float* __restrict__ lse, int64_t L, int64_t W,
                                                           int64_t s, int64_t n_groups, float scale,
                                                           int accumulate) {
-  constexpr int kLds = CoreOf<T>::type::template lds_bytes<kPipe>();
+  constexpr int kLds = CoreFor<T, kPipe>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -1131,7 +1294,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   const int64_t u = u0 + n;
   const bool exists = u < Lc;
   const int64_t qrow = s * (exists ? u : Lc - 1) + p;
-  typename CoreOf<T>::type core;
+  typename CoreFor<T, kPipe>::type core;
   core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
   TileState st;
   st.init();
@@ -1283,11 +1446,12 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   profile_mark_begin(a.stream);
   // fp32 tiles keep the K fragment in registers; fp16 tiles stage K in LDS (measured best)
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
-  hipLaunchKernelGGL((tile_attend_kernel<T, kPipe>), dim3((unsigned)a.H, (unsigned)per_head), dim3(256),
-                     0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes,
-                     a.accumulate ? 1 : 0);
+  constexpr int kPipeAlt = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeSplit;
+  auto kernel = a.split ? tile_attend_kernel<T, kPipeAlt> : tile_attend_kernel<T, kPipe>;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0, a.stream, Q, K, V, O,
+                     a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   profile_mark_end(a.stream);
-  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(64, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
+  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(16, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
                      O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   return hip_status(hipGetLastError());
 }
@@ -1319,7 +1483,8 @@ sga_status run_tile_implicit(const AttnArgs& a) {
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
                        (int64_t)a.window, s, n_groups, a.scale, acc);
   } else {
-    hipLaunchKernelGGL((tile_window_kernel<float, kPipeRegK>), grid, dim3(256), 0, a.stream,
+    auto kernel = a.split ? tile_window_kernel<float, kPipeSplit> : tile_window_kernel<float, kPipeRegK>;
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, a.stream,
                        static_cast<const float*>(a.Q), static_cast<const float*>(a.K),
                        static_cast<const float*>(a.V), static_cast<float*>(a.O), a.lse, a.L,
                        (int64_t)a.window, s, n_groups, a.scale, acc);

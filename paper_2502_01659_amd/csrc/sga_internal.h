@@ -193,6 +193,8 @@ struct AttnArgs {
   int32_t block;       // implicit 2-D dilated mask
   // continue from the (O, lse) state already in the output buffers instead of overwriting it
   bool accumulate;
+  // fp32 storage: products as three fp16 matrix-core terms instead of fp32 MFMA (tile path)
+  bool split;
   // workspace
   void* ws;
   size_t ws_bytes;

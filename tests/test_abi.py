@@ -72,7 +72,12 @@ def test_forward_argument_errors_without_touching_the_gpu():
     assert f(ok, ok, ok, None, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
     assert f(ok, ok, ok, ok, ok, ok, 0, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
     assert f(ok, ok, ok, ok, ok, ok, 64, 0, 64, 0.1, None, 0, None, None, 0, 0) == -1
-    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 32, 0.1, None, 0, None, None, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 48, 0.1, None, 0, None, None, 0, 0) == -2
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 128, 0.1, None, 0, None, None, 0, sga.PATH_TILE) == -2
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 1, None, None, 0, sga.PATH_TILE_SPLIT) == -2
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, sga.PATH_TILE_SPLIT) == -3
+    a = sga.sga_attention_accumulate        # the state vector lse is required
+    assert a(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
     assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 5, None, None, 0, 0) == -1
     assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 9) == -1
     assert f(ok + 4, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
@@ -87,7 +92,8 @@ def test_forward_argument_errors_without_touching_the_gpu():
 def test_workspace_bytes():
     st, n = sga.sga_workspace_bytes(65536, 8, 64, 0, 18919024)
     assert st == 0 and n % 256 == 0 and n > 0
-    assert sga.sga_workspace_bytes(65536, 8, 128, 0, 10)[0] == -2
+    assert sga.sga_workspace_bytes(65536, 8, 96, 0, 10)[0] == -2
+    assert sga.sga_workspace_bytes(65536, 8, 128, 0, 10)[0] == 0
     assert sga.sga_workspace_bytes(0, 8, 64, 0, 10)[0] == -1
     st, n_impl = sga.sga_workspace_bytes(160_000_000, 1, 64, 1, -1)
     assert st == 0 and n_impl < (1 << 28)

@@ -346,3 +346,58 @@ def test_other_head_dimensions(d, dtype):
     # the tile kernels exist for d = 64 only
     with pytest.raises(sga.SgaError):
         sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, path=sga.PATH_TILE)
+
+
+@pytest.mark.parametrize("wl", [w for w in small_variants() if w.dtype == "f32"], ids=lambda w: w.name)
+def test_split_precision_path_small_workloads(wl):
+    """fp32 storage with the products on the fp16 matrix cores (three-term split): same
+    tolerance as the true-fp32 kernels, explicit and implicit."""
+    print("case split", wl.name, flush=True)
+    Q, K, V = small_inputs(wl)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    O, lse = _run_explicit(wl, Q, K, V, sga.PATH_TILE_SPLIT)
+    assert max_err(O, O_ref) <= TOL["f32"]
+    assert max_err(lse, lse_ref) <= 1e-4
+    if wl.mask.kind in (KIND_SLIDING, KIND_DILATED):
+        O, lse = _run_implicit(wl, Q, K, V, sga.PATH_TILE_SPLIT)
+        assert max_err(O, O_ref) <= TOL["f32"]
+        assert max_err(lse, lse_ref) <= 1e-4
+
+
+@pytest.mark.parametrize("sigma", [0.02, 1.0, 6.0])
+def test_split_precision_path_value_ranges(sigma):
+    """Small, unit and large input magnitudes (the remainders of small values are subnormal in
+    fp16 unless scaled; large scores stress the exponent), a mask with global rows (multi-
+    segment tiles), ragged tail, negative scale, and the composition call."""
+    print("case split sigma", sigma, flush=True)
+    spec = MaskSpec(KIND_GLOBAL_LOCAL, 1500, window=40, n_global=5)
+    wl = Workload("t", H=2, L=spec.L, d=64, dtype="f32", sigma=sigma, mask=spec, explicit=True, seed=71)
+    Q, K, V = small_inputs(wl)
+    dQ, dK, dV = to_device(Q, K, V)
+    rp, ci = sga.build_mask(spec)
+    ws = sga.alloc_workspace(wl.L, wl.H, 64, "f32", int(rp[-1]))
+    for scale in (wl.scale, -wl.scale):
+        O_ref, lse_ref = R.attention_masked(Q, K, V, spec, scale)
+        O, lse = sga.attention_forward(dQ, dK, dV, rp, ci, scale, workspace=ws, path=sga.PATH_TILE_SPLIT,
+                                       want_lse=True)
+        O32 = sga.attention_forward(dQ, dK, dV, rp, ci, scale, workspace=ws, path=sga.PATH_TILE)
+        # O scales with |V|; with scores of +-150 (sigma = 6) the fp32 rounding of the scores
+        # themselves dominates, so the true-fp32 kernel's own error is the yardstick there
+        tol = max(TOL["f32"] * max(1.0, sigma), 2.0 * max_err(O32.cpu().numpy(), O_ref))
+        assert max_err(O.cpu().numpy(), O_ref) <= tol
+        assert max_err(lse.cpu().numpy(), lse_ref) <= 1e-4 * max(1.0, sigma * sigma)
+    loc, nl = MaskSpec(KIND_SLIDING, spec.L, window=40), MaskSpec(KIND_NONLOCAL, spec.L, window=40, n_global=5)
+    wsi = sga.alloc_workspace(wl.L, wl.H, 64, "f32", -1)
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi,
+                                            path=sga.PATH_TILE_SPLIT, want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O, lse, workspace=wsi)
+    O32, lse32 = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi,
+                                                path=sga.PATH_TILE, want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O32, lse32, workspace=wsi)
+    O_ref, lse_ref = R.attention_masked(Q, K, V, spec, wl.scale)
+    tol = max(2 * TOL["f32"] * max(1.0, sigma), 2.0 * max_err(O32.cpu().numpy(), O_ref))
+    assert max_err(O.cpu().numpy(), O_ref) <= tol
+    # fp16 storage has no split path
+    with pytest.raises(sga.SgaError):
+        h = dQ.half()
+        sga.attention_forward_implicit(h, h, h, loc, wl.scale, path=sga.PATH_TILE_SPLIT)

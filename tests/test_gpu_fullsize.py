@@ -114,6 +114,18 @@ def test_cfg2_full_size():
         assert max_err(O[h][rows].cpu().numpy(), O_ref) <= TOL["f32"], h
         assert max_err(lse[h][rows].cpu().numpy(), lse_ref) <= 1e-4, h
     _check_ones(wl, Q, K)
+    # the split-precision path (fp16 matrix-core products) on the same problem: two heads against
+    # the oracle sample, all heads against the true-fp32 result
+    rp, ci = sga.build_mask(wl.mask)
+    ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, int(rp[-1]))
+    Os, lses = sga.attention_forward(Q, K, V, rp, ci, wl.scale, workspace=ws, path=sga.PATH_TILE_SPLIT,
+                                     want_lse=True)
+    for h in (0, wl.H - 1):
+        O_ref, lse_ref, _ = C.attend_rows(wl.mask, Q[h].cpu().numpy(), K[h].cpu().numpy(),
+                                          V[h].cpu().numpy(), wl.scale, rows)
+        assert max_err(Os[h][rows].cpu().numpy(), O_ref) <= TOL["f32"], h
+        assert max_err(lses[h][rows].cpu().numpy(), lse_ref) <= 1e-4, h
+    assert float((Os - O).abs().max()) <= 2 * TOL["f32"]
 
 
 def test_cfg3_full_size():
