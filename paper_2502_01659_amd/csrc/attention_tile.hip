@@ -1187,7 +1187,7 @@ __device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(__half* p, float v) { *p = __float2half_rn(v); }
 
 // Merge of a multi-segment tile's partial states.  grid = (tiles of the merge list, head,
-// groups of 4 rows); the 4 wavefronts of a workgroup take every 4th segment of a row, reduce
+// rows of the tile in groups of 32 / gridDim.z); the 4 wavefronts of a workgroup take every 4th segment of a row, reduce
 // theirs in segment order, and wavefront 0 combines the four results in wavefront order, so
 // the summation order is fixed.  lane = channel.
 template <typename T>
@@ -1216,7 +1216,8 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
     const int nseg = tile_segments(row_ptr, L, S, t);
     const float* p0 = parts + ((int64_t)tile_pbase[t] * H + hd) * kTilePartialFloats;
     const int64_t step = (int64_t)H * kTilePartialFloats;
-    for (int r = blockIdx.z * 4; r < blockIdx.z * 4 + 4; ++r) {
+    const int rows_per_wg = kTile / (int)gridDim.z;
+    for (int r = blockIdx.z * rows_per_wg; r < (int)(blockIdx.z + 1) * rows_per_wg; ++r) {
       const int64_t row = t * kTile + r;
       float M = kMinusHuge;
       for (int c = wave; c < nseg; c += 4) M = fmaxf(M, p0[c * step + kTile * 64 + r]);
@@ -1451,7 +1452,7 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   hipLaunchKernelGGL(kernel, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0, a.stream, Q, K, V, O,
                      a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   profile_mark_end(a.stream);
-  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(16, (unsigned)a.H, kTile / 4), dim3(256), 0, a.stream,
+  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(16, (unsigned)a.H, kTile), dim3(256), 0, a.stream,
                      O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   return hip_status(hipGetLastError());
 }
