@@ -31,11 +31,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 5_699_200,
-    "cfg2_longformer_64k": 1_091_642_472,
-    "cfg3_dilated_1m": 2_149_410_513,
-    "cfg4_bigbird_1m": 11_124_049_191,
-    "cfg5_sliding_160m": 81_918_574_954,
+    "cfg1_sliding_4k": 5_759_710,
+    "cfg2_longformer_64k": 1_111_578_474,
+    "cfg3_dilated_1m": 2_149_415_249,
+    "cfg4_bigbird_1m": 12_092_431_228,
+    "cfg5_sliding_160m": 82_545_058_653,
 }
 
 
@@ -126,8 +126,15 @@ class Runner:
         return (t1 - t0) * 1e3 / steps, fwd, bld, kern_ms
 
 
-KERNEL_NAME = {("tile", True): "tile_attend_kernel", ("tile", False): "tile_window_kernel",
-               ("gather", True): "gather_csr_kernel", ("gather", False): "gather_window_kernel"}
+def kernel_name(wl, path_used):
+    """Name of the fused attention kernel a forward of this workload launches."""
+    if path_used == "gather":
+        return "gather_csr_kernel" if wl.explicit else "gather_window_kernel"
+    if wl.explicit:
+        return "tile_attend_kernel"
+    if wl.dtype == "f16":     # narrow windows: workgroup-staged K/V; wide: two sub-tiles per wavefront
+        return "tile_window_wg_kernel" if 128 + 2 * wl.mask.window <= 256 else "tile_window_pair_kernel"
+    return "tile_window_kernel"
 
 
 def roofline_of(wl, nnz, kern_ms, path_used):
@@ -155,7 +162,7 @@ def roofline_of(wl, nnz, kern_ms, path_used):
             "hbm_algorithmic_GBps": algorithmic_bytes(wl, nnz) / t / 1e9,
             "algorithmic_bytes": algorithmic_bytes(wl, nnz),
             "algorithmic_flops": FLOPS_PER_EDGE * edges,
-            "kernel": KERNEL_NAME[(path_used, wl.explicit)], "kernel_ms": kern_ms}
+            "kernel": kernel_name(wl, path_used), "kernel_ms": kern_ms}
 
 
 def cpu_baseline(wl, runner, budget_s=12.0):
