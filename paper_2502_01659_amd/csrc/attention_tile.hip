@@ -1103,6 +1103,8 @@ __device__ __forceinline__ bool tile_parts_fit(const WorkspacePlan& pl, const vo
   return (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTilePartsNeeded] <= pl.cap_tparts;
 }
 
+constexpr uint32_t kXcdRun = 4;   // consecutive workgroups of the static schedule that share an XCD
+
 // Persistent wavefronts: every wavefront claims the next unprocessed work item of its head from
 // a device counter until none is left (items are ordered long segments first, so the greedy
 // order balances the load and no workgroup has to be re-launched between items).  A segment
@@ -1129,15 +1131,27 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
   const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
   const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
   const bool parts_fit = tile_parts_fit(pl, ws);
-  const int64_t hoff = (int64_t)blockIdx.x * L * kHeadDim;
-  uint32_t* work_next = reinterpret_cast<uint32_t*>(base_ws + pl.off_work_next) + blockIdx.x;
+  constexpr bool kDynamic = DtypeOf<T>::code == SGA_F32;
+  // Workgroups go to the 8 XCDs (each with its own L2) round-robin in launch order.  The static
+  // schedule hands every XCD runs of kXcdRun consecutive workgroups of one head, so that the key
+  // blocks neighbouring tiles share (window blocks, global blocks) are fetched into one L2 instead
+  // of several.  (gridDim.y is a multiple of 8 * kXcdRun for this schedule.)
+  uint32_t head = blockIdx.x, ywg = blockIdx.y;
+  if (!kDynamic && gridDim.y % (8 * kXcdRun) == 0) {
+    const uint32_t lin = blockIdx.x + gridDim.x * blockIdx.y;
+    const uint32_t xcd = lin & 7, slot = lin >> 3;
+    const uint32_t v = ((slot / kXcdRun) * 8 + xcd) * kXcdRun + slot % kXcdRun;
+    head = v / gridDim.y;
+    ywg = v % gridDim.y;
+  }
+  const int64_t hoff = (int64_t)head * L * kHeadDim;
+  uint32_t* work_next = reinterpret_cast<uint32_t*>(base_ws + pl.off_work_next) + head;
   // fp32 items are long (4096 matrix-core cycles per block): wavefronts stay resident and claim
   // the next item of their head from a device counter (greedy balance, no re-launch gaps).
   // fp16 items are short and bound by the memory path: the 4 wavefronts of a workgroup take 4
   // neighbouring tiles at the same time (static stride), so that the key blocks they share are
   // fetched together and hit the CU's L1.
-  constexpr bool kDynamic = DtypeOf<T>::code == SGA_F32;
-  int64_t w_static = (int64_t)blockIdx.y * 4 + wave;
+  int64_t w_static = (int64_t)ywg * 4 + wave;
   while (true) {
     int64_t w_cur;
     if (kDynamic) {
@@ -1172,10 +1186,10 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
     core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, c, lane, st, lds);
     if (nseg > 1) {
       float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
-                    (((int64_t)tile_pbase[t] + seg) * H + blockIdx.x) * (int64_t)kTilePartialFloats;
+                    (((int64_t)tile_pbase[t] + seg) * H + head) * (int64_t)kTilePartialFloats;
       store_partial(part, st, n, h);
     } else {
-      finish_tile<T>(O + hoff, lse ? lse + (int64_t)blockIdx.x * L : nullptr, qrow, qrow, exists, st, h,
+      finish_tile<T>(O + hoff, lse ? lse + (int64_t)head * L : nullptr, qrow, qrow, exists, st, h,
                      accumulate != 0);
     }
   }
@@ -1438,7 +1452,7 @@ sga_status run_tile_explicit(const AttnArgs& a) {
                      a.col_idx, a.L, a.H, a.dtype, a.ws, a.ws_bytes);
   // fp32: resident workgroups only (256 CUs x 2 wavefronts per SIMD, shared by the heads), which
   // claim items dynamically; fp16: one pass of workgroups over the items of each head
-  int64_t per_head = nwg;
+  int64_t per_head = (nwg + 8 * kXcdRun - 1) / (8 * kXcdRun) * (8 * kXcdRun);
   if (a.dtype == SGA_F32) {
     per_head = 512 / a.H;
     if (per_head < 1) per_head = 1;
