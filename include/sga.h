@@ -29,9 +29,11 @@
  *     undefined behaviour of the forward.
  *   - A row with no neighbour yields O_i = 0 and lse_i = -inf (the initial state
  *     of Algorithm 1: O = 0, l = 0, m = -inf).
- *   - Supported head dimensions: d = 64 on every path; d = 32, 128 and 256 (the other sizes of
- *     the paper's verification and microbenchmark runs, Section V-A and V-C) on the per-row
- *     kernels only (SGA_PATH_AUTO selects them; SGA_PATH_TILE returns SGA_ERR_UNSUPPORTED).
+ *   - Supported head dimensions: d = 64, 128 and 256 on every path (the sizes of the paper's
+ *     microbenchmark runs, Section V-C; the MFMA tile kernels work on 64-channel slices, one
+ *     wavefront per slice), and d = 32 (the size of the verification runs, Section V-A) on the
+ *     per-row kernels only (SGA_PATH_AUTO selects them; SGA_PATH_TILE returns
+ *     SGA_ERR_UNSUPPORTED).  SGA_PATH_TILE_SPLIT: d = 64.
  */
 #ifndef SGA_H_
 #define SGA_H_

@@ -29,7 +29,7 @@ sga_status check_common(const void* Q, const void* K, const void* V, const void*
     return SGA_ERR_INVALID_ARG;
   if (path == SGA_PATH_TILE_SPLIT && (dtype != SGA_F32 || d != kHeadDim)) return SGA_ERR_UNSUPPORTED;
   if (d != 32 && d != 64 && d != 128 && d != 256) return SGA_ERR_UNSUPPORTED;
-  if (path == SGA_PATH_TILE && d != kHeadDim) return SGA_ERR_UNSUPPORTED;
+  if (path == SGA_PATH_TILE && d < kHeadDim) return SGA_ERR_UNSUPPORTED;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return SGA_ERR_INVALID_ARG;
   if (ws && (reinterpret_cast<uintptr_t>(ws) & 255u)) return SGA_ERR_INVALID_ARG;
   if (!ws && ws_bytes != 0) return SGA_ERR_INVALID_ARG;
@@ -147,8 +147,8 @@ sga_status run_explicit_call(const void* Q, const void* K, const void* V, const 
   a.split = path == SGA_PATH_TILE_SPLIT;
   if ((path == SGA_PATH_TILE || path == SGA_PATH_TILE_SPLIT) && (!workspace || workspace_bytes < 256))
     return SGA_ERR_WORKSPACE;
-  // the MFMA tile kernels exist for d = 64; other head dimensions run on the per-row kernels
-  const bool gather_only = path == SGA_PATH_GATHER || d != kHeadDim;
+  // the MFMA tile kernels work on 64-channel slices (d = 64, 128, 256); d = 32 runs on the per-row kernels
+  const bool gather_only = path == SGA_PATH_GATHER || d < kHeadDim;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   if (workspace && workspace_bytes >= 256) clear_workspace(a, !gather_only);
   if (gather_only) return launch_gather_explicit(a, true, false);
@@ -190,7 +190,7 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
       return SGA_ERR_WORKSPACE;
     return launch_gather_implicit(a);
   }
-  if (kind == SGA_MASK_DILATED_2D || path == SGA_PATH_GATHER || d != kHeadDim)
+  if (kind == SGA_MASK_DILATED_2D || path == SGA_PATH_GATHER || d < kHeadDim)
     return launch_gather_implicit(a);
   return launch_tile_implicit(a);
 }

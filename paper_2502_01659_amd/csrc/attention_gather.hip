@@ -554,9 +554,11 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
     hipLaunchKernelGGL(split_prepass_kernel, dim3((unsigned)((a.L + 255) / 256)), dim3(256), 0,
                        a.stream, a.row_ptr, a.L, a.H, a.dtype, D, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
   }
-  // after the tile path only leftover rows remain: a small grid strides over the rows
+  // after the tile path only leftover rows remain: a grid of about one chip-full of wavefronts
+  // over all heads strides over the rows (it returns at once when the tiles covered everything)
   int64_t nwg = (a.L + 3) / 4;
-  if (skip_tiled && nwg > 256) nwg = 256;
+  const int64_t leftover_wgs = 2048 / a.H > 256 ? 2048 / a.H : 256;
+  if (skip_tiled && nwg > leftover_wgs) nwg = leftover_wgs;
   const dim3 grid((unsigned)nwg, (unsigned)a.H);
   if (!skip_tiled) profile_mark_begin(a.stream);
   hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
@@ -564,7 +566,7 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
                      skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
   if (!skip_tiled) profile_mark_end(a.stream);
   if (split) {
-    hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
+    hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled && a.H >= 8 ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
     hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
                        a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);

@@ -60,6 +60,14 @@ __device__ __forceinline__ void wait_loads_except() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
+// Waits until at most `keep` of the most recently issued vector memory operations are still in
+// flight; keep is wave-uniform and one of 0, 4, 8 (any other value: no wait).
+__device__ __forceinline__ void wait_loads_keep(int keep) {
+  if (keep == 0) wait_loads_except<0>();
+  else if (keep == 4) wait_loads_except<4>();
+  else if (keep == 8) wait_loads_except<8>();
+}
+
 // The value held by the lane 32 positions away (the same query in the other half-wave), by the
 // gfx950 half-wave swap: one vector instruction instead of a round trip through the LDS
 // permute network.  h = lane / 32.
@@ -77,12 +85,12 @@ constexpr int kPipeRegK = 0;   // K fragment prefetched into registers, V block 
 constexpr int kPipeLdsK = 1;   // K and V blocks staged in LDS, one block ahead
 constexpr int kPipeSplit = 2;  // fp32 storage, products as three fp16 matrix-core terms (CoreSplit)
 
-struct BlockInfo {
-  int raw;          // explicit masks: block record as loaded (row0, nvalid, full follow from it)
+struct BlockInfo {   // (no padding bytes: copies of the struct stay in registers)
   int64_t row0;     // tensor row of the block's first key (wave-uniform)
+  int raw;          // explicit masks: block record as loaded (row0, nvalid, full follow from it)
   int nvalid;       // keys of the block that exist (1..32); others are masked off (wave-uniform)
   uint32_t word;    // mask bits of this lane's query against the block's 32 keys
-  bool full;        // all 32x32 bits set (wave-uniform)
+  int full;         // non-zero: all 32x32 bits set (wave-uniform)
 };
 
 __device__ __forceinline__ int64_t uniform64(int64_t v) {
@@ -227,9 +235,13 @@ __device__ __forceinline__ void softmax_block(floatx16 sv, float c, const BlockI
 // from the block's first row); the per-block part is wave-uniform, so a copy costs no vector
 // arithmetic.  Blocks cut short by the end of the sequence (nvalid < 32) re-read their last
 // row instead of running past it; those keys are masked off.
-template <typename T>
+//
+// kD is the row length of the tensors in global memory; a block always holds 64 channels of a
+// key (for kD > 64 the caller passes tensor pointers already advanced to its 64-channel slice).
+template <typename T, int kD = kHeadDim>
 struct StageMap {
-  static constexpr int kRowBytes = kHeadDim * (int)sizeof(T);
+  static constexpr int kRowBytes = kHeadDim * (int)sizeof(T);   // staged row (one 64-channel slice)
+  static constexpr int kGlobalRowBytes = kD * (int)sizeof(T);   // tensor row
   static constexpr int kLanes = kRowBytes / 16;          // lanes per row
   static constexpr int kRows = kWave / kLanes;           // rows per copy
   static constexpr int kCopies = kTile / kRows;          // copies per block
@@ -238,7 +250,7 @@ struct StageMap {
   uint32_t koff[kLanes / 4 > 1 ? 4 : 1];                 // K: same with the chunk swizzled, per copy % 4
 
   __device__ void init(int64_t stride, int lane) {
-    stride_bytes = stride * kRowBytes;
+    stride_bytes = stride * kGlobalRowBytes;
     const int lr = lane / kLanes, lc = lane % kLanes;
     const uint32_t rowoff = (uint32_t)(lr * stride_bytes);
     voff = rowoff + lc * 16;
@@ -253,7 +265,7 @@ struct StageMap {
   }
   __device__ void stage_v(const T* __restrict__ Vh, const BlockInfo& b, int lane, char* dst) const {
     if (b.nvalid == kTile) {
-      const char* base = reinterpret_cast<const char*>(Vh) + b.row0 * kRowBytes;
+      const char* base = reinterpret_cast<const char*>(Vh) + b.row0 * kGlobalRowBytes;
 #pragma unroll
       for (int i = 0; i < kCopies; ++i)
         copy16_to_lds(base + i * kRows * stride_bytes + voff, dst + i * 1024);
@@ -262,7 +274,7 @@ struct StageMap {
       for (int i = 0; i < kCopies; ++i) {
         int key = kRows * i + lane / kLanes;
         key = key < b.nvalid ? key : b.nvalid - 1;
-        copy16_to_lds(reinterpret_cast<const char*>(Vh) + b.row0 * kRowBytes + key * stride_bytes +
+        copy16_to_lds(reinterpret_cast<const char*>(Vh) + b.row0 * kGlobalRowBytes + key * stride_bytes +
                           (lane % kLanes) * 16,
                       dst + i * 1024);
       }
@@ -270,7 +282,7 @@ struct StageMap {
   }
   __device__ void stage_k(const T* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) const {
     if (b.nvalid == kTile) {
-      const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * kRowBytes;
+      const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * kGlobalRowBytes;
 #pragma unroll
       for (int i = 0; i < kCopies; ++i)
         copy16_to_lds(base + i * kRows * stride_bytes + koff[kLanes == 8 ? 0 : i % 4], dst + i * 1024);
@@ -280,7 +292,7 @@ struct StageMap {
         const int row = kRows * i + lane / kLanes;
         const int key = row < b.nvalid ? row : b.nvalid - 1;
         const int chunk = (lane % kLanes) ^ (row % kLanes);
-        copy16_to_lds(reinterpret_cast<const char*>(Kh) + b.row0 * kRowBytes + key * stride_bytes +
+        copy16_to_lds(reinterpret_cast<const char*>(Kh) + b.row0 * kGlobalRowBytes + key * stride_bytes +
                           chunk * 16,
                       dst + i * 1024);
       }
@@ -288,10 +300,51 @@ struct StageMap {
   }
 };
 
+// Head dimensions above 64: the kD / 64 wavefronts of a workgroup own one tile together, each
+// with one 64-channel slice of Q, K, V and O.  The products S^T = K Q^T of the slices are partial
+// sums over the channels; every wavefront leaves its 32x32 partial in LDS and, after one
+// workgroup barrier, all of them add the partials in slice order, so that every wavefront
+// continues with bit-identical scores (and therefore identical m, l and P).  Two buffers
+// alternate, which makes one barrier per block enough: a wavefront overwrites a buffer only
+// after the barrier that every reader of its previous contents has passed.
+template <int kD>
+struct SliceExchange {
+  static constexpr int kSlices = kD / kHeadDim;
+  static constexpr int kBytes = 2 * kSlices * 4096;   // [2][slice][4][64 lanes] float4
+  float4* xs;      // the workgroup's exchange buffers
+  int slice;       // this wavefront's slice
+  int parity;
+  __device__ void init(char* lds, int slice_) {
+    xs = reinterpret_cast<float4*>(lds);
+    slice = slice_;
+    parity = 0;
+  }
+  __device__ void sum_slices(floatx16& s, int lane) {
+    float4* buf = xs + parity * (kSlices * 256);
+    parity ^= 1;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+      buf[(slice * 4 + j) * 64 + lane] = make_float4(s[4 * j], s[4 * j + 1], s[4 * j + 2], s[4 * j + 3]);
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      float4 t = buf[j * 64 + lane];
+#pragma unroll
+      for (int w = 1; w < kSlices; ++w) {
+        const float4 v = buf[(w * 4 + j) * 64 + lane];
+        t.x += v.x; t.y += v.y; t.z += v.z; t.w += v.w;
+      }
+      s[4 * j] = t.x; s[4 * j + 1] = t.y; s[4 * j + 2] = t.z; s[4 * j + 3] = t.w;
+    }
+  }
+};
+
 // ---- fp32 storage ---------------------------------------------------------------------------
-struct CoreF32 {
-  using Stage = StageMap<float>;
-  float qf[32];   // Q[query n][h*32 + t]
+template <int kD>
+struct CoreF32T {
+  using Stage = StageMap<float, kD>;
+  float qf[32];   // Q[query n][h*32 + t] (of this wavefront's 64-channel slice)
+  SliceExchange<kD> xchg;   // used for kD > 64 only
 
   __device__ void load_q(const float* Qrow, int h, bool negate) {
     const float4* src = reinterpret_cast<const float4*>(Qrow + h * 32);
@@ -310,7 +363,7 @@ struct CoreF32 {
   // per lane.  lane_off = byte offset of the lane's key row and half inside a whole block.
   __device__ static void load_k(const float* __restrict__ Kh, const BlockInfo& b, int64_t stride_bytes,
                                 uint32_t lane_off, int n, int h, float (&kf)[32]) {
-    const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * Stage::kRowBytes;
+    const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * Stage::kGlobalRowBytes;
     const float4* kp;
     if (b.nvalid == kTile) {
       kp = reinterpret_cast<const float4*>(base + lane_off);
@@ -342,16 +395,17 @@ struct CoreF32 {
   }
 
   // S^T = K_blk Q^T, softmax, O^T += V_blk^T P^T for one block whose V rows are staged at ldsv.
-  template <typename WaitV>
+  // (v_keep: the staged V block is complete once at most this many later copies are in flight)
   __device__ void block_math(const float (&kf)[32], const BlockInfo& b, float c, int n, int h,
-                             TileState& st, const char* ldsv, WaitV wait_v) {
+                             TileState& st, const char* ldsv, int v_keep) {
     floatx16 s = {0};
 #pragma unroll
     for (int t = 0; t < 32; ++t)
       s = __builtin_amdgcn_mfma_f32_32x32x2f32(kf[t], qf[t], s, 0, 0, 0);
+    if (kD > kHeadDim) xchg.sum_slices(s, 32 * h + n);
     float p[16];
     softmax_block(s, c, b, h, st, p);
-    wait_v();
+    wait_loads_keep(v_keep);
     __builtin_amdgcn_wave_barrier();
     const float* vread = reinterpret_cast<const float*>(ldsv) + h * 4 * kHeadDim + n;
 #pragma unroll
@@ -398,9 +452,7 @@ struct CoreF32 {
       __builtin_amdgcn_wave_barrier();
       if (more) sm.stage_k(Kh, b1, lane, ldsk);
       // V block k is older than the 8 K copies issued above (if any)
-      block_math(kf, b, c, n, h, st, ldsv, [more] {
-        if (more) wait_loads_except<8>(); else wait_loads_except<0>();
-      });
+      block_math(kf, b, c, n, h, st, ldsv, more ? 8 : 0);
       b = b1;
       b1 = b2;
     }
@@ -431,7 +483,7 @@ struct CoreF32 {
       sm.stage_v(Vh, b, lane, lds);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
-      block_math(kf, b, c, n, h, st, lds, [] { wait_loads_except<0>(); });
+      block_math(kf, b, c, n, h, st, lds, 0);
       b = b1;
       b1 = b2;
     };
@@ -477,11 +529,14 @@ struct CoreF32 {
       }
   }
 };
+using CoreF32 = CoreF32T<kHeadDim>;
 
 // ---- fp16 storage ---------------------------------------------------------------------------
-struct CoreF16 {
-  using Stage = StageMap<__half>;
-  half8 qf[4];    // Q[query n][h*32 + 8s .. +7], s = 0..3
+template <int kD>
+struct CoreF16T {
+  using Stage = StageMap<__half, kD>;
+  half8 qf[4];    // Q[query n][h*32 + 8s .. +7], s = 0..3 (of this wavefront's 64-channel slice)
+  SliceExchange<kD> xchg;   // used for kD > 64 only
 
   __device__ void load_q(const __half* Qrow, int h, bool negate) {
     const half8* src = reinterpret_cast<const half8*>(Qrow + h * 32);
@@ -517,16 +572,18 @@ struct CoreF16 {
     return __builtin_bit_cast(half4, raw);
   }
 
-  template <typename WaitV>
+  // (v_keep: the staged V block is complete once at most this many later copies are in flight;
+  // negative: it is known to be complete)
   __device__ void block_math(const half8 (&kf)[4], const BlockInfo& b, float c, int lane, int h,
-                             TileState& st, const char* ldsv, WaitV wait_v) {
+                             TileState& st, const char* ldsv, int v_keep) {
     floatx16 sacc = {0};
 #pragma unroll
     for (int s = 0; s < 4; ++s)
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
+    if (kD > kHeadDim) xchg.sum_slices(sacc, lane);
     float p[16];
     softmax_block(sacc, c, b, h, st, p);
-    wait_v();
+    wait_loads_keep(v_keep);
     __builtin_amdgcn_wave_barrier();
     // this lane's address for key0 = 4h, channel group 0; the other reads are constant offsets
     const int i = lane & 15, grp16 = (lane >> 4) & 1;
@@ -577,9 +634,7 @@ struct CoreF16 {
       __builtin_amdgcn_wave_barrier();
       if (more) sm.stage_k(Kh, b1, lane, ldsk);
       // V block k is older than the 4 K copies issued above (if any)
-      block_math(kf, b, c, lane, h, st, ldsv, [more] {
-        if (more) wait_loads_except<4>(); else wait_loads_except<0>();
-      });
+      block_math(kf, b, c, lane, h, st, ldsv, more ? 4 : 0);
       b = b1;
       b1 = b2;
     }
@@ -692,6 +747,7 @@ struct CoreF16 {
       }
   }
 };
+using CoreF16 = CoreF16T<kHeadDim>;
 
 // ---- fp32 storage, split-precision products -----------------------------------------------------
 // Every fp32 operand x is written as hi + lo with hi = fp16(x) and lo = fp16(x - hi) (x - hi is
@@ -850,6 +906,10 @@ template <> struct CoreOf<__half> { using type = CoreF16; };
 // the core that runs pipeline kPipe on storage type T
 template <typename T, int kPipe> struct CoreFor { using type = typename CoreOf<T>::type; };
 template <> struct CoreFor<float, kPipeSplit> { using type = CoreSplit; };
+// the core of a 64-channel slice of kD-wide rows
+template <typename T, int kD> struct WideCoreOf;
+template <int kD> struct WideCoreOf<float, kD> { using type = CoreF32T<kD>; };
+template <int kD> struct WideCoreOf<__half, kD> { using type = CoreF16T<kD>; };
 
 // Normalise and store the tile's rows (row(n) = tensor row of query n, < 0 if it does not exist).
 template <typename T>
@@ -884,6 +944,32 @@ __device__ __forceinline__ void store_partial(float* part, TileState& st, int n,
     part[kTile * 64 + n] = st.m;
     part[kTile * 64 + kTile + n] = l;
   }
+}
+
+// finish_tile for one 64-channel slice of a kD-wide tile (Oslice = first channel of the slice in
+// the head's O).  Every slice wavefront holds the same (m, l); when the call continues an earlier
+// state, all of them read the earlier lse before the workgroup barrier and slice 0 replaces it
+// after it.
+template <typename T, int kD>
+__device__ __forceinline__ void finish_tile_wide(T* Oslice, float* lse_h, int64_t row, bool exists,
+                                                 TileState& st, int h, int slice, bool accumulate) {
+  const float l = st.l + other_half(st.l, h);
+  const bool empty = !(l > 0.f);
+  float inv = empty ? 0.f : 1.0f / l;
+  float lse_row = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(l)) * kLn2;
+  float w_prev = 0.f;
+  if (accumulate) {
+    if (exists) {
+      const CarryWeights cw = carry_weights(lse_h[row], lse_row);
+      inv *= cw.w_now;
+      w_prev = cw.w_prev;
+      lse_row = cw.lse;
+    }
+    __syncthreads();
+  }
+  if (!exists) return;
+  CoreOf<T>::type::store_row(Oslice + row * kD, st, inv, w_prev, accumulate, h);
+  if (lse_h && h == 0 && slice == 0) lse_h[row] = lse_row;
 }
 
 __device__ __forceinline__ int half_min(int v) {   // min over the 32 lanes of a half-wave
@@ -966,8 +1052,8 @@ __device__ __forceinline__ WorkId locate_work(const int64_t* __restrict__ row_pt
 __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __restrict__ row_ptr,
                                                            const int32_t* __restrict__ col_idx,
                                                            int64_t L, int32_t H, int32_t dtype,
-                                                           void* ws, size_t ws_bytes) {
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+                                                           int32_t d, void* ws, size_t ws_bytes) {
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
   if (pl.total_bytes > ws_bytes) return;
   const int64_t S = seg_edges(dtype);
   const int lane = threadIdx.x & (kWave - 1);
@@ -1195,24 +1281,95 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
   }
 }
 
+// Head dimensions 128 and 256: one workgroup of kD / 64 wavefronts per work item, wavefront w
+// owning channels 64w .. 64w+63 (CoreF32T / CoreF16T with SliceExchange).  Workgroups stay
+// resident and claim items from the head's counter like the fp32 kernel above; wavefront 0
+// claims and the item index travels through LDS.
+template <typename T, int kD, int kPipe>
+__global__ __launch_bounds__(kD) void tile_attend_wide_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
+    size_t ws_bytes, int accumulate) {
+  using Core = typename WideCoreOf<T, kD>::type;
+  constexpr int kSlices = kD / kHeadDim;
+  constexpr int kLds = Core::template lds_bytes<kPipe>();
+  __shared__ __attribute__((aligned(16))) char lds_all[kSlices * kLds + SliceExchange<kD>::kBytes];
+  __shared__ uint32_t claim;
+  const int32_t H = (int32_t)gridDim.x;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code, kD);
+  if (pl.total_bytes > ws_bytes) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  char* lds = lds_all + slice * kLds;
+  char* base_ws = static_cast<char*>(ws);
+  const bool negate = scale < 0.f;
+  const float c = softmax_factor(scale);
+  const TileItem* items = reinterpret_cast<const TileItem*>(base_ws + pl.off_items_rec);
+  const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
+  const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
+  const bool parts_fit = tile_parts_fit(pl, ws);
+  const int64_t head = blockIdx.x;
+  const int64_t hoff = head * L * kD + slice * kHeadDim;   // this wavefront's slice of the head
+  uint32_t* work_next = reinterpret_cast<uint32_t*>(base_ws + pl.off_work_next) + head;
+  Core core;
+  core.xchg.init(lds_all + kSlices * kLds, slice);
+  while (true) {
+    __syncthreads();           // every wavefront has read the previous claim and left its item
+    if (threadIdx.x == 0) claim = atomicAdd(work_next, 1u);
+    __syncthreads();
+    const int64_t w_cur = __builtin_amdgcn_readfirstlane(claim);
+    if (w_cur >= pl.n_work) break;
+    const int4 r0 = reinterpret_cast<const int4*>(items + w_cur)[0];
+    const int64_t slot_raw = reinterpret_cast<const int64_t*>(items + w_cur)[2];
+    const int32_t t = __builtin_amdgcn_readfirstlane(r0.x);
+    const int32_t nblk = __builtin_amdgcn_readfirstlane(r0.y);
+    const int32_t seg = __builtin_amdgcn_readfirstlane(r0.z);
+    const int32_t nseg = __builtin_amdgcn_readfirstlane(r0.w);
+    const int64_t slot0 = uniform64(slot_raw);
+    if (t < 0 || nblk < 0) continue;
+    if (nseg > 1 && (!parts_fit || tile_bad[t])) continue;
+    const int64_t row_first = (int64_t)t * kTile;
+    ExplicitBlocks src{reinterpret_cast<const int32_t*>(base_ws + pl.off_pair_blk) + slot0,
+                       reinterpret_cast<const uint32_t*>(base_ws + pl.off_pair_mask) + slot0 * kTile, L};
+    const int64_t qrow = row_first + n;
+    const bool exists = qrow < L;
+    core.load_q(Q + hoff + (exists ? qrow : L - 1) * kD, h, negate);
+    TileState st;
+    st.init();
+    core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, c, lane, st, lds);
+    if (nseg > 1) {
+      float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
+                    ((((int64_t)tile_pbase[t] + seg) * H + head) * kSlices + slice) *
+                        (int64_t)kTilePartialFloats;
+      store_partial(part, st, n, h);
+    } else {
+      finish_tile_wide<T, kD>(O + hoff, lse ? lse + head * L : nullptr, qrow, exists, st, h, slice,
+                              accumulate != 0);
+    }
+  }
+}
+
 __device__ __forceinline__ float load_out(const float* p) { return *p; }
 __device__ __forceinline__ float load_out(const __half* p) { return __half2float(*p); }
 __device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(__half* p, float v) { *p = __float2half_rn(v); }
 
 // Merge of a multi-segment tile's partial states.  grid = (tiles of the merge list, head,
-// rows of the tile in groups of 32 / gridDim.z); the 4 wavefronts of a workgroup take every 4th segment of a row, reduce
-// theirs in segment order, and wavefront 0 combines the four results in wavefront order, so
-// the summation order is fixed.  lane = channel.
-template <typename T>
+// rows of the tile in groups of 32 / gridDim.z); the 4 wavefronts of a workgroup take every 4th
+// segment of a row, reduce theirs in segment order, and wavefront 0 combines the four results in
+// wavefront order, so the summation order is fixed.  lane = channel within each 64-channel slice
+// (a partial of a kD-wide tile is kD / 64 records, one per slice, with the same m and l).
+template <typename T, int kD>
 __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                          const int64_t* __restrict__ row_ptr, int64_t L,
                                                          void* ws, size_t ws_bytes, int accumulate) {
-  __shared__ float sm_acc[4][kHeadDim];
+  constexpr int kSlices = kD / kHeadDim;
+  __shared__ float sm_acc[4][kD];
   __shared__ float sm_m[4], sm_l[4];
   const int32_t H = (int32_t)gridDim.y;
   constexpr int32_t dtype = DtypeOf<T>::code;
-  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype);
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, kD);
   if (pl.total_bytes > ws_bytes || !tile_parts_fit(pl, ws)) return;
   char* base_ws = static_cast<char*>(ws);
   const uint32_t n_multi = reinterpret_cast<const uint32_t*>(ws)[kCtrMultiTiles];
@@ -1228,21 +1385,26 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
     const int64_t t = multi[i];
     if (tile_bad[t]) continue;
     const int nseg = tile_segments(row_ptr, L, S, t);
-    const float* p0 = parts + ((int64_t)tile_pbase[t] * H + hd) * kTilePartialFloats;
-    const int64_t step = (int64_t)H * kTilePartialFloats;
+    const float* p0 = parts + ((int64_t)tile_pbase[t] * H + hd) * (kSlices * kTilePartialFloats);
+    const int64_t step = (int64_t)H * (kSlices * kTilePartialFloats);
     const int rows_per_wg = kTile / (int)gridDim.z;
     for (int r = blockIdx.z * rows_per_wg; r < (int)(blockIdx.z + 1) * rows_per_wg; ++r) {
       const int64_t row = t * kTile + r;
       float M = kMinusHuge;
       for (int c = wave; c < nseg; c += 4) M = fmaxf(M, p0[c * step + kTile * 64 + r]);
-      float l = 0.f, acc = 0.f;
+      float l = 0.f, acc[kSlices];
+#pragma unroll
+      for (int sl = 0; sl < kSlices; ++sl) acc[sl] = 0.f;
       for (int c = wave; c < nseg; c += 4) {
         const float wgt = __builtin_amdgcn_exp2f(p0[c * step + kTile * 64 + r] - M);
         l = __builtin_fmaf(p0[c * step + kTile * 64 + kTile + r], wgt, l);
-        acc = __builtin_fmaf(p0[c * step + r * 64 + lane], wgt, acc);
+#pragma unroll
+        for (int sl = 0; sl < kSlices; ++sl)
+          acc[sl] = __builtin_fmaf(p0[c * step + sl * kTilePartialFloats + r * 64 + lane], wgt, acc[sl]);
       }
       __syncthreads();            // previous row's combine has read the shared arrays
-      sm_acc[wave][lane] = acc;
+#pragma unroll
+      for (int sl = 0; sl < kSlices; ++sl) sm_acc[wave][sl * 64 + lane] = acc[sl];
       if (lane == 0) {
         sm_m[wave] = M;
         sm_l[wave] = l;
@@ -1250,23 +1412,29 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
       __syncthreads();
       if (wave == 0 && row < L) {
         float Mt = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
-        float lt = 0.f, at = 0.f;
+        float lt = 0.f, wv[4];
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
-          const float wgt = __builtin_amdgcn_exp2f(sm_m[v] - Mt);
-          lt = __builtin_fmaf(sm_l[v], wgt, lt);
-          at = __builtin_fmaf(sm_acc[v][lane], wgt, at);
+          wv[v] = __builtin_amdgcn_exp2f(sm_m[v] - Mt);
+          lt = __builtin_fmaf(sm_l[v], wv[v], lt);
         }
         const bool empty = !(lt > 0.f);
-        T* dst = O + hd * L * kHeadDim + row * kHeadDim + lane;
-        float o = empty ? 0.f : at / lt;
         float lse_row = empty ? -INFINITY : (Mt + __builtin_amdgcn_logf(lt)) * kLn2;
+        CarryWeights cw{0.f, 1.f, lse_row};
         if (accumulate) {
-          const CarryWeights cw = carry_weights(lse[hd * L + row], lse_row);
-          o = cw.w_prev * load_out(dst) + cw.w_now * o;
+          cw = carry_weights(lse[hd * L + row], lse_row);
           lse_row = cw.lse;
         }
-        store_out(dst, o);
+#pragma unroll
+        for (int sl = 0; sl < kSlices; ++sl) {
+          float at = 0.f;
+#pragma unroll
+          for (int v = 0; v < 4; ++v) at = __builtin_fmaf(sm_acc[v][sl * 64 + lane], wv[v], at);
+          T* dst = O + hd * L * kD + row * kD + sl * 64 + lane;
+          float o = empty ? 0.f : at / lt;
+          if (accumulate) o = cw.w_prev * load_out(dst) + cw.w_now * o;
+          store_out(dst, o);
+        }
         if (lse && lane == 0) lse[hd * L + row] = lse_row;
       }
     }
@@ -1315,6 +1483,50 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   st.init();
   core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st, lds);
   finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h, accumulate != 0);
+}
+
+// Window masks at head dimensions 128 and 256: one workgroup of kD / 64 wavefronts per
+// 32-query tile (see tile_attend_wide_kernel); grid mapping as in tile_window_kernel with one
+// tile per workgroup.
+template <typename T, int kD, int kPipe>
+__global__ __launch_bounds__(kD) void tile_window_wide_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_tiles, float scale,
+    int accumulate) {
+  using Core = typename WideCoreOf<T, kD>::type;
+  constexpr int kSlices = kD / kHeadDim;
+  constexpr int kLds = Core::template lds_bytes<kPipe>();
+  __shared__ __attribute__((aligned(16))) char lds_all[kSlices * kLds + SliceExchange<kD>::kBytes];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  const int64_t chunk = gridDim.x / 8;
+  const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  // (every condition below is the same for all wavefronts of the workgroup)
+  if (bid >= n_tiles * s) return;
+  const int64_t p = bid % s;                       // residue class
+  if (p >= L) return;
+  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
+  const int64_t u0 = (bid / s) * kTile;
+  if (u0 >= Lc) return;
+  const int64_t hd = blockIdx.y;
+  const int64_t hoff = hd * L * kD + slice * kHeadDim;
+  const int64_t vlo = u0 - W > 0 ? u0 - W : 0;
+  const int64_t vhi = u0 + kTile - 1 + W < Lc - 1 ? u0 + kTile - 1 + W : Lc - 1;
+  WindowBlocks src{vlo, Lc, s, p, u0, W};
+  const int nblk = (int)((vhi - vlo) / kTile + 1);
+  const int64_t u = u0 + n;
+  const bool exists = u < Lc;
+  const int64_t qrow = s * (exists ? u : Lc - 1) + p;
+  Core core;
+  core.xchg.init(lds_all + kSlices * kLds, slice);
+  core.load_q(Q + hoff + qrow * kD, h, scale < 0.f);
+  TileState st;
+  st.init();
+  core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st,
+                           lds_all + slice * kLds);
+  finish_tile_wide<T, kD>(O + hoff, lse ? lse + hd * L : nullptr, qrow, exists, st, h, slice,
+                          accumulate != 0);
 }
 
 // fp16 window masks, 64 queries per wavefront: two neighbouring 32-query sub-tiles share every
@@ -1432,13 +1644,17 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
     const BlockInfo b = src.get(k, n);
     half8 kf[4];
     CoreF16::read_k(lds_k + k * CoreF16::kBlockBytes, n, h, kf);
-    core.block_math(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, [] {});
+    core.block_math(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, -1);
   }
   finish_tile<__half>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h, accumulate != 0);
 }
 
 template <typename T>
+sga_status run_tile_explicit_wide(const AttnArgs& a);
+
+template <typename T>
 sga_status run_tile_explicit(const AttnArgs& a) {
+  if (a.d != kHeadDim) return run_tile_explicit_wide<T>(a);
   const T* Q = static_cast<const T*>(a.Q);
   const T* K = static_cast<const T*>(a.K);
   const T* V = static_cast<const T*>(a.V);
@@ -1449,7 +1665,7 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   int64_t nwg = (n_tiles + 3) / 4 + 64;
   if (nwg > 16384) nwg = 16384;
   hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
-                     a.col_idx, a.L, a.H, a.dtype, a.ws, a.ws_bytes);
+                     a.col_idx, a.L, a.H, a.dtype, kHeadDim, a.ws, a.ws_bytes);
   // fp32: resident workgroups only (256 CUs x 2 wavefronts per SIMD, shared by the heads), which
   // claim items dynamically; fp16: one pass of workgroups over the items of each head
   int64_t per_head = (nwg + 8 * kXcdRun - 1) / (8 * kXcdRun) * (8 * kXcdRun);
@@ -1466,12 +1682,72 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   hipLaunchKernelGGL(kernel, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0, a.stream, Q, K, V, O,
                      a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   profile_mark_end(a.stream);
-  hipLaunchKernelGGL(tile_merge_kernel<T>, dim3(16, (unsigned)a.H, kTile), dim3(256), 0, a.stream,
+  hipLaunchKernelGGL((tile_merge_kernel<T, kHeadDim>), dim3(16, (unsigned)a.H, kTile), dim3(256), 0,
+                     a.stream, O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
+  return hip_status(hipGetLastError());
+}
+
+template <typename T, int kD>
+sga_status run_tile_explicit_wide_d(const AttnArgs& a) {
+  const T* Q = static_cast<const T*>(a.Q);
+  const T* K = static_cast<const T*>(a.K);
+  const T* V = static_cast<const T*>(a.V);
+  T* O = static_cast<T*>(a.O);
+  constexpr int kSlices = kD / kHeadDim;
+  const int64_t n_tiles = (a.L + kTile - 1) / kTile;
+  int64_t nwg = (n_tiles + 3) / 4 + 64;
+  if (nwg > 16384) nwg = 16384;
+  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
+                     a.col_idx, a.L, a.H, a.dtype, kD, a.ws, a.ws_bytes);
+  // resident workgroups (2 wavefronts per SIMD over the chip), shared by the heads
+  int64_t per_head = (2048 / kSlices) / a.H;
+  if (per_head < 1) per_head = 1;
+  if (per_head > n_tiles + 64) per_head = n_tiles + 64;
+  constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
+  profile_mark_begin(a.stream);
+  hipLaunchKernelGGL((tile_attend_wide_kernel<T, kD, kPipe>), dim3((unsigned)a.H, (unsigned)per_head),
+                     dim3(kD), 0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes,
+                     a.accumulate ? 1 : 0);
+  profile_mark_end(a.stream);
+  hipLaunchKernelGGL((tile_merge_kernel<T, kD>), dim3(16, (unsigned)a.H, kTile), dim3(256), 0, a.stream,
                      O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   return hip_status(hipGetLastError());
 }
 
+template <typename T>
+sga_status run_tile_explicit_wide(const AttnArgs& a) {
+  if (a.d == 128) return run_tile_explicit_wide_d<T, 128>(a);
+  if (a.d == 256) return run_tile_explicit_wide_d<T, 256>(a);
+  return SGA_ERR_UNSUPPORTED;
+}
+
+template <typename T, int kD>
+sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
+  const int64_t s = a.stride;
+  const int64_t Lc = (a.L + s - 1) / s;                 // tokens of the largest residue class
+  const int64_t n_tiles = (Lc + kTile - 1) / kTile;     // workgroups per class
+  const int64_t n_wg = (n_tiles * s + 7) / 8 * 8;
+  if (n_wg >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;
+  constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
+  profile_mark_begin(a.stream);
+  hipLaunchKernelGGL((tile_window_wide_kernel<T, kD, kPipe>), dim3((unsigned)n_wg, (unsigned)a.H),
+                     dim3(kD), 0, a.stream, static_cast<const T*>(a.Q), static_cast<const T*>(a.K),
+                     static_cast<const T*>(a.V), static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s,
+                     n_tiles, a.scale, a.accumulate ? 1 : 0);
+  profile_mark_end(a.stream);
+  return hip_status(hipGetLastError());
+}
+
+template <typename T>
+sga_status run_tile_implicit_wide(const AttnArgs& a) {
+  if (a.d == 128) return run_tile_implicit_wide_d<T, 128>(a);
+  if (a.d == 256) return run_tile_implicit_wide_d<T, 256>(a);
+  return SGA_ERR_UNSUPPORTED;
+}
+
 sga_status run_tile_implicit(const AttnArgs& a) {
+  if (a.d != kHeadDim)
+    return a.dtype == SGA_F32 ? run_tile_implicit_wide<float>(a) : run_tile_implicit_wide<__half>(a);
   const int64_t s = a.stride;
   const int64_t Lc = (a.L + s - 1) / s;                 // tokens of the largest residue class
   // fp16, 128 queries' key range fits the LDS: one workgroup stages it once (128 queries per
@@ -1519,8 +1795,10 @@ sga_status launch_tile_explicit(const AttnArgs& a) {
 }
 
 sga_status launch_tile_implicit(const AttnArgs& a) {
-  // (the tile kernels keep per-lane row offsets in 32 bits, which bounds the stride)
-  if (a.H > 65535 || a.stride > (1 << 20)) return launch_gather_implicit(a);
+  // (the tile kernels keep per-lane byte offsets of up to 31 keys in 32 bits, which bounds the
+  // distance between consecutive keys of a class to 2^27 bytes)
+  const int64_t key_bytes = (int64_t)a.stride * a.d * (a.dtype == SGA_F32 ? 4 : 2);
+  if (a.H > 65535 || key_bytes > (int64_t(1) << 27)) return launch_gather_implicit(a);
   return run_tile_implicit(a);
 }
 

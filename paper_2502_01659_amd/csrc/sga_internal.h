@@ -45,7 +45,7 @@ __host__ __device__ inline int64_t seg_edges(int32_t dtype) { return dtype == SG
 // pair_blk            cap_pairs x int32: key block id (| full flag); tile t owns slots
 //                     [row_ptr[32t]/128, row_ptr[32(t+1)]/128), split evenly among its segments
 // pair_mask           cap_pairs x 32 x uint32: bit j of word r = edge (row 32t+r, key 32b+j)
-// tpartials           cap_tparts x H x kTilePartialFloats floats
+// tpartials           cap_tparts x H x max(1, d / 64) x kTilePartialFloats floats
 // work_next           H x uint32: next unclaimed tile work item of each head (dynamic scheduling)
 enum WsCounter : int {
   kCtrChunksNeeded = 0,   // sum of chunk counts of all long rows
@@ -126,7 +126,8 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   p.off_pair_mask = off;
   off = (off + (size_t)p.cap_pairs * kTile * sizeof(uint32_t) + 255) & ~size_t(255);
   p.off_tpartials = off;
-  off = (off + (size_t)p.cap_tparts * H * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
+  const int64_t slices = d > kHeadDim ? d / kHeadDim : 1;   // a wide tile leaves one record per 64 channels
+  off = (off + (size_t)p.cap_tparts * H * slices * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
   p.off_work_next = off;
   off = (off + (tiles ? (size_t)H * 4 : 0) + 255) & ~size_t(255);
   p.total_bytes = off;

@@ -73,7 +73,7 @@ def test_forward_argument_errors_without_touching_the_gpu():
     assert f(ok, ok, ok, ok, ok, ok, 0, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
     assert f(ok, ok, ok, ok, ok, ok, 64, 0, 64, 0.1, None, 0, None, None, 0, 0) == -1
     assert f(ok, ok, ok, ok, ok, ok, 64, 1, 48, 0.1, None, 0, None, None, 0, 0) == -2
-    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 128, 0.1, None, 0, None, None, 0, sga.PATH_TILE) == -2
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 32, 0.1, None, 0, None, None, 0, sga.PATH_TILE) == -2
     assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 1, None, None, 0, sga.PATH_TILE_SPLIT) == -2
     assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, sga.PATH_TILE_SPLIT) == -3
     a = sga.sga_attention_accumulate        # the state vector lse is required

@@ -15,7 +15,7 @@ from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
                         KIND_NONLOCAL, KIND_DILATED_2D,
                         numpy_qkv, small_variants, Workload)
 from oracle import reference as R
-from gpu_util import TOL, to_device, small_inputs, oracle_full, max_err
+from gpu_util import TOL, to_device, small_inputs, oracle_full, max_err, sample_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -317,9 +317,13 @@ def test_other_head_dimensions(d, dtype):
         _close(O, lse, O_ref, lse_ref, dtype)
         O, lse = _run_explicit(wl, Q, K, V, sga.PATH_GATHER, with_ws=False)
         _close(O, lse, O_ref, lse_ref, dtype)
-        if implicit:
-            O, lse = _run_implicit(wl, Q, K, V, sga.PATH_AUTO)
+        if d >= 128:      # matrix-core kernels on 64-channel slices
+            O, lse = _run_explicit(wl, Q, K, V, sga.PATH_TILE)
             _close(O, lse, O_ref, lse_ref, dtype)
+        if implicit:
+            for path in [sga.PATH_AUTO, sga.PATH_GATHER] + ([sga.PATH_TILE] if d >= 128 else []):
+                O, lse = _run_implicit(wl, Q, K, V, path)
+                _close(O, lse, O_ref, lse_ref, dtype)
     # Bernoulli mask with empty rows (the verification protocol's kind of mask)
     L = 300
     rng = np.random.default_rng(8)
@@ -343,9 +347,55 @@ def test_other_head_dimensions(d, dtype):
     sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O, lse, workspace=wsi)
     O_ref, lse_ref = R.attention_masked(Q, K, V, MaskSpec(KIND_GLOBAL_LOCAL, L, window=5, n_global=2), wl.scale)
     _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
-    # the tile kernels exist for d = 64 only
-    with pytest.raises(sga.SgaError):
-        sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, path=sga.PATH_TILE)
+    # the tile kernels work on 64-channel slices
+    if d < 64:
+        with pytest.raises(sga.SgaError):
+            sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, path=sga.PATH_TILE)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("d", [128, 256])
+def test_wide_tiles_segments_and_composition(d, dtype):
+    """Head dimensions 128 and 256 on the tile path: dense global rows long enough for
+    multi-segment tiles (partial states per 64-channel slice and their merge), a ragged tail, a
+    negative scale, and the composed local -> non-local pass through the merge's carry."""
+    print("case wide", d, dtype, flush=True)
+    L = 3001 if dtype == "f32" else 17001       # 40 global rows: 2 segments or more in either type
+    spec = MaskSpec(KIND_GLOBAL_LOCAL, L, window=40, n_global=40)
+    wl = Workload("t", H=2, L=L, d=d, dtype=dtype, sigma=0.7, mask=spec, explicit=True, seed=81)
+    Q, K, V = small_inputs(wl)
+    rows = np.arange(L) if L < 4000 else sample_rows(L, 9, 150, edge=120)
+    O_ref, lse_ref = R.attention_masked(Q, K, V, spec, wl.scale, rows=rows)
+    O_neg, lse_neg = R.attention_masked(-Q, K, V, spec, wl.scale, rows=rows)
+
+    def close(O, lse, ref, lref, factor=1.0):
+        _close(O.cpu().numpy()[:, rows], lse.cpu().numpy()[:, rows], ref, lref, dtype, factor)
+
+    dQ, dK, dV = to_device(Q, K, V)
+    rp, ci = sga.build_mask(spec)
+    ws = sga.alloc_workspace(L, wl.H, d, dtype, int(rp[-1]))
+    O, lse = sga.attention_forward(dQ, dK, dV, rp, ci, wl.scale, workspace=ws, path=sga.PATH_TILE,
+                                   want_lse=True)
+    close(O, lse, O_ref, lse_ref)
+    # negative scale: the oracle on -Q
+    O, lse = sga.attention_forward(dQ, dK, dV, rp, ci, -wl.scale, workspace=ws, path=sga.PATH_TILE,
+                                   want_lse=True)
+    close(O, lse, O_neg, lse_neg)
+    # local (implicit) then non-local (CSR, multi-segment tiles) on one state
+    loc = MaskSpec(KIND_SLIDING, L, window=40)
+    nl = MaskSpec(KIND_NONLOCAL, L, window=40, n_global=40)
+    rp2, ci2 = sga.build_mask(nl)
+    ws2 = sga.alloc_workspace(L, wl.H, d, dtype, int(rp2[-1]))
+    wsi = sga.alloc_workspace(L, wl.H, d, dtype, -1)
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, path=sga.PATH_TILE,
+                                            want_lse=True)
+    sga.attention_accumulate(dQ, dK, dV, rp2, ci2, wl.scale, O, lse, workspace=ws2, path=sga.PATH_TILE)
+    close(O, lse, O_ref, lse_ref, factor=2.0)
+    # and in the other order, the window pass continuing the state
+    O, lse = sga.attention_forward(dQ, dK, dV, rp2, ci2, wl.scale, workspace=ws2, path=sga.PATH_TILE,
+                                   want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, loc, wl.scale, O, lse, workspace=wsi, path=sga.PATH_TILE)
+    close(O, lse, O_ref, lse_ref, factor=2.0)
 
 
 @pytest.mark.parametrize("wl", [w for w in small_variants() if w.dtype == "f32"], ids=lambda w: w.name)
