@@ -177,6 +177,8 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
   a.stride = (kind == SGA_MASK_DILATED || kind == SGA_MASK_DILATED_2D) ? desc->stride : 1;
   const int64_t wmax = (L - 1) / a.stride;
   a.window = (int32_t)(desc->window < wmax ? desc->window : wmax);
+  // 2-D dilated blocks: the selected rows of a block all see each other
+  if (kind == SGA_MASK_DILATED_2D) a.window = (int32_t)(((desc->block < L ? desc->block : L) - 1) / a.stride);
   a.n_global = desc->n_global;
   a.block = desc->block;
   a.ws = workspace; a.ws_bytes = workspace_bytes;
@@ -190,7 +192,7 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
       return SGA_ERR_WORKSPACE;
     return launch_gather_implicit(a);
   }
-  if (kind == SGA_MASK_DILATED_2D || path == SGA_PATH_GATHER || d < kHeadDim)
+  if (path == SGA_PATH_GATHER || d < kHeadDim)
     return launch_gather_implicit(a);
   return launch_tile_implicit(a);
 }

@@ -1441,6 +1441,52 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
   }
 }
 
+// A workgroup's place among the window tiles.  Whole-sequence masks (seg_len = 0): residue class
+// bid % s of the sequence, group bid / s of that class.  Block-diagonal masks (seg_len > 0: the
+// 2-D dilated blocks of Section II-C, where the rows at in-block multiples of s attend each
+// other inside every block of seg_len tokens): block bid / n_groups, the one class that starts
+// at the block's first token, group bid % n_groups.  p = token of class index 0, Lc = tokens of
+// the class; token = s * index + p in both cases.
+struct WindowSlot {
+  int64_t p, Lc, grp;
+};
+__device__ __forceinline__ bool locate_window_slot(int64_t bid, int64_t L, int64_t s, int64_t n_groups,
+                                                   int64_t seg_len, WindowSlot& w) {
+  if (seg_len > 0) {
+    const int64_t base = (bid / n_groups) * seg_len;
+    if (base >= L) return false;
+    const int64_t len = L - base < seg_len ? L - base : seg_len;
+    w.p = base;
+    w.Lc = (len + s - 1) / s;
+    w.grp = bid % n_groups;
+  } else {
+    if (bid >= n_groups * s) return false;
+    w.p = bid % s;
+    if (w.p >= L) return false;
+    w.Lc = (L - w.p + s - 1) / s;
+    w.grp = bid / s;
+  }
+  return true;
+}
+
+// Rows of a 2-D dilated mask that are no in-block multiple of the stride have no neighbour:
+// O = 0, lse = -inf (Algorithm 1's initial state).  One thread per 16 bytes of O.
+template <typename T>
+__global__ __launch_bounds__(256) void clear_unselected_rows_kernel(T* __restrict__ O,
+                                                                    float* __restrict__ lse, int64_t L,
+                                                                    int64_t H, int32_t d, int64_t b,
+                                                                    int64_t s) {
+  const int64_t per_row = d * (int64_t)sizeof(T) / 16;
+  const int64_t total = H * L * per_row;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < total;
+       i += (int64_t)gridDim.x * blockDim.x) {
+    const int64_t row = (i / per_row) % L;
+    if (((row % b) % s) == 0) continue;
+    reinterpret_cast<uint4*>(O)[i] = make_uint4(0, 0, 0, 0);
+    if (lse && i % per_row == 0) lse[i / per_row] = -INFINITY;
+  }
+}
+
 // Implicit window masks.  grid.x = workgroups (4 tiles each) over all residue classes, grid.y = head.
 // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2, and neighbouring tiles
 // share most of their K/V rows, so the linear workgroup id is remapped to give every XCD one
@@ -1452,7 +1498,7 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
                                                           const T* __restrict__ V, T* __restrict__ O,
                                                           float* __restrict__ lse, int64_t L, int64_t W,
                                                           int64_t s, int64_t n_groups, float scale,
-                                                          int accumulate) {
+                                                          int accumulate, int64_t seg_len) {
   constexpr int kLds = CoreFor<T, kPipe>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int lane = threadIdx.x & (kWave - 1);
@@ -1462,11 +1508,10 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   // gridDim.x is a multiple of 8: XCD x handles the workgroups [x*chunk, (x+1)*chunk)
   const int64_t chunk = gridDim.x / 8;
   const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
-  if (bid >= n_groups * s) return;
-  const int64_t p = bid % s;                       // residue class
-  if (p >= L) return;
-  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
-  const int64_t u0 = ((bid / s) * 4 + wave) * kTile;
+  WindowSlot slot;
+  if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
+  const int64_t p = slot.p, Lc = slot.Lc;
+  const int64_t u0 = (slot.grp * 4 + wave) * kTile;
   if (u0 >= Lc) return;
   const int64_t hd = blockIdx.y;
   const int64_t hoff = hd * L * kHeadDim;
@@ -1492,7 +1537,7 @@ template <typename T, int kD, int kPipe>
 __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_tiles, float scale,
-    int accumulate) {
+    int accumulate, int64_t seg_len) {
   using Core = typename WideCoreOf<T, kD>::type;
   constexpr int kSlices = kD / kHeadDim;
   constexpr int kLds = Core::template lds_bytes<kPipe>();
@@ -1503,11 +1548,10 @@ __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
   const int64_t chunk = gridDim.x / 8;
   const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
   // (every condition below is the same for all wavefronts of the workgroup)
-  if (bid >= n_tiles * s) return;
-  const int64_t p = bid % s;                       // residue class
-  if (p >= L) return;
-  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
-  const int64_t u0 = (bid / s) * kTile;
+  WindowSlot slot;
+  if (!locate_window_slot(bid, L, s, n_tiles, seg_len, slot)) return;
+  const int64_t p = slot.p, Lc = slot.Lc;
+  const int64_t u0 = slot.grp * kTile;
   if (u0 >= Lc) return;
   const int64_t hd = blockIdx.y;
   const int64_t hoff = hd * L * kD + slice * kHeadDim;
@@ -1536,7 +1580,7 @@ __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
 __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_pair_kernel(
     const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
     __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
-    float scale, int accumulate) {
+    float scale, int accumulate, int64_t seg_len) {
   constexpr int kLds = 2 * CoreF16::kBlockBytes;
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int lane = threadIdx.x & (kWave - 1);
@@ -1545,11 +1589,10 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   char* lds = lds_all + wave * kLds;
   const int64_t chunk = gridDim.x / 8;
   const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
-  if (bid >= n_groups * s) return;
-  const int64_t p = bid % s;                       // residue class
-  if (p >= L) return;
-  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
-  const int64_t u0 = ((bid / s) * 4 + wave) * (2 * kTile);
+  WindowSlot slot;
+  if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
+  const int64_t p = slot.p, Lc = slot.Lc;
+  const int64_t u0 = (slot.grp * 4 + wave) * (2 * kTile);
   if (u0 >= Lc) return;
   const int64_t hd = blockIdx.y;
   const int64_t hoff = hd * L * kHeadDim;
@@ -1586,7 +1629,7 @@ constexpr int kWgBlocks = 8;
 __global__ __launch_bounds__(256) void tile_window_wg_kernel(
     const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
     __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
-    float scale, int accumulate, int nb_max) {
+    float scale, int accumulate, int nb_max, int64_t seg_len) {
   // nb_max K blocks, then nb_max V blocks (dynamic: narrow windows leave room for more workgroups)
   extern __shared__ __attribute__((aligned(16))) char lds_wg[];
   char* lds_k = lds_wg;
@@ -1599,12 +1642,21 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
   const uint32_t chunk = gridDim.x / 8;
   const uint32_t bid = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
   const uint32_t s32 = (uint32_t)s;
-  if ((int64_t)bid >= n_groups * s) return;
-  const uint32_t grp = bid / s32;
-  const int64_t p = bid - grp * s32;               // residue class
-  if (p >= L) return;
-  const int64_t Lc = (L - p + s - 1) / s;          // tokens of this residue class
-  const int64_t q0 = (int64_t)grp * (4 * kTile);   // first query of the workgroup
+  int64_t p, Lc, q0;                               // class start, tokens of the class, first query
+  if (seg_len > 0) {
+    WindowSlot slot;
+    if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
+    p = slot.p;
+    Lc = slot.Lc;
+    q0 = slot.grp * (4 * kTile);
+  } else {
+    if ((int64_t)bid >= n_groups * s) return;
+    const uint32_t grp = bid / s32;
+    p = bid - grp * s32;                           // residue class
+    if (p >= L) return;
+    Lc = (L - p + s - 1) / s;
+    q0 = (int64_t)grp * (4 * kTile);
+  }
   if (q0 >= Lc) return;                            // (the whole workgroup leaves: no barrier is missed)
   const int64_t hd = blockIdx.y;
   const int64_t hoff = hd * L * kHeadDim;
@@ -1721,19 +1773,55 @@ sga_status run_tile_explicit_wide(const AttnArgs& a) {
   return SGA_ERR_UNSUPPORTED;
 }
 
+// Shape of a window launch: the classes the tiles are dealt over (residue classes of the whole
+// sequence, or one class per block of a 2-D dilated mask) and the longest class.
+struct WindowShape {
+  int64_t seg_len;   // 0, or the block length of a 2-D dilated mask
+  int64_t n_slots;   // residue classes, or blocks
+  int64_t Lc;        // tokens of the longest class
+};
+WindowShape window_shape(const AttnArgs& a) {
+  WindowShape w;
+  if (a.mask_kind == SGA_MASK_DILATED_2D) {
+    const int64_t span = a.block < a.L ? a.block : a.L;
+    w.seg_len = a.block;
+    w.n_slots = (a.L + a.block - 1) / a.block;
+    w.Lc = (span + a.stride - 1) / a.stride;
+  } else {
+    w.seg_len = 0;
+    w.n_slots = a.stride;
+    w.Lc = (a.L + a.stride - 1) / a.stride;
+  }
+  return w;
+}
+
+// 2-D dilated masks: rows off the stride have no neighbour; a forward call writes their initial
+// state, a continuing call leaves them as they are.
+template <typename T>
+void clear_unselected_rows(const AttnArgs& a) {
+  if (a.mask_kind != SGA_MASK_DILATED_2D || a.stride == 1 || a.accumulate) return;
+  const int64_t chunks = (int64_t)a.H * a.L * (a.d * (int64_t)sizeof(T) / 16);
+  int64_t nwg = (chunks + 255) / 256;
+  if (nwg > 8192) nwg = 8192;
+  hipLaunchKernelGGL(clear_unselected_rows_kernel<T>, dim3((unsigned)nwg), dim3(256), 0, a.stream,
+                     static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.H, a.d, (int64_t)a.block,
+                     (int64_t)a.stride);
+}
+
 template <typename T, int kD>
 sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
   const int64_t s = a.stride;
-  const int64_t Lc = (a.L + s - 1) / s;                 // tokens of the largest residue class
-  const int64_t n_tiles = (Lc + kTile - 1) / kTile;     // workgroups per class
-  const int64_t n_wg = (n_tiles * s + 7) / 8 * 8;
+  const WindowShape shape = window_shape(a);
+  const int64_t n_tiles = (shape.Lc + kTile - 1) / kTile;     // workgroups per class
+  const int64_t n_wg = (n_tiles * shape.n_slots + 7) / 8 * 8;
   if (n_wg >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
+  clear_unselected_rows<T>(a);
   profile_mark_begin(a.stream);
   hipLaunchKernelGGL((tile_window_wide_kernel<T, kD, kPipe>), dim3((unsigned)n_wg, (unsigned)a.H),
                      dim3(kD), 0, a.stream, static_cast<const T*>(a.Q), static_cast<const T*>(a.K),
                      static_cast<const T*>(a.V), static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s,
-                     n_tiles, a.scale, a.accumulate ? 1 : 0);
+                     n_tiles, a.scale, a.accumulate ? 1 : 0, shape.seg_len);
   profile_mark_end(a.stream);
   return hip_status(hipGetLastError());
 }
@@ -1749,7 +1837,8 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   if (a.d != kHeadDim)
     return a.dtype == SGA_F32 ? run_tile_implicit_wide<float>(a) : run_tile_implicit_wide<__half>(a);
   const int64_t s = a.stride;
-  const int64_t Lc = (a.L + s - 1) / s;                 // tokens of the largest residue class
+  const WindowShape shape = window_shape(a);
+  const int64_t Lc = shape.Lc;
   // fp16, 128 queries' key range fits the LDS: one workgroup stages it once (128 queries per
   // workgroup, as in the fp32 kernel); wider fp16 windows: 64 queries per wavefront
   const bool wg = a.dtype == SGA_F16 && 4 * kTile + 2 * (int64_t)a.window <= kWgBlocks * kTile;
@@ -1757,28 +1846,29 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const int64_t per_wave = pair ? 2 * kTile : kTile;
   const int64_t n_tiles = (Lc + per_wave - 1) / per_wave;
   const int64_t n_groups = (n_tiles + 3) / 4;           // workgroups per class
-  const int64_t n_wg = (n_groups * s + 7) / 8 * 8;
+  const int64_t n_wg = (n_groups * shape.n_slots + 7) / 8 * 8;
   if (n_wg >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;
   const dim3 grid((unsigned)n_wg, (unsigned)a.H);
   const int acc = a.accumulate ? 1 : 0;
+  if (a.dtype == SGA_F32) clear_unselected_rows<float>(a); else clear_unselected_rows<__half>(a);
   profile_mark_begin(a.stream);
   if (wg) {
     const int nb_max = (int)((4 * kTile - 1 + 2 * (int64_t)a.window) / kTile + 1);
     hipLaunchKernelGGL(tile_window_wg_kernel, grid, dim3(256), (size_t)nb_max * 2 * CoreF16::kBlockBytes,
                        a.stream, static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
-                       (int64_t)a.window, s, n_groups, a.scale, acc, nb_max);
+                       (int64_t)a.window, s, n_groups, a.scale, acc, nb_max, shape.seg_len);
   } else if (pair) {
     hipLaunchKernelGGL(tile_window_pair_kernel, grid, dim3(256), 0, a.stream,
                        static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
-                       (int64_t)a.window, s, n_groups, a.scale, acc);
+                       (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len);
   } else {
     auto kernel = a.split ? tile_window_kernel<float, kPipeSplit> : tile_window_kernel<float, kPipeRegK>;
     hipLaunchKernelGGL(kernel, grid, dim3(256), 0, a.stream,
                        static_cast<const float*>(a.Q), static_cast<const float*>(a.K),
                        static_cast<const float*>(a.V), static_cast<float*>(a.O), a.lse, a.L,
-                       (int64_t)a.window, s, n_groups, a.scale, acc);
+                       (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len);
   }
   profile_mark_end(a.stream);
   return hip_status(hipGetLastError());

@@ -242,8 +242,50 @@ def test_nonlocal_and_dilated_2d_masks(spec, dtype):
     for path in PATHS:
         O, lse = _run_explicit(wl, Q, K, V, path)
         _close(O, lse, O_ref, lse_ref, dtype)
-    O, lse = _run_implicit(wl, Q, K, V, sga.PATH_AUTO)
-    _close(O, lse, O_ref, lse_ref, dtype)
+    for path in PATHS:
+        O, lse = _run_implicit(wl, Q, K, V, path)
+        _close(O, lse, O_ref, lse_ref, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("block,stride", [(1000, 3), (700, 2), (4000, 1), (200, 5)])
+def test_dilated_2d_implicit_tiles(block, stride, d, dtype):
+    """2-D dilated blocks through the implicit tile kernels: blocks of several tiles with a
+    ragged last block, blocks longer than the sequence, stride 1 (no empty row), and a continuing
+    call, which must leave the rows without neighbours as they are."""
+    print("case 2d", block, stride, d, dtype, flush=True)
+    L = 2500
+    spec = MaskSpec(KIND_DILATED_2D, L, block=block, stride=stride)
+    wl = Workload("t", H=2, L=L, d=d, dtype=dtype, sigma=0.9, mask=spec, explicit=True, seed=33)
+    Q, K, V = small_inputs(wl)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    for path in (sga.PATH_TILE, sga.PATH_AUTO):
+        O, lse = _run_implicit(wl, Q, K, V, path)
+        _close(O, lse, O_ref, lse_ref, dtype)
+    # local window first, then the 2-D dilated edges that the window does not already hold (as
+    # an explicit CSR), then the whole 2-D mask again on top of a copy: rows off the stride keep
+    # the earlier state
+    dQ, dK, dV = to_device(Q, K, V)
+    loc = MaskSpec(KIND_SLIDING, L, window=6)
+    wsi = sga.alloc_workspace(L, wl.H, d, dtype, -1)
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, want_lse=True)
+    O0, lse0 = O.clone(), lse.clone()
+    sga.attention_accumulate_implicit(dQ, dK, dV, spec, wl.scale, O, lse, workspace=wsi, path=sga.PATH_TILE)
+    off = (np.arange(L) % block) % stride != 0
+    assert (O.cpu().numpy()[:, off] == O0.cpu().numpy()[:, off]).all()
+    assert (lse.cpu().numpy()[:, off] == lse0.cpu().numpy()[:, off]).all()
+    # on the stride: the state of window + block edges, counted twice where both masks hold
+    # them; compare against the oracle's two-pass composition of the same two masks
+    m1 = R.dense_mask(loc)
+    m2 = R.dense_mask(spec)
+    for h in range(wl.H):
+        O1, l1 = R.attention_dense(Q[h], K[h], V[h], m1, wl.scale)
+        O2, l2 = R.attention_dense(Q[h], K[h], V[h], m2, wl.scale)
+        lse_c = np.logaddexp(l1, l2)
+        w1 = np.exp(l1 - lse_c)[:, None]
+        w2 = np.where(np.isneginf(l2), 0.0, np.exp(l2 - lse_c))[:, None]
+        _close(O[h].cpu().numpy(), lse[h].cpu().numpy(), w1 * O1 + w2 * O2, lse_c, dtype, factor=2.0)
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
