@@ -51,6 +51,11 @@ __device__ __forceinline__ void copy16_to_lds(const void* src, char* dst) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
                                    (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
 }
+// Same with 4 bytes per lane: lane l's word lands at dst + 4*l.
+__device__ __forceinline__ void copy4_to_lds(const void* src, char* dst) {
+  __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
+                                   (void __attribute__((address_space(3)))*)dst, 4, 0, 0);
+}
 
 // s_waitcnt vmcnt(N): all but the N most recently issued vector memory operations (global
 // loads, LDS copies included) have completed.  The 6-bit count sits in bits 3:0 and 15:14.
@@ -61,11 +66,20 @@ __device__ __forceinline__ void wait_loads_except() {
 }
 
 // Waits until at most `keep` of the most recently issued vector memory operations are still in
-// flight; keep is wave-uniform and one of 0, 4, 8 (any other value: no wait).
+// flight; keep is wave-uniform and one of 0, 4, 8, 9 (any other value: no wait).
 __device__ __forceinline__ void wait_loads_keep(int keep) {
   if (keep == 0) wait_loads_except<0>();
   else if (keep == 4) wait_loads_except<4>();
   else if (keep == 8) wait_loads_except<8>();
+  else if (keep == 9) wait_loads_except<9>();
+}
+
+// K-ready wait of the LDS pipelines: the K copies of block k are older than the kCopies V copies
+// and, if a block record was requested after them, its kGetLoads loads.
+template <int kCopies, int kGetLoads>
+__device__ __forceinline__ void wait_k_block(bool record_requested) {
+  if (kGetLoads > 0 && record_requested) wait_loads_except<kCopies + kGetLoads>();
+  else wait_loads_except<kCopies>();
 }
 
 // The value held by the lane 32 positions away (the same query in the other half-wave), by the
@@ -104,6 +118,7 @@ struct ExplicitBlocks {
   const int32_t* blk;
   const uint32_t* mask;
   int64_t L;
+  static constexpr int kGetLoads = 2;   // vector memory loads issued by one get()
   __device__ int64_t key_stride() const { return 1; }
   // get() only issues the loads (two blocks ahead of their use); resolve() turns the loaded
   // record into wave-uniform values once the block is about to be staged, so that the loads are
@@ -121,6 +136,16 @@ struct ExplicitBlocks {
     const int64_t left = L - b.row0;
     b.nvalid = left < kTile ? (int)left : kTile;
   }
+  // Block k without its mask word, read through the scalar (constant) path: the list is only
+  // written by an earlier kernel, and a scalar load neither occupies a vector register nor counts
+  // among the vector memory operations, so the pipelines' counted waits stay exact.
+  // (like get(), this only issues the load; resolve() completes the record)
+  __device__ BlockInfo block(int k) const {
+    BlockInfo b;
+    b.raw = ((const int32_t __attribute__((address_space(4)))*)blk)[k];
+    b.word = ~0u;
+    return b;
+  }
 };
 
 // Block list of a window tile in one residue class p of stride s: queries u0..u0+31 and keys
@@ -128,6 +153,7 @@ struct ExplicitBlocks {
 // word is wave-uniform and is computed from differences that fit 32 bits.
 struct WindowBlocks {
   int64_t vfirst, Lc, s, p, u0, W;   // blocks start at the tile's first key, not at multiples of 32
+  static constexpr int kGetLoads = 0;
   __device__ int64_t key_stride() const { return s; }
   __device__ static int clamp64(int64_t v) { return v < -64 ? -64 : (v > 64 ? 64 : (int)v); }
   __device__ void resolve(BlockInfo&) const {}
@@ -444,7 +470,7 @@ struct CoreF32T {
       sm.stage_v(Vh, b, lane, ldsv);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
-      wait_loads_except<8>();            // K block k is older than the 8 V copies just issued
+      wait_k_block<8, Src::kGetLoads>(k + 2 < k1);   // K block k: older than the V copies (and the record loads)
       __builtin_amdgcn_wave_barrier();
       float kf[32];
       read_k(ldsk, n, h, kf);
@@ -494,11 +520,62 @@ struct CoreF32T {
     }
   }
 
+  // Explicit block lists: as run_regk, with the block ids read through the scalar path and the
+  // mask words of block k+1 copied global -> LDS while block k is computed (two 256-byte slots
+  // behind the V block), as in CoreF16T::run_ldsk.  The only loads into vector registers are the
+  // K fragments, and the step's own waits are counted: V block k, then the words of block k+1,
+  // then the K fragment of block k+1 are issued in this order, so the fragment may still be in
+  // flight during the PV products.  (Workload 2: 0.51 ms against 0.53 ms with the records loaded
+  // into vector registers two blocks ahead.)
+  __device__ void run_regk(const float* __restrict__ Kh, const float* __restrict__ Vh,
+                           const ExplicitBlocks& src, int k0, int k1, float c, int lane, TileState& st,
+                           char* lds) {
+    if (k0 >= k1) return;
+    const int n = lane & 31, h = lane >> 5;
+    Stage sm;
+    sm.init(1, lane);
+    const uint32_t klane = (uint32_t)(n * sm.stride_bytes) + h * 128;
+    char* ldsw = lds + kBlockBytes;              // two slots of 64 mask words (both half-waves)
+    const uint32_t* wsrc = src.mask + n;         // this lane's word of block k: wsrc[32 k]
+    BlockInfo b = src.block(k0);
+    BlockInfo b1 = src.block(k0 + 1 < k1 ? k0 + 1 : k0);
+    src.resolve(b);
+    __builtin_amdgcn_wave_barrier();     // reads of the buffers by an earlier work item are done
+    copy4_to_lds(wsrc + (int64_t)k0 * kTile, ldsw + (k0 & 1) * 256);
+    float kfa[32], kfb[32];
+    load_k(Kh, b, sm.stride_bytes, klane, n, h, kfa);
+    auto step = [&](int k, float (&kf)[32], float (&kf_next)[32]) {
+      const bool more = k + 1 < k1;      // wave-uniform
+      src.resolve(b1);
+      __builtin_amdgcn_wave_barrier();   // the previous block's reads of V and of the other word slot are done
+      sm.stage_v(Vh, b, lane, lds);
+      if (more) {
+        copy4_to_lds(wsrc + (int64_t)(k + 1) * kTile, ldsw + ((k + 1) & 1) * 256);
+        load_k(Kh, b1, sm.stride_bytes, klane, n, h, kf_next);
+      }
+      BlockInfo b2 = b1;
+      if (k + 2 < k1) b2 = src.block(k + 2);
+      // the words and the K fragment of block k are older than the 8 (+ 1 + 8) operations above
+      if (more) wait_loads_except<17>(); else wait_loads_except<8>();
+      __builtin_amdgcn_wave_barrier();
+      b.word = *reinterpret_cast<const uint32_t*>(ldsw + (k & 1) * 256 + lane * 4);
+      // V block k is older than the word copy and the 8 fragment loads (if any)
+      block_math(kf, b, c, n, h, st, lds, more ? 9 : 0);
+      b = b1;
+      b1 = b2;
+    };
+    for (int k = k0; k < k1; k += 2) {
+      step(k, kfa, kfb);
+      if (k + 1 >= k1) break;
+      step(k + 1, kfb, kfa);
+    }
+  }
+
   // kLdsK selects the pipeline: K block staged in LDS (coalesced whole-row copies; best with many
   // blocks per tile) or K fragment loaded straight into registers (no LDS round trip before the
   // first product; best with two or three blocks per tile).
   template <int kPipe>
-  static constexpr int lds_bytes() { return kPipe == kPipeRegK ? kBlockBytes : 2 * kBlockBytes; }
+  static constexpr int lds_bytes() { return kPipe == kPipeRegK ? kBlockBytes + 512 : 2 * kBlockBytes; }
 
   template <int kPipe, typename Src>
   __device__ void run(const float* __restrict__ Kh, const float* __restrict__ Vh, const Src& src,
@@ -576,15 +653,27 @@ struct CoreF16T {
   // negative: it is known to be complete)
   __device__ void block_math(const half8 (&kf)[4], const BlockInfo& b, float c, int lane, int h,
                              TileState& st, const char* ldsv, int v_keep) {
+    float p[16];
+    scores(kf, b, c, lane, h, st, p);
+    wait_loads_keep(v_keep);
+    __builtin_amdgcn_wave_barrier();
+    accumulate(p, lane, h, st, ldsv);
+  }
+
+  // First half of the block step: S^T = K_blk Q^T and the softmax update; p = numerators.
+  __device__ void scores(const half8 (&kf)[4], const BlockInfo& b, float c, int lane, int h,
+                         TileState& st, float (&p)[16]) {
     floatx16 sacc = {0};
 #pragma unroll
     for (int s = 0; s < 4; ++s)
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
     if (kD > kHeadDim) xchg.sum_slices(sacc, lane);
-    float p[16];
     softmax_block(sacc, c, b, h, st, p);
-    wait_loads_keep(v_keep);
-    __builtin_amdgcn_wave_barrier();
+  }
+
+  // Second half: O^T += V_blk^T P^T with the V block staged (complete) at ldsv.
+  __device__ static void accumulate(const float (&p)[16], int lane, int h, TileState& st,
+                                    const char* ldsv) {
     // this lane's address for key0 = 4h, channel group 0; the other reads are constant offsets
     const int i = lane & 15, grp16 = (lane >> 4) & 1;
     const char* vt = ldsv + (4 * h + (i >> 2)) * (kHeadDim * 2) + (grp16 * 16 + 4 * (i & 3)) * 2;
@@ -626,14 +715,14 @@ struct CoreF16T {
       sm.stage_v(Vh, b, lane, ldsv);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
-      wait_loads_except<4>();            // K block k is older than the 4 V copies just issued
+      wait_k_block<4, Src::kGetLoads>(k + 2 < k1);   // K block k: older than the V copies (and the record loads)
       __builtin_amdgcn_wave_barrier();
       half8 kf[4];
       read_k(ldsk, n, h, kf);
       wait_lds_reads();                  // the K buffer may be overwritten now
       __builtin_amdgcn_wave_barrier();
       if (more) sm.stage_k(Kh, b1, lane, ldsk);
-      // V block k is older than the 4 K copies issued above (if any)
+      // V block k (and any record load after it) is older than the 4 K copies issued above (if any)
       block_math(kf, b, c, lane, h, st, ldsv, more ? 4 : 0);
       b = b1;
       b1 = b2;
@@ -713,8 +802,59 @@ struct CoreF16T {
     }
   }
 
+  // Explicit block lists: as run_ldsk, with no vector load into registers inside the loop.  Block
+  // ids come through the scalar path (ExplicitBlocks::block), and the 32 mask words of block k+1
+  // are copied global -> LDS (one 4-byte copy per lane into one of two 256-byte slots) while block
+  // k is computed.  Every vector memory operation of the loop is then an LDS copy whose
+  // completion only the counted waits below ask for; a register load carried around the loop
+  // would make the compiler drain all of them, the prefetched K block included, once per block.
+  __device__ void run_ldsk(const __half* __restrict__ Kh, const __half* __restrict__ Vh,
+                           const ExplicitBlocks& src, int k0, int k1, float c, int lane, TileState& st,
+                           char* lds) {
+    if (k0 >= k1) return;
+    const int n = lane & 31, h = lane >> 5;
+    Stage sm;
+    sm.init(1, lane);
+    char* ldsk = lds;
+    char* ldsv = lds + kBlockBytes;
+    char* ldsw = lds + 2 * kBlockBytes;          // two slots of 64 mask words (both half-waves)
+    const uint32_t* wsrc = src.mask + n;         // this lane's word of block k: wsrc[32 k]
+    BlockInfo b = src.block(k0);
+    BlockInfo b1 = src.block(k0 + 1 < k1 ? k0 + 1 : k0);
+    src.resolve(b);
+    __builtin_amdgcn_wave_barrier();     // reads of the buffers by an earlier work item are done
+    copy4_to_lds(wsrc + (int64_t)k0 * kTile, ldsw + (k0 & 1) * 256);
+    sm.stage_k(Kh, b, lane, ldsk);
+    for (int k = k0; k < k1; ++k) {
+      const bool more = k + 1 < k1;      // wave-uniform
+      src.resolve(b1);
+      __builtin_amdgcn_wave_barrier();   // the previous block's reads of V and of the other word slot are done
+      if (more) copy4_to_lds(wsrc + (int64_t)(k + 1) * kTile, ldsw + ((k + 1) & 1) * 256);
+      sm.stage_v(Vh, b, lane, ldsv);
+      BlockInfo b2 = b1;
+      if (k + 2 < k1) b2 = src.block(k + 2);
+      // K block k and the words of block k are older than the copies issued in this step
+      if (more) wait_loads_except<5>(); else wait_loads_except<4>();
+      __builtin_amdgcn_wave_barrier();
+      half8 kf[4];
+      read_k(ldsk, n, h, kf);
+      b.word = *reinterpret_cast<const uint32_t*>(ldsw + (k & 1) * 256 + lane * 4);
+      wait_lds_reads();                  // the K buffer may be overwritten now
+      __builtin_amdgcn_wave_barrier();
+      if (more) sm.stage_k(Kh, b1, lane, ldsk);
+      float p[16];
+      scores(kf, b, c, lane, h, st, p);
+      // V block k (and the words of block k+1) are older than the 4 K copies issued above (if any)
+      if (more) wait_loads_except<4>(); else wait_loads_except<0>();
+      __builtin_amdgcn_wave_barrier();
+      accumulate(p, lane, h, st, ldsv);
+      b = b1;
+      b1 = b2;
+    }
+  }
+
   template <int kPipe>
-  static constexpr int lds_bytes() { return 2 * kBlockBytes; }
+  static constexpr int lds_bytes() { return 2 * kBlockBytes + 512; }
 
   template <int kPipe, typename Src>
   __device__ void run(const __half* __restrict__ Kh, const __half* __restrict__ Vh, const Src& src,
@@ -820,7 +960,7 @@ struct CoreSplit {
       sm.stage_v(Vh, b, lane, ldsv);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
-      wait_loads_except<8>();            // K block k is older than the 8 V copies just issued
+      wait_k_block<8, Src::kGetLoads>(k + 2 < k1);   // K block k: older than the V copies (and the record loads)
       __builtin_amdgcn_wave_barrier();
       half8 kh[4], kl[4];
       {
@@ -843,8 +983,10 @@ struct CoreSplit {
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kh[s], qh[s], sacc, 0, 0, 0);
       float p[16];
       softmax_block(sacc, c, b, h, st, p);
-      // V block k is older than the 8 K copies issued above (if any)
+      // V block k (and any record load after it) is older than the 8 K copies issued above (if any)
       if (more) wait_loads_except<8>(); else wait_loads_except<0>();
+      b = b1;
+      b1 = b2;
       __builtin_amdgcn_wave_barrier();
       {
         // split the staged fp32 V block in place: rows 4i + lr, channels 4*lc .. +3 per copy i
@@ -889,8 +1031,6 @@ struct CoreSplit {
           st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vh, ph, st.o[cb], 0, 0, 0);
         }
       }
-      b = b1;
-      b1 = b2;
     }
   }
 
