@@ -31,11 +31,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 5_759_710,
-    "cfg2_longformer_64k": 1_111_578_474,
-    "cfg3_dilated_1m": 2_149_415_249,
-    "cfg4_bigbird_1m": 12_092_431_228,
-    "cfg5_sliding_160m": 82_545_058_653,
+    "cfg1_sliding_4k": 5_464_071,
+    "cfg2_longformer_64k": 1_079_664_036,
+    "cfg3_dilated_1m": 2_149_419_825,
+    "cfg4_bigbird_1m": 9_491_396_214,
+    "cfg5_sliding_160m": 82_485_963_452,
 }
 
 
