@@ -1188,7 +1188,9 @@ __device__ __forceinline__ WorkId locate_work(const int64_t* __restrict__ row_pt
 // lane r < 32 walks row 32t + r.  A 32-way merge by key block id: every round takes the
 // smallest block id at the head of any row and lets each row consume its columns inside that
 // block into a 32-bit word.  A row whose remaining columns are consecutive integers (windows,
-// global rows) is walked arithmetically without reading col_idx again.
+// global rows) is walked arithmetically without reading col_idx again; otherwise a run of
+// consecutive columns up to the end of the block costs two loads, and only scattered columns
+// are read one by one.
 __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __restrict__ row_ptr,
                                                            const int32_t* __restrict__ col_idx,
                                                            int64_t L, int32_t H, int32_t dtype,
@@ -1235,23 +1237,28 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
       pos = lower_bound_col(col_idx, pos, end, B0 * kTile);
       end = lower_bound_col(col_idx, pos, end, B1 * kTile);
     }
-    // a row whose remaining columns are one run of consecutive integers needs no more loads
+    // a row whose remaining columns are one run of consecutive integers needs no more loads;
+    // the test is repeated with every column that starts a round (it costs nothing: the last
+    // column is kept), so a row of a few runs turns arithmetic once its last run is reached
     int run_lo = 0, run_hi = -1;
     bool arith = false;
-    if (pos < end) {
-      const int c0 = col_idx[pos], c1 = col_idx[end - 1];
-      if ((int64_t)c1 - c0 == end - 1 - pos) {
-        arith = true;
-        run_lo = c0;
-        run_hi = c1;
-      }
-    }
+    const int c_last = pos < end ? col_idx[end - 1] : -1;
     int nblk = 0;
     bool overflow = false;
     while (true) {
-      int cur;
+      int cur = INT32_MAX;
+      if (!arith && pos < end) {
+        const int c0 = col_idx[pos];
+        if ((int64_t)c_last - c0 == end - 1 - pos) {
+          arith = true;
+          run_lo = c0;
+          run_hi = c_last;
+          pos = end;
+        } else {
+          cur = c0 >> 5;
+        }
+      }
       if (arith) cur = run_lo <= run_hi ? (run_lo >> 5) : INT32_MAX;
-      else cur = pos < end ? (col_idx[pos] >> 5) : INT32_MAX;
       const int b = __shfl(half_min(cur), 0, kWave);
       if (b == INT32_MAX) break;
       if (nblk >= cap) {
@@ -1266,10 +1273,16 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
           word = (~0u >> (31 - hi)) & (~0u << lo);
           run_lo = (b + 1) << 5;
         } else {
+          // if the row's columns run consecutively up to the end of the block (or of the row),
+          // one more load settles the whole word: the list is sorted and free of duplicates, so
+          // equal ends mean every column in between is present
           const int c0 = col_idx[pos];
-          if ((c0 & 31) == 0 && pos + 31 < end && col_idx[pos + 31] == c0 + 31) {
-            word = ~0u;   // 32 consecutive columns: the whole block row
-            pos += 32;
+          const int lo = c0 & 31;
+          const int64_t left = end - pos;
+          const int cnt = left < 32 - lo ? (int)left : 32 - lo;
+          if (col_idx[pos + cnt - 1] == c0 + cnt - 1) {
+            word = (~0u >> (32 - cnt)) << lo;
+            pos += cnt;
           } else {
             // the row's columns inside block b are the next entries of its sorted list: take
             // them four per load while four remain, then one by one
@@ -1856,7 +1869,11 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   const int64_t n_tiles = (a.L + kTile - 1) / kTile;
   int64_t nwg = (n_tiles + 3) / 4 + 64;
   if (nwg > 16384) nwg = 16384;
-  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
+  // (the CSR -> tile pass is a chain of dependent loads per item: one wavefront per tile and a
+  // margin for the extra segments keeps every item's chain in flight at once)
+  int64_t nwg_analyze = n_tiles + 64;
+  if (nwg_analyze > 16384) nwg_analyze = 16384;
+  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg_analyze), dim3(256), 0, a.stream, a.row_ptr,
                      a.col_idx, a.L, a.H, a.dtype, kHeadDim, a.ws, a.ws_bytes);
   // fp32: resident workgroups only (256 CUs x 2 wavefronts per SIMD, shared by the heads), which
   // claim items dynamically; fp16: one pass of workgroups over the items of each head
@@ -1889,7 +1906,9 @@ sga_status run_tile_explicit_wide_d(const AttnArgs& a) {
   const int64_t n_tiles = (a.L + kTile - 1) / kTile;
   int64_t nwg = (n_tiles + 3) / 4 + 64;
   if (nwg > 16384) nwg = 16384;
-  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.row_ptr,
+  int64_t nwg_analyze = n_tiles + 64;
+  if (nwg_analyze > 16384) nwg_analyze = 16384;
+  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg_analyze), dim3(256), 0, a.stream, a.row_ptr,
                      a.col_idx, a.L, a.H, a.dtype, kD, a.ws, a.ws_bytes);
   // resident workgroups (2 wavefronts per SIMD over the chip), shared by the heads
   int64_t per_head = (2048 / kSlices) / a.H;
