@@ -381,6 +381,8 @@ def main():
     ap.add_argument("--suite", default=None, choices=["table3", "e2"],
                     help="instead of the benchmark line, time the shapes of the paper's Table III "
                          "or of its microbenchmark grid and print one JSON object")
+    ap.add_argument("--dims", default="64,128,256",
+                    help="head dimensions of --suite e2 (comma-separated)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of known size (1 GiB read + 1 GiB written) and "
                          "exit: the reference against which rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -405,7 +407,8 @@ def main():
         return
     path = {"auto": 0, "gather": 1, "tile": 2, "tile_split": 3}[args.path]
     if args.suite:
-        print(json.dumps(suite_table3(path) if args.suite == "table3" else suite_e2(path)))
+        print(json.dumps(suite_table3(path) if args.suite == "table3"
+                         else suite_e2(path, tuple(int(x) for x in args.dims.split(",")))))
         return
     wl = WORKLOADS[args.workload]
     run = Runner(wl, path)
