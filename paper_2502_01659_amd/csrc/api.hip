@@ -194,6 +194,10 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
   }
   if (path == SGA_PATH_GATHER || d < kHeadDim)
     return launch_gather_implicit(a);
+  // 2-D dilated blocks with fewer than 16 selected rows would leave most of a 32-query tile
+  // empty: the per-row kernels handle them
+  if (kind == SGA_MASK_DILATED_2D && path == SGA_PATH_AUTO && a.window + 1 < 16)
+    return launch_gather_implicit(a);
   return launch_tile_implicit(a);
 }
 

@@ -493,3 +493,56 @@ def test_split_precision_path_value_ranges(sigma):
     with pytest.raises(sga.SgaError):
         h = dQ.half()
         sga.attention_forward_implicit(h, h, h, loc, wl.scale, path=sga.PATH_TILE_SPLIT)
+
+
+def _random_case(seed):
+    """A seeded random (mask, shape) draw over every mask family, ragged lengths and both
+    storage types; parameters stay inside the ranges the descriptors document."""
+    rng = np.random.default_rng(1000 + seed)
+    kind = [KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD, KIND_NONLOCAL,
+            KIND_DILATED_2D][seed % 6]
+    L = int(rng.integers(1, 900))
+    d = int(rng.choice([64, 64, 128, 256, 32]))
+    dtype = "f32" if rng.random() < 0.5 else "f16"
+    H = int(rng.integers(1, 4))
+    if kind == KIND_SLIDING:
+        spec = MaskSpec(kind, L, window=int(rng.integers(0, 2 * L + 2)) if rng.random() < 0.3
+                        else int(rng.integers(0, 70)))
+    elif kind == KIND_DILATED:
+        spec = MaskSpec(kind, L, window=int(rng.integers(0, 40)), stride=int(rng.integers(1, 9)))
+    elif kind in (KIND_GLOBAL_LOCAL, KIND_NONLOCAL):
+        spec = MaskSpec(kind, L, window=int(rng.integers(0, 50)), n_global=int(rng.integers(0, 40)))
+    elif kind == KIND_DILATED_2D:
+        spec = MaskSpec(kind, L, block=int(rng.integers(1, 2 * L + 2)), stride=int(rng.integers(1, 6)))
+    else:
+        block = int(rng.choice([8, 16, 32, 64]))
+        nb = int(rng.integers(8, 24))
+        L = block * nb
+        wb, g, r = int(rng.integers(0, 2)), int(rng.integers(0, 3)), int(rng.integers(0, 3))
+        spec = MaskSpec(kind, L, block=block, window_blocks=wb, n_global_blocks=g, n_random_blocks=r,
+                        seed=int(rng.integers(0, 1 << 30)))
+    sigma = float(rng.choice([0.3, 0.6, 1.0]))   # (the absolute tolerances are stated for |O| of order 1)
+    return Workload(f"r{seed}", H=H, L=L, d=d, dtype=dtype, sigma=sigma, mask=spec, explicit=True,
+                    seed=500 + seed)
+
+
+@pytest.mark.parametrize("seed", range(36))
+def test_random_shapes_every_path(seed):
+    """Seeded random draws over mask family, length, head dimension, heads and storage type:
+    the explicit call on every path the shape allows, and the implicit call where the family has
+    a generator, against the dense oracle."""
+    wl = _random_case(seed)
+    print("case", wl.name, wl.mask, wl.d, wl.dtype, wl.H, flush=True)
+    Q, K, V = small_inputs(wl)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    paths = [sga.PATH_AUTO, sga.PATH_GATHER] + ([sga.PATH_TILE] if wl.d >= 64 else [])
+    for path in paths:
+        O, lse = _run_explicit(wl, Q, K, V, path)
+        _close(O, lse, O_ref, lse_ref, wl.dtype)
+    kind = wl.mask.kind
+    implicit_ok = kind in (KIND_SLIDING, KIND_DILATED, KIND_DILATED_2D) or \
+        (kind == KIND_NONLOCAL and wl.mask.n_global <= 64)
+    if implicit_ok:
+        for path in paths:
+            O, lse = _run_implicit(wl, Q, K, V, path)
+            _close(O, lse, O_ref, lse_ref, wl.dtype)
