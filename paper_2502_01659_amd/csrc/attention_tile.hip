@@ -907,12 +907,27 @@ struct CoreSplit {
   static constexpr int kBlockBytes = kTile * kHeadDim * 4;
   half8 qh[4], ql[4];   // Q[query n][h*32 + 8s .. +7], high and low parts
 
+  typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+
+  // Two values at a time: hi = fp16(x) packed into one register, x - hi by the mixed-precision
+  // fma (the fp16 operand is read straight out of the packed pair, no conversion back), and the
+  // remainders packed again: four instructions per pair.
+  __device__ static void split2(float x0, float x1, half2v& hi, half2v& lo) {
+    hi = half2v{(_Float16)x0, (_Float16)x1};
+    const uint32_t hp = __builtin_bit_cast(uint32_t, hi);
+    float r0, r1;
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel_hi:[1,0,0]" : "=v"(r0) : "v"(hp), "v"(x0));
+    asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r1) : "v"(hp), "v"(x1));
+    lo = half2v{(_Float16)r0, (_Float16)r1};
+  }
+
   __device__ static void split8(const float* x, half8& hi, half8& lo) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const _Float16 hv = (_Float16)x[e];
-      hi[e] = hv;
-      lo[e] = (_Float16)(x[e] - (float)hv);
+    for (int e = 0; e < 8; e += 2) {
+      half2v h2, l2;
+      split2(x[e], x[e + 1], h2, l2);
+      hi[e] = h2[0]; hi[e + 1] = h2[1];
+      lo[e] = l2[0]; lo[e + 1] = l2[1];
     }
   }
 
@@ -1002,10 +1017,11 @@ struct CoreSplit {
         for (int i = 0; i < 8; ++i) {
           half4 vh, vl;
 #pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            const _Float16 hv = (_Float16)vraw[4 * i + e];
-            vh[e] = hv;
-            vl[e] = (_Float16)(vraw[4 * i + e] - (float)hv);
+          for (int e = 0; e < 4; e += 2) {
+            half2v h2, l2;
+            split2(vraw[4 * i + e], vraw[4 * i + e + 1], h2, l2);
+            vh[e] = h2[0]; vh[e + 1] = h2[1];
+            vl[e] = l2[0]; vl[e + 1] = l2[1];
           }
           char* row = ldsv + (4 * i + lr) * (kHeadDim * 2) + lc * 8;
           *reinterpret_cast<half4*>(row) = vh;
