@@ -116,8 +116,9 @@ MaskParams make_params(const sga_mask_desc& d) {
   return p;
 }
 
-__global__ __launch_bounds__(256) void row_ptr_kernel(MaskParams p, int64_t* __restrict__ row_ptr) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+__device__ __forceinline__ void row_ptr_part(const MaskParams& p, int64_t* __restrict__ row_ptr,
+                                             int64_t bid) {
+  const int64_t i = bid * blockDim.x + threadIdx.x;
   if (i <= p.L) row_ptr[i] = row_offset(p, i);
 }
 
@@ -140,16 +141,16 @@ __host__ __device__ inline int64_t group_rows(const MaskParams& p) {
 // One wavefront per row group: lane 0 derives the group's segments once, then the wavefront
 // streams every row of the group with coalesced 256-byte stores.  Full rows are left to
 // fill_full_rows_kernel.
-__global__ __launch_bounds__(256) void fill_kernel(MaskParams p, const int64_t* __restrict__ row_ptr,
-                                                   int32_t* __restrict__ col_idx) {
-  __shared__ Segment seg_all[4][kMaxSegments];
-  __shared__ int n_seg_all[4];
-  __shared__ int64_t picks_all[4][kMaxRandom];
+// (row offsets are evaluated in closed form, not read from row_ptr, so that this part does not
+// depend on the part of the launch that writes row_ptr)
+__device__ __forceinline__ void fill_part(const MaskParams& p, int32_t* __restrict__ col_idx, int64_t bid,
+                                          Segment (*seg_all)[kMaxSegments], int* n_seg_all,
+                                          int64_t (*picks_all)[kMaxRandom]) {
   const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
   Segment* seg = seg_all[wave];
   int64_t* picks = picks_all[wave];
   const int64_t R = group_rows(p);
-  const int64_t group = (int64_t)blockIdx.x * 4 + wave;
+  const int64_t group = bid * 4 + wave;
   const int64_t i = group * R;                      // first row of the group
   if (i >= p.L || i < full_rows(p)) return;
   if (lane == 0) {
@@ -221,8 +222,12 @@ __global__ __launch_bounds__(256) void fill_kernel(MaskParams p, const int64_t* 
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
   const int n = n_seg_all[wave];
   const int64_t rows = imin(R, p.L - i);
+  // the rows of a group hold the same columns, so they follow each other at equal distances
+  int64_t row_len = 0;
+  for (int k = 0; k < n; ++k) row_len += seg[k].len;
+  const int64_t base = row_offset(p, i);
   for (int64_t r = 0; r < rows; ++r) {
-    int32_t* out = col_idx + row_ptr[i + r];
+    int32_t* out = col_idx + base + r * row_len;
     for (int k = 0; k < n; ++k) {
       const Segment sg = seg[k];
       for (int32_t t = lane; t < sg.len; t += kWave) out[t] = sg.start + t * sg.step;
@@ -231,17 +236,36 @@ __global__ __launch_bounds__(256) void fill_kernel(MaskParams p, const int64_t* 
   }
 }
 
-// Rows [0, n_full) attend every key: col_idx of such a row is 0, 1, ..., L-1.
-// grid = (chunks of 4096 columns, full rows); 16 consecutive entries per thread.
-__global__ __launch_bounds__(256) void fill_full_rows_kernel(int64_t L,
-                                                             const int64_t* __restrict__ row_ptr,
-                                                             int32_t* __restrict__ col_idx) {
-  int32_t* out = col_idx + row_ptr[blockIdx.y];
-  const int64_t base = (int64_t)blockIdx.x * 4096;
+// Rows [0, n_full) attend every key: col_idx of such a row is 0, 1, ..., L-1.  One workgroup per
+// chunk of 4096 columns of one full row; 16 consecutive entries per thread.
+__device__ __forceinline__ void full_rows_part(const MaskParams& p, int32_t* __restrict__ col_idx,
+                                               int64_t row, int64_t chunk) {
+  int32_t* out = col_idx + row_offset(p, row);
+  const int64_t base = chunk * 4096;
 #pragma unroll
   for (int u = 0; u < 16; ++u) {
     const int64_t j = base + u * 256 + threadIdx.x;
-    if (j < L) out[j] = (int32_t)j;
+    if (j < p.L) out[j] = (int32_t)j;
+  }
+}
+
+// The whole mask -> CSR pass in one launch: workgroups [0, n_rp) write row_ptr, the next n_fill
+// write the column runs of the ordinary rows, the rest the full rows (chunks_per_row workgroups
+// each).  The three parts do not depend on each other.
+__global__ __launch_bounds__(256) void build_mask_kernel(MaskParams p, int64_t* __restrict__ row_ptr,
+                                                         int32_t* __restrict__ col_idx, uint32_t n_rp,
+                                                         uint32_t n_fill, uint32_t chunks_per_row) {
+  __shared__ Segment seg_all[4][kMaxSegments];
+  __shared__ int n_seg_all[4];
+  __shared__ int64_t picks_all[4][kMaxRandom];
+  const uint32_t bid = blockIdx.x;
+  if (bid < n_rp) {
+    row_ptr_part(p, row_ptr, bid);
+  } else if (bid < n_rp + n_fill) {
+    fill_part(p, col_idx, bid - n_rp, seg_all, n_seg_all, picks_all);
+  } else {
+    const uint32_t idx = bid - n_rp - n_fill;
+    full_rows_part(p, col_idx, idx / chunks_per_row, idx % chunks_per_row);
   }
 }
 
@@ -283,20 +307,15 @@ int64_t mask_total_edges(const sga_mask_desc& d) {
 sga_status launch_build_mask(const sga_mask_desc& d, int64_t* row_ptr, int32_t* col_idx,
                              hipStream_t stream) {
   const MaskParams p = make_params(d);
-  const unsigned nblk = (unsigned)((p.L + 1 + 255) / 256);
-  hipLaunchKernelGGL(row_ptr_kernel, dim3(nblk), dim3(256), 0, stream, p, row_ptr);
+  const int64_t n_rp = (p.L + 1 + 255) / 256;
   const int64_t groups = (p.L + group_rows(p) - 1) / group_rows(p);
-  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((groups + 3) / 4)), dim3(256), 0, stream, p, row_ptr,
-                     col_idx);
+  const int64_t n_fill = (groups + 3) / 4;
   const int64_t n_full = full_rows(p) < p.L ? full_rows(p) : p.L;
-  if (n_full > 0) {
-    // grid.y is limited to 65535 rows per launch
-    for (int64_t r0 = 0; r0 < n_full; r0 += 65535) {
-      const int64_t rows = n_full - r0 < 65535 ? n_full - r0 : 65535;
-      hipLaunchKernelGGL(fill_full_rows_kernel, dim3((unsigned)((p.L + 4095) / 4096), (unsigned)rows),
-                         dim3(256), 0, stream, p.L, row_ptr + r0, col_idx);
-    }
-  }
+  const int64_t chunks = (p.L + 4095) / 4096;
+  const int64_t total = n_rp + n_fill + n_full * chunks;
+  if (total >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;   // (more than 2^31 workgroups: L^2 / 4096 full-row chunks)
+  hipLaunchKernelGGL(build_mask_kernel, dim3((unsigned)total), dim3(256), 0, stream, p, row_ptr, col_idx,
+                     (uint32_t)n_rp, (uint32_t)n_fill, (uint32_t)(chunks > 0 ? chunks : 1));
   return hip_status(hipGetLastError());
 }
 
