@@ -290,14 +290,12 @@ __device__ __forceinline__ bool row_done_by_tiles(const int64_t* row_ptr, int64_
   return tile_handled(pl, ws, row_ptr, L, dtype, i / kTile);
 }
 
-// One wavefront per query row over the row's CSR slice.  (bid, nb): this workgroup's index among
-// the nb workgroups that share the rows.
 template <typename T, int D>
-__device__ __forceinline__ void gather_csr_rows(
+__global__ __launch_bounds__(256) void gather_csr_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
     int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split, int skip_tiled,
-    int accumulate, int64_t bid, int64_t nb) {
+    int accumulate) {
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
@@ -307,7 +305,8 @@ __device__ __forceinline__ void gather_csr_rows(
     const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code, D);
     if (pl.total_bytes <= ws_bytes && tiles_cover_everything(pl, ws)) return;
   }
-  for (int64_t i = bid * waves + (threadIdx.x / kWave); i < L; i += nb * waves) {
+  for (int64_t i = (int64_t)blockIdx.x * waves + (threadIdx.x / kWave); i < L;
+       i += (int64_t)gridDim.x * waves) {
     if (skip_tiled && row_done_by_tiles(row_ptr, L, H, DtypeOf<T>::code, D, ws, ws_bytes, i)) continue;
     const int64_t r0 = row_ptr[i], r1 = row_ptr[i + 1];
     if (use_split && r1 - r0 > kSplitThreshold && split_active(row_ptr, L, H, DtypeOf<T>::code, D, ws, ws_bytes))
@@ -320,16 +319,6 @@ __device__ __forceinline__ void gather_csr_rows(
     attend_range<T, D>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
     finish_row<T, D>(O + hoff + i * D, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
   }
-}
-
-template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_csr_kernel(
-    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
-    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-    int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split, int skip_tiled,
-    int accumulate) {
-  gather_csr_rows<T, D>(Q, K, V, O, lse, row_ptr, col_idx, L, scale, ws, ws_bytes, use_split, skip_tiled,
-                        accumulate, blockIdx.x, gridDim.x);
 }
 
 template <typename T, int D>
@@ -484,13 +473,12 @@ __global__ __launch_bounds__(64) void nonlocal_merge_kernel(T* __restrict__ O, f
                            lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
 }
 
-// One wavefront per (chunk item, head): partial state of a slice of a long row.  (bid, nb) as in
-// gather_csr_rows.
+// One wavefront per (chunk item, head): partial state of a slice of a long row.
 template <typename T, int D>
-__device__ __forceinline__ void gather_chunk_items(
+__global__ __launch_bounds__(256) void gather_chunk_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t L, float scale,
-    void* ws, size_t ws_bytes, uint32_t bid, uint32_t nb) {
+    void* ws, size_t ws_bytes) {
   const int32_t H = (int32_t)gridDim.y;
   constexpr int32_t dtype = DtypeOf<T>::code;
   if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
@@ -502,7 +490,8 @@ __device__ __forceinline__ void gather_chunk_items(
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
   const int64_t hoff = h * L * D;
-  for (uint32_t it = bid * waves + threadIdx.x / kWave; it < n_items; it += nb * waves) {
+  for (uint32_t it = blockIdx.x * waves + threadIdx.x / kWave; it < n_items;
+       it += gridDim.x * waves) {
     const int2 item = items[it];
     const int64_t i = item.x;
     const int64_t r0 = row_ptr[i], deg = row_ptr[i + 1] - r0;
@@ -527,30 +516,6 @@ __device__ __forceinline__ void gather_chunk_items(
       p[D + 1] = st.l;
     }
   }
-}
-
-template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_chunk_kernel(
-    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
-    const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t L, float scale,
-    void* ws, size_t ws_bytes) {
-  gather_chunk_items<T, D>(Q, K, V, row_ptr, col_idx, L, scale, ws, ws_bytes, blockIdx.x, gridDim.x);
-}
-
-// The rows the tile path left over, in one launch: the first n_rows workgroups (per head) take the
-// ordinary rows, the others the chunks of the long rows.  The two parts write different rows and
-// both depend only on the pre-pass.
-template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_leftover_kernel(
-    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
-    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
-    int64_t L, float scale, void* ws, size_t ws_bytes, int accumulate, uint32_t n_rows) {
-  if (blockIdx.x < n_rows)
-    gather_csr_rows<T, D>(Q, K, V, O, lse, row_ptr, col_idx, L, scale, ws, ws_bytes, 1, 1, accumulate,
-                          blockIdx.x, n_rows);
-  else
-    gather_chunk_items<T, D>(Q, K, V, row_ptr, col_idx, L, scale, ws, ws_bytes, blockIdx.x - n_rows,
-                             gridDim.x - n_rows);
 }
 
 // One wavefront per (long row, head): combine the row's partials in chunk order.
@@ -595,23 +560,14 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   const int64_t leftover_wgs = 2048 / a.H > 256 ? 2048 / a.H : 256;
   if (skip_tiled && nwg > leftover_wgs) nwg = leftover_wgs;
   const dim3 grid((unsigned)nwg, (unsigned)a.H);
-  const unsigned n_chunk_wgs = skip_tiled && a.H >= 8 ? 128 : 1024;
-  if (skip_tiled && split) {
-    // leftover rows and the chunks of leftover long rows in one launch
-    hipLaunchKernelGGL((gather_leftover_kernel<T, D>), dim3((unsigned)nwg + n_chunk_wgs, (unsigned)a.H),
-                       dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.col_idx, a.L, a.scale, a.ws,
-                       a.ws_bytes, a.accumulate ? 1 : 0, (uint32_t)nwg);
-  } else {
-    if (!skip_tiled) profile_mark_begin(a.stream);
-    hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
-                       a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
-                       skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
-    if (!skip_tiled) profile_mark_end(a.stream);
-    if (split)
-      hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(n_chunk_wgs, (unsigned)a.H), dim3(256), 0,
-                         a.stream, Q, K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
-  }
+  if (!skip_tiled) profile_mark_begin(a.stream);
+  hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
+                     a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
+                     skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
+  if (!skip_tiled) profile_mark_end(a.stream);
   if (split) {
+    hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled && a.H >= 8 ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
+                       K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
     hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
                        a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   }
