@@ -31,11 +31,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 6_219_701,
-    "cfg2_longformer_64k": 1_082_002_717,
-    "cfg3_dilated_1m": 2_149_420_056,
-    "cfg4_bigbird_1m": 9_473_808_104,
-    "cfg5_sliding_160m": 82_484_313_119,
+    "cfg1_sliding_4k": 5_792_232,
+    "cfg2_longformer_64k": 1_087_770_485,
+    "cfg3_dilated_1m": 2_149_423_131,
+    "cfg4_bigbird_1m": 9_516_834_861,
+    "cfg5_sliding_160m": 82_488_502_580,
 }
 
 
