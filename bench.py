@@ -31,11 +31,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 5_792_232,
-    "cfg2_longformer_64k": 1_087_770_485,
-    "cfg3_dilated_1m": 2_149_423_131,
-    "cfg4_bigbird_1m": 9_516_834_861,
-    "cfg5_sliding_160m": 82_488_502_580,
+    "cfg1_sliding_4k": 6_449_258,
+    "cfg2_longformer_64k": 1_082_157_601,
+    "cfg3_dilated_1m": 2_149_419_235,
+    "cfg4_bigbird_1m": 9_468_071_832,
+    "cfg5_sliding_160m": 82_492_343_833,
 }
 
 
@@ -423,6 +423,7 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "gather", "tile", "tile_split"])
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache launches")
     ap.add_argument("--suite", default=None, choices=["table3", "e2"],
                     help="instead of the benchmark line, time the shapes of the paper's Table III "
                          "or of its microbenchmark grid and print one JSON object")
@@ -478,7 +479,7 @@ def main():
         "forward_edges_per_s": edges / (fwd_ms * 1e-3),
         "roofline": roofline_of(wl, run.nnz, kern_ms, args.path),
     }
-    if 4 * wl.d * (4 if wl.dtype == "f32" else 2) * wl.L <= (256 << 20):
+    if not args.no_cold and 4 * wl.d * (4 if wl.dtype == "f32" else 2) * wl.L <= (256 << 20):
         # one head's tensors fit the last-level cache: also report launches that start cold
         cf, ck = run.cold()
         out["cold_cache"] = {"forward_ms": cf, "kernel_ms": ck,
