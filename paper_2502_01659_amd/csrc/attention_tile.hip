@@ -1250,8 +1250,17 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
       const int64_t span = bmax - bmin + 1;
       const int64_t B0 = bmin + span * id.seg / id.nseg;
       const int64_t B1 = bmin + span * (id.seg + 1) / id.nseg;
-      pos = lower_bound_col(col_idx, pos, end, B0 * kTile);
-      end = lower_bound_col(col_idx, pos, end, B1 * kTile);
+      if (pos < end && (int64_t)last_c - first_c == end - 1 - pos) {
+        // the row is one run of consecutive columns (global-token rows): its share follows by
+        // arithmetic instead of two binary searches over the column list
+        const int64_t p0 = pos;
+        const int64_t lo = B0 * kTile - first_c, hi = B1 * kTile - first_c;
+        pos = p0 + (lo < 0 ? 0 : (lo > end - p0 ? end - p0 : lo));
+        end = p0 + (hi < 0 ? 0 : (hi > end - p0 ? end - p0 : hi));
+      } else {
+        pos = lower_bound_col(col_idx, pos, end, B0 * kTile);
+        end = lower_bound_col(col_idx, pos, end, B1 * kTile);
+      }
     }
     // a row whose remaining columns are one run of consecutive integers needs no more loads;
     // the test is repeated with every column that starts a round (it costs nothing: the last
