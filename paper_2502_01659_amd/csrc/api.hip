@@ -44,7 +44,9 @@ void profile_mark_begin(hipStream_t stream) {
   if (!g_prof.on) return;
   if (g_prof.used == g_prof.start.size()) {
     hipEvent_t a, b;
-    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) {
+    // (no system-scope fence at the records: they only take time stamps on the stream)
+    if (hipEventCreateWithFlags(&a, hipEventDisableSystemFence) != hipSuccess ||
+        hipEventCreateWithFlags(&b, hipEventDisableSystemFence) != hipSuccess) {
       g_prof.on = false;
       return;
     }
