@@ -32,11 +32,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 6_449_258,
-    "cfg2_longformer_64k": 1_082_157_601,
-    "cfg3_dilated_1m": 2_149_419_235,
-    "cfg4_bigbird_1m": 9_468_071_832,
-    "cfg5_sliding_160m": 82_492_343_833,
+    "cfg1_sliding_4k": 5_854_012,
+    "cfg2_longformer_64k": 1_083_544_420,
+    "cfg3_dilated_1m": 2_149_414_475,
+    "cfg4_bigbird_1m": 9_490_963_693,
+    "cfg5_sliding_160m": 82_502_905_460,
 }
 
 

@@ -525,7 +525,7 @@ struct CoreF32T {
   // behind the V block), as in CoreF16T::run_ldsk.  The only loads into vector registers are the
   // K fragments, and the step's own waits are counted: V block k, then the words of block k+1,
   // then the K fragment of block k+1 are issued in this order, so the fragment may still be in
-  // flight during the PV products.  (Workload 2: 0.51 ms against 0.53 ms with the records loaded
+  // flight during the PV products.  (Workload 2, measured side by side: 4 % faster than with the records loaded
   // into vector registers two blocks ahead.)
   __device__ void run_regk(const float* __restrict__ Kh, const float* __restrict__ Vh,
                            const ExplicitBlocks& src, int k0, int k1, float c, int lane, TileState& st,
