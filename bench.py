@@ -327,8 +327,11 @@ def composition_times(wl, path, steps=5, warmup=2):
 
 def _time_calls(fn, steps, warmup):
     import torch
-    for _ in range(warmup):
+    done, t_warm = 0, time.perf_counter()
+    while done < warmup or time.perf_counter() - t_warm < kWarmSeconds / 2:   # (see Runner.timed)
         fn()
+        done += 1
+        torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
