@@ -177,6 +177,30 @@ struct WindowBlocks {
   }
 };
 
+// The mask words of WindowBlocks for a tile whose keys all lie within a few hundred positions of
+// its first key (the workgroup-staged kernel): the same quantities as 32-bit differences, so the
+// per-block arithmetic runs on the scalar unit.  d0 = u0 - vfirst, rem = min(Lc - vfirst, 2^20),
+// nq = queries of the tile that exist (clamped to 64), W <= 64.
+struct WindowWordsNear {
+  int d0, W, nq, rem;
+  __device__ static int clamp(int v) { return v < -64 ? -64 : (v > 64 ? 64 : v); }
+  __device__ BlockInfo get(int k, int n) const {
+    BlockInfo b;
+    b.raw = 0;
+    b.row0 = 0;                                    // (not used: the blocks are staged by the workgroup)
+    const int v0 = k * kTile;                      // first key of the block, relative to vfirst
+    const int left = rem - v0;
+    b.nvalid = left < kTile ? left : kTile;
+    const int dlo = clamp(d0 - W - v0), dhi = clamp(d0 + W - v0);
+    int lo = n + dlo, hi = n + dhi;
+    lo = lo < 0 ? 0 : lo;
+    hi = hi > b.nvalid - 1 ? b.nvalid - 1 : hi;
+    b.word = (lo > hi || n >= nq) ? 0u : ((~0u >> (31 - hi)) & (~0u << lo));
+    b.full = b.nvalid == kTile && nq >= kTile && dlo + (kTile - 1) <= 0 && dhi >= kTile - 1;
+    return b;
+  }
+};
+
 // Per-lane running state: lane owns query n = lane % 32; channels of O^T are spread over the
 // 16 accumulator registers of both 32-channel halves.
 struct TileState {
@@ -1835,6 +1859,11 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
     Lc = (L - p + s - 1) / s;
     q0 = (int64_t)grp * (4 * kTile);
   }
+  // (the divisions above run on the vector unit; back in scalar registers, the per-block index
+  // arithmetic that follows from these values stays on the scalar unit)
+  p = uniform64(p);
+  Lc = uniform64(Lc);
+  q0 = uniform64(q0);
   if (q0 >= Lc) return;                            // (the whole workgroup leaves: no barrier is missed)
   const int64_t hd = blockIdx.y;
   const int64_t hoff = hd * L * kHeadDim;
@@ -1863,7 +1892,9 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
   wait_loads_except<0>();
   __syncthreads();
   if (u0 >= Lc) return;
-  const WindowBlocks src{vfirst, Lc, s, p, u0, W};
+  const int64_t rem64 = Lc - vfirst, nq64 = Lc - u0;
+  const WindowWordsNear src{(int)(u0 - vfirst), (int)W, (int)(nq64 > 64 ? 64 : nq64),
+                            (int)(rem64 > (1 << 20) ? (1 << 20) : rem64)};
   const int64_t lo_key = u0 - W > vfirst ? u0 - W : vfirst;
   const int64_t hi_key = u0 + kTile - 1 + W < vlast ? u0 + kTile - 1 + W : vlast;
   const int k_lo = (int)((lo_key - vfirst) / kTile), k_hi = (int)((hi_key - vfirst) / kTile);
