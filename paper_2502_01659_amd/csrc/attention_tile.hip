@@ -1831,7 +1831,7 @@ constexpr int kWgBlocks = 8;
 __global__ __launch_bounds__(256) void tile_window_wg_kernel(
     const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
     __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
-    float scale, int accumulate, int nb_max, int64_t seg_len) {
+    float scale, int accumulate, int nb_max, int64_t seg_len, int64_t Lq, int64_t Lr) {
   // nb_max K blocks, then nb_max V blocks (dynamic: narrow windows leave room for more workgroups)
   extern __shared__ __attribute__((aligned(16))) char lds_wg[];
   char* lds_k = lds_wg;
@@ -1839,24 +1839,28 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int n = lane & 31, h = lane >> 5;
-  // (workgroup indices fit 32 bits: the host checks the grid size; 32-bit division by the
-  // stride is several times shorter than the 64-bit one)
+  // The place among the window tiles as in locate_window_slot, without its 64-bit divisions
+  // (each is a chain of about a hundred dependent scalar instructions ahead of the first load):
+  // workgroup indices and the stride fit 32 bits (the host checks the grid size), and the host
+  // passes the class lengths.  Whole-sequence masks: Lq = L / s, Lr = L % s, class p holds
+  // Lq + (p < Lr) tokens.  Block-diagonal masks: Lq = tokens of the class of a whole block,
+  // Lr = of the sequence's last block.
   const uint32_t chunk = gridDim.x / 8;
   const uint32_t bid = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
-  const uint32_t s32 = (uint32_t)s;
   int64_t p, Lc, q0;                               // class start, tokens of the class, first query
   if (seg_len > 0) {
-    WindowSlot slot;
-    if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
-    p = slot.p;
-    Lc = slot.Lc;
-    q0 = slot.grp * (4 * kTile);
+    const uint32_t ng32 = (uint32_t)n_groups;
+    const uint32_t seg = bid / ng32;
+    p = (int64_t)seg * seg_len;
+    if (p >= L) return;
+    Lc = p + seg_len <= L ? Lq : Lr;
+    q0 = (int64_t)(bid - seg * ng32) * (4 * kTile);
   } else {
     if ((int64_t)bid >= n_groups * s) return;
+    const uint32_t s32 = (uint32_t)s;
     const uint32_t grp = bid / s32;
     p = bid - grp * s32;                           // residue class
-    if (p >= L) return;
-    Lc = (L - p + s - 1) / s;
+    Lc = Lq + (p < Lr ? 1 : 0);
     q0 = (int64_t)grp * (4 * kTile);
   }
   // (the divisions above run on the vector unit; back in scalar registers, the per-block index
@@ -2069,10 +2073,16 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   profile_mark_begin(a.stream);
   if (wg) {
     const int nb_max = (int)((4 * kTile - 1 + 2 * (int64_t)a.window) / kTile + 1);
+    int64_t Lq = a.L / s, Lr = a.L % s;             // class lengths, see the kernel
+    if (shape.seg_len > 0) {
+      const int64_t last_len = a.L - (a.L - 1) / shape.seg_len * shape.seg_len;
+      Lq = (shape.seg_len + s - 1) / s;
+      Lr = (last_len + s - 1) / s;
+    }
     hipLaunchKernelGGL(tile_window_wg_kernel, grid, dim3(256), (size_t)nb_max * 2 * CoreF16::kBlockBytes,
                        a.stream, static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
-                       (int64_t)a.window, s, n_groups, a.scale, acc, nb_max, shape.seg_len);
+                       (int64_t)a.window, s, n_groups, a.scale, acc, nb_max, shape.seg_len, Lq, Lr);
   } else if (pair) {
     hipLaunchKernelGGL(tile_window_pair_kernel, grid, dim3(256), 0, a.stream,
                        static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
