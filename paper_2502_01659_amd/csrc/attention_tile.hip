@@ -1614,10 +1614,13 @@ __device__ __forceinline__ void store_out(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_out(__half* p, float v) { *p = __float2half_rn(v); }
 
 // Merge of a multi-segment tile's partial states.  grid = (tiles of the merge list, head,
-// rows of the tile in groups of 32 / gridDim.z); the 4 wavefronts of a workgroup take every 4th
-// segment of a row, reduce theirs in segment order, and wavefront 0 combines the four results in
-// wavefront order, so the summation order is fixed.  lane = channel within each 64-channel slice
-// (a partial of a kD-wide tile is kD / 64 records, one per slice, with the same m and l).
+// rows of the tile in groups of 32 / gridDim.z).  Per row: the running maximum M over all
+// segments (every thread takes every 256th segment, so all loads are in flight together), the
+// weights 2^(m_c - M), and the weighted sums of l and of the accumulators.  The 4 wavefronts of
+// a workgroup take every 4th segment (lane = channel within each 64-channel slice; a partial
+// of a kD-wide tile is kD / 64 records, one per slice, with the same m and l), four segments per
+// trip so that their loads overlap, each in ascending segment order; the four results are added
+// in wavefront order, so the summation order is fixed.
 template <typename T, int kD>
 __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                          const int64_t* __restrict__ row_ptr, int64_t L,
@@ -1648,36 +1651,44 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
     const int rows_per_wg = kTile / (int)gridDim.z;
     for (int r = blockIdx.z * rows_per_wg; r < (int)(blockIdx.z + 1) * rows_per_wg; ++r) {
       const int64_t row = t * kTile + r;
+      const float* pm = p0 + kTile * 64 + r;       // segment c: m = pm[c * step], l = pm[c * step + kTile]
       float M = kMinusHuge;
-      for (int c = wave; c < nseg; c += 4) M = fmaxf(M, p0[c * step + kTile * 64 + r]);
+      for (int c = threadIdx.x; c < nseg; c += 256) M = fmaxf(M, pm[c * step]);
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
+      __syncthreads();            // the previous row's combine has read the shared arrays
+      if (lane == 0) sm_m[wave] = M;
+      __syncthreads();
+      M = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
       float l = 0.f, acc[kSlices];
 #pragma unroll
       for (int sl = 0; sl < kSlices; ++sl) acc[sl] = 0.f;
-      for (int c = wave; c < nseg; c += 4) {
-        const float wgt = __builtin_amdgcn_exp2f(p0[c * step + kTile * 64 + r] - M);
-        l = __builtin_fmaf(p0[c * step + kTile * 64 + kTile + r], wgt, l);
+      for (int c = wave; c < nseg; c += 16) {
+        float mc[4], lc[4], oc[4][kSlices];
 #pragma unroll
-        for (int sl = 0; sl < kSlices; ++sl)
-          acc[sl] = __builtin_fmaf(p0[c * step + sl * kTilePartialFloats + r * 64 + lane], wgt, acc[sl]);
+        for (int u = 0; u < 4; ++u) {
+          const int cc = c + 4 * u < nseg ? c + 4 * u : c;
+          mc[u] = pm[cc * step];
+          lc[u] = pm[cc * step + kTile];
+#pragma unroll
+          for (int sl = 0; sl < kSlices; ++sl) oc[u][sl] = p0[cc * step + sl * kTilePartialFloats + r * 64 + lane];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const float wgt = c + 4 * u < nseg ? __builtin_amdgcn_exp2f(mc[u] - M) : 0.f;
+          l = __builtin_fmaf(lc[u], wgt, l);
+#pragma unroll
+          for (int sl = 0; sl < kSlices; ++sl) acc[sl] = __builtin_fmaf(oc[u][sl], wgt, acc[sl]);
+        }
       }
-      __syncthreads();            // previous row's combine has read the shared arrays
 #pragma unroll
       for (int sl = 0; sl < kSlices; ++sl) sm_acc[wave][sl * 64 + lane] = acc[sl];
-      if (lane == 0) {
-        sm_m[wave] = M;
-        sm_l[wave] = l;
-      }
+      if (lane == 0) sm_l[wave] = l;
       __syncthreads();
       if (wave == 0 && row < L) {
-        float Mt = fmaxf(fmaxf(sm_m[0], sm_m[1]), fmaxf(sm_m[2], sm_m[3]));
-        float lt = 0.f, wv[4];
-#pragma unroll
-        for (int v = 0; v < 4; ++v) {
-          wv[v] = __builtin_amdgcn_exp2f(sm_m[v] - Mt);
-          lt = __builtin_fmaf(sm_l[v], wv[v], lt);
-        }
+        const float lt = ((sm_l[0] + sm_l[1]) + sm_l[2]) + sm_l[3];
         const bool empty = !(lt > 0.f);
-        float lse_row = empty ? -INFINITY : (Mt + __builtin_amdgcn_logf(lt)) * kLn2;
+        float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(lt)) * kLn2;
         CarryWeights cw{0.f, 1.f, lse_row};
         if (accumulate) {
           cw = carry_weights(lse[hd * L + row], lse_row);
@@ -1685,9 +1696,8 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
         }
 #pragma unroll
         for (int sl = 0; sl < kSlices; ++sl) {
-          float at = 0.f;
-#pragma unroll
-          for (int v = 0; v < 4; ++v) at = __builtin_fmaf(sm_acc[v][sl * 64 + lane], wv[v], at);
+          const float at = ((sm_acc[0][sl * 64 + lane] + sm_acc[1][sl * 64 + lane]) +
+                            sm_acc[2][sl * 64 + lane]) + sm_acc[3][sl * 64 + lane];
           T* dst = O + hd * L * kD + row * kD + sl * 64 + lane;
           float o = empty ? 0.f : at / lt;
           if (accumulate) o = cw.w_prev * load_out(dst) + cw.w_now * o;
