@@ -51,6 +51,15 @@ __device__ __forceinline__ void copy16_to_lds(const void* src, char* dst) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
                                    (void __attribute__((address_space(3)))*)dst, 16, 0, 0);
 }
+// The same copy issued behind the compiler's back.  While it knows of copies in flight, the
+// compiler waits for all of them before any LDS read it cannot prove to be elsewhere; the
+// caller of this one orders the reads itself, by counted waits.
+__device__ __forceinline__ void copy16_to_lds_untracked(const void* src, char* dst) {
+  const uint32_t at = __builtin_amdgcn_readfirstlane(
+      (uint32_t)(uintptr_t)(char __attribute__((address_space(3)))*)dst);
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+               :: "s"(at), "v"(src) : "m0", "memory");
+}
 // Same with 4 bytes per lane: lane l's word lands at dst + 4*l.
 __device__ __forceinline__ void copy4_to_lds(const void* src, char* dst) {
   __builtin_amdgcn_global_load_lds((const void __attribute__((address_space(1)))*)src,
@@ -329,6 +338,18 @@ struct StageMap {
                       dst + i * 1024);
       }
     }
+  }
+  // stage_k and stage_v of a whole block with untracked copies
+  __device__ void stage_whole_untracked(const T* __restrict__ Kh, const T* __restrict__ Vh, int64_t row0,
+                                        char* dst_k, char* dst_v) const {
+    const char* kb = reinterpret_cast<const char*>(Kh) + row0 * kGlobalRowBytes;
+    const char* vb = reinterpret_cast<const char*>(Vh) + row0 * kGlobalRowBytes;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i)
+      copy16_to_lds_untracked(kb + i * kRows * stride_bytes + koff[kLanes == 8 ? 0 : i % 4], dst_k + i * 1024);
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i)
+      copy16_to_lds_untracked(vb + i * kRows * stride_bytes + voff, dst_v + i * 1024);
   }
   __device__ void stage_k(const T* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) const {
     if (b.nvalid == kTile) {
@@ -651,6 +672,14 @@ struct CoreF16T {
 #pragma unroll
       for (int s = 0; s < 4; ++s) qf[s] = -qf[s];
     }
+  }
+
+  // The loads of load_q have completed (the caller has waited for them): taking qf as read and
+  // written here keeps the compiler from waiting for them again at their first use, where
+  // copies issued in between would be waited for as well.
+  __device__ void q_arrived() {
+#pragma unroll
+    for (int s = 0; s < 4; ++s) asm volatile("" : "+v"(qf[s]));
   }
 
   static constexpr int kBlockBytes = kTile * kHeadDim * 2;   // one staged K or V block
@@ -1955,9 +1984,15 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
   const int64_t vfirst = q0 - W > 0 ? q0 - W : 0;
   const int64_t vlast = q0 + 4 * kTile - 1 + W < Lc - 1 ? q0 + 4 * kTile - 1 + W : Lc - 1;
   const int nb = (int)((vlast - vfirst) / kTile + 1);          // <= kWgBlocks
+  const int64_t u0 = q0 + (int64_t)wave * kTile;
+  const int64_t u = u0 + n;
+  const bool exists = u < Lc;
+  const int64_t qrow = s * (exists ? u : Lc - 1) + p;
+  CoreF16 core;
+  core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
   CoreF16::Stage sm;
   sm.init(s, lane);
-  for (int j = wave; j < nb; j += 4) {
+  auto stage = [&](int j) {
     BlockInfo b;
     const int64_t v0 = vfirst + (int64_t)j * kTile;
     b.raw = 0;
@@ -1967,32 +2002,51 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
     b.full = false;
     sm.stage_k(K + hoff, b, lane, lds_k + j * CoreF16::kBlockBytes);
     sm.stage_v(V + hoff, b, lane, lds_v + j * CoreF16::kBlockBytes);
-  }
-  const int64_t u0 = q0 + (int64_t)wave * kTile;
-  const int64_t u = u0 + n;
-  const bool exists = u < Lc;
-  const int64_t qrow = s * (exists ? u : Lc - 1) + p;
-  CoreF16 core;
-  core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
-  wait_loads_except<0>();
-  __syncthreads();
-  const bool active = u0 < Lc;                     // (a wavefront without queries still meets the barrier below)
+  };
+  const bool active = u0 < Lc;                     // (a wavefront without queries still meets the barriers below)
   TileState st;
   st.init();
-  if (active) {
   const int64_t rem64 = Lc - vfirst, nq64 = Lc - u0;
-  const WindowWordsNear src{(int)(u0 - vfirst), (int)W, (int)(nq64 > 64 ? 64 : nq64),
+  const WindowWordsNear src{(int)(u0 - vfirst), (int)W, (int)(nq64 > 64 ? 64 : (nq64 > 0 ? nq64 : 0)),
                             (int)(rem64 > (1 << 20) ? (1 << 20) : rem64)};
   const int64_t lo_key = u0 - W > vfirst ? u0 - W : vfirst;
   const int64_t hi_key = u0 + kTile - 1 + W < vlast ? u0 + kTile - 1 + W : vlast;
-  const int k_lo = (int)((lo_key - vfirst) / kTile), k_hi = (int)((hi_key - vfirst) / kTile);
+  const int k_lo = (int)((lo_key - vfirst) / kTile);
+  const int k_hi = active ? (int)((hi_key - vfirst) / kTile) : k_lo - 1;
   const float c = softmax_factor(scale);
-  for (int k = k_lo; k <= k_hi; ++k) {
-    const BlockInfo b = src.get(k, n);
-    half8 kf[4];
-    CoreF16::read_k(lds_k + k * CoreF16::kBlockBytes, n, h, kf);
-    core.block_math(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, -1);
-  }
+  auto blocks = [&](int ka, int kb) {
+    for (int k = ka; k <= kb; ++k) {
+      const BlockInfo b = src.get(k, n);
+      half8 kf[4];
+      CoreF16::read_k(lds_k + k * CoreF16::kBlockBytes, n, h, kf);
+      core.block_math(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, -1);
+    }
+  };
+  if (vlast - vfirst + 1 == kWgBlocks * kTile) {
+    // A full window of whole blocks, every wavefront copies two of them: blocks 0..3 are
+    // computed on while blocks 4..7 are still on their way.  The copies are issued untracked
+    // (see copy16_to_lds_untracked), the second round once Q and the first have arrived (the
+    // waits ask for every operation in flight: no order between loads into registers and
+    // copies to LDS is assumed), and the first barrier is a plain one: __syncthreads() would
+    // wait for every copy.
+    auto stage_whole = [&](int j) {
+      sm.stage_whole_untracked(K + hoff, V + hoff, s * (vfirst + (int64_t)j * kTile) + p,
+                               lds_k + j * CoreF16::kBlockBytes, lds_v + j * CoreF16::kBlockBytes);
+    };
+    stage_whole(wave);
+    wait_loads_except<0>();
+    core.q_arrived();
+    stage_whole(wave + 4);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    blocks(k_lo, k_hi < 3 ? k_hi : 3);
+    wait_loads_except<0>();
+    __syncthreads();
+    blocks(k_lo > 4 ? k_lo : 4, k_hi);
+  } else {
+    for (int j = wave; j < nb; j += 4) stage(j);
+    wait_loads_except<0>();
+    __syncthreads();
+    blocks(k_lo, k_hi);
   }
   float* lse_h = lse ? lse + hd * L : nullptr;
   if (accumulate) {
