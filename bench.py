@@ -32,11 +32,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 6_198_035,
-    "cfg2_longformer_64k": 1_083_819_471,
-    "cfg3_dilated_1m": 2_149_417_086,
-    "cfg4_bigbird_1m": 9_513_035_275,
-    "cfg5_sliding_160m": 82_553_646_278,
+    "cfg1_sliding_4k": 6_148_692,
+    "cfg2_longformer_64k": 1_081_593_542,
+    "cfg3_dilated_1m": 2_149_478_806,
+    "cfg4_bigbird_1m": 9_511_697_450,
+    "cfg5_sliding_160m": 81_960_335_303,
 }
 
 
