@@ -89,6 +89,31 @@ def test_ragged_and_degenerate_shapes(spec, dtype, path):
         assert max_err(O2, O_ref) <= TOL[dtype]
 
 
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+@pytest.mark.parametrize("spec", [
+    MaskSpec(KIND_SLIDING, 320, window=64),      # last workgroup: a full 256-key window that ends at L
+    MaskSpec(KIND_SLIDING, 319, window=64),
+    MaskSpec(KIND_SLIDING, 321, window=64),
+    MaskSpec(KIND_SLIDING, 640, window=64),      # interior workgroups with full windows, first and last ragged
+    MaskSpec(KIND_SLIDING, 513, window=63),
+    MaskSpec(KIND_SLIDING, 513, window=65),      # one key past the workgroup kernel's window
+    MaskSpec(KIND_SLIDING, 131, window=16),
+    MaskSpec(KIND_DILATED, 1931, window=64, stride=3),   # classes of 644, 644 and 643 tokens
+    MaskSpec(KIND_DILATED, 769, window=48, stride=2),
+], ids=lambda s: f"{s.name}-L{s.L}-w{s.window}")
+def test_window_staging_boundaries(spec, dtype):
+    """Implicit windows on the tile path at the sizes where the staging of the fp16 workgroup
+    kernel changes shape: full 8-block windows (staged in two rounds) next to ragged ones, the
+    widest window that kernel takes and the first one it does not, short sequences."""
+    print("case", spec, dtype, flush=True)
+    wl = Workload("t", H=2, L=spec.L, d=64, dtype=dtype, sigma=0.8, mask=spec, explicit=False, seed=123)
+    Q, K, V = small_inputs(wl)
+    O, lse = _run_implicit(wl, Q, K, V, sga.PATH_TILE)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    assert max_err(O, O_ref) <= TOL[dtype]
+    assert max_err(lse, lse_ref) <= 1e-4
+
+
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("sf", [1.0, 0.5, 0.1, 0.01])
 def test_verification_protocol_bernoulli_masks(sf, path):
