@@ -1268,38 +1268,55 @@ struct WorkId {
   int32_t seg, nseg;
 };
 
-__device__ __forceinline__ WorkId locate_work(const int64_t* __restrict__ row_ptr, int64_t L,
-                                              int64_t S, int64_t n_tiles, int64_t n_work, int64_t w) {
-  // interpolation guess, then galloping, then bisection: largest t with f(t) <= w
-  int64_t lo, hi;
+// (Called by a whole wavefront with the same w.)  f is increasing, and for masks of even density
+// the item index is close to proportional to the tile index: the 64 lanes evaluate f at the 64
+// tiles around that guess in one round of loads, and only a guess that misses this window falls
+// back to galloping and bisection, one dependent load per step.
+__device__ __forceinline__ WorkId locate_work(const int64_t* __restrict__ row_ptr, int64_t L, int sh,
+                                              int64_t n_tiles, int64_t n_work, int64_t w, int lane) {
   int64_t g = (int64_t)((double)w * (double)n_tiles / (double)n_work);
   if (g >= n_tiles) g = n_tiles - 1;
-  if (work_first(row_ptr, L, S, g) <= w) {
-    lo = g;
-    int64_t step = 1;
-    hi = n_tiles;
-    while (lo + step < n_tiles) {
-      if (work_first(row_ptr, L, S, lo + step) <= w) { lo += step; step <<= 1; }
-      else { hi = lo + step; break; }
-    }
+  // (the guess errs upwards where rows with many edges come first: most of the window lies below it)
+  int64_t base = g - 47;
+  if (base + kWave > n_tiles) base = n_tiles - kWave;
+  if (base < 0) base = 0;
+  const int64_t tc = base + lane;
+  const int64_t fc = tc < n_tiles ? work_first(row_ptr, L, sh, tc) : INT64_MAX;
+  const uint64_t below = __builtin_amdgcn_ballot_w64(fc <= w);       // a prefix of the lanes
+  const int n_below = __builtin_popcountll(below);
+  int64_t lo, f0;
+  if (n_below > 0 && (n_below < kWave || base + kWave >= n_tiles)) {
+    lo = base + n_below - 1;
+    f0 = __shfl(fc, n_below - 1, kWave);
   } else {
-    hi = g;
-    int64_t step = 1;
-    lo = 0;
-    while (hi - step > 0) {
-      if (work_first(row_ptr, L, S, hi - step) > w) { hi -= step; step <<= 1; }
-      else { lo = hi - step; break; }
+    int64_t hi;
+    if (n_below > 0) {                 // beyond the window
+      lo = base + kWave - 1;
+      int64_t step = 1;
+      hi = n_tiles;
+      while (lo + step < n_tiles) {
+        if (work_first(row_ptr, L, sh, lo + step) <= w) { lo += step; step <<= 1; }
+        else { hi = lo + step; break; }
+      }
+    } else {                           // before it
+      hi = base;
+      int64_t step = 1;
+      lo = 0;
+      while (hi - step > 0) {
+        if (work_first(row_ptr, L, sh, hi - step) > w) { hi -= step; step <<= 1; }
+        else { lo = hi - step; break; }
+      }
     }
-  }
-  while (hi - lo > 1) {
-    const int64_t mid = lo + ((hi - lo) >> 1);
-    if (work_first(row_ptr, L, S, mid) <= w) lo = mid; else hi = mid;
+    while (hi - lo > 1) {
+      const int64_t mid = lo + ((hi - lo) >> 1);
+      if (work_first(row_ptr, L, sh, mid) <= w) lo = mid; else hi = mid;
+    }
+    f0 = work_first(row_ptr, L, sh, lo);
   }
   WorkId id;
   id.tile = lo;
-  const int64_t f0 = work_first(row_ptr, L, S, lo);
   id.seg = (int32_t)(w - f0);
-  id.nseg = tile_segments(row_ptr, L, S, lo);
+  id.nseg = tile_segments(row_ptr, L, sh, lo);
   return id;
 }
 
@@ -1317,7 +1334,6 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
                                                            int32_t d, void* ws, size_t ws_bytes) {
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
   if (pl.total_bytes > ws_bytes) return;
-  const int64_t S = seg_edges(dtype);
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   char* base_ws = static_cast<char*>(ws);
@@ -1329,7 +1345,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   for (int64_t w = (int64_t)blockIdx.x * waves + threadIdx.x / kWave; w < pl.n_work;
        w += (int64_t)gridDim.x * waves) {
-    const WorkId id = locate_work(row_ptr, L, S, pl.n_tiles, pl.n_work, w);
+    const WorkId id = locate_work(row_ptr, L, seg_shift(dtype), pl.n_tiles, pl.n_work, w, lane);
     if (id.seg >= id.nseg) {          // spare item of a tile whose edge range crosses a multiple of S
       if (lane == 0) items[w].tile = -1;
       continue;
@@ -1670,11 +1686,10 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int64_t hd = blockIdx.y;
-  const int64_t S = seg_edges(dtype);
   for (uint32_t i = blockIdx.x; i < n_multi; i += gridDim.x) {
     const int64_t t = multi[i];
     if (tile_bad[t]) continue;
-    const int nseg = tile_segments(row_ptr, L, S, t);
+    const int nseg = tile_segments(row_ptr, L, seg_shift(dtype), t);
     const float* p0 = parts + ((int64_t)tile_pbase[t] * H + hd) * (kSlices * kTilePartialFloats);
     const int64_t step = (int64_t)H * (kSlices * kTilePartialFloats);
     const int rows_per_wg = kTile / (int)gridDim.z;

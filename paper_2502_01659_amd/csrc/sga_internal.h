@@ -30,7 +30,9 @@ constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32]
 // crosses; the first max(1, edges(t)/S) of them are the tile's segments, the rest stay idle.
 // The mapping follows from row_ptr alone and needs neither a scan nor atomics.  A dense
 // 32x32 block is 1024 edges: S is 32 dense blocks of fp32 MFMA work or 256 of fp16 work.
-__host__ __device__ inline int64_t seg_edges(int32_t dtype) { return dtype == SGA_F32 ? 32768 : 262144; }
+// (a power of two: the kernels divide edge counts by S with a shift by seg_shift)
+__host__ __device__ inline int seg_shift(int32_t dtype) { return dtype == SGA_F32 ? 15 : 18; }
+__host__ __device__ inline int64_t seg_edges(int32_t dtype) { return int64_t(1) << seg_shift(dtype); }
 
 // ---- workspace layout -------------------------------------------------------
 // [0, 256)            counters (uint32): see WsCounter
@@ -136,16 +138,16 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
 
 // First work item of tile t: f(t) = t + row_ptr[min(32t, L)] / S.
 __device__ __forceinline__ int64_t work_first(const int64_t* __restrict__ row_ptr, int64_t L,
-                                              int64_t S, int64_t t) {
+                                              int sh, int64_t t) {
   const int64_t r = t * kTile;
-  return t + row_ptr[r < L ? r : L] / S;
+  return t + (row_ptr[r < L ? r : L] >> sh);
 }
 
 // Segments tile t is cut into: max(1, edges(t) / S).
 __device__ __forceinline__ int32_t tile_segments(const int64_t* __restrict__ row_ptr, int64_t L,
-                                                 int64_t S, int64_t t) {
+                                                 int sh, int64_t t) {
   const int64_t r0 = t * kTile, r1 = r0 + kTile < L ? r0 + kTile : L;
-  const int64_t n = (row_ptr[r1] - row_ptr[r0]) / S;
+  const int64_t n = (row_ptr[r1] - row_ptr[r0]) >> sh;
   return n < 1 ? 1 : (int32_t)n;
 }
 
@@ -156,8 +158,7 @@ __device__ __forceinline__ bool tile_handled(const WorkspacePlan& pl, const void
                                              int32_t dtype, int64_t t) {
   const char* base = static_cast<const char*>(ws);
   if (reinterpret_cast<const int32_t*>(base + pl.off_tile_bad)[t] != 0) return false;
-  const int64_t S = seg_edges(dtype);
-  if (tile_segments(row_ptr, L, S, t) == 1) return true;
+  if (tile_segments(row_ptr, L, seg_shift(dtype), t) == 1) return true;
   return (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTilePartsNeeded] <= pl.cap_tparts;
 }
 
