@@ -57,8 +57,10 @@ __device__ __forceinline__ void copy16_to_lds(const void* src, char* dst) {
 __device__ __forceinline__ void copy16_to_lds_untracked(const void* src, char* dst) {
   const uint32_t at = __builtin_amdgcn_readfirstlane(
       (uint32_t)(uintptr_t)(char __attribute__((address_space(3)))*)dst);
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-               :: "s"(at), "v"(src) : "m0", "memory");
+  uint32_t m0_kept;    // (M0 holds the LDS address of the copy; the compiler's own value is put back)
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\t"
+               "s_mov_b32 m0, %0"
+               : "=&s"(m0_kept) : "s"(at), "v"(src) : "memory");
 }
 // Same with 4 bytes per lane: lane l's word lands at dst + 4*l.
 __device__ __forceinline__ void copy4_to_lds(const void* src, char* dst) {
@@ -1232,22 +1234,32 @@ __device__ __forceinline__ void finish_tile_wide(T* Oslice, float* lse_h, int64_
   if (lse_h && h == 0 && slice == 0) lse_h[row] = lse_row;
 }
 
-__device__ __forceinline__ int half_min(int v) {   // min over the 32 lanes of a half-wave
-#pragma unroll
-  for (int off = 16; off > 0; off >>= 1) {
-    const int o = __shfl_xor(v, off, kWave);
-    v = o < v ? o : v;
-  }
-  return v;
+// Minimum (maximum) of v over lanes 0..31, as a wave-uniform value.  Data-parallel-primitive
+// moves inside the 16-lane rows (a running minimum towards lane 15), then lane 15 of row 0 into
+// row 1, and lane 31 holds the result: a chain of short vector instructions, where shuffles
+// through the LDS crossbar cost a round trip each (this reduction sits in the block loop of the
+// CSR -> tile pass, once per key block).
+template <int CTRL, int ROWS>
+__device__ __forceinline__ int dpp_from(int v) {     // lanes without a source keep v
+  return __builtin_amdgcn_update_dpp(v, v, CTRL, ROWS, 0xf, false);
 }
-
-__device__ __forceinline__ int half_max(int v) {
-#pragma unroll
-  for (int off = 16; off > 0; off >>= 1) {
-    const int o = __shfl_xor(v, off, kWave);
-    v = o > v ? o : v;
-  }
-  return v;
+__device__ __forceinline__ int first_half_min(int v) {
+  int o;
+  o = dpp_from<0x111, 0xf>(v); v = o < v ? o : v;    // row_shr:1
+  o = dpp_from<0x112, 0xf>(v); v = o < v ? o : v;    // row_shr:2
+  o = dpp_from<0x114, 0xf>(v); v = o < v ? o : v;    // row_shr:4
+  o = dpp_from<0x118, 0xf>(v); v = o < v ? o : v;    // row_shr:8
+  o = dpp_from<0x142, 0xa>(v); v = o < v ? o : v;    // row_bcast:15 into rows 1 and 3
+  return __builtin_amdgcn_readlane(v, 31);
+}
+__device__ __forceinline__ int first_half_max(int v) {
+  int o;
+  o = dpp_from<0x111, 0xf>(v); v = o > v ? o : v;
+  o = dpp_from<0x112, 0xf>(v); v = o > v ? o : v;
+  o = dpp_from<0x114, 0xf>(v); v = o > v ? o : v;
+  o = dpp_from<0x118, 0xf>(v); v = o > v ? o : v;
+  o = dpp_from<0x142, 0xa>(v); v = o > v ? o : v;
+  return __builtin_amdgcn_readlane(v, 31);
 }
 
 // First position in [lo, hi) of the sorted column list whose column is >= key.
@@ -1365,8 +1377,8 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
       // this segment's share of the tile's key-block span
       const int first_c = pos < end ? col_idx[pos] : INT32_MAX;
       const int last_c = pos < end ? col_idx[end - 1] : -1;
-      const int64_t bmin = __shfl(half_min(first_c), 0, kWave) >> 5;
-      const int64_t bmax = __shfl(half_max(last_c), 0, kWave) >> 5;
+      const int64_t bmin = first_half_min(first_c) >> 5;
+      const int64_t bmax = first_half_max(last_c) >> 5;
       const int64_t span = bmax - bmin + 1;
       const int64_t B0 = bmin + span * id.seg / id.nseg;
       const int64_t B1 = bmin + span * (id.seg + 1) / id.nseg;
@@ -1404,7 +1416,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
         }
       }
       if (arith) cur = run_lo <= run_hi ? (run_lo >> 5) : INT32_MAX;
-      const int b = __shfl(half_min(cur), 0, kWave);
+      const int b = first_half_min(cur);
       if (b == INT32_MAX) break;
       if (nblk >= cap) {
         overflow = true;
