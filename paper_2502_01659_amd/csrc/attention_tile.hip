@@ -1416,6 +1416,33 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
         }
       }
       if (arith) cur = run_lo <= run_hi ? (run_lo >> 5) : INT32_MAX;
+      if (__all(arith || pos >= end)) {
+        // Every row is down to one run of consecutive columns (or to nothing).  If the runs'
+        // block ranges overlap or touch, the remaining blocks are the whole range from the first
+        // to the last, and each row's word follows from its run alone: no minimum per block.
+        const bool some = arith && run_lo <= run_hi;
+        const int blo = first_half_min(some ? run_lo >> 5 : INT32_MAX);
+        if (blo == INT32_MAX) break;
+        const int bhi = first_half_max(some ? run_hi >> 5 : -1);
+        const int lo_max = first_half_max(some ? run_lo >> 5 : -1);
+        const int hi_min = first_half_min(some ? run_hi >> 5 : INT32_MAX);
+        if (lo_max <= hi_min + 1) {
+          for (int b = blo; b <= bhi; ++b) {
+            if (nblk >= cap) {
+              overflow = true;
+              break;
+            }
+            const int lo = run_lo - (b << 5) > 0 ? run_lo - (b << 5) : 0;
+            const int hi = run_hi - (b << 5) < 31 ? run_hi - (b << 5) : 31;
+            const uint32_t word = some && lo <= hi ? (~0u >> (31 - hi)) & (~0u << lo) : 0u;
+            const bool full = __all(lane >= kTile || word == ~0u);
+            if (lane < kTile) pair_mask[(slot0 + nblk) * kTile + lane] = word;
+            if (lane == 0) pair_blk[slot0 + nblk] = b | (full ? kFullBit : 0);
+            ++nblk;
+          }
+          break;
+        }
+      }
       const int b = first_half_min(cur);
       if (b == INT32_MAX) break;
       if (nblk >= cap) {
