@@ -141,6 +141,57 @@ def test_verification_protocol_bernoulli_masks(sf, path):
         assert max_err(lse[h][~empty], lse_ref[~empty]) <= 1e-4
 
 
+def _run_masks(L):
+    """Dense masks whose rows are made of runs of consecutive columns, one shape per branch of the
+    CSR -> tile conversion: every row one run with touching block ranges (the loop without
+    reductions), one run per row at far-apart places (block ranges with gaps), two and three
+    runs per row, runs that end exactly at block borders, empty rows in between, and dense
+    leading rows next to short ones (a tile that is cut into segments)."""
+    i = np.arange(L)[:, None]
+    j = np.arange(L)[None, :]
+    out = {}
+    out["band"] = np.abs(i - j) <= 70
+    start = (i * 37) % (L - 60)
+    out["staircase"] = (j >= start) & (j < start + 1 + (i % 50))
+    out["two_runs"] = (j < 24) | ((j >= i // 2) & (j < i // 2 + 90))
+    out["three_runs"] = (j < 32) | ((j >= 64 + (i % 7)) & (j < 160)) | (j >= L - 32 - (i % 3))
+    out["block_borders"] = (j >= 32 * (i // 64)) & (j < 32 * (i // 64) + 96)
+    sparse_rows = out["band"].copy()
+    sparse_rows[(np.arange(L) % 5) == 2] = False
+    out["empty_rows"] = sparse_rows
+    dense_head = out["band"].copy()
+    dense_head[:20, :] = True
+    out["dense_leading_rows"] = dense_head
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("name", ["band", "staircase", "two_runs", "three_runs", "block_borders",
+                                  "empty_rows", "dense_leading_rows"])
+def test_run_structured_masks_every_path(name, dtype):
+    L, d, H = 4133, 64, 2
+    mask = _run_masks(L)[name]
+    Q, K, V = numpy_qkv(H, L, d, dtype, 0.7, 900)
+    rp, ci = R.csr_from_dense(mask)
+    dQ, dK, dV = to_device(Q, K, V)
+    drp, dci = to_device(rp, ci)
+    ws = sga.alloc_workspace(L, H, d, dtype, int(rp[-1]))
+    rows = sample_rows(L, 5, 100)
+    refs = [R.attention_dense(Q[h][rows].astype(np.float64), K[h].astype(np.float64),
+                              V[h].astype(np.float64), mask[rows], 0.125) for h in range(H)]
+    for path in PATHS:
+        print("case", name, dtype, path, flush=True)
+        O, lse = sga.attention_forward(dQ, dK, dV, drp, dci, 0.125, workspace=ws, path=path, want_lse=True)
+        O = O.cpu().numpy()
+        lse = lse.cpu().numpy()
+        for h in range(H):
+            O_ref, lse_ref = refs[h]
+            empty = ~mask[rows].any(axis=1)
+            assert max_err(O[h][rows], O_ref) <= TOL[dtype]
+            assert (O[h][rows][empty] == 0).all() and np.isneginf(lse[h][rows][empty]).all()
+            assert max_err(lse[h][rows][~empty], lse_ref[~empty]) <= 1e-4
+
+
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 def test_single_neighbour_rows_return_v_exactly(dtype, path):
