@@ -481,13 +481,30 @@ struct CoreF32T {
     wait_loads_keep(v_keep);
     __builtin_amdgcn_wave_barrier();
     const float* vread = reinterpret_cast<const float*>(ldsv) + h * 4 * kHeadDim + n;
+    if (b.full) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      // A operand: V^T[channel cb*32+n][key acc_row(r,h)] = staged V[key][channel]
-      const float v0 = vread[acc_row(r, 0) * kHeadDim];
-      const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
-      st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
-      st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
+      for (int r = 0; r < 16; ++r) {
+        // A operand: V^T[channel cb*32+n][key acc_row(r,h)] = staged V[key][channel]
+        const float v0 = vread[acc_row(r, 0) * kHeadDim];
+        const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
+        st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
+        st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
+      }
+    } else {
+      // A masked block: registers 4g..4g+3 hold the keys 8g..8g+7 of the block; a group of keys
+      // that no query of the tile attends (p = 0 in every lane) is skipped, which is exact
+      // (e.g. the upper half of a block that holds 16 global tokens).
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        if (__builtin_amdgcn_ballot_w64(((b.word >> (8 * g)) & 0xffu) != 0) == 0) continue;
+#pragma unroll
+        for (int r = 4 * g; r < 4 * g + 4; ++r) {
+          const float v0 = vread[acc_row(r, 0) * kHeadDim];
+          const float v1 = vread[acc_row(r, 0) * kHeadDim + 32];
+          st.o[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(v0, p[r], st.o[0], 0, 0, 0);
+          st.o[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(v1, p[r], st.o[1], 0, 0, 0);
+        }
+      }
     }
   }
 
