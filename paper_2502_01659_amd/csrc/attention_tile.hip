@@ -2094,8 +2094,9 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
     }
   };
   if (vlast - vfirst + 1 == kWgBlocks * kTile) {
-    // A full window of whole blocks, every wavefront copies two of them: blocks 0..3 are
-    // computed on while blocks 4..7 are still on their way.  The copies are issued untracked
+    // A full window of whole blocks, every wavefront copies two of them: the four middle blocks
+    // (2..5; wavefront w needs blocks w..w+4, so each has three or four of them to work on) are
+    // computed on while blocks 0, 1, 6 and 7 are still on their way.  The copies are issued untracked
     // (see copy16_to_lds_untracked), the second round once Q and the first have arrived (the
     // waits ask for every operation in flight: no order between loads into registers and
     // copies to LDS is assumed), and the first barrier is a plain one: __syncthreads() would
@@ -2104,15 +2105,16 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
       sm.stage_whole_untracked(K + hoff, V + hoff, s * (vfirst + (int64_t)j * kTile) + p,
                                lds_k + j * CoreF16::kBlockBytes, lds_v + j * CoreF16::kBlockBytes);
     };
-    stage_whole(wave);
+    stage_whole(2 + wave);
     wait_loads_except<0>();
     core.q_arrived();
-    stage_whole(wave + 4);
+    stage_whole(wave < 2 ? wave : wave + 4);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    blocks(k_lo, k_hi < 3 ? k_hi : 3);
+    blocks(k_lo > 2 ? k_lo : 2, k_hi < 5 ? k_hi : 5);
     wait_loads_except<0>();
     __syncthreads();
-    blocks(k_lo > 4 ? k_lo : 4, k_hi);
+    blocks(k_lo, k_hi < 1 ? k_hi : 1);
+    blocks(k_lo > 6 ? k_lo : 6, k_hi);
   } else {
     for (int j = wave; j < nb; j += 4) stage(j);
     wait_loads_except<0>();
