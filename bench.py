@@ -32,11 +32,11 @@ DEFAULT_WORKLOAD = "cfg2_longformer_64k"
 # HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (see profiles/); None where not measured.
 MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 5_766_751,
-    "cfg2_longformer_64k": 1_083_006_985,
-    "cfg3_dilated_1m": 2_149_483_503,
-    "cfg4_bigbird_1m": 9_304_704_347,
-    "cfg5_sliding_160m": 81_970_136_321,
+    "cfg1_sliding_4k": 5_960_696,
+    "cfg2_longformer_64k": 1_073_989_511,
+    "cfg3_dilated_1m": 2_149_725_262,
+    "cfg4_bigbird_1m": 9_272_662_955,
+    "cfg5_sliding_160m": 81_961_935_671,
 }
 
 
