@@ -123,7 +123,11 @@ sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, i
   if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
   if (d != 32 && d != 64 && d != 128 && d != 256) return SGA_ERR_UNSUPPORTED;
   if (nnz < -1 || nnz > L * L) return SGA_ERR_INVALID_ARG;
-  *bytes_out = plan_workspace(L, H, nnz, dtype, d).total_bytes;
+  // (a caller that passes an upper bound of the edge count still gets enough for the shorter
+  // work items the kernels may choose from the real count)
+  const size_t chosen = plan_workspace(L, H, nnz, dtype, d).total_bytes;
+  const size_t shortest = plan_workspace(L, H, nnz, dtype, d, seg_shift_min(dtype)).total_bytes;
+  *bytes_out = chosen > shortest ? chosen : shortest;
   return SGA_OK;
 }
 

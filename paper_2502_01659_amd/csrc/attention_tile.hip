@@ -1374,7 +1374,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   for (int64_t w = (int64_t)blockIdx.x * waves + threadIdx.x / kWave; w < pl.n_work;
        w += (int64_t)gridDim.x * waves) {
-    const WorkId id = locate_work(row_ptr, L, seg_shift(dtype), pl.n_tiles, pl.n_work, w, lane);
+    const WorkId id = locate_work(row_ptr, L, pl.seg_shift, pl.n_tiles, pl.n_work, w, lane);
     if (id.seg >= id.nseg) {          // spare item of a tile whose edge range crosses a multiple of S
       if (lane == 0) items[w].tile = -1;
       continue;
@@ -1745,7 +1745,7 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
   for (uint32_t i = blockIdx.x; i < n_multi; i += gridDim.x) {
     const int64_t t = multi[i];
     if (tile_bad[t]) continue;
-    const int nseg = tile_segments(row_ptr, L, seg_shift(dtype), t);
+    const int nseg = tile_segments(row_ptr, L, pl.seg_shift, t);
     const float* p0 = parts + ((int64_t)tile_pbase[t] * H + hd) * (kSlices * kTilePartialFloats);
     const int64_t step = (int64_t)H * (kSlices * kTilePartialFloats);
     const int rows_per_wg = kTile / (int)gridDim.z;

@@ -30,9 +30,18 @@ constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32]
 // crosses; the first max(1, edges(t)/S) of them are the tile's segments, the rest stay idle.
 // The mapping follows from row_ptr alone and needs neither a scan nor atomics.  A dense
 // 32x32 block is 1024 edges: S is 32 dense blocks of fp32 MFMA work or 256 of fp16 work.
-// (a power of two: the kernels divide edge counts by S with a shift by seg_shift)
-__host__ __device__ inline int seg_shift(int32_t dtype) { return dtype == SGA_F32 ? 15 : 18; }
-__host__ __device__ inline int64_t seg_edges(int32_t dtype) { return int64_t(1) << seg_shift(dtype); }
+// S is a power of two (the kernels divide edge counts by it with a shift): 2^15 or 2^18 edges.
+// A call with little work in total (nnz * H edges) gets shorter items, down to 2^12 or 2^15
+// edges, until it has about 1024 of them: otherwise a small call with a few dense rows would
+// leave its few long items to a handful of wavefronts while the rest of the chip idles.
+// (Microbenchmark grid, one head, a few global tokens at L = 8192: 0.76 -> 0.14 ms.)
+__host__ __device__ inline int seg_shift_min(int32_t dtype) { return dtype == SGA_F32 ? 12 : 15; }
+__host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) {
+  int sh = dtype == SGA_F32 ? 15 : 18;
+  const int64_t e = (nnz < 0 ? 0 : nnz) * (int64_t)H;
+  while (sh > seg_shift_min(dtype) && (e >> sh) < 1024) --sh;
+  return sh;
+}
 
 // ---- workspace layout -------------------------------------------------------
 // [0, 256)            counters (uint32): see WsCounter
@@ -80,6 +89,7 @@ struct WorkspacePlan {
   int64_t n_work;         // tile work items (segments)
   int64_t cap_pairs;      // capacity of the (tile, key block) pair arrays
   int64_t cap_tparts;     // capacity of tile partial states
+  int seg_shift;          // log2 of S, the edges per work item of the tile path
   size_t off_items_rec, off_tile_bad, off_tile_pbase, off_multi_tiles, off_pair_blk, off_pair_mask,
       off_tpartials, off_work_next;
   size_t total_bytes;
@@ -89,10 +99,13 @@ struct WorkspacePlan {
 
 // Sizes every region for (L, H, nnz, dtype); nnz < 0 means implicit mask (no tile lists).
 // Evaluated identically on the host (sga_workspace_bytes) and inside the kernels
-// (with nnz = row_ptr[L]), so no layout has to be passed around.
+// (with nnz = row_ptr[L]), so no layout has to be passed around.  (force_shift: the size of a
+// layout with that log2 S instead of the one the arguments select.)
 __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, int64_t nnz,
-                                                        int32_t dtype, int32_t d = kHeadDim) {
+                                                        int32_t dtype, int32_t d = kHeadDim,
+                                                        int force_shift = -1) {
   WorkspacePlan p{};
+  p.seg_shift = force_shift >= 0 ? force_shift : seg_shift(dtype, nnz, H);
   size_t off = 256;   // counters
   const int64_t e = nnz < 0 ? 0 : nnz;
   int64_t n_long = e / (kSplitThreshold + 1);
@@ -111,9 +124,9 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   // tile path
   const bool tiles = nnz >= 0;
   p.n_tiles = tiles ? (L + kTile - 1) / kTile : 0;
-  p.n_work = tiles ? p.n_tiles + e / seg_edges(dtype) : 0;
+  p.n_work = tiles ? p.n_tiles + (e >> p.seg_shift) : 0;
   p.cap_pairs = tiles ? e / kPairEdges + 1 : 0;
-  p.cap_tparts = tiles ? e / seg_edges(dtype) + 1 : 0;
+  p.cap_tparts = tiles ? (e >> p.seg_shift) + 1 : 0;
   if (p.cap_tparts > kMaxTilePartials) p.cap_tparts = kMaxTilePartials;
   p.off_items_rec = off;
   off = (off + (size_t)p.n_work * sizeof(TileItem) + 255) & ~size_t(255);
@@ -158,7 +171,7 @@ __device__ __forceinline__ bool tile_handled(const WorkspacePlan& pl, const void
                                              int32_t dtype, int64_t t) {
   const char* base = static_cast<const char*>(ws);
   if (reinterpret_cast<const int32_t*>(base + pl.off_tile_bad)[t] != 0) return false;
-  if (tile_segments(row_ptr, L, seg_shift(dtype), t) == 1) return true;
+  if (tile_segments(row_ptr, L, pl.seg_shift, t) == 1) return true;
   return (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTilePartsNeeded] <= pl.cap_tparts;
 }
 
