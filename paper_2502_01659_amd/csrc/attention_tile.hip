@@ -1866,7 +1866,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
                                                           const T* __restrict__ V, T* __restrict__ O,
                                                           float* __restrict__ lse, int64_t L, int64_t W,
                                                           int64_t s, int64_t n_groups, float scale,
-                                                          int accumulate, int64_t seg_len) {
+                                                          int accumulate, int64_t seg_len, int nsplit,
+                                                          float* __restrict__ parts) {
   constexpr int kLds = CoreFor<T, kPipe>::type::template lds_bytes<kPipe>();
   __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
   const int lane = threadIdx.x & (kWave - 1);
@@ -1875,7 +1876,11 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   char* lds = lds_all + wave * kLds;
   // gridDim.x is a multiple of 8: XCD x handles the workgroups [x*chunk, (x+1)*chunk)
   const int64_t chunk = gridDim.x / 8;
-  const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  const int64_t bid_all = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  // (nsplit > 1: nsplit consecutive workgroups share four tiles, each takes one range of their
+  // key blocks and leaves partial states for window_merge_kernel)
+  const int64_t bid = bid_all / nsplit;
+  const int part = (int)(bid_all - bid * nsplit);
   WindowSlot slot;
   if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
   const int64_t p = slot.p, Lc = slot.Lc;
@@ -1894,6 +1899,13 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
   TileState st;
   st.init();
+  if (nsplit > 1) {
+    const int k0 = (int)((int64_t)nblk * part / nsplit), k1 = (int)((int64_t)nblk * (part + 1) / nsplit);
+    core.template run<kPipe>(K + hoff, V + hoff, src, k0, k1, softmax_factor(scale), lane, st, lds);
+    store_partial(parts + (((bid * 4 + wave) * gridDim.y + hd) * nsplit + part) * (int64_t)kTilePartialFloats,
+                  st, n, h);
+    return;
+  }
   core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st, lds);
   if (accumulate || !CoreOf<T>::type::kTileStore) {
     finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, qrow, qrow, exists, st, h, accumulate != 0);
@@ -1901,6 +1913,48 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
     static_assert(CoreOf<T>::type::kTileBytes <= kLds, "output tile fits the wavefront's LDS");
     finish_tile_rows<T>(O + hoff, lse ? lse + hd * L : nullptr, s * u0 + p, s,
                         Lc - u0 < kTile ? (int)(Lc - u0) : kTile, st, lane, lds);
+  }
+}
+
+// Merge of the partial states that tile_window_kernel leaves when it cuts the key blocks of its
+// tiles into nsplit ranges.  grid = (workgroups of the uncut launch, head); wavefront w merges
+// tile w of the group, lane = channel, rows one after the other, the ranges in ascending order.
+template <typename T>
+__global__ __launch_bounds__(256) void window_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
+                                                           const float* __restrict__ parts, int64_t L,
+                                                           int64_t s, int64_t n_groups, int accumulate,
+                                                           int64_t seg_len, int nsplit) {
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = threadIdx.x / kWave;
+  const int64_t bid = blockIdx.x, hd = blockIdx.y;
+  WindowSlot slot;
+  if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
+  const int64_t u0 = (slot.grp * 4 + wave) * kTile;
+  if (u0 >= slot.Lc) return;
+  const float* p0 = parts + (((bid * 4 + wave) * gridDim.y + hd) * nsplit) * (int64_t)kTilePartialFloats;
+  for (int r = 0; r < kTile && u0 + r < slot.Lc; ++r) {
+    const int64_t row = s * (u0 + r) + slot.p;
+    float M = kMinusHuge;
+    for (int c = 0; c < nsplit; ++c) M = fmaxf(M, p0[c * kTilePartialFloats + kTile * 64 + r]);
+    float l = 0.f, acc = 0.f;
+    for (int c = 0; c < nsplit; ++c) {
+      const float* pc = p0 + c * kTilePartialFloats;
+      const float wgt = __builtin_amdgcn_exp2f(pc[kTile * 64 + r] - M);
+      l = __builtin_fmaf(pc[kTile * 64 + kTile + r], wgt, l);
+      acc = __builtin_fmaf(pc[r * 64 + lane], wgt, acc);
+    }
+    const bool empty = !(l > 0.f);
+    float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+    CarryWeights cw{0.f, 1.f, lse_row};
+    if (accumulate) {
+      cw = carry_weights(lse[hd * L + row], lse_row);
+      lse_row = cw.lse;
+    }
+    T* dst = O + hd * L * kHeadDim + row * kHeadDim + lane;
+    float o = empty ? 0.f : acc / l;
+    if (accumulate) o = cw.w_prev * load_out(dst) + cw.w_now * o;
+    store_out(dst, o);
+    if (lse && lane == 0) lse[hd * L + row] = lse_row;
   }
 }
 
@@ -2309,11 +2363,43 @@ sga_status run_tile_implicit(const AttnArgs& a) {
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
                        (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len);
   } else {
+    // A call with few tiles and many key blocks per tile (a short sequence with a wide window,
+    // one head) is cut into ranges of at least 16 key blocks.  The chip runs 2048 of these wavefronts
+    // at a time, so k ranges cost about ceil(tiles * k / 2048) rounds of ceil(blocks / k) blocks each,
+    // plus the partial states and their merge (taken as 4 blocks per range): the cheapest k <= 8 wins;
+    // the partial states go to the workspace, if it has room for them, and are merged afterwards.
+    int nsplit = 1;
+    float* parts = nullptr;
+    const int64_t tile_heads = n_wg * 4 * a.H;
+    const int64_t blocks_per_tile = (2 * (int64_t)a.window + kTile - 1) / kTile + 1;
+    if (a.ws && tile_heads < 2048 && blocks_per_tile >= 32) {
+      const WorkspacePlan pl = plan_workspace(a.L, a.H, -1, a.dtype, a.d);
+      if (pl.total_bytes <= a.ws_bytes && tile_heads <= pl.cap_wparts) {
+        int64_t want = 1, best = blocks_per_tile * ((tile_heads + 2047) / 2048);
+        for (int64_t k = 2; k <= kMaxWindowSplit && blocks_per_tile / k >= 16; ++k) {
+          const int64_t cost = (tile_heads * k + 2047) / 2048 * ((blocks_per_tile + k - 1) / k) + 4 * k;
+          if (cost < best) {
+            best = cost;
+            want = k;
+          }
+        }
+        if (want >= 2) {
+          nsplit = (int)want;
+          parts = reinterpret_cast<float*>(static_cast<char*>(a.ws) + pl.off_wparts);
+        }
+      }
+    }
     auto kernel = a.split ? tile_window_kernel<float, kPipeSplit> : tile_window_kernel<float, kPipeRegK>;
-    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, a.stream,
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(n_wg * nsplit), (unsigned)a.H), dim3(256), 0, a.stream,
                        static_cast<const float*>(a.Q), static_cast<const float*>(a.K),
                        static_cast<const float*>(a.V), static_cast<float*>(a.O), a.lse, a.L,
-                       (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len);
+                       (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len, nsplit, parts);
+    if (nsplit > 1) {
+      profile_mark_end(a.stream);
+      hipLaunchKernelGGL(window_merge_kernel<float>, grid, dim3(256), 0, a.stream, static_cast<float*>(a.O),
+                         a.lse, parts, a.L, s, n_groups, acc, shape.seg_len, nsplit);
+      return hip_status(hipGetLastError());
+    }
   }
   profile_mark_end(a.stream);
   return hip_status(hipGetLastError());

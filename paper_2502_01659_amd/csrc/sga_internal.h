@@ -18,6 +18,12 @@ constexpr int kSplitThreshold = 2048; // rows with more neighbours are split
 constexpr int kSplitChunk = 2048;     // target edges per chunk
 constexpr int kMaxSplit = 64;         // at most this many chunks per row
 constexpr int kMaxImplicitGlobal = 64;  // global rows the implicit non-local kernels can split
+// Implicit window masks on few tiles (a short sequence, one head): a tile's key blocks are cut
+// into up to kMaxWindowSplit ranges that separate wavefronts reduce to partial states, so that
+// the call fills the chip.  The workspace holds the partials of up to kWindowSplitTiles
+// (tile, head) pairs; larger calls have tiles enough and are not cut.
+constexpr int kMaxWindowSplit = 8;
+constexpr int kWindowSplitTiles = 4096;
 
 // ---- tile path parameters -----------------------------------------------------
 constexpr int kTile = 32;                 // query rows per tile = keys per block
@@ -91,7 +97,8 @@ struct WorkspacePlan {
   int64_t cap_tparts;     // capacity of tile partial states
   int seg_shift;          // log2 of S, the edges per work item of the tile path
   size_t off_items_rec, off_tile_bad, off_tile_pbase, off_multi_tiles, off_pair_blk, off_pair_mask,
-      off_tpartials, off_work_next;
+      off_tpartials, off_work_next, off_wparts;
+  int64_t cap_wparts;     // (tile, head) pairs whose window partials fit (implicit masks)
   size_t total_bytes;
 };
 
@@ -145,6 +152,14 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   off = (off + (size_t)p.cap_tparts * H * slices * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
   p.off_work_next = off;
   off = (off + (tiles ? (size_t)H * 4 : 0) + 255) & ~size_t(255);
+  // implicit window masks, d = 64: partial states of cut tiles (short sequences only)
+  p.cap_wparts = 0;
+  if (nnz < 0 && d == kHeadDim) {
+    const int64_t pairs = ((L + kTile - 1) / kTile + 256) * H;     // (tiles of every class: + a margin) x heads
+    if (pairs <= kWindowSplitTiles) p.cap_wparts = pairs;
+  }
+  p.off_wparts = off;
+  off = (off + (size_t)p.cap_wparts * kMaxWindowSplit * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
   p.total_bytes = off;
   return p;
 }

@@ -114,6 +114,38 @@ def test_window_staging_boundaries(spec, dtype):
     assert max_err(lse, lse_ref) <= 1e-4
 
 
+@pytest.mark.parametrize("spec", [
+    MaskSpec(KIND_SLIDING, 3000, window=700),
+    MaskSpec(KIND_SLIDING, 1537, window=1536),             # every row attends every key
+    MaskSpec(KIND_DILATED, 3001, window=300, stride=3),
+    MaskSpec(KIND_DILATED_2D, 2500, block=1100, stride=1),
+], ids=lambda s: f"{s.name}-L{s.L}")
+@pytest.mark.parametrize("H", [1, 3])
+def test_short_sequences_with_wide_windows_are_cut_into_key_ranges(spec, H):
+    """fp32 window tiles of a call with few tiles and many key blocks per tile are cut into
+    ranges of key blocks whose partial states are merged afterwards (only with a workspace):
+    results with and without a workspace against the oracle, and a continuing call on top."""
+    print("case", spec, H, flush=True)
+    wl = Workload("t", H=H, L=spec.L, d=64, dtype="f32", sigma=0.9, mask=spec, explicit=False, seed=31)
+    Q, K, V = small_inputs(wl)
+    O_ref, lse_ref = oracle_full(wl, Q, K, V)
+    dQ, dK, dV = to_device(Q, K, V)
+    ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, -1)
+    for workspace in (ws, None):
+        O, lse = sga.attention_forward_implicit(dQ, dK, dV, spec, wl.scale, workspace=workspace,
+                                                path=sga.PATH_TILE, want_lse=True)
+        assert max_err(O.cpu().numpy(), O_ref) <= TOL["f32"]
+        assert max_err(lse.cpu().numpy(), lse_ref) <= 1e-4
+    # the same mask applied twice in a row: the second call continues the first one's state,
+    # which leaves O unchanged and adds ln 2 to lse
+    O, lse = sga.attention_forward_implicit(dQ, dK, dV, spec, wl.scale, workspace=ws, path=sga.PATH_TILE,
+                                            want_lse=True)
+    sga.attention_accumulate_implicit(dQ, dK, dV, spec, wl.scale, O, lse, workspace=ws, path=sga.PATH_TILE)
+    nonempty = np.isfinite(lse_ref)
+    assert max_err(O.cpu().numpy(), O_ref) <= TOL["f32"]
+    assert max_err(lse.cpu().numpy()[nonempty], lse_ref[nonempty] + math.log(2.0)) <= 1e-4
+
+
 @pytest.mark.parametrize("path", PATHS, ids=PATH_IDS)
 @pytest.mark.parametrize("sf", [1.0, 0.5, 0.1, 0.01])
 def test_verification_protocol_bernoulli_masks(sf, path):
