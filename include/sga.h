@@ -184,8 +184,9 @@ sga_status sga_attention_forward(const void* Q, const void* K, const void* V,
  * required: the global rows are split over the key range) through the per-row kernels;
  * other kinds return SGA_ERR_UNSUPPORTED (build their CSR instead).
  * The workspace is optional for the window masks; with one of sga_workspace_bytes(..., nnz = -1)
- * bytes, fp32 calls with few query tiles and wide windows (short sequences) split each tile's
- * key range over several wavefronts and merge the partial states in key order.
+ * bytes, calls with few query tiles and wide windows (short sequences; fp32 at d = 64, both
+ * types at d = 128 and 256) split each tile's key range over several wavefronts and merge the
+ * partial states in key order.
  * Arguments as in sga_attention_forward; desc: host; desc->L must equal L.
  * Element offsets are 64-bit (L*d may pass 2^31).
  */

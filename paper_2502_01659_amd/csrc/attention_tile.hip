@@ -1916,29 +1916,35 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   }
 }
 
-// Merge of the partial states that tile_window_kernel leaves when it cuts the key blocks of its
-// tiles into nsplit ranges.  grid = (workgroups of the uncut launch, head); wavefront w merges
-// tile w of the group, lane = channel, rows one after the other, the ranges in ascending order.
-template <typename T>
-__global__ __launch_bounds__(256) void window_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
-                                                           const float* __restrict__ parts, int64_t L,
-                                                           int64_t s, int64_t n_groups, int accumulate,
-                                                           int64_t seg_len, int nsplit) {
+// Merge of the partial states that the window kernels leave when they cut the key blocks of
+// their tiles into nsplit ranges.  grid = (workgroups of the uncut launch, head).  d = 64: the
+// workgroup's four wavefronts merge its four tiles; wider heads: one tile per workgroup, one
+// wavefront per 64-channel slice.  lane = channel, rows one after the other, the ranges in
+// ascending order.
+template <typename T, int kD>
+__global__ __launch_bounds__(kD == kHeadDim ? 256 : kD) void window_merge_kernel(
+    T* __restrict__ O, float* __restrict__ lse, const float* __restrict__ parts, int64_t L, int64_t s,
+    int64_t n_groups, int accumulate, int64_t seg_len, int nsplit) {
+  constexpr int kSlices = kD / kHeadDim;
+  constexpr int kTilesPerWg = kSlices == 1 ? 4 : 1;
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
+  const int tile_in_wg = kSlices == 1 ? wave : 0, slice = kSlices == 1 ? 0 : wave;
   const int64_t bid = blockIdx.x, hd = blockIdx.y;
   WindowSlot slot;
   if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
-  const int64_t u0 = (slot.grp * 4 + wave) * kTile;
+  const int64_t u0 = (slot.grp * kTilesPerWg + tile_in_wg) * kTile;
   if (u0 >= slot.Lc) return;
-  const float* p0 = parts + (((bid * 4 + wave) * gridDim.y + hd) * nsplit) * (int64_t)kTilePartialFloats;
+  const int64_t range_step = (int64_t)kSlices * kTilePartialFloats;
+  const float* p0 = parts + ((((bid * kTilesPerWg + tile_in_wg) * gridDim.y + hd) * nsplit) * kSlices + slice) *
+                                (int64_t)kTilePartialFloats;
   for (int r = 0; r < kTile && u0 + r < slot.Lc; ++r) {
     const int64_t row = s * (u0 + r) + slot.p;
     float M = kMinusHuge;
-    for (int c = 0; c < nsplit; ++c) M = fmaxf(M, p0[c * kTilePartialFloats + kTile * 64 + r]);
+    for (int c = 0; c < nsplit; ++c) M = fmaxf(M, p0[c * range_step + kTile * 64 + r]);
     float l = 0.f, acc = 0.f;
     for (int c = 0; c < nsplit; ++c) {
-      const float* pc = p0 + c * kTilePartialFloats;
+      const float* pc = p0 + c * range_step;
       const float wgt = __builtin_amdgcn_exp2f(pc[kTile * 64 + r] - M);
       l = __builtin_fmaf(pc[kTile * 64 + kTile + r], wgt, l);
       acc = __builtin_fmaf(pc[r * 64 + lane], wgt, acc);
@@ -1949,12 +1955,13 @@ __global__ __launch_bounds__(256) void window_merge_kernel(T* __restrict__ O, fl
     if (accumulate) {
       cw = carry_weights(lse[hd * L + row], lse_row);
       lse_row = cw.lse;
+      if (kSlices > 1) __syncthreads();     // every slice has read the earlier lse before slice 0 replaces it
     }
-    T* dst = O + hd * L * kHeadDim + row * kHeadDim + lane;
+    T* dst = O + hd * L * kD + row * kD + slice * kHeadDim + lane;
     float o = empty ? 0.f : acc / l;
     if (accumulate) o = cw.w_prev * load_out(dst) + cw.w_now * o;
     store_out(dst, o);
-    if (lse && lane == 0) lse[hd * L + row] = lse_row;
+    if (lse && lane == 0 && slice == 0) lse[hd * L + row] = lse_row;
   }
 }
 
@@ -1965,7 +1972,7 @@ template <typename T, int kD, int kPipe>
 __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_tiles, float scale,
-    int accumulate, int64_t seg_len) {
+    int accumulate, int64_t seg_len, int nsplit, float* __restrict__ parts) {
   using Core = typename WideCoreOf<T, kD>::type;
   constexpr int kSlices = kD / kHeadDim;
   constexpr int kLds = Core::template lds_bytes<kPipe>();
@@ -1974,7 +1981,10 @@ __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
   const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int n = lane & 31, h = lane >> 5;
   const int64_t chunk = gridDim.x / 8;
-  const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  const int64_t bid_all = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  // (nsplit > 1: nsplit consecutive workgroups share a tile, see tile_window_kernel)
+  const int64_t bid = bid_all / nsplit;
+  const int part = (int)(bid_all - bid * nsplit);
   // (every condition below is the same for all wavefronts of the workgroup)
   WindowSlot slot;
   if (!locate_window_slot(bid, L, s, n_tiles, seg_len, slot)) return;
@@ -1995,6 +2005,15 @@ __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
   core.load_q(Q + hoff + qrow * kD, h, scale < 0.f);
   TileState st;
   st.init();
+  if (nsplit > 1) {
+    const int k0 = (int)((int64_t)nblk * part / nsplit), k1 = (int)((int64_t)nblk * (part + 1) / nsplit);
+    core.template run<kPipe>(K + hoff, V + hoff, src, k0, k1, softmax_factor(scale), lane, st,
+                             lds_all + slice * kLds);
+    store_partial(parts + (((bid * gridDim.y + hd) * nsplit + part) * kSlices + slice) *
+                              (int64_t)kTilePartialFloats,
+                  st, n, h);
+    return;
+  }
   core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st,
                            lds_all + slice * kLds);
   finish_tile_wide<T, kD>(O + hoff, lse ? lse + hd * L : nullptr, qrow, exists, st, h, slice,
@@ -2301,6 +2320,30 @@ void clear_unselected_rows(const AttnArgs& a) {
                      (int64_t)a.stride);
 }
 
+// A window call with few tiles and many key blocks per tile (a short sequence with a wide
+// window, one head) is cut into ranges of at least 16 key blocks per tile.  The chip runs
+// `resident` tiles at a time, so k ranges cost about ceil(tiles * k / resident) rounds of
+// ceil(blocks / k) blocks each, plus the partial states and their merge (taken as 4 blocks per
+// range): the cheapest k <= kMaxWindowSplit wins.  The partial states go to the workspace; without
+// room for them (or without a workspace) the call is not cut.  Returns k and sets *parts.
+int choose_window_split(const AttnArgs& a, int64_t tile_heads, int64_t resident, float** parts) {
+  *parts = nullptr;
+  const int64_t blocks_per_tile = (2 * (int64_t)a.window + kTile - 1) / kTile + 1;
+  if (!a.ws || tile_heads >= resident || blocks_per_tile < 32) return 1;
+  const WorkspacePlan pl = plan_workspace(a.L, a.H, -1, a.dtype, a.d);
+  if (pl.total_bytes > a.ws_bytes || tile_heads > pl.cap_wparts) return 1;
+  int64_t want = 1, best = blocks_per_tile * ((tile_heads + resident - 1) / resident);
+  for (int64_t k = 2; k <= kMaxWindowSplit && blocks_per_tile / k >= 16; ++k) {
+    const int64_t cost = (tile_heads * k + resident - 1) / resident * ((blocks_per_tile + k - 1) / k) + 4 * k;
+    if (cost < best) {
+      best = cost;
+      want = k;
+    }
+  }
+  if (want > 1) *parts = reinterpret_cast<float*>(static_cast<char*>(a.ws) + pl.off_wparts);
+  return (int)want;
+}
+
 template <typename T, int kD>
 sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
   const int64_t s = a.stride;
@@ -2309,13 +2352,20 @@ sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
   const int64_t n_wg = (n_tiles * shape.n_slots + 7) / 8 * 8;
   if (n_wg >= (int64_t(1) << 31)) return SGA_ERR_OVERFLOW;
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
+  constexpr int kSlices = kD / kHeadDim;
   clear_unselected_rows<T>(a);
+  float* parts = nullptr;
+  const int nsplit = choose_window_split(a, n_wg * a.H, 2048 / kSlices, &parts);
+  const int acc = a.accumulate ? 1 : 0;
   profile_mark_begin(a.stream);
-  hipLaunchKernelGGL((tile_window_wide_kernel<T, kD, kPipe>), dim3((unsigned)n_wg, (unsigned)a.H),
+  hipLaunchKernelGGL((tile_window_wide_kernel<T, kD, kPipe>), dim3((unsigned)(n_wg * nsplit), (unsigned)a.H),
                      dim3(kD), 0, a.stream, static_cast<const T*>(a.Q), static_cast<const T*>(a.K),
                      static_cast<const T*>(a.V), static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s,
-                     n_tiles, a.scale, a.accumulate ? 1 : 0, shape.seg_len);
+                     n_tiles, a.scale, acc, shape.seg_len, nsplit, parts);
   profile_mark_end(a.stream);
+  if (nsplit > 1)
+    hipLaunchKernelGGL((window_merge_kernel<T, kD>), dim3((unsigned)n_wg, (unsigned)a.H), dim3(kD), 0, a.stream,
+                       static_cast<T*>(a.O), a.lse, parts, a.L, s, n_tiles, acc, shape.seg_len, nsplit);
   return hip_status(hipGetLastError());
 }
 
@@ -2363,32 +2413,8 @@ sga_status run_tile_implicit(const AttnArgs& a) {
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
                        (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len);
   } else {
-    // A call with few tiles and many key blocks per tile (a short sequence with a wide window,
-    // one head) is cut into ranges of at least 16 key blocks.  The chip runs 2048 of these wavefronts
-    // at a time, so k ranges cost about ceil(tiles * k / 2048) rounds of ceil(blocks / k) blocks each,
-    // plus the partial states and their merge (taken as 4 blocks per range): the cheapest k <= 8 wins;
-    // the partial states go to the workspace, if it has room for them, and are merged afterwards.
-    int nsplit = 1;
     float* parts = nullptr;
-    const int64_t tile_heads = n_wg * 4 * a.H;
-    const int64_t blocks_per_tile = (2 * (int64_t)a.window + kTile - 1) / kTile + 1;
-    if (a.ws && tile_heads < 2048 && blocks_per_tile >= 32) {
-      const WorkspacePlan pl = plan_workspace(a.L, a.H, -1, a.dtype, a.d);
-      if (pl.total_bytes <= a.ws_bytes && tile_heads <= pl.cap_wparts) {
-        int64_t want = 1, best = blocks_per_tile * ((tile_heads + 2047) / 2048);
-        for (int64_t k = 2; k <= kMaxWindowSplit && blocks_per_tile / k >= 16; ++k) {
-          const int64_t cost = (tile_heads * k + 2047) / 2048 * ((blocks_per_tile + k - 1) / k) + 4 * k;
-          if (cost < best) {
-            best = cost;
-            want = k;
-          }
-        }
-        if (want >= 2) {
-          nsplit = (int)want;
-          parts = reinterpret_cast<float*>(static_cast<char*>(a.ws) + pl.off_wparts);
-        }
-      }
-    }
+    const int nsplit = choose_window_split(a, n_wg * 4 * a.H, 2048, &parts);
     auto kernel = a.split ? tile_window_kernel<float, kPipeSplit> : tile_window_kernel<float, kPipeRegK>;
     hipLaunchKernelGGL(kernel, dim3((unsigned)(n_wg * nsplit), (unsigned)a.H), dim3(256), 0, a.stream,
                        static_cast<const float*>(a.Q), static_cast<const float*>(a.K),
@@ -2396,8 +2422,8 @@ sga_status run_tile_implicit(const AttnArgs& a) {
                        (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len, nsplit, parts);
     if (nsplit > 1) {
       profile_mark_end(a.stream);
-      hipLaunchKernelGGL(window_merge_kernel<float>, grid, dim3(256), 0, a.stream, static_cast<float*>(a.O),
-                         a.lse, parts, a.L, s, n_groups, acc, shape.seg_len, nsplit);
+      hipLaunchKernelGGL((window_merge_kernel<float, kHeadDim>), grid, dim3(256), 0, a.stream,
+                         static_cast<float*>(a.O), a.lse, parts, a.L, s, n_groups, acc, shape.seg_len, nsplit);
       return hip_status(hipGetLastError());
     }
   }

@@ -152,14 +152,15 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   off = (off + (size_t)p.cap_tparts * H * slices * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
   p.off_work_next = off;
   off = (off + (tiles ? (size_t)H * 4 : 0) + 255) & ~size_t(255);
-  // implicit window masks, d = 64: partial states of cut tiles (short sequences only)
+  // implicit window masks: partial states of cut tiles (short sequences only)
   p.cap_wparts = 0;
-  if (nnz < 0 && d == kHeadDim) {
+  if (nnz < 0 && d >= kHeadDim) {
     const int64_t pairs = ((L + kTile - 1) / kTile + 256) * H;     // (tiles of every class: + a margin) x heads
     if (pairs <= kWindowSplitTiles) p.cap_wparts = pairs;
   }
   p.off_wparts = off;
-  off = (off + (size_t)p.cap_wparts * kMaxWindowSplit * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
+  off = (off + (size_t)p.cap_wparts * kMaxWindowSplit * slices * kTilePartialFloats * sizeof(float) + 255) &
+        ~size_t(255);
   p.total_bytes = off;
   return p;
 }

@@ -121,12 +121,14 @@ def test_window_staging_boundaries(spec, dtype):
     MaskSpec(KIND_DILATED_2D, 2500, block=1100, stride=1),
 ], ids=lambda s: f"{s.name}-L{s.L}")
 @pytest.mark.parametrize("H", [1, 3])
-def test_short_sequences_with_wide_windows_are_cut_into_key_ranges(spec, H):
-    """fp32 window tiles of a call with few tiles and many key blocks per tile are cut into
-    ranges of key blocks whose partial states are merged afterwards (only with a workspace):
-    results with and without a workspace against the oracle, and a continuing call on top."""
-    print("case", spec, H, flush=True)
-    wl = Workload("t", H=H, L=spec.L, d=64, dtype="f32", sigma=0.9, mask=spec, explicit=False, seed=31)
+@pytest.mark.parametrize("d,dtype", [(64, "f32"), (128, "f32"), (128, "f16"), (256, "f32")])
+def test_short_sequences_with_wide_windows_are_cut_into_key_ranges(spec, H, d, dtype):
+    """Window tiles of a call with few tiles and many key blocks per tile (fp32 at d = 64, both
+    types at d = 128 and 256) are cut into ranges of key blocks whose partial states are merged
+    afterwards (only with a workspace): results with and without a workspace against the oracle,
+    and a continuing call on top."""
+    print("case", spec, H, d, dtype, flush=True)
+    wl = Workload("t", H=H, L=spec.L, d=d, dtype=dtype, sigma=0.9, mask=spec, explicit=False, seed=31)
     Q, K, V = small_inputs(wl)
     O_ref, lse_ref = oracle_full(wl, Q, K, V)
     dQ, dK, dV = to_device(Q, K, V)
@@ -134,7 +136,7 @@ def test_short_sequences_with_wide_windows_are_cut_into_key_ranges(spec, H):
     for workspace in (ws, None):
         O, lse = sga.attention_forward_implicit(dQ, dK, dV, spec, wl.scale, workspace=workspace,
                                                 path=sga.PATH_TILE, want_lse=True)
-        assert max_err(O.cpu().numpy(), O_ref) <= TOL["f32"]
+        assert max_err(O.cpu().numpy(), O_ref) <= TOL[dtype]
         assert max_err(lse.cpu().numpy(), lse_ref) <= 1e-4
     # the same mask applied twice in a row: the second call continues the first one's state,
     # which leaves O unchanged and adds ln 2 to lse
@@ -142,7 +144,7 @@ def test_short_sequences_with_wide_windows_are_cut_into_key_ranges(spec, H):
                                             want_lse=True)
     sga.attention_accumulate_implicit(dQ, dK, dV, spec, wl.scale, O, lse, workspace=ws, path=sga.PATH_TILE)
     nonempty = np.isfinite(lse_ref)
-    assert max_err(O.cpu().numpy(), O_ref) <= TOL["f32"]
+    assert max_err(O.cpu().numpy(), O_ref) <= TOL[dtype]
     assert max_err(lse.cpu().numpy()[nonempty], lse_ref[nonempty] + math.log(2.0)) <= 1e-4
 
 
