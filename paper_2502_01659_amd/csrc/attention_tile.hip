@@ -1916,52 +1916,79 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   }
 }
 
+__device__ __forceinline__ float lane_value(float v, int src_lane) {     // v of lane src_lane (uniform index)
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
+}
+
 // Merge of the partial states that the window kernels leave when they cut the key blocks of
-// their tiles into nsplit ranges.  grid = (workgroups of the uncut launch, head).  d = 64: the
-// workgroup's four wavefronts merge its four tiles; wider heads: one tile per workgroup, one
-// wavefront per 64-channel slice.  lane = channel, rows one after the other, the ranges in
-// ascending order.
+// their tiles into nsplit <= kMaxWindowSplit ranges.  grid = (tiles: 4 per workgroup of the uncut
+// d = 64 launch, 1 per workgroup of the wider ones; head; quarter of the tile's rows), one
+// wavefront per 64-channel slice.  Lanes 0..7 first reduce the (m, l) of the quarter's eight rows
+// over the ranges, in ascending order, to the rows' weights; then lane = channel and the
+// weighted accumulators are summed row by row, every load independent of the others.
 template <typename T, int kD>
-__global__ __launch_bounds__(kD == kHeadDim ? 256 : kD) void window_merge_kernel(
+__global__ __launch_bounds__(kD) void window_merge_kernel(
     T* __restrict__ O, float* __restrict__ lse, const float* __restrict__ parts, int64_t L, int64_t s,
     int64_t n_groups, int accumulate, int64_t seg_len, int nsplit) {
   constexpr int kSlices = kD / kHeadDim;
-  constexpr int kTilesPerWg = kSlices == 1 ? 4 : 1;
+  constexpr int kTilesPerWg = kSlices == 1 ? 4 : 1;    // of the launch that wrote the partial states
+  constexpr int kRows = kTile / 4;
   const int lane = threadIdx.x & (kWave - 1);
-  const int wave = threadIdx.x / kWave;
-  const int tile_in_wg = kSlices == 1 ? wave : 0, slice = kSlices == 1 ? 0 : wave;
-  const int64_t bid = blockIdx.x, hd = blockIdx.y;
+  const int slice = threadIdx.x / kWave;
+  const int64_t bid = blockIdx.x / kTilesPerWg, hd = blockIdx.y;
+  const int tile_in_wg = blockIdx.x % kTilesPerWg;
   WindowSlot slot;
   if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
-  const int64_t u0 = (slot.grp * kTilesPerWg + tile_in_wg) * kTile;
+  const int64_t u0 = (slot.grp * kTilesPerWg + tile_in_wg) * kTile + blockIdx.z * kRows;
   if (u0 >= slot.Lc) return;
+  const int r0 = blockIdx.z * kRows;
   const int64_t range_step = (int64_t)kSlices * kTilePartialFloats;
   const float* p0 = parts + ((((bid * kTilesPerWg + tile_in_wg) * gridDim.y + hd) * nsplit) * kSlices + slice) *
                                 (int64_t)kTilePartialFloats;
-  for (int r = 0; r < kTile && u0 + r < slot.Lc; ++r) {
-    const int64_t row = s * (u0 + r) + slot.p;
-    float M = kMinusHuge;
-    for (int c = 0; c < nsplit; ++c) M = fmaxf(M, p0[c * range_step + kTile * 64 + r]);
-    float l = 0.f, acc = 0.f;
-    for (int c = 0; c < nsplit; ++c) {
-      const float* pc = p0 + c * range_step;
-      const float wgt = __builtin_amdgcn_exp2f(pc[kTile * 64 + r] - M);
-      l = __builtin_fmaf(pc[kTile * 64 + kTile + r], wgt, l);
-      acc = __builtin_fmaf(pc[r * 64 + lane], wgt, acc);
-    }
-    const bool empty = !(l > 0.f);
-    float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
-    CarryWeights cw{0.f, 1.f, lse_row};
-    if (accumulate) {
-      cw = carry_weights(lse[hd * L + row], lse_row);
-      lse_row = cw.lse;
-      if (kSlices > 1) __syncthreads();     // every slice has read the earlier lse before slice 0 replaces it
+  // row statistics: lane j < kRows owns row r0 + j
+  const int jr = lane < kRows ? lane : 0;
+  const int64_t row_j = s * (u0 + jr < slot.Lc ? u0 + jr : slot.Lc - 1) + slot.p;
+  float mc[kMaxWindowSplit], lc[kMaxWindowSplit];
+  float M = kMinusHuge;
+#pragma unroll
+  for (int c = 0; c < kMaxWindowSplit; ++c) {
+    const int cc = c < nsplit ? c : 0;
+    mc[c] = p0[cc * range_step + kTile * 64 + r0 + jr];
+    lc[c] = c < nsplit ? p0[cc * range_step + kTile * 64 + kTile + r0 + jr] : 0.f;
+    if (c < nsplit) M = fmaxf(M, mc[c]);
+  }
+  float l = 0.f, w[kMaxWindowSplit];
+#pragma unroll
+  for (int c = 0; c < kMaxWindowSplit; ++c) {
+    w[c] = c < nsplit ? __builtin_amdgcn_exp2f(mc[c] - M) : 0.f;
+    l = __builtin_fmaf(lc[c], w[c], l);
+  }
+  const bool empty = !(l > 0.f);
+  float lse_row = empty ? -INFINITY : (M + __builtin_amdgcn_logf(l)) * kLn2;
+  float w_now = empty ? 0.f : 1.0f / l, w_prev = 0.f;
+  if (accumulate) {
+    const CarryWeights cw = carry_weights(lse[hd * L + row_j], lse_row);
+    w_now *= cw.w_now;
+    w_prev = cw.w_prev;
+    lse_row = cw.lse;
+    if (kSlices > 1) __syncthreads();     // every slice has read the earlier lse before slice 0 replaces it
+  }
+  if (lse && slice == 0 && lane < kRows && u0 + lane < slot.Lc) lse[hd * L + row_j] = lse_row;
+#pragma unroll
+  for (int c = 0; c < kMaxWindowSplit; ++c) w[c] *= w_now;        // weights of the normalised sum
+#pragma unroll
+  for (int j = 0; j < kRows; ++j) {
+    if (u0 + j >= slot.Lc) break;
+    const int64_t row = s * (u0 + j) + slot.p;
+    float acc = 0.f;
+#pragma unroll
+    for (int c = 0; c < kMaxWindowSplit; ++c) {
+      if (c < nsplit)
+        acc = __builtin_fmaf(p0[c * range_step + (r0 + j) * 64 + lane], lane_value(w[c], j), acc);
     }
     T* dst = O + hd * L * kD + row * kD + slice * kHeadDim + lane;
-    float o = empty ? 0.f : acc / l;
-    if (accumulate) o = cw.w_prev * load_out(dst) + cw.w_now * o;
-    store_out(dst, o);
-    if (lse && lane == 0 && slice == 0) lse[hd * L + row] = lse_row;
+    if (accumulate) acc = __builtin_fmaf(lane_value(w_prev, j), load_out(dst), acc);
+    store_out(dst, acc);
   }
 }
 
@@ -2364,7 +2391,7 @@ sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
                      n_tiles, a.scale, acc, shape.seg_len, nsplit, parts);
   profile_mark_end(a.stream);
   if (nsplit > 1)
-    hipLaunchKernelGGL((window_merge_kernel<T, kD>), dim3((unsigned)n_wg, (unsigned)a.H), dim3(kD), 0, a.stream,
+    hipLaunchKernelGGL((window_merge_kernel<T, kD>), dim3((unsigned)n_wg, (unsigned)a.H, 4), dim3(kD), 0, a.stream,
                        static_cast<T*>(a.O), a.lse, parts, a.L, s, n_tiles, acc, shape.seg_len, nsplit);
   return hip_status(hipGetLastError());
 }
@@ -2422,8 +2449,9 @@ sga_status run_tile_implicit(const AttnArgs& a) {
                        (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len, nsplit, parts);
     if (nsplit > 1) {
       profile_mark_end(a.stream);
-      hipLaunchKernelGGL((window_merge_kernel<float, kHeadDim>), grid, dim3(256), 0, a.stream,
-                         static_cast<float*>(a.O), a.lse, parts, a.L, s, n_groups, acc, shape.seg_len, nsplit);
+      hipLaunchKernelGGL((window_merge_kernel<float, kHeadDim>), dim3((unsigned)(n_wg * 4), (unsigned)a.H, 4),
+                         dim3(kHeadDim), 0, a.stream, static_cast<float*>(a.O), a.lse, parts, a.L, s, n_groups,
+                         acc, shape.seg_len, nsplit);
       return hip_status(hipGetLastError());
     }
   }
