@@ -2356,7 +2356,7 @@ void clear_unselected_rows(const AttnArgs& a) {
 int choose_window_split(const AttnArgs& a, int64_t tile_heads, int64_t resident, float** parts) {
   *parts = nullptr;
   const int64_t blocks_per_tile = (2 * (int64_t)a.window + kTile - 1) / kTile + 1;
-  if (!a.ws || tile_heads >= resident || blocks_per_tile < 32) return 1;
+  if (!a.ws || tile_heads >= 4 * resident || blocks_per_tile < 32) return 1;
   const WorkspacePlan pl = plan_workspace(a.L, a.H, -1, a.dtype, a.d);
   if (pl.total_bytes > a.ws_bytes || tile_heads > pl.cap_wparts) return 1;
   int64_t want = 1, best = blocks_per_tile * ((tile_heads + resident - 1) / resident);
