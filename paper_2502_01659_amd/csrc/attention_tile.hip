@@ -26,6 +26,8 @@
 // Tiles with many edges (global-token rows) are cut into segments of their key-block span;
 // each segment is one more work item of the same launches, leaves a partial (m, l, acc)
 // state, and tile_merge_kernel combines the partials in segment order (deterministic).
+// Window masks on short sequences (few tiles, many key blocks each) are cut the same way by a
+// host rule, into ranges of key blocks whose partial states window_merge_kernel combines.
 #include "sga_internal.h"
 
 namespace sga {
