@@ -98,6 +98,9 @@ def test_ragged_and_degenerate_shapes(spec, dtype, path):
     MaskSpec(KIND_SLIDING, 513, window=63),
     MaskSpec(KIND_SLIDING, 513, window=65),      # one key past the workgroup kernel's window
     MaskSpec(KIND_SLIDING, 131, window=16),
+    MaskSpec(KIND_SLIDING, 900, window=32),      # 6 whole blocks per interior workgroup
+    MaskSpec(KIND_SLIDING, 901, window=48),      # 7
+    MaskSpec(KIND_DILATED, 1801, window=40, stride=2),
     MaskSpec(KIND_DILATED, 1931, window=64, stride=3),   # classes of 644, 644 and 643 tokens
     MaskSpec(KIND_DILATED, 769, window=48, stride=2),
 ], ids=lambda s: f"{s.name}-L{s.L}-w{s.window}")
