@@ -97,3 +97,23 @@ def test_workspace_bytes():
     assert sga.sga_workspace_bytes(0, 8, 64, 0, 10)[0] == -1
     st, n_impl = sga.sga_workspace_bytes(160_000_000, 1, 64, 1, -1)
     assert st == 0 and n_impl < (1 << 28)
+
+
+def test_workspace_bytes_grow_with_the_edge_count_and_cover_short_sequences():
+    """The size for an explicit mask never shrinks when the edge count grows (the kernels may
+    choose shorter work items from the real count than the host does from an upper bound), and
+    the implicit entry point's workspace holds the partial states of cut window tiles only for
+    short sequences."""
+    prev = 0
+    for nnz in (0, 1, 1000, 70_000, 700_000, 7_000_000, 70_000_000, 600_000_000):
+        for dtype in (0, 1):
+            st, n = sga.sga_workspace_bytes(24576, 1, 64, dtype, nnz)
+            assert st == 0 and n % 256 == 0
+        st, n = sga.sga_workspace_bytes(24576, 1, 64, 0, nnz)
+        assert n >= prev
+        prev = n
+    small = sga.sga_workspace_bytes(8192, 1, 64, 0, -1)[1]
+    mid = sga.sga_workspace_bytes(24576, 2, 64, 0, -1)[1]
+    large = sga.sga_workspace_bytes(1 << 20, 4, 64, 0, -1)[1]
+    assert small > large and mid > small        # room for 8 partial states per (tile, head) pair
+    assert sga.sga_workspace_bytes(8192, 1, 256, 0, -1)[1] > small
