@@ -27,6 +27,7 @@ constexpr int kWindowSplitTiles = 4096;
 
 // ---- tile path parameters -----------------------------------------------------
 constexpr int kTile = 32;                 // query rows per tile = keys per block
+constexpr int kCutEdges = 16384;          // tiles with fewer edges are never cut into segments
 constexpr int kPairEdges = 128;           // a tile qualifies if it averages >= this many edges per block
 constexpr int kMaxTilePartials = 32768;   // partial states of split tiles per call
 constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32], l[32]
@@ -172,12 +173,14 @@ __device__ __forceinline__ int64_t work_first(const int64_t* __restrict__ row_pt
   return t + (row_ptr[r < L ? r : L] >> sh);
 }
 
-// Segments tile t is cut into: max(1, edges(t) / S).
+// Segments tile t is cut into: max(1, edges(t) / S); a tile below kCutEdges edges (every tile of
+// a window mask up to +-255) stays whole also where a small call has S below that.
 __device__ __forceinline__ int32_t tile_segments(const int64_t* __restrict__ row_ptr, int64_t L,
                                                  int sh, int64_t t) {
   const int64_t r0 = t * kTile, r1 = r0 + kTile < L ? r0 + kTile : L;
-  const int64_t n = (row_ptr[r1] - row_ptr[r0]) >> sh;
-  return n < 1 ? 1 : (int32_t)n;
+  const int64_t e = row_ptr[r1] - row_ptr[r0];
+  const int64_t n = e >> sh;
+  return n < 1 || e < kCutEdges ? 1 : (int32_t)n;
 }
 
 // True when the tile path of this call produces the rows of tile t: its block lists fitted
