@@ -213,8 +213,8 @@ __device__ __forceinline__ void finish_row(T* Orow, float* lse_i, int lane,
   if (lse_i && lane == 0) *lse_i = lse_row;
 }
 
-__host__ __device__ inline void split_shape(int64_t deg, int32_t& nchunks, int32_t& len) {
-  int64_t n = (deg + kSplitChunk - 1) / kSplitChunk;
+__host__ __device__ inline void split_shape(int64_t deg, int chunk, int32_t& nchunks, int32_t& len) {
+  int64_t n = (deg + chunk - 1) / chunk;
   if (n > kMaxSplit) n = kMaxSplit;
   int64_t l = (deg + n - 1) / n;
   l = (l + 31) / 32 * 32;
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __res
     return;
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   int32_t n, len;
-  split_shape(deg, n, len);
+  split_shape(deg, pl.split_chunk, n, len);
   atomicAdd(&ctr[kCtrChunksNeeded], (uint32_t)n);
   const uint32_t base = atomicAdd(&ctr[kCtrItemsAlloc], (uint32_t)n);
   if ((int64_t)base + n > pl.cap_items) return;
@@ -496,7 +496,7 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
     const int64_t i = item.x;
     const int64_t r0 = row_ptr[i], deg = row_ptr[i + 1] - r0;
     int32_t n, len;
-    split_shape(deg, n, len);
+    split_shape(deg, pl.split_chunk, n, len);
     const int64_t e0 = (int64_t)item.y * len;
     const int64_t e1 = min(deg, e0 + len);
     float q[Row<T, D>::VEC];
@@ -632,7 +632,7 @@ static sga_status run_implicit(const AttnArgs& a) {
   if (g > 0) {
     // the g global rows: split over the key range, partial states in the workspace
     int32_t n_chunks, len;
-    split_shape(a.L, n_chunks, len);
+    split_shape(a.L, kSplitChunk, n_chunks, len);
     float* partials = reinterpret_cast<float*>(static_cast<char*>(a.ws) +
                                                plan_workspace(a.L, a.H, -1, a.dtype, D).off_partials);
     hipLaunchKernelGGL((nonlocal_chunk_kernel<T, D>), dim3((unsigned)n_chunks, (unsigned)g, (unsigned)a.H),

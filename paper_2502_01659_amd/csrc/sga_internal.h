@@ -16,6 +16,7 @@ constexpr int kWave = 64;             // CDNA wavefront width
 // ---- split-row parameters (gather path) -----------------------------------
 constexpr int kSplitThreshold = 2048; // rows with more neighbours are split
 constexpr int kSplitChunk = 2048;     // target edges per chunk
+constexpr int kSplitChunkMin = 256;   // ... of a call with little work in total (split_chunk)
 constexpr int kMaxSplit = 64;         // at most this many chunks per row
 constexpr int kMaxImplicitGlobal = 64;  // global rows the implicit non-local kernels can split
 // Implicit window masks on few tiles (a short sequence, one head): a tile's key blocks are cut
@@ -42,6 +43,14 @@ constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32]
 // edges, until it has about 1024 of them: otherwise a small call with a few dense rows would
 // leave its few long items to a handful of wavefronts while the rest of the chip idles.
 // (Microbenchmark grid, one head, a few global tokens at L = 8192: 0.76 -> 0.14 ms.)
+// Edges per chunk of a split row: kSplitChunk, halved down to kSplitChunkMin while the call
+// (nnz * H edges) has fewer than about 1024 such chunks, for the same reason as seg_shift.
+__host__ __device__ inline int split_chunk(int64_t nnz, int32_t H) {
+  int c = kSplitChunk;
+  const int64_t e = (nnz < 0 ? 0 : nnz) * (int64_t)H;
+  while (c > kSplitChunkMin && e / c < 1024) c >>= 1;
+  return c;
+}
 __host__ __device__ inline int seg_shift_min(int32_t dtype) { return dtype == SGA_F32 ? 12 : 15; }
 __host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) {
   int sh = dtype == SGA_F32 ? 15 : 18;
@@ -97,6 +106,7 @@ struct WorkspacePlan {
   int64_t cap_pairs;      // capacity of the (tile, key block) pair arrays
   int64_t cap_tparts;     // capacity of tile partial states
   int seg_shift;          // log2 of S, the edges per work item of the tile path
+  int split_chunk;        // target edges per chunk of a split row
   size_t off_items_rec, off_tile_bad, off_tile_pbase, off_multi_tiles, off_pair_blk, off_pair_mask,
       off_tpartials, off_work_next, off_wparts;
   int64_t cap_wparts;     // (tile, head) pairs whose window partials fit (implicit masks)
@@ -108,17 +118,18 @@ struct WorkspacePlan {
 // Sizes every region for (L, H, nnz, dtype); nnz < 0 means implicit mask (no tile lists).
 // Evaluated identically on the host (sga_workspace_bytes) and inside the kernels
 // (with nnz = row_ptr[L]), so no layout has to be passed around.  (force_shift: the size of a
-// layout with that log2 S instead of the one the arguments select.)
+// layout with that log2 S and the shortest row chunks instead of those the arguments select.)
 __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, int64_t nnz,
                                                         int32_t dtype, int32_t d = kHeadDim,
                                                         int force_shift = -1) {
   WorkspacePlan p{};
   p.seg_shift = force_shift >= 0 ? force_shift : seg_shift(dtype, nnz, H);
+  p.split_chunk = force_shift >= 0 ? kSplitChunkMin : split_chunk(nnz, H);
   size_t off = 256;   // counters
   const int64_t e = nnz < 0 ? 0 : nnz;
   int64_t n_long = e / (kSplitThreshold + 1);
   if (n_long > L) n_long = L;
-  int64_t cap = e / kSplitChunk + n_long;
+  int64_t cap = e / p.split_chunk + n_long;
   if (cap > (int64_t)kMaxSplit * n_long) cap = (int64_t)kMaxSplit * n_long;
   // implicit masks: only the dense rows of the global (non-local) mask are split
   if (nnz < 0) cap = (int64_t)kMaxImplicitGlobal * kMaxSplit;
