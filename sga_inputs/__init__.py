@@ -8,11 +8,12 @@ without sharing any computation.
 """
 from .masks import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
                     KIND_BIGBIRD, KIND_NONLOCAL, KIND_DILATED_2D, KIND_NAMES)
-from .configs import Workload, WORKLOADS, BASE_SEED, small_variants
+from .configs import Workload, WORKLOADS, TABLE3_WORKLOADS, BASE_SEED, small_variants
 from .tensors import (numpy_qkv, torch_qkv, DTYPE_F32, DTYPE_F16)
 
 __all__ = [
     "MaskSpec", "KIND_SLIDING", "KIND_DILATED", "KIND_GLOBAL_LOCAL",
-    "KIND_BIGBIRD", "KIND_NONLOCAL", "KIND_DILATED_2D", "KIND_NAMES", "Workload", "WORKLOADS", "BASE_SEED",
+    "KIND_BIGBIRD", "KIND_NONLOCAL", "KIND_DILATED_2D", "KIND_NAMES", "Workload", "WORKLOADS", "TABLE3_WORKLOADS",
+    "BASE_SEED",
     "small_variants", "numpy_qkv", "torch_qkv", "DTYPE_F32", "DTYPE_F16",
 ]

@@ -60,6 +60,23 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
+def _table3(name, L, s_f):
+    """Local attention of the long-context runs (Table III, Section V-E): fp16, one head, the
+    window sized so that the mask's sparsity factor is s_f (2w + 1 = round(s_f * L) keys per row)."""
+    w = max(0, (int(round(s_f * L)) - 1) // 2)
+    return Workload(name, H=1, L=L, d=64, dtype="f16", sigma=0.5,
+                    mask=MaskSpec(KIND_SLIDING, L, window=w), explicit=False)
+
+
+# The four sequence lengths of Table III with the sparsity factors printed there.
+TABLE3_WORKLOADS: Dict[str, Workload] = {
+    "table3_1p6m": _table3("table3_1p6m", 1_600_000, 0.0017),
+    "table3_8m": _table3("table3_8m", 8_000_000, 0.00034),
+    "table3_16m": _table3("table3_16m", 16_000_000, 0.00017),
+    "table3_160m": _table3("table3_160m", 160_000_000, 0.00001),
+}
+
+
 def small_variants() -> List[Workload]:
     """Reduced-L versions of the five workloads that a dense CPU oracle finishes
     in seconds while still spanning several 32/64-row tiles and a ragged tail."""

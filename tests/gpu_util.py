@@ -40,6 +40,14 @@ def sample_rows(L, seed, n_random, edge=300, tiles=(32, 64, 128, 256), n_tile_id
     return np.unique(np.concatenate(rows)).astype(np.int64)
 
 
+def neighbor_lists(spec, rows):
+    """Neighbour lists of `rows` from the oracle's predicate scan over all L keys of each row
+    (one scan per row, rows spread over the host cores)."""
+    from concurrent.futures import ThreadPoolExecutor
+    with ThreadPoolExecutor(max_workers=max(1, C.num_threads())) as pool:
+        return list(pool.map(lambda i: C.row_neighbors(spec, int(i)), rows))
+
+
 def oracle_rows_gathered(spec, scale, rows, fetch_q, fetch_kv):
     """Row-sampled oracle for problems whose K/V do not fit on the host: neighbour lists by
     scanning the predicate over all keys, K/V rows fetched from the device by index only.

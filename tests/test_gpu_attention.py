@@ -327,6 +327,12 @@ def test_scale_sign_zero_and_non_power_of_two(scale, dtype, path):
             assert max_err(lse.cpu().numpy(), lse_ref) <= 1e-4
 
 
+def _carry_factor(dtype, calls):
+    """Tolerance factor of a state continued over `calls` calls: fp16 storage rounds O to fp16
+    after every call, so the bar scales with the number of calls; fp32 keeps the single-call bar."""
+    return calls if dtype == "f16" else 1.0
+
+
 def _close(O, lse, O_ref, lse_ref, dtype, factor=1.0):
     assert max_err(O, O_ref) <= factor * TOL[dtype]
     empty = np.isneginf(lse_ref)
@@ -398,7 +404,7 @@ def test_dilated_2d_implicit_tiles(block, stride, d, dtype):
         lse_c = np.logaddexp(l1, l2)
         w1 = np.exp(l1 - lse_c)[:, None]
         w2 = np.where(np.isneginf(l2), 0.0, np.exp(l2 - lse_c))[:, None]
-        _close(O[h].cpu().numpy(), lse[h].cpu().numpy(), w1 * O1 + w2 * O2, lse_c, dtype, factor=2.0)
+        _close(O[h].cpu().numpy(), lse[h].cpu().numpy(), w1 * O1 + w2 * O2, lse_c, dtype, factor=_carry_factor(dtype, 2.0))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
@@ -420,7 +426,7 @@ def test_sequential_composition_equals_single_mask(dtype, path):
     O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=ws_i, path=path,
                                             want_lse=True)
     sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O, lse, workspace=ws_i, path=path)
-    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=_carry_factor(dtype, 2.0))
     # explicit local -> explicit non-local
     rp1, ci1 = sga.build_mask(loc)
     rp2, ci2 = sga.build_mask(nl)
@@ -429,12 +435,12 @@ def test_sequential_composition_equals_single_mask(dtype, path):
     O, lse = sga.attention_forward(dQ, dK, dV, rp1, ci1, wl.scale, workspace=ws1, path=path,
                                    want_lse=True)
     sga.attention_accumulate(dQ, dK, dV, rp2, ci2, wl.scale, O, lse, workspace=ws2, path=path)
-    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=_carry_factor(dtype, 2.0))
     # non-local first (rows >= g with no global column in reach start empty), then local
     O, lse = sga.attention_forward(dQ, dK, dV, rp2, ci2, wl.scale, workspace=ws2, path=path,
                                    want_lse=True)
     sga.attention_accumulate_implicit(dQ, dK, dV, loc, wl.scale, O, lse, workspace=ws_i, path=path)
-    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=_carry_factor(dtype, 2.0))
     # three parts: local, non-local, then a random CSR with the first two removed
     rng = np.random.default_rng(5)
     extra = rng.random((L, L)) < 0.002
@@ -450,7 +456,7 @@ def test_sequential_composition_equals_single_mask(dtype, path):
     ws3 = sga.alloc_workspace(L, wl.H, 64, dtype, int(rp3[-1]))
     sga.attention_accumulate(dQ, dK, dV, rp3, ci3, wl.scale, O, lse, workspace=ws3, path=path)
     O3_ref, lse3_ref = R.attention_dense(Q[0], K[0], V[0], covered | extra, wl.scale)
-    _close(O[0].cpu().numpy(), lse[0].cpu().numpy(), O3_ref, lse3_ref, dtype, factor=3.0)
+    _close(O[0].cpu().numpy(), lse[0].cpu().numpy(), O3_ref, lse3_ref, dtype, factor=_carry_factor(dtype, 3.0))
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16"])
@@ -501,7 +507,7 @@ def test_other_head_dimensions(d, dtype):
     O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, want_lse=True)
     sga.attention_accumulate_implicit(dQ, dK, dV, nl, wl.scale, O, lse, workspace=wsi)
     O_ref, lse_ref = R.attention_masked(Q, K, V, MaskSpec(KIND_GLOBAL_LOCAL, L, window=5, n_global=2), wl.scale)
-    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=2.0)
+    _close(O.cpu().numpy(), lse.cpu().numpy(), O_ref, lse_ref, dtype, factor=_carry_factor(dtype, 2.0))
     # the tile kernels work on 64-channel slices
     if d < 64:
         with pytest.raises(sga.SgaError):
@@ -545,12 +551,12 @@ def test_wide_tiles_segments_and_composition(d, dtype):
     O, lse = sga.attention_forward_implicit(dQ, dK, dV, loc, wl.scale, workspace=wsi, path=sga.PATH_TILE,
                                             want_lse=True)
     sga.attention_accumulate(dQ, dK, dV, rp2, ci2, wl.scale, O, lse, workspace=ws2, path=sga.PATH_TILE)
-    close(O, lse, O_ref, lse_ref, factor=2.0)
+    close(O, lse, O_ref, lse_ref, factor=_carry_factor(dtype, 2.0))
     # and in the other order, the window pass continuing the state
     O, lse = sga.attention_forward(dQ, dK, dV, rp2, ci2, wl.scale, workspace=ws2, path=sga.PATH_TILE,
                                    want_lse=True)
     sga.attention_accumulate_implicit(dQ, dK, dV, loc, wl.scale, O, lse, workspace=wsi, path=sga.PATH_TILE)
-    close(O, lse, O_ref, lse_ref, factor=2.0)
+    close(O, lse, O_ref, lse_ref, factor=_carry_factor(dtype, 2.0))
 
 
 @pytest.mark.parametrize("wl", [w for w in small_variants() if w.dtype == "f32"], ids=lambda w: w.name)

@@ -12,9 +12,9 @@ import numpy as np
 import pytest
 
 import paper_2502_01659_amd as sga
-from sga_inputs import WORKLOADS, torch_qkv
+from sga_inputs import WORKLOADS, TABLE3_WORKLOADS, torch_qkv
 from oracle import rowscan as C
-from gpu_util import TOL, max_err, sample_rows
+from gpu_util import TOL, max_err, neighbor_lists, sample_rows
 
 pytestmark = pytest.mark.gpu
 
@@ -37,9 +37,9 @@ def _check_sampled(wl, Q, K, V, O, lse, rows, heads):
     """Row-scan oracle on `rows` of `heads`; K/V rows are fetched from the device by index."""
     import torch
     worst = 0.0
+    lists = neighbor_lists(wl.mask, rows)
     for h in heads:
-        for i in rows:
-            nb = C.row_neighbors(wl.mask, int(i))
+        for i, nb in zip(rows, lists):
             idx = torch.from_numpy(nb).cuda()
             Kg = K[h].index_select(0, idx).float().cpu().numpy()
             Vg = V[h].index_select(0, idx).float().cpu().numpy()
@@ -159,23 +159,40 @@ def test_cfg5_full_size():
     wl = WORKLOADS["cfg5_sliding_160m"]
     Q, K, V = torch_qkv(wl.H, wl.L, wl.d, wl.dtype, wl.sigma, wl.seed, "cuda")
     O, lse = _forward(wl, Q, K, V)
-    rows = sample_rows(wl.L, wl.seed + 4, n_random=150, edge=40, n_tile_idx=4)
+    # every sampled row takes its neighbour list from the oracle's scan of the predicate over
+    # all 160M keys (both sequence ends, rows around tile boundaries, random rows)
+    rows = sample_rows(wl.L, wl.seed + 4, n_random=24, edge=12, n_tile_idx=2)
     print("cfg5 sampled rows", len(rows), flush=True)
-    # sliding window: the row scan is replaced by its closed form (the predicate |i-j| <= w is
-    # evaluated for the 2w+1 candidates only; scanning 160M keys per row adds nothing here)
-    w = wl.mask.window
-    for i in rows:
-        lo, hi = max(0, int(i) - w), min(wl.L - 1, int(i) + w)
-        Kg = K[0, lo:hi + 1].float().cpu().numpy()
-        Vg = V[0, lo:hi + 1].float().cpu().numpy()
-        o_ref, lse_ref = C.attend_gathered(Q[0, int(i)].float().cpu().numpy(), Kg, Vg, wl.scale)
-        assert max_err(O[0, int(i)].float().cpu().numpy(), o_ref) <= TOL["f16"], int(i)
-        assert abs(float(lse[0, int(i)]) - lse_ref) <= 1e-3
-    # a handful of rows with the full 160M-key predicate scan
-    for i in rows[:: max(1, len(rows) // 6)]:
-        nb = C.row_neighbors(wl.mask, int(i))
-        assert nb[0] == max(0, int(i) - w) and nb[-1] == min(wl.L - 1, int(i) + w)
-        assert len(nb) == nb[-1] - nb[0] + 1
+    _check_sampled(wl, Q, K, V, O, lse, rows, heads=[0])
     del O, lse
     torch.cuda.empty_cache()
     _check_moving_average(wl, K, V)
+
+
+def _table3_case(wl, n_random, edge):
+    """A long-context shape of Table III (Section V-E) through sga_attention_forward_implicit:
+    sampled rows against the row-scan oracle, V = ones on every row, Q = 0 (moving average by
+    fp64 prefix sums) on every row."""
+    import torch
+    Q, K, V = torch_qkv(wl.H, wl.L, wl.d, wl.dtype, wl.sigma, wl.seed, "cuda")
+    O, lse = _forward(wl, Q, K, V)
+    rows = sample_rows(wl.L, wl.seed + 4, n_random=n_random, edge=edge, n_tile_idx=2)
+    print(wl.name, "window", wl.mask.window, "sampled rows", len(rows), flush=True)
+    worst = _check_sampled(wl, Q, K, V, O, lse, rows, heads=[0])
+    print(wl.name, "worst sampled error", worst, flush=True)
+    del O, lse
+    torch.cuda.empty_cache()
+    _check_ones(wl, Q, K)
+    del Q
+    torch.cuda.empty_cache()
+    _check_moving_average(wl, K, V)
+
+
+def test_table3_1p6m_wide_band():
+    # +-1359 keys: 87 key blocks per 64-query pair of tiles
+    _table3_case(TABLE3_WORKLOADS["table3_1p6m"], n_random=60, edge=24)
+
+
+def test_table3_160m_wide_band():
+    # +-799 keys at 160M tokens: element offsets pass 2^31 and 2^33
+    _table3_case(TABLE3_WORKLOADS["table3_160m"], n_random=16, edge=8)

@@ -59,6 +59,24 @@ def test_p1_weights_sum_to_one(spec):
     assert (P[~R.dense_mask(spec)] == 0).all()
 
 
+@pytest.mark.parametrize("spec", SPECS, ids=lambda s: s.name)
+def test_weights_match_library_softmax_row_by_row(spec):
+    """attention_weights at value level: each row's weights equal scipy's softmax over that
+    row's neighbours only (entry by entry), and weights @ V equals the output of the definition.
+    A dropped or misplaced scale, a transposed operand or a wrong normaliser fails here."""
+    Q, K, V = _qkv(spec.L, 16, seed=23)
+    scale = 0.37
+    A = R.dense_mask(spec)
+    P = R.attention_weights(Q[0], K[0], A, scale)
+    q, k, v = (x[0].astype(np.float64) for x in (Q, K, V))
+    for i in range(spec.L):
+        nb = np.flatnonzero(A[i])
+        want = scipy.special.softmax(np.array([scale * float(q[i] @ k[j]) for j in nb]))
+        assert np.abs(P[i, nb] - want).max() < 1e-14
+    O, _ = R.attention_dense(Q[0], K[0], V[0], A, scale)
+    assert np.abs(P @ v - O).max() < 1e-13
+
+
 def test_p2_full_mask_is_dense_attention_scipy():
     L, d = 96, 24
     Q, K, V = _qkv(L, d, seed=11)
