@@ -163,8 +163,8 @@ sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, i
  *             high-degree rows and per-tile block lists.  Its contents need not be
  *             preserved between calls; concurrent calls need separate workspaces.
  *   path      sga_path
- * Errors: SGA_ERR_INVALID_ARG (null pointer, L < 1 or >= 2^31, H < 1, unknown
- * dtype/path, misaligned pointers), SGA_ERR_UNSUPPORTED (d not in {32, 64, 128, 256}, or
+ * Errors: SGA_ERR_INVALID_ARG (null pointer, L < 1 or >= 2^31, H < 1 or > 65535 (heads are a
+ * grid dimension), unknown dtype/path, misaligned pointers), SGA_ERR_UNSUPPORTED (d not in {32, 64, 128, 256}, or
  * SGA_PATH_TILE with d != 64),
  * SGA_ERR_WORKSPACE (path = SGA_PATH_TILE without a sufficient workspace).
  */
@@ -224,6 +224,72 @@ sga_status sga_attention_accumulate_implicit(const void* Q, const void* K, const
                                              size_t workspace_bytes, int32_t path);
 
 /*
+ * Prepared graphs: Get_Neighbors of an explicit mask evaluated once for many forward calls.
+ *
+ * The masks of Section II-C are fixed patterns: the same CSR serves every layer and every step,
+ * while sga_attention_forward regroups it into 32 x 32 tiles (and sizes the split of its dense
+ * rows) on every call.  sga_graph_prepare does that regrouping once, leaves the result in the
+ * caller's workspace and describes it in a small host record; the *_prepared calls then launch
+ * only the kernels that this graph needs (for a mask whose tiles all qualify: the fused
+ * attention kernel alone, plus one merge kernel if some tiles are cut into segments).
+ *
+ *   sga_graph_prepare   row_ptr, col_idx, L, H, d, dtype: as in sga_attention_forward (d >= 64).
+ *                       workspace: device, 256-byte aligned, at least sga_workspace_bytes(...)
+ *                       bytes for the true edge count (else SGA_ERR_WORKSPACE).
+ *                       plan_out: host, written.  Unlike every other entry point this call
+ *                       WAITS for the stream (it reads the edge count and the analysis counters
+ *                       back), so it cannot be captured into a HIP graph.
+ *   *_prepared          arguments as in sga_attention_forward / sga_attention_accumulate, plus
+ *                       the plan.  path: SGA_PATH_AUTO, SGA_PATH_TILE or SGA_PATH_TILE_SPLIT.
+ *                       They enqueue kernels only (no wait, no allocation, capturable) and give
+ *                       bit-identical results to the unprepared calls on the same workspace size.
+ * Contract: between sga_graph_prepare and the last *_prepared call that uses its plan, the
+ * workspace must not be written by anyone else (no unprepared call on it, no other graph), and
+ * row_ptr / col_idx must keep their contents; Q, K, V, O, lse, scale and the stream may change
+ * from call to call.  Calls that overlap in time need separate workspaces (and plans).
+ * Errors: SGA_ERR_INVALID_ARG when the plan does not belong to these arguments (other L, H, d,
+ * dtype, row_ptr, col_idx, workspace or size, or a foreign struct), otherwise as the forward.
+ */
+typedef struct {
+  uint32_t struct_bytes;    /* = sizeof(sga_graph_plan)                                      */
+  uint32_t magic;           /* set by sga_graph_prepare                                      */
+  int64_t L, nnz;           /* nnz = row_ptr[L] as read from the device                      */
+  int32_t H, d, dtype;
+  uint32_t tiles_left;      /* tiles whose block lists did not fit (their rows run per row)  */
+  uint32_t multi_tiles;     /* tiles cut into segments (partial states + merge)              */
+  uint32_t tile_parts;      /* partial states those tiles need                               */
+  uint32_t long_rows;       /* rows left to the per-row kernels that are split into chunks   */
+  uint32_t row_chunks;      /* chunk work items of those rows                                */
+  uint32_t flags;           /* SGA_GRAPH_* bits below                                        */
+  const void* row_ptr;      /* the buffers the plan was prepared for (identity check only)   */
+  const void* col_idx;
+  const void* workspace;
+  size_t workspace_bytes;
+} sga_graph_plan;
+
+enum {
+  SGA_GRAPH_TILES_COVER_ALL = 1,   /* every row is produced by the tile kernels               */
+  SGA_GRAPH_TILE_PARTS_FIT = 2,    /* the partial states of the multi-segment tiles fit       */
+  SGA_GRAPH_ROW_CHUNKS_FIT = 4     /* the chunk items of the split rows fit                   */
+};
+
+sga_status sga_graph_prepare(const int64_t* row_ptr, const int32_t* col_idx, int64_t L, int32_t H,
+                             int32_t d, int32_t dtype, void* workspace, size_t workspace_bytes,
+                             void* stream, sga_graph_plan* plan_out);
+sga_status sga_attention_forward_prepared(const void* Q, const void* K, const void* V,
+                                          const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                          int64_t L, int32_t H, int32_t d, float scale, void* stream,
+                                          int32_t dtype, float* lse, void* workspace,
+                                          size_t workspace_bytes, int32_t path,
+                                          const sga_graph_plan* plan);
+sga_status sga_attention_accumulate_prepared(const void* Q, const void* K, const void* V,
+                                             const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                             int64_t L, int32_t H, int32_t d, float scale,
+                                             void* stream, int32_t dtype, float* lse,
+                                             void* workspace, size_t workspace_bytes, int32_t path,
+                                             const sga_graph_plan* plan);
+
+/*
  * Benchmark hook: timing of the dominant attention kernel of each forward call.
  * For callers that measure kernel time on the launch stream (a benchmark computing a
  * roofline); it is the one piece of process-wide state in the library and is not
@@ -231,15 +297,20 @@ sga_status sga_attention_accumulate_implicit(const void* Q, const void* K, const
  * launch of its main attention kernel (the fused SDDMM -> softmax -> SpMM kernel of
  * Algorithm 1; helper kernels such as mask analysis and partial merges are outside the
  * pair) on the call's stream.
- *   sga_profile_enable(on)   on != 0 starts a fresh recording, 0 stops it.
- *   sga_profile_collect      waits for the recorded calls, writes up to `capacity` durations
- *                            in milliseconds (oldest first) to ms_out (host), their count to
- *                            n_out (host), and clears the recording.
- * Errors: SGA_ERR_INVALID_ARG for null outputs or negative capacity, SGA_ERR_HIP if an
- * event cannot be read.
+ *   sga_profile_enable(on)   on != 0 starts a fresh recording, 0 stops it and releases its events.
+ *   sga_profile_collect      waits for the recorded calls, writes the durations of the first
+ *                            `capacity` of them in milliseconds (oldest first) to ms_out (host),
+ *                            the number of calls recorded to n_out (host; a count above
+ *                            `capacity` means the rest were not written), and clears the recording.
+ *   sga_profile_last_kernel  name of the kernel inside the most recently recorded pair ("" if
+ *                            none): a static string.
+ * Errors: SGA_ERR_INVALID_ARG for null outputs or negative capacity, SGA_ERR_HIP if an event
+ * could not be created or read (the recording is then incomplete and should be discarded).
+ * No forward call may run on another thread while the hook is enabled, collected or disabled.
  */
 sga_status sga_profile_enable(int32_t on);
 sga_status sga_profile_collect(float* ms_out, int32_t capacity, int32_t* n_out);
+const char* sga_profile_last_kernel(void);
 
 #ifdef __cplusplus
 }

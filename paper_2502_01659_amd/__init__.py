@@ -11,7 +11,11 @@ from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, PATH_TILE_SPL
                       sga_attention_accumulate, sga_attention_accumulate_implicit,
                       sga_mask_nnz, sga_build_mask, sga_workspace_bytes,
                       sga_attention_forward, sga_attention_forward_implicit,
-                      sga_status_string, sga_profile_enable, sga_profile_collect)
+                      sga_status_string, sga_profile_enable, sga_profile_collect, sga_profile_last_kernel,
+                      GraphPlan, GRAPH_TILES_COVER_ALL, GRAPH_TILE_PARTS_FIT, GRAPH_ROW_CHUNKS_FIT,
+                      graph_prepare, attention_forward_prepared, attention_accumulate_prepared,
+                      sga_graph_prepare, sga_attention_forward_prepared,
+                      sga_attention_accumulate_prepared)
 
 __all__ = [
     "SgaError", "PATH_AUTO", "PATH_GATHER", "PATH_TILE", "PATH_TILE_SPLIT", "load", "lib_path",
@@ -21,5 +25,8 @@ __all__ = [
     "sga_attention_accumulate", "sga_attention_accumulate_implicit",
     "sga_mask_nnz", "sga_build_mask", "sga_workspace_bytes",
     "sga_attention_forward", "sga_attention_forward_implicit", "sga_status_string",
-    "sga_profile_enable", "sga_profile_collect",
+    "sga_profile_enable", "sga_profile_collect", "sga_profile_last_kernel",
+    "GraphPlan", "GRAPH_TILES_COVER_ALL", "GRAPH_TILE_PARTS_FIT", "GRAPH_ROW_CHUNKS_FIT",
+    "graph_prepare", "attention_forward_prepared", "attention_accumulate_prepared",
+    "sga_graph_prepare", "sga_attention_forward_prepared", "sga_attention_accumulate_prepared",
 ]

@@ -34,6 +34,23 @@ class _MaskDesc(ctypes.Structure):
     ]
 
 
+class GraphPlan(ctypes.Structure):
+    """sga_graph_plan: host record of a prepared tile graph (see include/sga.h)."""
+    _fields_ = [
+        ("struct_bytes", ctypes.c_uint32), ("magic", ctypes.c_uint32),
+        ("L", ctypes.c_int64), ("nnz", ctypes.c_int64),
+        ("H", ctypes.c_int32), ("d", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("tiles_left", ctypes.c_uint32), ("multi_tiles", ctypes.c_uint32),
+        ("tile_parts", ctypes.c_uint32), ("long_rows", ctypes.c_uint32),
+        ("row_chunks", ctypes.c_uint32), ("flags", ctypes.c_uint32),
+        ("row_ptr", ctypes.c_void_p), ("col_idx", ctypes.c_void_p),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_size_t),
+    ]
+
+
+GRAPH_TILES_COVER_ALL, GRAPH_TILE_PARTS_FIT, GRAPH_ROW_CHUNKS_FIT = 1, 2, 4
+
+
 def lib_path():
     return _LIB_PATH
 
@@ -67,10 +84,18 @@ def load():
     lib.sga_attention_accumulate.argtypes = lib.sga_attention_forward.argtypes
     lib.sga_attention_accumulate_implicit.restype = ctypes.c_int
     lib.sga_attention_accumulate_implicit.argtypes = lib.sga_attention_forward_implicit.argtypes
+    lib.sga_graph_prepare.restype = ctypes.c_int
+    lib.sga_graph_prepare.argtypes = [vp, vp, i64, i32, i32, i32, vp, ctypes.c_size_t, vp, P(GraphPlan)]
+    lib.sga_attention_forward_prepared.restype = ctypes.c_int
+    lib.sga_attention_forward_prepared.argtypes = lib.sga_attention_forward.argtypes + [P(GraphPlan)]
+    lib.sga_attention_accumulate_prepared.restype = ctypes.c_int
+    lib.sga_attention_accumulate_prepared.argtypes = lib.sga_attention_forward.argtypes + [P(GraphPlan)]
     lib.sga_profile_enable.restype = ctypes.c_int
     lib.sga_profile_enable.argtypes = [i32]
     lib.sga_profile_collect.restype = ctypes.c_int
     lib.sga_profile_collect.argtypes = [P(ctypes.c_float), i32, P(ctypes.c_int32)]
+    lib.sga_profile_last_kernel.restype = ctypes.c_char_p
+    lib.sga_profile_last_kernel.argtypes = []
     _lib = lib
     return lib
 
@@ -134,6 +159,28 @@ def sga_attention_accumulate_implicit(Q, K, V, spec, O, L, H, d, scale, stream, 
                                                     workspace_bytes_, path)
 
 
+def sga_graph_prepare(row_ptr, col_idx, L, H, d, dtype_code, workspace, workspace_bytes_, stream):
+    """-> (status, GraphPlan)"""
+    plan = GraphPlan()
+    st = load().sga_graph_prepare(row_ptr, col_idx, L, H, d, dtype_code, workspace, workspace_bytes_,
+                                  stream, ctypes.byref(plan))
+    return st, plan
+
+
+def sga_attention_forward_prepared(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype_code,
+                                   lse, workspace, workspace_bytes_, path, plan):
+    return load().sga_attention_forward_prepared(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream,
+                                                 dtype_code, lse, workspace, workspace_bytes_, path,
+                                                 ctypes.byref(plan))
+
+
+def sga_attention_accumulate_prepared(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream,
+                                      dtype_code, lse, workspace, workspace_bytes_, path, plan):
+    return load().sga_attention_accumulate_prepared(Q, K, V, row_ptr, col_idx, O, L, H, d, scale,
+                                                    stream, dtype_code, lse, workspace,
+                                                    workspace_bytes_, path, ctypes.byref(plan))
+
+
 def sga_profile_enable(on):
     return load().sga_profile_enable(int(on))
 
@@ -143,7 +190,11 @@ def sga_profile_collect(capacity=4096):
     buf = (ctypes.c_float * capacity)()
     n = ctypes.c_int32(0)
     st = load().sga_profile_collect(buf, capacity, ctypes.byref(n))
-    return st, [buf[i] for i in range(n.value)]
+    return st, [buf[i] for i in range(min(n.value, capacity))]
+
+
+def sga_profile_last_kernel():
+    return load().sga_profile_last_kernel().decode()
 
 
 # ---- tensor-level helpers ---------------------------------------------------------
@@ -211,16 +262,40 @@ def _col_ptr(row_ptr, col_idx):
     return col_idx.data_ptr() if col_idx.numel() > 0 else row_ptr.data_ptr()
 
 
+def _check_csr(Q, row_ptr, col_idx):
+    import torch
+    L = Q.shape[1]
+    if row_ptr.dtype != torch.int64 or row_ptr.numel() != L + 1 or not row_ptr.is_contiguous():
+        raise ValueError("row_ptr must be contiguous int64 [L+1]")
+    if col_idx.dtype != torch.int32 or not col_idx.is_contiguous():
+        raise ValueError("col_idx must be contiguous int32")
+    if row_ptr.device != Q.device or (col_idx.numel() > 0 and col_idx.device != Q.device):
+        raise ValueError("row_ptr and col_idx must be on Q's device")
+
+
+def _check_outputs(Q, O, lse, workspace):
+    """Caller-supplied output and scratch buffers: the kernels write H*L*d elements of O and H*L
+    floats of lse without further checks, so a wrong shape here would be an out-of-bounds write."""
+    import torch
+    H, L, d = Q.shape
+    if O is not None and (O.shape != Q.shape or O.dtype != Q.dtype or not O.is_contiguous()
+                          or O.device != Q.device):
+        raise ValueError("O must match Q in shape, dtype and device, and be contiguous")
+    if lse is not None and (lse.shape != (H, L) or lse.dtype != torch.float32
+                            or not lse.is_contiguous() or lse.device != Q.device):
+        raise ValueError("lse must be contiguous float32 [H, L] on Q's device")
+    if workspace is not None and (workspace.device != Q.device or not workspace.is_contiguous()):
+        raise ValueError("workspace must be a contiguous tensor on Q's device")
+
+
 def attention_forward(Q, K, V, row_ptr, col_idx, scale, O=None, lse=None, workspace=None,
                       path=PATH_AUTO, want_lse=False):
     """Masked attention over an explicit CSR mask.  Returns O (and lse if requested)."""
     import torch
     _check_qkv(Q, K, V)
     H, L, d = Q.shape
-    if row_ptr.dtype != torch.int64 or row_ptr.numel() != L + 1 or not row_ptr.is_contiguous():
-        raise ValueError("row_ptr must be contiguous int64 [L+1]")
-    if col_idx.dtype != torch.int32 or not col_idx.is_contiguous():
-        raise ValueError("col_idx must be contiguous int32")
+    _check_csr(Q, row_ptr, col_idx)
+    _check_outputs(Q, O, lse, workspace)
     if O is None:
         O = torch.empty_like(Q)
     if want_lse and lse is None:
@@ -243,6 +318,7 @@ def attention_forward_implicit(Q, K, V, spec: MaskSpec, scale, O=None, lse=None,
     import torch
     _check_qkv(Q, K, V)
     H, L, d = Q.shape
+    _check_outputs(Q, O, lse, workspace)
     if O is None:
         O = torch.empty_like(Q)
     if want_lse and lse is None:
@@ -276,10 +352,8 @@ def attention_accumulate(Q, K, V, row_ptr, col_idx, scale, O, lse, workspace=Non
     _check_qkv(Q, K, V)
     _check_state(Q, O, lse)
     H, L, d = Q.shape
-    if row_ptr.dtype != torch.int64 or row_ptr.numel() != L + 1 or not row_ptr.is_contiguous():
-        raise ValueError("row_ptr must be contiguous int64 [L+1]")
-    if col_idx.dtype != torch.int32 or not col_idx.is_contiguous():
-        raise ValueError("col_idx must be contiguous int32")
+    _check_csr(Q, row_ptr, col_idx)
+    _check_outputs(Q, None, None, workspace)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(Q.device):
@@ -298,6 +372,7 @@ def attention_accumulate_implicit(Q, K, V, spec: MaskSpec, scale, O, lse, worksp
     _check_qkv(Q, K, V)
     _check_state(Q, O, lse)
     H, L, d = Q.shape
+    _check_outputs(Q, None, None, workspace)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_n = workspace.numel() * workspace.element_size() if workspace is not None else 0
     with torch.cuda.device(Q.device):
@@ -306,4 +381,67 @@ def attention_accumulate_implicit(Q, K, V, spec: MaskSpec, scale, O, lse, worksp
                                                _dtype_code(Q), lse.data_ptr(), ws_ptr, ws_n, path)
     if st != 0:
         raise SgaError(st, "sga_attention_accumulate_implicit")
+    return O, lse
+
+
+def graph_prepare(row_ptr, col_idx, H, d, dtype, workspace):
+    """Prepare the tile graph of an explicit mask once (waits for the stream).  Returns the
+    GraphPlan to pass to attention_forward_prepared / attention_accumulate_prepared together with
+    the same row_ptr, col_idx and workspace."""
+    import torch
+    L = row_ptr.numel() - 1
+    if row_ptr.dtype != torch.int64 or not row_ptr.is_contiguous() or not row_ptr.is_cuda:
+        raise ValueError("row_ptr must be a contiguous int64 device tensor")
+    if col_idx.dtype != torch.int32 or not col_idx.is_contiguous():
+        raise ValueError("col_idx must be contiguous int32")
+    if workspace is None or workspace.device != row_ptr.device or not workspace.is_contiguous():
+        raise ValueError("workspace must be a contiguous tensor on row_ptr's device")
+    code = _DTYPE_CODE[dtype] if isinstance(dtype, str) else dtype
+    with torch.cuda.device(row_ptr.device):
+        st, plan = sga_graph_prepare(row_ptr.data_ptr(), _col_ptr(row_ptr, col_idx), L, H, d, code,
+                                     workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                                     _stream())
+    if st != 0:
+        raise SgaError(st, "sga_graph_prepare")
+    return plan
+
+
+def _prepared_call(fn, name, Q, K, V, row_ptr, col_idx, scale, plan, O, lse, workspace, path):
+    import torch
+    H, L, d = Q.shape
+    with torch.cuda.device(Q.device):
+        st = fn(Q.data_ptr(), K.data_ptr(), V.data_ptr(), row_ptr.data_ptr(), _col_ptr(row_ptr, col_idx),
+                O.data_ptr(), L, H, d, float(scale), _stream(), _dtype_code(Q),
+                lse.data_ptr() if lse is not None else None, workspace.data_ptr(),
+                workspace.numel() * workspace.element_size(), path, plan)
+    if st != 0:
+        raise SgaError(st, name)
+
+
+def attention_forward_prepared(Q, K, V, row_ptr, col_idx, scale, plan, workspace, O=None, lse=None,
+                               path=PATH_AUTO, want_lse=False):
+    """attention_forward on a graph prepared by graph_prepare (same row_ptr, col_idx, workspace)."""
+    import torch
+    _check_qkv(Q, K, V)
+    H, L, d = Q.shape
+    _check_csr(Q, row_ptr, col_idx)
+    _check_outputs(Q, O, lse, workspace)
+    if O is None:
+        O = torch.empty_like(Q)
+    if want_lse and lse is None:
+        lse = torch.empty((H, L), dtype=torch.float32, device=Q.device)
+    _prepared_call(sga_attention_forward_prepared, "sga_attention_forward_prepared", Q, K, V, row_ptr,
+                   col_idx, scale, plan, O, lse, workspace, path)
+    return (O, lse) if (want_lse or lse is not None) else O
+
+
+def attention_accumulate_prepared(Q, K, V, row_ptr, col_idx, scale, plan, workspace, O, lse,
+                                  path=PATH_AUTO):
+    """attention_accumulate on a prepared graph, in place."""
+    _check_qkv(Q, K, V)
+    _check_state(Q, O, lse)
+    _check_csr(Q, row_ptr, col_idx)
+    _check_outputs(Q, None, None, workspace)
+    _prepared_call(sga_attention_accumulate_prepared, "sga_attention_accumulate_prepared", Q, K, V,
+                   row_ptr, col_idx, scale, plan, O, lse, workspace, path)
     return O, lse

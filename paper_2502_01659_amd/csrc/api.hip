@@ -7,14 +7,18 @@ using namespace sga;
 
 namespace {
 
-// Profiling state (benchmark use only; not thread-safe).  Event pairs are created lazily and
-// kept until the process ends.
+// Profiling state (benchmark use only; not thread-safe).  Event pairs are created while a
+// recording runs and destroyed when it is switched off.
 struct ProfileState {
   bool on = false;
+  bool failed = false;          // an event could not be created: reported by sga_profile_collect
   size_t used = 0;
+  const char* kernel = "";      // name of the kernel inside the most recent pair
   std::vector<hipEvent_t> start, stop;
 };
 ProfileState g_prof;
+
+constexpr uint32_t kPlanMagic = 0x53474150u;   // marks a record written by sga_graph_prepare
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -40,24 +44,29 @@ sga_status check_common(const void* Q, const void* K, const void* V, const void*
 
 namespace sga {
 
-void profile_mark_begin(hipStream_t stream) {
-  if (!g_prof.on) return;
+void profile_mark_begin(hipStream_t stream, const char* kernel) {
+  if (!g_prof.on || g_prof.failed) return;
   if (g_prof.used == g_prof.start.size()) {
     hipEvent_t a, b;
     // (no system-scope fence at the records: they only take time stamps on the stream)
-    if (hipEventCreateWithFlags(&a, hipEventDisableSystemFence) != hipSuccess ||
-        hipEventCreateWithFlags(&b, hipEventDisableSystemFence) != hipSuccess) {
-      g_prof.on = false;
+    if (hipEventCreateWithFlags(&a, hipEventDisableSystemFence) != hipSuccess) {
+      g_prof.failed = true;
+      return;
+    }
+    if (hipEventCreateWithFlags(&b, hipEventDisableSystemFence) != hipSuccess) {
+      (void)hipEventDestroy(a);
+      g_prof.failed = true;
       return;
     }
     g_prof.start.push_back(a);
     g_prof.stop.push_back(b);
   }
+  g_prof.kernel = kernel;
   (void)hipEventRecord(g_prof.start[g_prof.used], stream);
 }
 
 void profile_mark_end(hipStream_t stream) {
-  if (!g_prof.on || g_prof.used >= g_prof.stop.size()) return;
+  if (!g_prof.on || g_prof.failed || g_prof.used >= g_prof.stop.size()) return;
   (void)hipEventRecord(g_prof.stop[g_prof.used], stream);
   ++g_prof.used;
 }
@@ -69,22 +78,34 @@ extern "C" {
 sga_status sga_profile_enable(int32_t on) {
   g_prof.on = on != 0;
   g_prof.used = 0;
+  g_prof.failed = false;
+  g_prof.kernel = "";
+  if (!g_prof.on) {             // the recording's events go with it
+    for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+    g_prof.start.clear();
+    g_prof.stop.clear();
+  }
   return SGA_OK;
 }
 
 sga_status sga_profile_collect(float* ms_out, int32_t capacity, int32_t* n_out) {
   if (!n_out || (capacity > 0 && !ms_out) || capacity < 0) return SGA_ERR_INVALID_ARG;
-  int32_t n = 0;
-  for (size_t i = 0; i < g_prof.used && n < capacity; ++i) {
+  *n_out = 0;
+  if (g_prof.failed) return SGA_ERR_HIP;
+  for (size_t i = 0; i < g_prof.used; ++i) {
     if (hipEventSynchronize(g_prof.stop[i]) != hipSuccess) return SGA_ERR_HIP;
+    if ((int64_t)i >= capacity) continue;
     float ms = 0.f;
     if (hipEventElapsedTime(&ms, g_prof.start[i], g_prof.stop[i]) != hipSuccess) return SGA_ERR_HIP;
-    ms_out[n++] = ms;
+    ms_out[i] = ms;
   }
-  *n_out = n;
+  *n_out = (int32_t)g_prof.used;
   g_prof.used = 0;
   return SGA_OK;
 }
+
+const char* sga_profile_last_kernel(void) { return g_prof.kernel; }
 
 const char* sga_status_string(sga_status s) {
   switch (s) {
@@ -138,11 +159,21 @@ namespace {
 sga_status run_explicit_call(const void* Q, const void* K, const void* V, const int64_t* row_ptr,
                              const int32_t* col_idx, void* O, int64_t L, int32_t H, int32_t d,
                              float scale, void* stream, int32_t dtype, float* lse, void* workspace,
-                             size_t workspace_bytes, int32_t path, bool accumulate) {
+                             size_t workspace_bytes, int32_t path, bool accumulate,
+                             const sga_graph_plan* plan = nullptr, bool prepared = false) {
   const sga_status st = check_common(Q, K, V, O, L, H, d, dtype, path, workspace, workspace_bytes);
   if (st != SGA_OK) return st;
   if (!row_ptr || !col_idx) return SGA_ERR_INVALID_ARG;
   if (accumulate && !lse) return SGA_ERR_INVALID_ARG;
+  if (prepared) {
+    // the plan must have been prepared for exactly these buffers and this problem
+    if (!plan || plan->struct_bytes != sizeof(sga_graph_plan) || plan->magic != kPlanMagic)
+      return SGA_ERR_INVALID_ARG;
+    if (plan->L != L || plan->H != H || plan->d != d || plan->dtype != dtype || plan->row_ptr != row_ptr ||
+        plan->col_idx != col_idx || plan->workspace != workspace || plan->workspace_bytes != workspace_bytes)
+      return SGA_ERR_INVALID_ARG;
+    if (path == SGA_PATH_GATHER) return SGA_ERR_INVALID_ARG;
+  }
   AttnArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.O = O; a.lse = lse;
   a.L = L; a.H = H; a.scale = scale; a.dtype = dtype; a.d = d;
@@ -156,6 +187,14 @@ sga_status run_explicit_call(const void* Q, const void* K, const void* V, const 
   // the MFMA tile kernels work on 64-channel slices (d = 64, 128, 256); d = 32 runs on the per-row kernels
   const bool gather_only = path == SGA_PATH_GATHER || d < kHeadDim;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
+  if (prepared) {
+    const bool parts_fit = (plan->flags & SGA_GRAPH_TILE_PARTS_FIT) != 0;
+    a.prepared = true;
+    a.plan_multi_tiles = parts_fit ? plan->multi_tiles : 0;
+    a.plan_tiles_cover_all = (plan->flags & SGA_GRAPH_TILES_COVER_ALL) != 0;
+    a.plan_long_rows = (plan->flags & SGA_GRAPH_ROW_CHUNKS_FIT) ? plan->long_rows : 0;
+    return launch_tile_explicit(a);
+  }
   if (workspace && workspace_bytes >= 256) clear_workspace(a, !gather_only);
   if (gather_only) return launch_gather_explicit(a, true, false);
   return launch_tile_explicit(a);
@@ -243,6 +282,75 @@ sga_status sga_attention_accumulate_implicit(const void* Q, const void* K, const
                                              int32_t path) {
   return run_implicit_call(Q, K, V, desc, O, L, H, d, scale, stream, dtype, lse, workspace,
                            workspace_bytes, path, true);
+}
+
+sga_status sga_graph_prepare(const int64_t* row_ptr, const int32_t* col_idx, int64_t L, int32_t H,
+                             int32_t d, int32_t dtype, void* workspace, size_t workspace_bytes,
+                             void* stream, sga_graph_plan* plan_out) {
+  if (!row_ptr || !col_idx || !plan_out) return SGA_ERR_INVALID_ARG;
+  if (L < 1 || L >= (int64_t(1) << 31) || H < 1 || H > 65535) return SGA_ERR_INVALID_ARG;
+  if (dtype != SGA_F32 && dtype != SGA_F16) return SGA_ERR_INVALID_ARG;
+  if (d != 64 && d != 128 && d != 256) return SGA_ERR_UNSUPPORTED;   // the tile kernels' sizes
+  if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u)) return SGA_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();
+  // the edge count sizes the workspace layout; only the device knows it
+  int64_t nnz = -1;
+  if (hipMemcpyAsync(&nnz, row_ptr + L, sizeof(nnz), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    return SGA_ERR_HIP;
+  if (nnz < 0 || nnz > L * L) return SGA_ERR_INVALID_ARG;
+  const WorkspacePlan pl = plan_workspace(L, H, nnz, dtype, d);
+  if (pl.total_bytes > workspace_bytes) return SGA_ERR_WORKSPACE;
+  AttnArgs a{};
+  a.L = L; a.H = H; a.dtype = dtype; a.d = d; a.stream = st;
+  a.row_ptr = row_ptr; a.col_idx = col_idx;
+  a.ws = workspace; a.ws_bytes = workspace_bytes;
+  clear_workspace(a, true);
+  launch_tile_analyze(a);
+  if (L > kSplitThreshold) launch_split_prepass(a, true);
+  uint32_t ctr[kNumCounters];
+  if (hipGetLastError() != hipSuccess ||
+      hipMemcpyAsync(ctr, workspace, sizeof(ctr), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    return SGA_ERR_HIP;
+  sga_graph_plan p{};
+  p.struct_bytes = sizeof(sga_graph_plan);
+  p.magic = kPlanMagic;
+  p.L = L; p.nnz = nnz; p.H = H; p.d = d; p.dtype = dtype;
+  p.tiles_left = ctr[kCtrTilesBad];
+  p.multi_tiles = ctr[kCtrMultiTiles];
+  p.tile_parts = ctr[kCtrTilePartsNeeded];
+  p.long_rows = ctr[kCtrLongRows];
+  p.row_chunks = ctr[kCtrChunksNeeded];
+  const bool parts_fit = (int64_t)p.tile_parts <= pl.cap_tparts;
+  const bool chunks_fit = (int64_t)p.row_chunks <= pl.cap_items;
+  p.flags = (parts_fit ? SGA_GRAPH_TILE_PARTS_FIT : 0) | (chunks_fit ? SGA_GRAPH_ROW_CHUNKS_FIT : 0) |
+            (p.tiles_left == 0 && parts_fit ? SGA_GRAPH_TILES_COVER_ALL : 0);
+  p.row_ptr = row_ptr; p.col_idx = col_idx;
+  p.workspace = workspace; p.workspace_bytes = workspace_bytes;
+  *plan_out = p;
+  return SGA_OK;
+}
+
+sga_status sga_attention_forward_prepared(const void* Q, const void* K, const void* V,
+                                          const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                          int64_t L, int32_t H, int32_t d, float scale, void* stream,
+                                          int32_t dtype, float* lse, void* workspace,
+                                          size_t workspace_bytes, int32_t path,
+                                          const sga_graph_plan* plan) {
+  return run_explicit_call(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype, lse, workspace,
+                           workspace_bytes, path, false, plan, true);
+}
+
+sga_status sga_attention_accumulate_prepared(const void* Q, const void* K, const void* V,
+                                             const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                             int64_t L, int32_t H, int32_t d, float scale,
+                                             void* stream, int32_t dtype, float* lse,
+                                             void* workspace, size_t workspace_bytes, int32_t path,
+                                             const sga_graph_plan* plan) {
+  return run_explicit_call(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype, lse, workspace,
+                           workspace_bytes, path, true, plan, true);
 }
 
 }  // extern "C"

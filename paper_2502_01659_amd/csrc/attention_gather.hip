@@ -239,9 +239,9 @@ __global__ __launch_bounds__(256) void clear_workspace_kernel(void* ws, size_t w
        t += (int64_t)gridDim.x * blockDim.x)
     bad[t] = 0;
   uint32_t* next = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + pl.off_work_next);
-  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < H;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < 2 * (int64_t)H;
        i += (int64_t)gridDim.x * blockDim.x)
-    next[i] = 0;
+    next[i] = 0;          // claim counters and exit counters of the heads
 }
 
 // One thread per row: rows over the split threshold reserve chunk work items.
@@ -550,22 +550,20 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   const T* V = static_cast<const T*>(a.V);
   T* O = static_cast<T*>(a.O);
   const bool split = allow_split && a.ws && a.ws_bytes >= 256 && a.L > kSplitThreshold;
-  if (split) {
-    hipLaunchKernelGGL(split_prepass_kernel, dim3((unsigned)((a.L + 255) / 256)), dim3(256), 0,
-                       a.stream, a.row_ptr, a.L, a.H, a.dtype, D, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
-  }
+  // (a prepared graph holds the chunk items of its split rows already)
+  if (split && !a.prepared) launch_split_prepass(a, skip_tiled);
   // after the tile path only leftover rows remain: a grid of about one chip-full of wavefronts
   // over all heads strides over the rows (it returns at once when the tiles covered everything)
   int64_t nwg = (a.L + 3) / 4;
   const int64_t leftover_wgs = 2048 / a.H > 256 ? 2048 / a.H : 256;
   if (skip_tiled && nwg > leftover_wgs) nwg = leftover_wgs;
   const dim3 grid((unsigned)nwg, (unsigned)a.H);
-  if (!skip_tiled) profile_mark_begin(a.stream);
+  if (!skip_tiled) profile_mark_begin(a.stream, "gather_csr_kernel");
   hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
                      a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
                      skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
   if (!skip_tiled) profile_mark_end(a.stream);
-  if (split) {
+  if (split && (!a.prepared || a.plan_long_rows > 0)) {
     hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled && a.H >= 8 ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
     hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
@@ -582,6 +580,11 @@ void clear_workspace(const AttnArgs& a, bool tile_flags) {
   if (nwg > 1024) nwg = 1024;
   hipLaunchKernelGGL(clear_workspace_kernel, dim3((unsigned)nwg), dim3(256), 0, a.stream, a.ws,
                      a.ws_bytes, a.row_ptr, a.L, a.H, a.dtype, a.d, tile_flags ? 1 : 0);
+}
+
+void launch_split_prepass(const AttnArgs& a, bool skip_tiled) {
+  hipLaunchKernelGGL(split_prepass_kernel, dim3((unsigned)((a.L + 255) / 256)), dim3(256), 0, a.stream,
+                     a.row_ptr, a.L, a.H, a.dtype, a.d, a.ws, a.ws_bytes, skip_tiled ? 1 : 0);
 }
 
 sga_status launch_gather_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
@@ -612,7 +615,7 @@ static sga_status run_implicit(const AttnArgs& a) {
   const int acc = a.accumulate ? 1 : 0;
   if (a.mask_kind == SGA_MASK_SLIDING || a.mask_kind == SGA_MASK_DILATED) {
     const dim3 grid((unsigned)((a.L + 3) / 4), (unsigned)a.H);
-    profile_mark_begin(a.stream);
+    profile_mark_begin(a.stream, "gather_window_kernel");
     hipLaunchKernelGGL((gather_window_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
                        (int64_t)a.window, (int64_t)a.stride, a.scale, acc);
     profile_mark_end(a.stream);
@@ -623,7 +626,7 @@ static sga_status run_implicit(const AttnArgs& a) {
   const int64_t g = a.mask_kind == SGA_MASK_NONLOCAL ? (a.n_global < a.L ? a.n_global : a.L) : 0;
   if (a.L > g) {
     const dim3 grid((unsigned)((a.L - g + 3) / 4), (unsigned)a.H);
-    profile_mark_begin(a.stream);
+    profile_mark_begin(a.stream, "gather_runs_kernel");
     hipLaunchKernelGGL((gather_runs_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.L,
                        a.mask_kind, (int64_t)a.window, (int64_t)a.stride, g, (int64_t)a.block, g, a.scale,
                        acc);

@@ -1545,6 +1545,18 @@ __device__ __forceinline__ bool tile_parts_fit(const WorkspacePlan& pl, const vo
   return (int64_t) reinterpret_cast<const uint32_t*>(ws)[kCtrTilePartsNeeded] <= pl.cap_tparts;
 }
 
+// A claimant (wavefront or workgroup) of the dynamic schedule found no item left.  The last of
+// the head's `claimants` to arrive puts the head's claim counter and this exit counter back to
+// zero (every other claimant has made its last claim by then), so the next call on the same
+// workspace starts from a clean schedule without a clearing launch of its own.  One lane calls.
+__device__ __forceinline__ void claim_exit(uint32_t* work_next, int32_t H, uint32_t claimants) {
+  uint32_t* done = work_next + H;
+  if (atomicAdd(done, 1u) == claimants - 1) {
+    atomicExch(work_next, 0u);
+    atomicExch(done, 0u);
+  }
+}
+
 constexpr uint32_t kXcdRun = 4;   // consecutive workgroups of the static schedule that share an XCD
 
 // Persistent wavefronts: every wavefront claims the next unprocessed work item of its head from
@@ -1600,7 +1612,10 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
       uint32_t claimed = 0;
       if (lane == 0) claimed = atomicAdd(work_next, 1u);
       w_cur = __builtin_amdgcn_readfirstlane(claimed);
-      if (w_cur >= pl.n_work) break;
+      if (w_cur >= pl.n_work) {
+        if (lane == 0) claim_exit(work_next, H, gridDim.y * 4);
+        break;
+      }
     } else {
       w_cur = w_static;
       w_static += (int64_t)gridDim.y * 4;
@@ -1680,7 +1695,10 @@ __global__ __launch_bounds__(kD) void tile_attend_wide_kernel(
     if (threadIdx.x == 0) claim = atomicAdd(work_next, 1u);
     __syncthreads();
     const int64_t w_cur = __builtin_amdgcn_readfirstlane(claim);
-    if (w_cur >= pl.n_work) break;
+    if (w_cur >= pl.n_work) {
+      if (threadIdx.x == 0) claim_exit(work_next, H, gridDim.y);
+      break;
+    }
     const int4 r0 = reinterpret_cast<const int4*>(items + w_cur)[0];
     const int64_t slot_raw = reinterpret_cast<const int64_t*>(items + w_cur)[2];
     const int32_t t = __builtin_amdgcn_readfirstlane(r0.x);
@@ -2251,12 +2269,7 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   const int64_t n_tiles = (a.L + kTile - 1) / kTile;
   int64_t nwg = (n_tiles + 3) / 4 + 64;
   if (nwg > 16384) nwg = 16384;
-  // (the CSR -> tile pass is a chain of dependent loads per item: one wavefront per tile and a
-  // margin for the extra segments keeps every item's chain in flight at once)
-  int64_t nwg_analyze = n_tiles + 64;
-  if (nwg_analyze > 16384) nwg_analyze = 16384;
-  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg_analyze), dim3(256), 0, a.stream, a.row_ptr,
-                     a.col_idx, a.L, a.H, a.dtype, kHeadDim, a.ws, a.ws_bytes);
+  if (!a.prepared) launch_tile_analyze(a);
   // fp32: resident workgroups only (256 CUs x 2 wavefronts per SIMD, shared by the heads), which
   // claim items dynamically; fp16: one pass of workgroups over the items of each head
   int64_t per_head = (nwg + 8 * kXcdRun - 1) / (8 * kXcdRun) * (8 * kXcdRun);
@@ -2265,7 +2278,7 @@ sga_status run_tile_explicit(const AttnArgs& a) {
     if (per_head < 1) per_head = 1;
     if (per_head > nwg) per_head = nwg;
   }
-  profile_mark_begin(a.stream);
+  profile_mark_begin(a.stream, "tile_attend_kernel");
   // fp32 tiles keep the K fragment in registers; fp16 tiles stage K in LDS (measured best)
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
   constexpr int kPipeAlt = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeSplit;
@@ -2273,8 +2286,10 @@ sga_status run_tile_explicit(const AttnArgs& a) {
   hipLaunchKernelGGL(kernel, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0, a.stream, Q, K, V, O,
                      a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   profile_mark_end(a.stream);
-  hipLaunchKernelGGL((tile_merge_kernel<T, kHeadDim>), dim3(16, (unsigned)a.H, kTile), dim3(256), 0,
-                     a.stream, O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
+  // (a prepared graph knows whether any tile was cut into segments)
+  if (!a.prepared || a.plan_multi_tiles > 0)
+    hipLaunchKernelGGL((tile_merge_kernel<T, kHeadDim>), dim3(16, (unsigned)a.H, kTile), dim3(256), 0,
+                       a.stream, O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   return hip_status(hipGetLastError());
 }
 
@@ -2286,24 +2301,20 @@ sga_status run_tile_explicit_wide_d(const AttnArgs& a) {
   T* O = static_cast<T*>(a.O);
   constexpr int kSlices = kD / kHeadDim;
   const int64_t n_tiles = (a.L + kTile - 1) / kTile;
-  int64_t nwg = (n_tiles + 3) / 4 + 64;
-  if (nwg > 16384) nwg = 16384;
-  int64_t nwg_analyze = n_tiles + 64;
-  if (nwg_analyze > 16384) nwg_analyze = 16384;
-  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg_analyze), dim3(256), 0, a.stream, a.row_ptr,
-                     a.col_idx, a.L, a.H, a.dtype, kD, a.ws, a.ws_bytes);
+  if (!a.prepared) launch_tile_analyze(a);
   // resident workgroups (2 wavefronts per SIMD over the chip), shared by the heads
   int64_t per_head = (2048 / kSlices) / a.H;
   if (per_head < 1) per_head = 1;
   if (per_head > n_tiles + 64) per_head = n_tiles + 64;
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
-  profile_mark_begin(a.stream);
+  profile_mark_begin(a.stream, "tile_attend_wide_kernel");
   hipLaunchKernelGGL((tile_attend_wide_kernel<T, kD, kPipe>), dim3((unsigned)a.H, (unsigned)per_head),
                      dim3(kD), 0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes,
                      a.accumulate ? 1 : 0);
   profile_mark_end(a.stream);
-  hipLaunchKernelGGL((tile_merge_kernel<T, kD>), dim3(16, (unsigned)a.H, kTile), dim3(256), 0, a.stream,
-                     O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
+  if (!a.prepared || a.plan_multi_tiles > 0)
+    hipLaunchKernelGGL((tile_merge_kernel<T, kD>), dim3(16, (unsigned)a.H, kTile), dim3(256), 0, a.stream,
+                       O, a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   return hip_status(hipGetLastError());
 }
 
@@ -2386,7 +2397,7 @@ sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
   float* parts = nullptr;
   const int nsplit = choose_window_split(a, n_wg * a.H, 2048 / kSlices, &parts);
   const int acc = a.accumulate ? 1 : 0;
-  profile_mark_begin(a.stream);
+  profile_mark_begin(a.stream, "tile_window_wide_kernel");
   hipLaunchKernelGGL((tile_window_wide_kernel<T, kD, kPipe>), dim3((unsigned)(n_wg * nsplit), (unsigned)a.H),
                      dim3(kD), 0, a.stream, static_cast<const T*>(a.Q), static_cast<const T*>(a.K),
                      static_cast<const T*>(a.V), static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, s,
@@ -2423,7 +2434,7 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const dim3 grid((unsigned)n_wg, (unsigned)a.H);
   const int acc = a.accumulate ? 1 : 0;
   if (a.dtype == SGA_F32) clear_unselected_rows<float>(a); else clear_unselected_rows<__half>(a);
-  profile_mark_begin(a.stream);
+  profile_mark_begin(a.stream, wg ? "tile_window_wg_kernel" : pair ? "tile_window_pair_kernel" : "tile_window_kernel");
   if (wg) {
     const int nb_max = (int)((4 * kTile - 1 + 2 * (int64_t)a.window) / kTile + 1);
     int64_t Lq = a.L / s, Lr = a.L % s;             // class lengths, see the kernel
@@ -2463,10 +2474,21 @@ sga_status run_tile_implicit(const AttnArgs& a) {
 
 }  // namespace
 
+// The CSR -> tile pass is a chain of dependent loads per item: one wavefront per tile and a
+// margin for the extra segments keeps every item's chain in flight at once.
+void launch_tile_analyze(const AttnArgs& a) {
+  const int64_t n_tiles = (a.L + kTile - 1) / kTile;
+  int64_t nwg_analyze = n_tiles + 64;
+  if (nwg_analyze > 16384) nwg_analyze = 16384;
+  hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg_analyze), dim3(256), 0, a.stream, a.row_ptr,
+                     a.col_idx, a.L, a.H, a.dtype, a.d, a.ws, a.ws_bytes);
+}
+
 sga_status launch_tile_explicit(const AttnArgs& a) {
   if (!a.ws || a.ws_bytes < 256) return launch_gather_explicit(a, false, false);
   sga_status st = a.dtype == SGA_F32 ? run_tile_explicit<float>(a) : run_tile_explicit<__half>(a);
   if (st != SGA_OK) return st;
+  if (a.prepared && a.plan_tiles_cover_all) return SGA_OK;
   // rows of tiles that did not qualify (or everything, if the workspace is too small)
   return launch_gather_explicit(a, true, true);
 }

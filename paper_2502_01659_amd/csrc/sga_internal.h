@@ -73,7 +73,8 @@ __host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) 
 //                     [row_ptr[32t]/128, row_ptr[32(t+1)]/128), split evenly among its segments
 // pair_mask           cap_pairs x 32 x uint32: bit j of word r = edge (row 32t+r, key 32b+j)
 // tpartials           cap_tparts x H x max(1, d / 64) x kTilePartialFloats floats
-// work_next           H x uint32: next unclaimed tile work item of each head (dynamic scheduling)
+// work_next           H x uint32: next unclaimed tile work item of each head (dynamic scheduling),
+//                     then H x uint32: wavefronts (workgroups) of the head that found no item left
 enum WsCounter : int {
   kCtrChunksNeeded = 0,   // sum of chunk counts of all long rows
   kCtrItemsAlloc = 1,     // bump allocator over items
@@ -163,7 +164,7 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   const int64_t slices = d > kHeadDim ? d / kHeadDim : 1;   // a wide tile leaves one record per 64 channels
   off = (off + (size_t)p.cap_tparts * H * slices * kTilePartialFloats * sizeof(float) + 255) & ~size_t(255);
   p.off_work_next = off;
-  off = (off + (tiles ? (size_t)H * 4 : 0) + 255) & ~size_t(255);
+  off = (off + (tiles ? (size_t)H * 8 : 0) + 255) & ~size_t(255);
   // implicit window masks: partial states of cut tiles (short sequences only)
   p.cap_wparts = 0;
   if (nnz < 0 && d >= kHeadDim) {
@@ -243,6 +244,12 @@ struct AttnArgs {
   // workspace
   void* ws;
   size_t ws_bytes;
+  // prepared graph (sga_graph_prepare): the workspace already holds the tile graph and the
+  // chunk items of the split rows, and the host knows what they contain
+  bool prepared;
+  uint32_t plan_multi_tiles;   // multi-segment tiles whose partial states fit (0: no merge launch)
+  bool plan_tiles_cover_all;   // no row is left to the per-row kernels
+  uint32_t plan_long_rows;     // split rows among the leftover rows whose chunk items fit
 };
 
 // gather path (attention_gather.hip)
@@ -255,6 +262,10 @@ sga_status launch_gather_implicit(const AttnArgs& a);
 
 // tile path (attention_tile.hip)
 sga_status launch_tile_explicit(const AttnArgs& a);
+// CSR -> tile graph pass alone (sga_graph_prepare); a.ws holds a full workspace
+void launch_tile_analyze(const AttnArgs& a);
+// reservation of the chunk items of the split rows the tile path leaves over (sga_graph_prepare)
+void launch_split_prepass(const AttnArgs& a, bool skip_tiled);
 sga_status launch_tile_implicit(const AttnArgs& a);
 
 // mask builder (mask_builder.hip)
@@ -265,7 +276,7 @@ sga_status launch_build_mask(const sga_mask_desc& d, int64_t* row_ptr, int32_t* 
 
 // Benchmark hook (api.hip): when enabled, brackets the dominant attention kernel of a forward
 // call with a pair of events on the call's stream.
-void profile_mark_begin(hipStream_t stream);
+void profile_mark_begin(hipStream_t stream, const char* kernel);
 void profile_mark_end(hipStream_t stream);
 
 // Sequential composition on one shared state (Section V-F runs a local, a global and a CSR

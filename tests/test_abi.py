@@ -89,6 +89,29 @@ def test_forward_argument_errors_without_touching_the_gpu():
     assert g(ok, ok, ok, spec, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
 
 
+def test_prepared_graph_argument_errors_without_touching_the_gpu():
+    ok = 0x1000
+    prep = sga.sga_graph_prepare
+    assert prep(None, ok, 64, 1, 64, 0, ok, 4096, None)[0] == -1
+    assert prep(ok, ok, 0, 1, 64, 0, ok, 4096, None)[0] == -1
+    assert prep(ok, ok, 64, 1, 32, 0, ok, 4096, None)[0] == -2      # the per-row kernels need no graph
+    assert prep(ok, ok, 64, 1, 64, 7, ok, 4096, None)[0] == -1
+    assert prep(ok, ok, 64, 1, 64, 0, None, 0, None)[0] == -1
+    assert prep(ok, ok, 64, 1, 64, 0, ok + 16, 4096, None)[0] == -1  # workspace alignment
+    f = sga.sga_attention_forward_prepared
+    plan = sga.GraphPlan()                                           # not written by sga_graph_prepare
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, ok, 4096, 0, plan) == -1
+    # a plan that names other buffers or another problem is refused
+    plan = sga.GraphPlan(struct_bytes=ctypes.sizeof(sga.GraphPlan), magic=0x53474150, L=64, nnz=64, H=1,
+                         d=64, dtype=0, row_ptr=ok, col_idx=ok, workspace=ok, workspace_bytes=4096)
+    assert f(ok, ok, ok, ok, ok, ok, 64, 2, 64, 0.1, None, 0, None, ok, 4096, 0, plan) == -1
+    assert f(ok, ok, ok, ok + 16, ok, ok, 64, 1, 64, 0.1, None, 0, None, ok, 4096, 0, plan) == -1
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, ok, 8192, 0, plan) == -1
+    assert f(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None, ok, 4096, sga.PATH_GATHER, plan) == -1
+    assert sga.sga_attention_accumulate_prepared(ok, ok, ok, ok, ok, ok, 64, 1, 64, 0.1, None, 0, None,
+                                                 ok, 4096, 0, plan) == -1   # lse is required
+
+
 def test_workspace_bytes():
     st, n = sga.sga_workspace_bytes(65536, 8, 64, 0, 18919024)
     assert st == 0 and n % 256 == 0 and n > 0
