@@ -27,25 +27,37 @@ ALU_F32_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GH
 kWarmSeconds = 0.05             # minimum untimed warm-up under load before the timed steps
 FLOPS_PER_EDGE = 256            # 2d (q.k) + 2d (p*v accumulate), d = 64
 
-DEFAULT_WORKLOAD = "cfg2_longformer_64k"
+# The largest single-GPU workload, and the one the >= 60 % HBM target is attached to.
+DEFAULT_WORKLOAD = "cfg5_sliding_160m"
 
-# HBM bytes per forward launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# (see profiles/); None where not measured.
-MEASURED_TRAFFIC_BYTES = {
-    "cfg1_sliding_4k": 5_960_696,
-    "cfg2_longformer_64k": 1_073_989_511,
-    "cfg3_dilated_1m": 2_149_725_262,
-    "cfg4_bigbird_1m": 9_272_662_955,
-    "cfg5_sliding_160m": 81_961_935_671,
-}
+# HBM bytes per forward measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, written by
+# `bench.py --traffic-summary` from the counter files of such runs (never edited by hand).
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+
+
+def measured_traffic(name, prepared=False):
+    """-> (bytes of the dominant kernel per launch, bytes of all kernels of one forward), or
+    (None, None) where no counter run is on file."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f).get(name + ("/prepared" if prepared else ""))
+    except (OSError, ValueError):
+        rec = None
+    if not rec:
+        return None, None
+    return rec.get("dominant_kernel_bytes"), rec.get("forward_bytes")
+
+
+def tensor_bytes(wl):
+    """Q, K, V read once and O written once: 4*d*sizeof per row and head."""
+    return 4 * wl.d * (4 if wl.dtype == "f32" else 2) * wl.L * wl.H
 
 
 def algorithmic_bytes(wl, nnz):
     """Compulsory HBM bytes of one forward: Q, K, V read once and O written once
     (4*d*sizeof per row and head) plus, for explicit masks, col_idx (4 B/edge) and
     row_ptr (8 B/row) read once for all heads."""
-    size = 4 if wl.dtype == "f32" else 2
-    b = 4 * wl.d * size * wl.L * wl.H
+    b = tensor_bytes(wl)
     if wl.explicit:
         b += 4 * nnz + 8 * (wl.L + 1)
     return b
@@ -70,6 +82,18 @@ class Runner:
                                       device=dev)
         self.stream = torch.cuda.current_stream().cuda_stream
         self.dt = 0 if wl.dtype == "f32" else 1
+        self.plan = None            # prepared graph (explicit workloads, see prepare())
+        self.prepared = False       # steps run the prepared forward only
+
+    def prepare(self):
+        """Mask -> CSR -> tile graph once; later steps reuse it (sga_attention_forward_prepared)."""
+        self.build()
+        st, self.plan = self.sga.sga_graph_prepare(self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+                                                   self.wl.L, self.wl.H, self.wl.d, self.dt,
+                                                   self.ws.data_ptr(), self.ws.numel(), self.stream)
+        if st != 0:
+            raise self.sga.SgaError(st, "sga_graph_prepare")
+        self.prepared = True
 
     def build(self):
         st = self.sga.sga_build_mask(self.wl.mask, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
@@ -79,7 +103,13 @@ class Runner:
 
     def forward(self):
         wl, sga = self.wl, self.sga
-        if wl.explicit:
+        if self.prepared:
+            st = sga.sga_attention_forward_prepared(self.Q.data_ptr(), self.K.data_ptr(), self.V.data_ptr(),
+                                                    self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
+                                                    self.O.data_ptr(), wl.L, wl.H, wl.d, wl.scale,
+                                                    self.stream, self.dt, None, self.ws.data_ptr(),
+                                                    self.ws.numel(), self.path, self.plan)
+        elif wl.explicit:
             st = sga.sga_attention_forward(self.Q.data_ptr(), self.K.data_ptr(), self.V.data_ptr(),
                                            self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
                                            self.O.data_ptr(), wl.L, wl.H, wl.d, wl.scale, self.stream,
@@ -93,7 +123,7 @@ class Runner:
             raise sga.SgaError(st, "sga_attention_forward")
 
     def step(self):
-        if self.wl.explicit:
+        if self.wl.explicit and not self.prepared:
             self.build()
         self.forward()
 
@@ -127,11 +157,12 @@ class Runner:
         torch.cuda.synchronize()
         t1 = time.perf_counter()
         st, kern = self.sga.sga_profile_collect(steps)
+        kernel_name_ = self.sga.sga_profile_last_kernel()
         self.sga.sga_profile_enable(0)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
         for k in range(steps):
             ev[k][0].record()
-            if self.wl.explicit:
+            if self.wl.explicit and not self.prepared:
                 self.build()
             ev[k][1].record()
             self.forward()
@@ -141,6 +172,7 @@ class Runner:
         fwd = sum(fwds) / steps
         bld = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
         kern_ms = sum(kern) / len(kern) if st == 0 and kern else fwd
+        self.kernel = kernel_name_ if st == 0 and kern else "forward (no event pair)"
         # fastest single launch (the paper's protocol reports mean and min)
         self.min_forward_ms = min(fwds)
         self.min_kernel_ms = min(kern) if st == 0 and kern else min(fwds)
@@ -152,7 +184,7 @@ class Runner:
         dominant-kernel ms).  Meaningful for the workloads whose tensors fit that cache."""
         torch = self.torch
         scratch = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
-        if self.wl.explicit:
+        if self.wl.explicit and not self.prepared:
             self.build()
         self.sga.sga_profile_enable(1)
         ev = [[torch.cuda.Event(enable_timing=True) for _ in range(2)] for _ in range(launches)]
@@ -169,23 +201,12 @@ class Runner:
         return fwd, (sum(kern) / len(kern) if st == 0 and kern else fwd)
 
 
-def kernel_name(wl, path_used):
-    """Name of the fused attention kernel a forward of this workload launches."""
-    if path_used == "gather":
-        return "gather_csr_kernel" if wl.explicit else "gather_window_kernel"
-    if wl.explicit:
-        return "tile_attend_kernel"
-    if wl.dtype == "f16":     # narrow windows: workgroup-staged K/V; wide: two sub-tiles per wavefront
-        return "tile_window_wg_kernel" if 128 + 2 * wl.mask.window <= 256 else "tile_window_pair_kernel"
-    return "tile_window_kernel"
-
-
-def gather_aware_bytes(wl, nnz):
+def gather_aware_bytes(wl, nnz, prepared=False):
     """Algorithmic bytes plus the K/V rows that no reuse can save: in the BigBird-style mask every
     non-global query block row fetches its random key blocks (K and V) for itself, and the global
     query rows pass over all of K and V once more per head.  Equal to the algorithmic bytes for
     the other masks."""
-    b = algorithmic_bytes(wl, nnz)
+    b = tensor_bytes(wl) if prepared else algorithmic_bytes(wl, nnz)
     m = wl.mask
     if m.name == "bigbird":
         size = 4 if wl.dtype == "f32" else 2
@@ -197,34 +218,43 @@ def gather_aware_bytes(wl, nnz):
     return b
 
 
-def roofline_of(wl, nnz, kern_ms, path_used):
-    """Roofline of the dominant kernel (the fused attention kernel) from its own duration."""
+def roofline_of(wl, nnz, kern_ms, fwd_ms, path_used, kernel, prepared=False):
+    """Roofline of the dominant kernel (the fused attention kernel) from its own duration, and
+    the same at the level of the whole forward call.
+
+    Dominant kernel: `achieved` counts only what that kernel touches -- for fp16 storage the
+    tensor bytes (Q, K, V read once, O written once; the tile kernel of an explicit mask reads
+    the tile graph, not col_idx, so no index bytes are counted for it), for fp32 storage the
+    256 flops per edge.  Forward level (`forward`): the algorithmic bytes of the call (tensor
+    bytes plus, for an unprepared explicit call, 4 B per edge of col_idx and 8 B per row of
+    row_ptr) and the same flops, over the duration of the whole call."""
     edges = nnz * wl.H
-    t = kern_ms * 1e-3
+    t, tf = kern_ms * 1e-3, fwd_ms * 1e-3
     split = path_used == "tile_split"
     path_used = "gather" if path_used == "gather" else "tile"
+    flops = FLOPS_PER_EDGE * edges
+    kbytes = tensor_bytes(wl)
+    fbytes = kbytes if prepared else algorithmic_bytes(wl, nnz)
     if wl.dtype == "f32" and not split:
-        flops = FLOPS_PER_EDGE * edges
-        if path_used == "gather":
-            bound, peak = "alu", ALU_F32_PEAK_TFLOPS
-        else:
-            bound, peak = "mfma", MFMA_F32_PEAK_TFLOPS
-        ach = flops / t / 1e12
-        unit = "TFLOP/s"
+        bound, peak = ("alu", ALU_F32_PEAK_TFLOPS) if path_used == "gather" else ("mfma", MFMA_F32_PEAK_TFLOPS)
+        ach, ach_f, unit = flops / t / 1e12, flops / tf / 1e12, "TFLOP/s"
     else:
         # fp16 storage, and fp32 storage on the split-precision path (three fp16 matrix-core
         # products per product: 0.12 PFLOP at workload 2, 46 us at the fp16 peak, below the
         # 77 us the compulsory bytes take): bound by HBM
         bound, peak, unit = "hbm", HBM_PEAK_GBPS, "GB/s"
-        ach = algorithmic_bytes(wl, nnz) / t / 1e9
+        ach, ach_f = kbytes / t / 1e9, fbytes / tf / 1e9
+    traffic_kernel, traffic_forward = measured_traffic(wl.name, prepared)
     return {"bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(wl.name),
-            "hbm_algorithmic_GBps": algorithmic_bytes(wl, nnz) / t / 1e9,
-            "algorithmic_bytes": algorithmic_bytes(wl, nnz),
-            "gather_aware_bytes": gather_aware_bytes(wl, nnz),
-            "hbm_gather_aware_GBps": gather_aware_bytes(wl, nnz) / t / 1e9,
-            "algorithmic_flops": FLOPS_PER_EDGE * edges,
-            "kernel": kernel_name(wl, path_used), "kernel_ms": kern_ms}
+            "traffic": traffic_kernel,
+            "kernel": kernel, "kernel_ms": kern_ms,
+            "kernel_bytes": kbytes, "kernel_hbm_GBps": kbytes / t / 1e9,
+            "algorithmic_flops": flops,
+            "forward": {"ms": fwd_ms, "achieved": ach_f, "unit": unit, "frac": ach_f / peak,
+                        "algorithmic_bytes": fbytes, "hbm_GBps": fbytes / tf / 1e9,
+                        "hbm_frac": fbytes / tf / 1e9 / HBM_PEAK_GBPS, "traffic": traffic_forward},
+            "gather_aware_bytes": gather_aware_bytes(wl, nnz, prepared),
+            "hbm_gather_aware_GBps": gather_aware_bytes(wl, nnz, prepared) / t / 1e9}
 
 
 def cpu_baseline(wl, runner, budget_s=12.0, target_s=1.5):
@@ -247,19 +277,23 @@ def cpu_baseline(wl, runner, budget_s=12.0, target_s=1.5):
             return time.perf_counter() - t0, edges
     else:
         def run(head, rows):
-            # K/V stay on the device; only the neighbours' rows are fetched
+            # K/V stay on the device; only the neighbours' rows are fetched.  The predicate scans
+            # (one per row, all L keys each) are spread over the host cores, one row per thread.
+            from concurrent.futures import ThreadPoolExecutor
             t0 = time.perf_counter()
+            with ThreadPoolExecutor(max_workers=threads) as pool:
+                lists = list(pool.map(lambda i: rowscan.row_neighbors(spec, int(i)), rows))
             edges = 0
             q = runner.Q[head][torch.from_numpy(rows).cuda()].float().cpu().numpy()
-            for r, i in enumerate(rows):
-                nb = rowscan.row_neighbors(spec, int(i))
+            for r, nb in enumerate(lists):
                 idx = torch.from_numpy(nb).cuda()
                 Kg = runner.K[head][idx].float().cpu().numpy()
                 Vg = runner.V[head][idx].float().cpu().numpy()
                 rowscan.attend_gathered(q[r], Kg, Vg, wl.scale)
                 edges += len(nb)
             return time.perf_counter() - t0, edges
-    probe = np.sort(rng.choice(wl.L, size=min(wl.L, 8 * threads), replace=False)).astype(np.int64)
+    probe = np.sort(rng.choice(wl.L, size=min(wl.L, (8 if wl.L <= (1 << 21) else 1) * threads),
+                               replace=False)).astype(np.int64)
     t_probe, _ = run(0, probe)
     per_row = max(t_probe / len(probe), 1e-7)
     n = int(min(wl.L, max(len(probe), budget_s / per_row)))
@@ -430,8 +464,106 @@ def suite_e2(path, dims=(64, 128, 256)):
     return {"suite": "e2", "unit": "ms per forward, one head, fp32", "rows": rows}
 
 
-def path_name(path, wl):
-    return {0: "auto", 1: "gather", 2: "tile"}[path]
+def fits_cache(wl):
+    """One head's Q, K, V, O fit the 256 MB last-level cache."""
+    return 4 * wl.d * (4 if wl.dtype == "f32" else 2) * wl.L <= (256 << 20)
+
+
+def steady_state(run, steps, warmup, path_name):
+    """Explicit workloads with the mask fixed across steps (the masks of Section II-C are static
+    patterns): CSR built and tile graph prepared once, then sga_attention_forward_prepared per
+    step.  -> forward and kernel times and the roofline figures of that forward."""
+    run.prepare()
+    ms, f, _, km = run.timed(steps, warmup)
+    wl = run.wl
+    p = run.plan
+    return {"step": "sga_attention_forward_prepared (sga_build_mask + sga_graph_prepare once, untimed)",
+            "ms_per_step": ms, "forward_ms": f, "forward_ms_min": run.min_forward_ms, "kernel_ms": km,
+            "forward_edges_per_s": run.nnz * wl.H / (f * 1e-3),
+            "plan": {"tiles_left": p.tiles_left, "multi_tiles": p.multi_tiles, "tile_parts": p.tile_parts,
+                     "long_rows": p.long_rows, "flags": p.flags},
+            "roofline": roofline_of(wl, run.nnz, km, f, path_name, run.kernel, prepared=True)}
+
+
+def _kernel_label(name):
+    """Short label of a kernel in a rocprofv3 csv: sga kernels by name and storage type, the copy
+    kernel of --calibrate-copy as 'copy', others None."""
+    import re
+    m = re.search(r"sga::\(anonymous namespace\)::(\w+)", name) or re.search(r"sga::(\w+)", name)
+    if m:
+        kind = "<half>" if "__half" in name else "<float>" if "<float" in name else ""
+        return m.group(1) + kind
+    if "copyBuffer" in name or "direct_copy" in name:     # the runtime's device-to-device copy kernel
+        return "copy"
+    return None
+
+
+def _counter_per_kernel(csv_path):
+    """-> {label: (dispatches, summed counter value in KiB)} of one rocprofv3 --pmc csv."""
+    import csv
+    out = {}
+    with open(csv_path, newline="") as f:
+        for row in csv.DictReader(f):
+            lab = _kernel_label(row["Kernel_Name"])
+            if lab is None:
+                continue
+            n, v = out.get(lab, (0, 0.0))
+            out[lab] = (n + 1, v + float(row["Counter_Value"]))
+    return out
+
+
+def traffic_summary(dir_, workload, prepared):
+    """Per-kernel HBM bytes of one forward from four rocprofv3 --pmc runs under `dir_`:
+    fetch_<tag>/, write_<tag>/ (bench.py --workload ... on FETCH_SIZE, then WRITE_SIZE) and
+    fetch_copy/, write_copy/ (bench.py --calibrate-copy: a plain 1 GiB device copy), each holding
+    one *_counter_collection.csv.  The copy fixes the scale of either counter (bytes per KiB
+    read).  Prints a table, and records the totals under profiles/hbm_traffic.json."""
+    import glob
+    tag = workload + ("_prepared" if prepared else "")
+
+    def load(sub):
+        files = glob.glob(os.path.join(dir_, sub, "**", "*counter_collection.csv"), recursive=True)
+        if len(files) != 1:
+            raise SystemExit(f"expected one counter csv under {dir_}/{sub}, found {len(files)}")
+        return _counter_per_kernel(files[0])
+
+    cal = {}
+    for which in ("fetch", "write"):
+        n, kib = load(f"{which}_copy")["copy"]
+        cal[which] = (1 << 30) / (kib / n * 1024.0)      # bytes moved per byte the counter shows
+    fetch, write = load(f"fetch_{tag}"), load(f"write_{tag}")
+    attend = [k for k in fetch if k.startswith(("tile_attend", "tile_window", "gather_csr", "gather_window"))]
+    dominant = max(attend, key=lambda k: fetch[k][1] + write.get(k, (0, 0))[1])
+    steps = fetch[dominant][0]
+    rows, total = [], 0.0
+    for k in sorted(fetch, key=lambda k: -(fetch[k][1] + write.get(k, (0, 0))[1])):
+        if k == "copy" or k == "build_mask_kernel":
+            continue
+        rd = fetch[k][1] * 1024.0 * cal["fetch"] / steps
+        wr = write.get(k, (0, 0.0))[1] * 1024.0 * cal["write"] / steps
+        rows.append((k, fetch[k][0] / steps, rd, wr))
+        total += rd + wr
+    dom = next(r for r in rows if r[0] == dominant)
+    print(f"HBM traffic per forward of {tag} (FETCH_SIZE x {cal['fetch']:.3f}, WRITE_SIZE x {cal['write']:.3f}; "
+          f"{steps} forwards)")
+    print(f"{'kernel':44s} {'launches':>8s} {'read MB':>12s} {'written MB':>12s}")
+    for k, n, rd, wr in rows:
+        print(f"{k:44s} {n:8.2f} {rd / 1e6:12.1f} {wr / 1e6:12.1f}")
+    print(f"{'all kernels of one forward':44s} {'':8s} {total / 1e6:12.1f} MB;  dominant kernel {dominant}: "
+          f"{(dom[2] + dom[3]) / 1e6:.1f} MB")
+    try:
+        with open(TRAFFIC_FILE) as f:
+            rec = json.load(f)
+    except (OSError, ValueError):
+        rec = {}
+    rec[workload + ("/prepared" if prepared else "")] = {
+        "dominant_kernel": dominant, "dominant_kernel_bytes": int(dom[2] + dom[3]),
+        "forward_bytes": int(total), "fetch_scale": cal["fetch"], "write_scale": cal["write"],
+        "per_kernel": {k: {"launches": n, "read_bytes": int(rd), "written_bytes": int(wr)}
+                       for k, n, rd, wr in rows}}
+    with open(TRAFFIC_FILE, "w") as f:
+        json.dump(rec, f, indent=1, sort_keys=True)
+        f.write("\n")
 
 
 def main():
@@ -449,6 +581,14 @@ def main():
                          "or of its microbenchmark grid and print one JSON object")
     ap.add_argument("--dims", default="64,128,256",
                     help="head dimensions of --suite e2 (comma-separated)")
+    ap.add_argument("--prepared", action="store_true",
+                    help="explicit workloads: build the mask and prepare its tile graph once, "
+                         "then time sga_attention_forward_prepared alone (the steady state that "
+                         "the default line reports under steady_state)")
+    ap.add_argument("--traffic-summary", default=None, metavar="DIR",
+                    help="no GPU work: read the rocprofv3 --pmc csv files under DIR (see "
+                         "traffic_summary) for --workload [--prepared], print the per-kernel HBM "
+                         "bytes of one forward and record them in profiles/hbm_traffic.json")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run a plain device copy of known size (1 GiB read + 1 GiB written) and "
                          "exit: the reference against which rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -459,6 +599,9 @@ def main():
               "no collectives exist). Re-run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
+    if args.traffic_summary:
+        traffic_summary(args.traffic_summary, args.workload, args.prepared)
+        return
     import torch
     from sga_inputs import WORKLOADS
     if args.calibrate_copy:
@@ -478,8 +621,13 @@ def main():
         return
     wl = WORKLOADS[args.workload]
     run = Runner(wl, path)
+    if args.prepared and wl.explicit:
+        run.prepare()
     ms_step, fwd_ms, bld_ms, kern_ms = run.timed(args.steps, args.warmup)
     edges = run.nnz * wl.H
+    step_name = ("sga_attention_forward_prepared (mask built and graph prepared once, outside the step)"
+                 if run.prepared else "sga_build_mask + sga_attention_forward" if wl.explicit
+                 else "sga_attention_forward_implicit")
     out = {
         "metric": "attention edges/s (q.k pairs)",
         "value": edges / (ms_step * 1e-3),
@@ -491,20 +639,20 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": wl.name, "H": wl.H, "L": wl.L, "d": wl.d,
                    "mask": wl.mask.name, "explicit_csr": wl.explicit, "edges_per_step": edges,
-                   "path": args.path, "seed": wl.seed,
-                   "step": "sga_build_mask + sga_attention_forward" if wl.explicit
-                           else "sga_attention_forward_implicit"},
+                   "path": args.path, "seed": wl.seed, "step": step_name},
         "forward_ms": fwd_ms, "build_mask_ms": bld_ms,
         "forward_ms_min": run.min_forward_ms, "kernel_ms_min": run.min_kernel_ms,
         "ms_per_head": fwd_ms / wl.H,
         "forward_edges_per_s": edges / (fwd_ms * 1e-3),
-        "roofline": roofline_of(wl, run.nnz, kern_ms, args.path),
+        "roofline": roofline_of(wl, run.nnz, kern_ms, fwd_ms, args.path, run.kernel, run.prepared),
     }
-    if not args.no_cold and 4 * wl.d * (4 if wl.dtype == "f32" else 2) * wl.L <= (256 << 20):
+    if not args.no_cold and fits_cache(wl):
         # one head's tensors fit the last-level cache: also report launches that start cold
         cf, ck = run.cold()
         out["cold_cache"] = {"forward_ms": cf, "kernel_ms": ck,
                              "how": "1 GiB scratch buffer overwritten before every launch, 5 launches"}
+    if wl.explicit and not run.prepared:
+        out["steady_state"] = steady_state(run, args.steps, args.warmup, args.path)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(wl, run)
     del run
@@ -524,31 +672,34 @@ def main():
                               "forward_ms_min": r.min_forward_ms, "kernel_ms_min": r.min_kernel_ms,
                               "build_mask_ms": b, "ms_per_head": f / w.H,
                               "forward_edges_per_s": e / (f * 1e-3),
-                              "roofline": roofline_of(w, r.nnz, km, args.path)})
-                if 4 * w.d * (4 if w.dtype == "f32" else 2) * w.L <= (256 << 20):
+                              "roofline": roofline_of(w, r.nnz, km, f, args.path, r.kernel)})
+                if fits_cache(w):
                     cf, ck = r.cold()
                     sweep[-1]["cold_cache"] = {"forward_ms": cf, "kernel_ms": ck}
+                if w.explicit:
+                    sweep[-1]["steady_state"] = steady_state(r, 5, 2, args.path)
                 del r
             except Exception as ex:    # a sweep entry must not lose the headline line
                 sweep.append({"workload": name, "error": repr(ex)})
             torch.cuda.empty_cache()
         out["sweep"] = sweep
-        if wl.dtype == "f32" and args.path == "auto":
-            # the same workload through the opt-in split-precision path (fp32 storage, three
-            # fp16 matrix-core products per product): reported beside the headline, never as it
+        w2 = WORKLOADS["cfg2_longformer_64k"]
+        if args.path == "auto":
+            # workload 2 through the opt-in split-precision path (fp32 storage, three fp16
+            # matrix-core products per product): reported beside the true-fp32 figures, never as them
             try:
-                r = Runner(wl, 3)
+                r = Runner(w2, 3)
                 ms, f, b, km = r.timed(5, 2)
-                out["split_precision"] = {"path": "tile_split", "ms_per_step": ms, "forward_ms": f,
-                                          "build_mask_ms": b, "forward_edges_per_s": edges / (f * 1e-3),
-                                          "roofline": roofline_of(wl, r.nnz, km, "tile_split")}
+                out["split_precision"] = {"workload": w2.name, "path": "tile_split", "ms_per_step": ms,
+                                          "forward_ms": f, "build_mask_ms": b,
+                                          "forward_edges_per_s": r.nnz * w2.H / (f * 1e-3),
+                                          "roofline": roofline_of(w2, r.nnz, km, f, "tile_split", r.kernel)}
                 del r
             except Exception as ex:
                 out["split_precision"] = {"error": repr(ex)}
             torch.cuda.empty_cache()
-        if wl.mask.name == "global_local":
             try:
-                out["composition"] = composition_times(wl, path)
+                out["composition"] = composition_times(w2, path)
             except Exception as ex:
                 out["composition"] = {"error": repr(ex)}
     print(json.dumps(out))
