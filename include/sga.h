@@ -290,6 +290,31 @@ sga_status sga_attention_accumulate_prepared(const void* Q, const void* K, const
                                              const sga_graph_plan* plan);
 
 /*
+ * sga_attention_forward for callers that cannot allocate device memory or size a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It is
+ * sga_attention_forward with the workspace replaced by an array that lives in the library's own
+ * device image (64 MiB per device, held from the first use of the library on that device until the
+ * process ends); the call itself allocates nothing and frees nothing.
+ *   nnz   host value: the edge count of the mask (row_ptr[L]) or an upper bound of it.  The call
+ *         is refused with SGA_ERR_WORKSPACE when sga_workspace_bytes(L, H, d, dtype, nnz) exceeds
+ *         sga_static_scratch_bytes() (a mask with more edges than stated still gives correct
+ *         results, on the slower kernels that need no workspace).
+ *   All other arguments, results and errors are those of sga_attention_forward; results are
+ *   bit-identical to it with a workspace of sga_workspace_bytes(L, H, d, dtype, row_ptr[L]) bytes.
+ * Every call on a device uses that device's one array (the current device's, which must be the
+ * stream's), so calls that overlap in time on one device race: serialise them (one stream).
+ * The array keeps the last call's contents; the call clears what it needs with a kernel.
+ * sga_static_scratch_init resolves the array's address on the current device ahead of time (the
+ * first forward on a device does it otherwise): call it once per device before capturing a graph.
+ */
+sga_status sga_static_scratch_init(void);
+size_t sga_static_scratch_bytes(void);
+sga_status sga_attention_forward_static(const void* Q, const void* K, const void* V,
+                                        const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                        int64_t L, int32_t H, int32_t d, float scale, void* stream,
+                                        int32_t dtype, float* lse, int64_t nnz, int32_t path);
+
+/*
  * Benchmark hook: timing of the dominant attention kernel of each forward call.
  * For callers that measure kernel time on the launch stream (a benchmark computing a
  * roofline); it is the one piece of process-wide state in the library and is not

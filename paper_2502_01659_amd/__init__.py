@@ -15,7 +15,8 @@ from .binding import (SgaError, PATH_AUTO, PATH_GATHER, PATH_TILE, PATH_TILE_SPL
                       GraphPlan, GRAPH_TILES_COVER_ALL, GRAPH_TILE_PARTS_FIT, GRAPH_ROW_CHUNKS_FIT,
                       graph_prepare, attention_forward_prepared, attention_accumulate_prepared,
                       sga_graph_prepare, sga_attention_forward_prepared,
-                      sga_attention_accumulate_prepared)
+                      sga_attention_accumulate_prepared,
+                      sga_static_scratch_init, sga_static_scratch_bytes, sga_attention_forward_static)
 
 __all__ = [
     "SgaError", "PATH_AUTO", "PATH_GATHER", "PATH_TILE", "PATH_TILE_SPLIT", "load", "lib_path",
@@ -29,4 +30,5 @@ __all__ = [
     "GraphPlan", "GRAPH_TILES_COVER_ALL", "GRAPH_TILE_PARTS_FIT", "GRAPH_ROW_CHUNKS_FIT",
     "graph_prepare", "attention_forward_prepared", "attention_accumulate_prepared",
     "sga_graph_prepare", "sga_attention_forward_prepared", "sga_attention_accumulate_prepared",
+    "sga_static_scratch_init", "sga_static_scratch_bytes", "sga_attention_forward_static",
 ]

@@ -94,6 +94,13 @@ def load():
     lib.sga_profile_enable.argtypes = [i32]
     lib.sga_profile_collect.restype = ctypes.c_int
     lib.sga_profile_collect.argtypes = [P(ctypes.c_float), i32, P(ctypes.c_int32)]
+    lib.sga_static_scratch_init.restype = ctypes.c_int
+    lib.sga_static_scratch_init.argtypes = []
+    lib.sga_static_scratch_bytes.restype = ctypes.c_size_t
+    lib.sga_static_scratch_bytes.argtypes = []
+    lib.sga_attention_forward_static.restype = ctypes.c_int
+    lib.sga_attention_forward_static.argtypes = [vp, vp, vp, vp, vp, vp, i64, i32, i32, f32, vp,
+                                                 i32, vp, i64, i32]
     lib.sga_profile_last_kernel.restype = ctypes.c_char_p
     lib.sga_profile_last_kernel.argtypes = []
     _lib = lib
@@ -179,6 +186,20 @@ def sga_attention_accumulate_prepared(Q, K, V, row_ptr, col_idx, O, L, H, d, sca
     return load().sga_attention_accumulate_prepared(Q, K, V, row_ptr, col_idx, O, L, H, d, scale,
                                                     stream, dtype_code, lse, workspace,
                                                     workspace_bytes_, path, ctypes.byref(plan))
+
+
+def sga_static_scratch_init():
+    return load().sga_static_scratch_init()
+
+
+def sga_static_scratch_bytes():
+    return int(load().sga_static_scratch_bytes())
+
+
+def sga_attention_forward_static(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype_code,
+                                 lse, nnz, path):
+    return load().sga_attention_forward_static(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream,
+                                               dtype_code, lse, nnz, path)
 
 
 def sga_profile_enable(on):

@@ -1,6 +1,7 @@
 // C ABI of libsga.so: argument validation and dispatch.  See include/sga.h for the contract.
 #include "sga_internal.h"
 
+#include <atomic>
 #include <vector>
 
 using namespace sga;
@@ -17,6 +18,32 @@ struct ProfileState {
   std::vector<hipEvent_t> start, stop;
 };
 ProfileState g_prof;
+
+// ---- scratch of the entry point that allocates nothing ------------------------------------------
+// One array per device, in the library's own device image: it exists from the moment the image is
+// loaded on a device until the process ends.  In host code `scratch` is only a handle for
+// hipGetSymbolAddress; the address a kernel can use is resolved once per device and kept here.
+constexpr size_t kScratchBytes = size_t(64) << 20;
+__device__ __align__(256) static unsigned char scratch[kScratchBytes];
+constexpr int kMaxDevices = 64;
+std::atomic<void*> g_scratch_ptr[kMaxDevices];
+
+// Device address of `scratch` on the current device (resolved on the first call per device).
+sga_status scratch_of_current_device(void** out) {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) return SGA_ERR_HIP;
+  if (dev < 0 || dev >= kMaxDevices) return SGA_ERR_UNSUPPORTED;
+  void* p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+      (void)hipGetLastError();
+      return SGA_ERR_HIP;
+    }
+    g_scratch_ptr[dev].store(p, std::memory_order_release);
+  }
+  *out = p;
+  return SGA_OK;
+}
 
 constexpr uint32_t kPlanMagic = 0x53474150u;   // marks a record written by sga_graph_prepare
 
@@ -351,6 +378,30 @@ sga_status sga_attention_accumulate_prepared(const void* Q, const void* K, const
                                              const sga_graph_plan* plan) {
   return run_explicit_call(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype, lse, workspace,
                            workspace_bytes, path, true, plan, true);
+}
+
+sga_status sga_static_scratch_init(void) {
+  void* p = nullptr;
+  return scratch_of_current_device(&p);
+}
+
+size_t sga_static_scratch_bytes(void) { return kScratchBytes; }
+
+sga_status sga_attention_forward_static(const void* Q, const void* K, const void* V,
+                                        const int64_t* row_ptr, const int32_t* col_idx, void* O,
+                                        int64_t L, int32_t H, int32_t d, float scale, void* stream,
+                                        int32_t dtype, float* lse, int64_t nnz, int32_t path) {
+  // the library's own scratch array takes the place of the caller's workspace
+  size_t need = 0;
+  const sga_status sized = sga_workspace_bytes(L, H, d, dtype, nnz, &need);
+  if (sized != SGA_OK) return sized;
+  if (nnz < 0) return SGA_ERR_INVALID_ARG;
+  if (need > kScratchBytes) return SGA_ERR_WORKSPACE;      // beyond the stated maximum
+  void* ws = nullptr;
+  const sga_status found = scratch_of_current_device(&ws);
+  if (found != SGA_OK) return found;
+  return run_explicit_call(Q, K, V, row_ptr, col_idx, O, L, H, d, scale, stream, dtype, lse, ws,
+                           kScratchBytes, path, false);
 }
 
 }  // extern "C"
