@@ -603,7 +603,7 @@ def main():
         traffic_summary(args.traffic_summary, args.workload, args.prepared)
         return
     import torch
-    from sga_inputs import WORKLOADS
+    from sga_inputs import WORKLOADS, TABLE3_WORKLOADS
     if args.calibrate_copy:
         n = 1 << 30
         src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -619,7 +619,8 @@ def main():
         print(json.dumps(suite_table3(path) if args.suite == "table3"
                          else suite_e2(path, tuple(int(x) for x in args.dims.split(",")))))
         return
-    wl = WORKLOADS[args.workload]
+    # (the long-context shapes of Table III can be named too, e.g. for a profile of one of them)
+    wl = WORKLOADS.get(args.workload) or TABLE3_WORKLOADS[args.workload]
     run = Runner(wl, path)
     if args.prepared and wl.explicit:
         run.prepare()

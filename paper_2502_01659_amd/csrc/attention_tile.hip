@@ -30,6 +30,8 @@
 // host rule, into ranges of key blocks whose partial states window_merge_kernel combines.
 #include "sga_internal.h"
 
+#include <type_traits>
+
 namespace sga {
 namespace {
 
@@ -170,6 +172,29 @@ struct WindowBlocks {
   __device__ int64_t key_stride() const { return s; }
   __device__ static int clamp64(int64_t v) { return v < -64 ? -64 : (v > 64 ? 64 : (int)v); }
   __device__ void resolve(BlockInfo&) const {}
+  // Where block k lies (wave-uniform; no mask word): what the staging needs.
+  __device__ BlockInfo place(int k) const {
+    BlockInfo b;
+    b.raw = 0;
+    const int64_t v0 = vfirst + (int64_t)k * kTile;
+    b.row0 = s * v0 + p;
+    const int64_t left = Lc - v0;
+    b.nvalid = left < kTile ? (int)left : kTile;
+    b.word = 0;
+    b.full = 0;
+    return b;
+  }
+  // Block k against the tile's queries, from wave-uniform quantities alone: 0 = no query of the
+  // tile sees a key of the block, 2 = every query sees every key, 1 = anything else (get() then
+  // gives the lanes' mask words).  Interior blocks of a wide window are all 2 and cost no
+  // per-lane arithmetic.
+  __device__ int classify(int k) const {
+    const int64_t v0 = vfirst + (int64_t)k * kTile;
+    const int64_t left = Lc - v0, nq = Lc - u0;
+    const int64_t dlo = u0 - W - v0, dhi = u0 + W - v0;
+    if (left <= 0 || nq <= 0 || dhi + (kTile - 1) < 0 || dlo > kTile - 1) return 0;
+    return left >= kTile && nq >= kTile && dlo + (kTile - 1) <= 0 && dhi >= kTile - 1 ? 2 : 1;
+  }
   __device__ BlockInfo get(int k, int n) const {
     BlockInfo b;
     b.raw = 0;
@@ -290,6 +315,74 @@ __device__ __forceinline__ void softmax_block(floatx16 sv, float c, const BlockI
     lsum += p[r];
   }
   st.l += lsum;
+}
+
+typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+typedef float float2v __attribute__((ext_vector_type(2)));
+
+// softmax_block for fp16 storage, in three steps that callers with two independent sub-tiles
+// interleave.  The numerators leave as the B operand of the PV products: rounded to fp16 two at a
+// time (one packed conversion per pair, to nearest even), ph[u][e] = p of accumulator register
+// 8u + e.  The running sum adds the *rounded* numerators (a dot product of each pair with (1, 1),
+// accumulated in fp32), i.e. exactly the weights the products apply, so that acc / l is a true
+// weighted mean of V rows.
+//
+// Entries outside the mask become -inf (word: mask bits of this lane's query).
+__device__ __forceinline__ void mask_scores(floatx16& sv, uint32_t word, int h) {
+  const uint32_t wh = word >> (4 * h);
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    // all-ones where the edge exists, else zero; then select the product or -inf bitwise
+    const int keep = ((int)(wh << (31 - acc_row(r, 0)))) >> 31;
+    const float x = sv[r];   // (a bit cast applied to the vector element itself reads element 0)
+    const int bits = (__builtin_bit_cast(int, x) & keep) | ((int)0xff800000 & ~keep);
+    sv[r] = __builtin_bit_cast(float, bits);
+  }
+}
+// Largest scaled score of this lane's query in the block (both half-waves agree).
+__device__ __forceinline__ float block_max(const floatx16& sv, float c, int h) {
+  float bm = fmaxf(sv[0], sv[1]);
+#pragma unroll
+  for (int r = 2; r < 16; r += 2) bm = __builtin_fmaxf(__builtin_fmaxf(bm, sv[r]), sv[r + 1]);
+  return fmaxf(bm, other_half(bm, h)) * c;
+}
+__device__ __forceinline__ bool needs_rescale(const TileState& st, float bm) {
+  return bm > st.m + kRescaleSlack;
+}
+// Raises m to bm where bm exceeds it by more than the slack, and rescales l and O (a factor of
+// exactly 1 elsewhere).
+__device__ __forceinline__ void rescale_state(TileState& st, float bm) {
+  const float m_new = needs_rescale(st, bm) ? bm : st.m;
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_new);
+  st.m = m_new;
+  st.l *= alpha;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) {
+    st.o[0][r] *= alpha;
+    st.o[1][r] *= alpha;
+  }
+}
+__device__ __forceinline__ void numerators_h(const floatx16& sv, float c, TileState& st, half8 (&ph)[2]) {
+  const float neg_m = -st.m;
+  const half2v ones = {(_Float16)1.0f, (_Float16)1.0f};
+  float l = st.l;
+#pragma unroll
+  for (int r = 0; r < 16; r += 2) {
+    const float2v p2 = {__builtin_amdgcn_exp2f(__builtin_fmaf(sv[r], c, neg_m)),
+                        __builtin_amdgcn_exp2f(__builtin_fmaf(sv[r + 1], c, neg_m))};
+    const half2v hp = __builtin_convertvector(p2, half2v);
+    l = __builtin_amdgcn_fdot2(hp, ones, l, false);
+    ph[r / 8][r % 8] = hp[0];
+    ph[r / 8][r % 8 + 1] = hp[1];
+  }
+  st.l = l;
+}
+__device__ __forceinline__ void softmax_block_h(floatx16 sv, float c, bool full, uint32_t word, int h,
+                                                TileState& st, half8 (&ph)[2]) {
+  if (!full) mask_scores(sv, word, h);
+  const float bm = block_max(sv, c, h);
+  if (__any(needs_rescale(st, bm))) rescale_state(st, bm);
+  numerators_h(sv, c, st, ph);
 }
 
 // Source addresses of the global -> LDS block copies.  A block's rows are row0 + j*stride
@@ -731,44 +824,48 @@ struct CoreF16T {
   // negative: it is known to be complete)
   __device__ void block_math(const half8 (&kf)[4], const BlockInfo& b, float c, int lane, int h,
                              TileState& st, const char* ldsv, int v_keep) {
-    float p[16];
-    scores(kf, b, c, lane, h, st, p);
+    half8 ph[2];
+    scores(kf, b, c, lane, h, st, ph);
     wait_loads_keep(v_keep);
     __builtin_amdgcn_wave_barrier();
-    accumulate(p, lane, h, st, ldsv);
+    accumulate(ph, lane, h, st, ldsv);
   }
 
-  // First half of the block step: S^T = K_blk Q^T and the softmax update; p = numerators.
+  // First half of the block step: S^T = K_blk Q^T and the softmax update; ph = numerators as the
+  // B operand of the PV products.
   __device__ void scores(const half8 (&kf)[4], const BlockInfo& b, float c, int lane, int h,
-                         TileState& st, float (&p)[16]) {
+                         TileState& st, half8 (&ph)[2]) {
     floatx16 sacc = {0};
 #pragma unroll
     for (int s = 0; s < 4; ++s)
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[s], qf[s], sacc, 0, 0, 0);
     if (kD > kHeadDim) xchg.sum_slices(sacc, lane);
-    softmax_block(sacc, c, b, h, st, p);
+    softmax_block_h(sacc, c, b.full != 0, b.word, h, st, ph);
+  }
+
+  // This lane's address of the V^T operand reads for key0 = 4h, channel group 0; the other reads
+  // are constant offsets from it.
+  __device__ static const char* vt_base(const char* ldsv, int lane, int h) {
+    const int i = lane & 15, grp16 = (lane >> 4) & 1;
+    return ldsv + (4 * h + (i >> 2)) * (kHeadDim * 2) + (grp16 * 16 + 4 * (i & 3)) * 2;
+  }
+
+  // A operand of one PV product: V^T[channel cb*32+n][slot (u,h,e)], slot key = 16u + 8(e/4) + 4h + e%4
+  __device__ static half8 read_va(const char* vt, int u, int cb) {
+    const half4 lo = read_vt(vt + (16 * u) * (kHeadDim * 2) + cb * 64);
+    const half4 hi = read_vt(vt + (16 * u + 8) * (kHeadDim * 2) + cb * 64);
+    return half8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
   }
 
   // Second half: O^T += V_blk^T P^T with the V block staged (complete) at ldsv.
-  __device__ static void accumulate(const float (&p)[16], int lane, int h, TileState& st,
+  __device__ static void accumulate(const half8 (&ph)[2], int lane, int h, TileState& st,
                                     const char* ldsv) {
-    // this lane's address for key0 = 4h, channel group 0; the other reads are constant offsets
-    const int i = lane & 15, grp16 = (lane >> 4) & 1;
-    const char* vt = ldsv + (4 * h + (i >> 2)) * (kHeadDim * 2) + (grp16 * 16 + 4 * (i & 3)) * 2;
+    const char* vt = vt_base(ldsv, lane, h);
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      half8 pb;
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
-      for (int e = 0; e < 8; ++e) pb[e] = (_Float16)p[8 * u + e];
-#pragma unroll
-      for (int cb = 0; cb < 2; ++cb) {
-        // A operand: V^T[channel cb*32+n][slot (u,h,e)], slot key = 16u + 8(e/4) + 4h + e%4
-        const half4 lo = read_vt(vt + (16 * u) * (kHeadDim * 2) + cb * 64);
-        const half4 hi = read_vt(vt + (16 * u + 8) * (kHeadDim * 2) + cb * 64);
-        const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-        st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pb, st.o[cb], 0, 0, 0);
-      }
-    }
+      for (int cb = 0; cb < 2; ++cb)
+        st.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(read_va(vt, u, cb), ph[u], st.o[cb], 0, 0, 0);
   }
 
   // Same pipeline as CoreF32::run_ldsk.
@@ -810,74 +907,108 @@ struct CoreF16T {
   // Two neighbouring 32-query sub-tiles in one wavefront (this->qf holds the first, qb the
   // second): every staged K and V block, the K fragment read and the V^T operand reads serve
   // both, and the two chains of products are independent of each other.  The block lists of
-  // the two sub-tiles (sa, sb) must start at the same key; a block outside a sub-tile's window
-  // (mask words all zero) is skipped for that sub-tile.  Pipeline as in run_ldsk.
-  template <typename Src>
+  // the two sub-tiles (sa, sb) must start at the same key.  Every block is classified per
+  // sub-tile from wave-uniform quantities (WindowBlocks::classify): a block outside a sub-tile's
+  // window is skipped for it, an interior block runs without mask words, and only the few
+  // blocks on the window's edges pay for the per-lane mask arithmetic.  Pipeline as in run_ldsk.
   __device__ void run_pair(const half8 (&qb)[4], const __half* __restrict__ Kh,
-                           const __half* __restrict__ Vh, const Src& sa, const Src& sb, int k1, float c,
-                           int lane, TileState& sta, TileState& stb, char* lds) {
+                           const __half* __restrict__ Vh, const WindowBlocks& sa, const WindowBlocks& sb,
+                           int k1, float c, int lane, TileState& sta, TileState& stb, char* lds) {
     if (k1 <= 0) return;
     const int n = lane & 31, h = lane >> 5;
     Stage sm;
     sm.init(sa.key_stride(), lane);
     char* ldsk = lds;
     char* ldsv = lds + kBlockBytes;
-    BlockInfo ba = sa.get(0, n), bb = sb.get(0, n);
+    BlockInfo cur = sa.place(0);
     __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
-    sm.stage_k(Kh, ba, lane, ldsk);
-    const int i16 = lane & 15, grp16 = (lane >> 4) & 1;
-    const char* vt = ldsv + (4 * h + (i16 >> 2)) * (kHeadDim * 2) + (grp16 * 16 + 4 * (i16 & 3)) * 2;
-    for (int k = 0; k < k1; ++k) {
+    sm.stage_k(Kh, cur, lane, ldsk);
+    const char* vt = vt_base(ldsv, lane, h);
+    // One block step; kInterior: the block is interior to both sub-tiles.  The pipeline state
+    // (cur, the staged K block) passes from step to step whatever their kind.
+    auto step = [&](int k, auto interior) {
+      constexpr bool kInterior = decltype(interior)::value;
       const bool more = k + 1 < k1;      // wave-uniform
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
-      sm.stage_v(Vh, ba, lane, ldsv);
-      const BlockInfo na = sa.get(more ? k + 1 : k, n), nb = sb.get(more ? k + 1 : k, n);
+      sm.stage_v(Vh, cur, lane, ldsv);
+      const BlockInfo nxt = sa.place(more ? k + 1 : k);
       wait_loads_except<4>();            // K block k is older than the 4 V copies just issued
       __builtin_amdgcn_wave_barrier();
       half8 kf[4];
       read_k(ldsk, n, h, kf);
       wait_lds_reads();                  // the K buffer may be overwritten now
       __builtin_amdgcn_wave_barrier();
-      if (more) sm.stage_k(Kh, na, lane, ldsk);
-      const bool act_a = __builtin_amdgcn_ballot_w64(ba.word != 0) != 0;
-      const bool act_b = __builtin_amdgcn_ballot_w64(bb.word != 0) != 0;
-      floatx16 sacc_a = {0}, sacc_b = {0};
-      if (act_a) {
+      if (more) sm.stage_k(Kh, nxt, lane, ldsk);
+      half8 pha[2], phb[2];
+      if constexpr (kInterior) {
+        // One stretch of straight-line code: the products of one sub-tile run on the matrix cores
+        // while the vector unit works on the other's softmax, and the V^T operand reads are all
+        // in flight before the first PV product.
+        floatx16 s_a = {0}, s_b = {0};
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          sacc_a = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qf[t], sacc_a, 0, 0, 0);
-      }
-      if (act_b) {
+        for (int t = 0; t < 4; ++t) s_a = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qf[t], s_a, 0, 0, 0);
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-          sacc_b = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qb[t], sacc_b, 0, 0, 0);
-      }
-      float pa[16], pb[16];
-      if (act_a) softmax_block(sacc_a, c, ba, h, sta, pa);
-      if (act_b) softmax_block(sacc_b, c, bb, h, stb, pb);
-      // V block k is older than the 4 K copies issued above (if any)
-      if (more) wait_loads_except<4>(); else wait_loads_except<0>();
-      __builtin_amdgcn_wave_barrier();
-#pragma unroll
-      for (int u = 0; u < 2; ++u) {
-        half8 pha, phb;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          pha[e] = act_a ? (_Float16)pa[8 * u + e] : (_Float16)0;
-          phb[e] = act_b ? (_Float16)pb[8 * u + e] : (_Float16)0;
+        for (int t = 0; t < 4; ++t) s_b = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qb[t], s_b, 0, 0, 0);
+        const float bm_a = block_max(s_a, c, h), bm_b = block_max(s_b, c, h);
+        if (__any(needs_rescale(sta, bm_a) || needs_rescale(stb, bm_b))) {
+          rescale_state(sta, bm_a);
+          rescale_state(stb, bm_b);
         }
+        numerators_h(s_a, c, sta, pha);
+        numerators_h(s_b, c, stb, phb);
+        // V block k is older than the 4 K copies issued above (if any)
+        if (more) wait_loads_except<4>(); else wait_loads_except<0>();
+        __builtin_amdgcn_wave_barrier();
+        half8 va[2][2];
 #pragma unroll
-        for (int cb = 0; cb < 2; ++cb) {
-          const half4 lo = read_vt(vt + (16 * u) * (kHeadDim * 2) + cb * 64);
-          const half4 hi = read_vt(vt + (16 * u + 8) * (kHeadDim * 2) + cb * 64);
-          const half8 va = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          if (act_a) sta.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pha, sta.o[cb], 0, 0, 0);
-          if (act_b) stb.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, phb, stb.o[cb], 0, 0, 0);
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) va[u][cb] = read_va(vt, u, cb);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) {
+            sta.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[u][cb], pha[u], sta.o[cb], 0, 0, 0);
+            stb.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[u][cb], phb[u], stb.o[cb], 0, 0, 0);
+          }
+      } else {
+        const int class_a = sa.classify(k), class_b = sb.classify(k);     // wave-uniform
+        if (class_a) {
+          floatx16 sacc = {0};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qf[t], sacc, 0, 0, 0);
+          const uint32_t word = class_a == 2 ? ~0u : sa.get(k, n).word;
+          softmax_block_h(sacc, c, class_a == 2, word, h, sta, pha);
         }
+        if (class_b) {
+          floatx16 sacc = {0};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qb[t], sacc, 0, 0, 0);
+          const uint32_t word = class_b == 2 ? ~0u : sb.get(k, n).word;
+          softmax_block_h(sacc, c, class_b == 2, word, h, stb, phb);
+        }
+        if (more) wait_loads_except<4>(); else wait_loads_except<0>();
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) {
+            const half8 va = read_va(vt, u, cb);
+            if (class_a) sta.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pha[u], sta.o[cb], 0, 0, 0);
+            if (class_b) stb.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, phb[u], stb.o[cb], 0, 0, 0);
+          }
       }
-      ba = na;
-      bb = nb;
-    }
+      cur = nxt;
+    };
+    // The blocks interior to both sub-tiles form one range [k_lo, k_hi): a few edge blocks, the
+    // interior in a loop of its own (no branch on the block's kind inside it), a few edge blocks.
+    int k_lo = 0, k_hi = k1;
+    while (k_lo < k1 && !(sa.classify(k_lo) == 2 && sb.classify(k_lo) == 2)) ++k_lo;
+    while (k_hi > k_lo && !(sa.classify(k_hi - 1) == 2 && sb.classify(k_hi - 1) == 2)) --k_hi;
+    int k = 0;
+    for (; k < k_lo; ++k) step(k, std::false_type{});
+    for (; k < k_hi; ++k) step(k, std::true_type{});
+    for (; k < k1; ++k) step(k, std::false_type{});
   }
 
   // Explicit block lists: as run_ldsk, with no vector load into registers inside the loop.  Block
@@ -920,12 +1051,12 @@ struct CoreF16T {
       wait_lds_reads();                  // the K buffer may be overwritten now
       __builtin_amdgcn_wave_barrier();
       if (more) sm.stage_k(Kh, b1, lane, ldsk);
-      float p[16];
-      scores(kf, b, c, lane, h, st, p);
+      half8 ph[2];
+      scores(kf, b, c, lane, h, st, ph);
       // V block k (and the words of block k+1) are older than the 4 K copies issued above (if any)
       if (more) wait_loads_except<4>(); else wait_loads_except<0>();
       __builtin_amdgcn_wave_barrier();
-      accumulate(p, lane, h, st, ldsv);
+      accumulate(ph, lane, h, st, ldsv);
       b = b1;
       b1 = b2;
     }
