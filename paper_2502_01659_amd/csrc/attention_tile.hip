@@ -929,7 +929,8 @@ struct CoreF16T {
     auto step = [&](int k, auto interior) {
       constexpr bool kInterior = decltype(interior)::value;
       const bool more = k + 1 < k1;      // wave-uniform
-      __builtin_amdgcn_wave_barrier();   // the previous block's reads of the staged V are done
+      wait_lds_reads();                  // the previous block's reads of the staged V are done
+      __builtin_amdgcn_wave_barrier();
       sm.stage_v(Vh, cur, lane, ldsv);
       const BlockInfo nxt = sa.place(more ? k + 1 : k);
       wait_loads_except<4>();            // K block k is older than the 4 V copies just issued
@@ -2234,6 +2235,9 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   TileState sta, stb;
   sta.init();
   stb.init();
+  wait_loads_except<0>();     // Q has arrived: the block loop counts only its own copies
+  core.q_arrived();
+  core_b.q_arrived();
   core.run_pair(core_b.qf, K + hoff, V + hoff, sa, sb, nblk, softmax_factor(scale), lane, sta, stb, lds);
   float* lse_h = lse ? lse + hd * L : nullptr;
   if (accumulate) {
