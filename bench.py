@@ -72,10 +72,16 @@ class Runner:
         from sga_inputs import torch_qkv
         self.torch, self.sga, self.wl, self.path = torch, sga, wl, path
         dev = "cuda:0"
-        self.nnz = sga.mask_nnz(wl.mask)
+        self.random = wl.mask.name == "random"      # CSR drawn once; no builder call per step
+        if self.random:
+            from sga_inputs import torch_random_csr
+            self.row_ptr, self.col_idx = torch_random_csr(wl.mask, dev)
+            self.nnz = int(self.row_ptr[-1])
+        else:
+            self.nnz = sga.mask_nnz(wl.mask)
         self.Q, self.K, self.V = torch_qkv(wl.H, wl.L, wl.d, wl.dtype, wl.sigma, wl.seed, dev)
         self.O = torch.empty_like(self.Q)
-        if wl.explicit:
+        if wl.explicit and not self.random:
             self.row_ptr = torch.empty(wl.L + 1, dtype=torch.int64, device=dev)
             self.col_idx = torch.empty(self.nnz, dtype=torch.int32, device=dev)
         self.ws = sga.alloc_workspace(wl.L, wl.H, wl.d, wl.dtype, self.nnz if wl.explicit else -1,
@@ -96,6 +102,8 @@ class Runner:
         self.prepared = True
 
     def build(self):
+        if self.random:
+            return
         st = self.sga.sga_build_mask(self.wl.mask, self.row_ptr.data_ptr(), self.col_idx.data_ptr(),
                                      self.col_idx.numel(), self.stream)
         if st != 0:
@@ -603,7 +611,7 @@ def main():
         traffic_summary(args.traffic_summary, args.workload, args.prepared)
         return
     import torch
-    from sga_inputs import WORKLOADS, TABLE3_WORKLOADS
+    from sga_inputs import WORKLOADS, TABLE3_WORKLOADS, E2_RANDOM_WORKLOADS
     if args.calibrate_copy:
         n = 1 << 30
         src = torch.empty(n, dtype=torch.uint8, device="cuda:0").fill_(1)
@@ -620,7 +628,8 @@ def main():
                          else suite_e2(path, tuple(int(x) for x in args.dims.split(",")))))
         return
     # (the long-context shapes of Table III can be named too, e.g. for a profile of one of them)
-    wl = WORKLOADS.get(args.workload) or TABLE3_WORKLOADS[args.workload]
+    wl = (WORKLOADS.get(args.workload) or TABLE3_WORKLOADS.get(args.workload)
+          or E2_RANDOM_WORKLOADS[args.workload])
     run = Runner(wl, path)
     if args.prepared and wl.explicit:
         run.prepare()
@@ -654,7 +663,7 @@ def main():
                              "how": "1 GiB scratch buffer overwritten before every launch, 5 launches"}
     if wl.explicit and not run.prepared:
         out["steady_state"] = steady_state(run, args.steps, args.warmup, args.path)
-    if not args.no_cpu:
+    if not args.no_cpu and not run.random:      # (the row-scan oracle takes mask predicates, not drawn CSR arrays)
         out["cpu_baseline"] = cpu_baseline(wl, run)
     del run
     torch.cuda.empty_cache()

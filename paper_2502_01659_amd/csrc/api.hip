@@ -219,6 +219,7 @@ sga_status run_explicit_call(const void* Q, const void* K, const void* V, const 
     a.prepared = true;
     a.plan_multi_tiles = parts_fit ? plan->multi_tiles : 0;
     a.plan_tiles_cover_all = (plan->flags & SGA_GRAPH_TILES_COVER_ALL) != 0;
+    a.plan_no_tiles = (int64_t)plan->tiles_left == (L + kTile - 1) / kTile;
     a.plan_long_rows = (plan->flags & SGA_GRAPH_ROW_CHUNKS_FIT) ? plan->long_rows : 0;
     return launch_tile_explicit(a);
   }

@@ -84,11 +84,6 @@ __device__ __forceinline__ float load_scalar(const __half* p) { return __half2fl
 __device__ __forceinline__ void store_scalar(float* p, float v) { *p = v; }
 __device__ __forceinline__ void store_scalar(__half* p, float v) { *p = __float2half_rn(v); }
 
-struct CsrNeighbours {      // Get_Neighbors, explicit: slice of col_idx
-  const int32_t* cols;
-  __device__ int64_t operator()(int64_t e) const { return cols[e]; }
-};
-
 struct WindowNeighbours {   // Get_Neighbors, implicit: j = first + e*step
   int64_t first, step;
   __device__ int64_t operator()(int64_t e) const { return first + e * step; }
@@ -105,6 +100,36 @@ struct State {
     for (int c = 0; c < VEC; ++c) acc[c] = 0.f;
   }
 };
+
+// One step of the recurrence for kUnroll keys per lane group, K and V rows already in registers.
+template <int LPK, int VEC>
+__device__ __forceinline__ void attend_loaded(const float (&q)[VEC], const float (&kf)[kUnroll][VEC],
+                                              const float (&vf)[kUnroll][VEC], const bool (&valid)[kUnroll],
+                                              State<VEC>& st) {
+  float s[kUnroll];
+  float smax = st.m;
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    float part = 0.f;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) part = __builtin_fmaf(q[c], kf[u][c], part);
+    part = group_sum<LPK>(part);
+    s[u] = valid[u] ? part : -INFINITY;
+    smax = fmaxf(smax, s[u]);
+  }
+  const float alpha = __builtin_amdgcn_exp2f(st.m - smax);
+  st.l *= alpha;
+#pragma unroll
+  for (int c = 0; c < VEC; ++c) st.acc[c] *= alpha;
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const float p = __builtin_amdgcn_exp2f(s[u] - smax);
+    st.l += p;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) st.acc[c] = __builtin_fmaf(p, vf[u][c], st.acc[c]);
+  }
+  st.m = smax;
+}
 
 // Visit edges [e0, e1) of one row.  q holds this lane's channels of Q_i * scale * log2(e).
 template <typename T, int D, typename Nbr>
@@ -126,29 +151,57 @@ __device__ __forceinline__ void attend_range(const T* __restrict__ Kh, const T* 
       Row<T, D>::load(Kh + j * D + cofs, kf[u]);
       Row<T, D>::load(Vh + j * D + cofs, vf[u]);
     }
-    float s[kUnroll];
-    float smax = st.m;
+    attend_loaded<LPK, VEC>(q, kf, vf, valid, st);
+  }
+}
+
+// attend_range over a slice of col_idx (explicit Get_Neighbors).  The column indices are read 64
+// at a time with one coalesced load (lane l holds column base + l) and handed to the lane groups
+// through the LDS crossbar, and the next 64 are requested before the current ones are used: the
+// K/V row gathers then no longer wait for an index load of their own each, and a third of the
+// vector memory instructions go away.
+// kNear: one head's K (and V) is below 4 GiB, so row offsets fit 32 bits.
+template <typename T, int D, bool kNear>
+__device__ __forceinline__ void attend_columns(const T* __restrict__ Kh, const T* __restrict__ Vh,
+                                               const float (&q)[Row<T, D>::VEC],
+                                               const int32_t* __restrict__ cols, int64_t e0, int64_t e1,
+                                               int lane, State<Row<T, D>::VEC>& st) {
+  constexpr int LPK = Row<T, D>::LPK, VEC = Row<T, D>::VEC, G = kWave / LPK;
+  constexpr int kStep = G * kUnroll;                 // edges per step of the recurrence
+  static_assert(kWave % kStep == 0, "a batch of 64 columns is a whole number of steps");
+  if (e0 >= e1) return;
+  const int grp = lane / LPK;
+  const int cofs = (lane % LPK) * VEC;
+  const int64_t last = e1 - 1;
+  int32_t cur = cols[e0 + lane < last ? e0 + lane : last];
+  for (int64_t base = e0; base < e1; base += kWave) {
+    const int64_t nb = base + kWave;
+    int32_t nxt = 0;
+    if (nb < e1) nxt = cols[nb + lane < last ? nb + lane : last];
+    const int n_here = e1 - base < kWave ? (int)(e1 - base) : kWave;     // columns of this batch
 #pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      float part = 0.f;
+    for (int sub = 0; sub < kWave / kStep; ++sub) {
+      if (sub * kStep >= n_here) break;
+      float kf[kUnroll][VEC], vf[kUnroll][VEC];
+      bool valid[kUnroll];
 #pragma unroll
-      for (int c = 0; c < VEC; ++c) part = __builtin_fmaf(q[c], kf[u][c], part);
-      part = group_sum<LPK>(part);
-      s[u] = valid[u] ? part : -INFINITY;
-      smax = fmaxf(smax, s[u]);
+      for (int u = 0; u < kUnroll; ++u) {
+        const int el = sub * kStep + u * G + grp;
+        valid[u] = el < n_here;
+        const int32_t j = __shfl(cur, valid[u] ? el : n_here - 1, kWave);   // out-of-range lanes re-read a real neighbour
+        if (kNear) {
+          // one 32-bit byte offset serves the K and the V row (wave-uniform base + per-lane offset)
+          const uint32_t off = (uint32_t)j * (uint32_t)(D * sizeof(T)) + (uint32_t)(cofs * sizeof(T));
+          Row<T, D>::load(reinterpret_cast<const T*>(reinterpret_cast<const char*>(Kh) + off), kf[u]);
+          Row<T, D>::load(reinterpret_cast<const T*>(reinterpret_cast<const char*>(Vh) + off), vf[u]);
+        } else {
+          Row<T, D>::load(Kh + (int64_t)j * D + cofs, kf[u]);
+          Row<T, D>::load(Vh + (int64_t)j * D + cofs, vf[u]);
+        }
+      }
+      attend_loaded<LPK, VEC>(q, kf, vf, valid, st);
     }
-    const float alpha = __builtin_amdgcn_exp2f(st.m - smax);
-    st.l *= alpha;
-#pragma unroll
-    for (int c = 0; c < VEC; ++c) st.acc[c] *= alpha;
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const float p = __builtin_amdgcn_exp2f(s[u] - smax);
-      st.l += p;
-#pragma unroll
-      for (int c = 0; c < VEC; ++c) st.acc[c] = __builtin_fmaf(p, vf[u][c], st.acc[c]);
-    }
-    st.m = smax;
+    cur = nxt;
   }
 }
 
@@ -244,7 +297,8 @@ __global__ __launch_bounds__(256) void clear_workspace_kernel(void* ws, size_t w
     next[i] = 0;          // claim counters and exit counters of the heads
 }
 
-// One thread per row: rows over the split threshold reserve chunk work items.
+// One thread per row: rows that are split reserve their partial slots and enter the list of
+// long rows.
 __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __restrict__ row_ptr,
                                                             int64_t L, int32_t H, int32_t dtype,
                                                             int32_t d, void* ws, size_t ws_bytes,
@@ -252,19 +306,17 @@ __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __res
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= L) return;
   const int64_t deg = row_ptr[i + 1] - row_ptr[i];
-  if (deg <= kSplitThreshold) return;
+  if (deg <= kSplitThreshold / 2) return;           // (no rule splits a row this short)
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
-  if (pl.total_bytes > ws_bytes) return;
+  if (pl.total_bytes > ws_bytes || !row_is_split(deg, pl)) return;
   if (skip_tiled && (tiles_cover_everything(pl, ws) || tile_handled(pl, ws, row_ptr, L, dtype, i / kTile)))
     return;
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   int32_t n, len;
-  split_shape(deg, pl.split_chunk, n, len);
+  row_split_shape(deg, pl, n, len);
   atomicAdd(&ctr[kCtrChunksNeeded], (uint32_t)n);
   const uint32_t base = atomicAdd(&ctr[kCtrItemsAlloc], (uint32_t)n);
   if ((int64_t)base + n > pl.cap_items) return;
-  int2* items = reinterpret_cast<int2*>(static_cast<char*>(ws) + pl.off_items);
-  for (int c = 0; c < n; ++c) items[base + c] = make_int2((int)i, c);
   const uint32_t slot = atomicAdd(&ctr[kCtrLongRows], 1u);
   int4* lr = reinterpret_cast<int4*>(static_cast<char*>(ws) + pl.off_long);
   lr[slot] = make_int4((int)i, (int)base, n, len);
@@ -309,14 +361,17 @@ __global__ __launch_bounds__(256) void gather_csr_kernel(
        i += (int64_t)gridDim.x * waves) {
     if (skip_tiled && row_done_by_tiles(row_ptr, L, H, DtypeOf<T>::code, D, ws, ws_bytes, i)) continue;
     const int64_t r0 = row_ptr[i], r1 = row_ptr[i + 1];
-    if (use_split && r1 - r0 > kSplitThreshold && split_active(row_ptr, L, H, DtypeOf<T>::code, D, ws, ws_bytes))
+    if (use_split && r1 - r0 > kSplitThreshold / 2 && split_active(row_ptr, L, H, DtypeOf<T>::code, D, ws, ws_bytes) &&
+        row_is_split(r1 - r0, plan_workspace(L, H, row_ptr[L], DtypeOf<T>::code, D)))
       continue;
     float q[Row<T, D>::VEC];
     load_query<T, D>(Q + hoff + i * D, scale, lane, q);
     State<Row<T, D>::VEC> st;
     st.init();
-    CsrNeighbours nbr{col_idx + r0};
-    attend_range<T, D>(K + hoff, V + hoff, q, nbr, 0, r1 - r0, lane, st);
+    if (L * D * (int64_t)sizeof(T) < (int64_t(1) << 32))
+      attend_columns<T, D, true>(K + hoff, V + hoff, q, col_idx + r0, 0, r1 - r0, lane, st);
+    else
+      attend_columns<T, D, false>(K + hoff, V + hoff, q, col_idx + r0, 0, r1 - r0, lane, st);
     finish_row<T, D>(O + hoff + i * D, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
   }
 }
@@ -473,7 +528,12 @@ __global__ __launch_bounds__(64) void nonlocal_merge_kernel(T* __restrict__ O, f
                            lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
 }
 
-// One wavefront per (chunk item, head): partial state of a slice of a long row.
+// One wavefront per (chunk of a long row, head): partial state of a slice of the row.  Chunk c
+// of every row is computed on XCD c % 8 (workgroups go to the XCDs round-robin in launch order
+// and gridDim.x is a multiple of 8): chunks are ranges of the rows' sorted neighbour lists, so
+// an XCD's L2 sees the same part of the key range from every row.  The work units of XCD x are
+// the pairs (long row s, j) with chunk c = x + 8j, numbered j * n_long + s (rows of few chunks
+// have no unit for the larger j) and dealt to the XCD's wavefronts in turn.
 template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_chunk_kernel(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
@@ -483,33 +543,37 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
   constexpr int32_t dtype = DtypeOf<T>::code;
   if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, D);
-  const uint32_t n_items = reinterpret_cast<const uint32_t*>(ws)[kCtrItemsAlloc];
-  const int2* items = reinterpret_cast<const int2*>(static_cast<char*>(ws) + pl.off_items);
+  const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrLongRows];
+  const int4* lr = reinterpret_cast<const int4*>(static_cast<char*>(ws) + pl.off_long);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_partials);
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
   const int64_t hoff = h * L * D;
-  for (uint32_t it = blockIdx.x * waves + threadIdx.x / kWave; it < n_items;
-       it += gridDim.x * waves) {
-    const int2 item = items[it];
-    const int64_t i = item.x;
+  const uint32_t xcd = blockIdx.x & 7;
+  const uint64_t n_units = (uint64_t)n_long * (kMaxSplit / 8);
+  for (uint64_t u = (uint64_t)(blockIdx.x >> 3) * waves + threadIdx.x / kWave; u < n_units;
+       u += (uint64_t)(gridDim.x >> 3) * waves) {
+    const int4 rec = lr[u % n_long];                         // {row, first partial slot, chunks, chunk length}
+    const int32_t c = (int32_t)(xcd + 8 * (u / n_long));
+    if (c >= rec.z) continue;
+    const int64_t i = rec.x;
     const int64_t r0 = row_ptr[i], deg = row_ptr[i + 1] - r0;
-    int32_t n, len;
-    split_shape(deg, pl.split_chunk, n, len);
-    const int64_t e0 = (int64_t)item.y * len;
-    const int64_t e1 = min(deg, e0 + len);
+    const int64_t e0 = (int64_t)c * rec.w;
+    const int64_t e1 = min(deg, e0 + rec.w);
     float q[Row<T, D>::VEC];
     load_query<T, D>(Q + hoff + i * D, scale, lane, q);
     State<Row<T, D>::VEC> st;
     st.init();
-    CsrNeighbours nbr{col_idx + r0};
-    attend_range<T, D>(K + hoff, V + hoff, q, nbr, e0, e1, lane, st);
+    if (L * D * (int64_t)sizeof(T) < (int64_t(1) << 32))
+      attend_columns<T, D, true>(K + hoff, V + hoff, q, col_idx + r0, e0, e1, lane, st);
+    else
+      attend_columns<T, D, false>(K + hoff, V + hoff, q, col_idx + r0, e0, e1, lane, st);
     merge_groups<Row<T, D>::LPK, Row<T, D>::VEC>(st);
-    float* p = partials + ((int64_t)it * H + h) * (D + 4);
+    float* p = partials + ((int64_t)(rec.y + c) * H + h) * (D + 4);
     if (lane < Row<T, D>::LPK) {
 #pragma unroll
-      for (int c = 0; c < Row<T, D>::VEC; ++c) p[lane * Row<T, D>::VEC + c] = st.acc[c];
+      for (int k = 0; k < Row<T, D>::VEC; ++k) p[lane * Row<T, D>::VEC + k] = st.acc[k];
     }
     if (lane == 0) {
       p[D] = st.m;
@@ -558,15 +622,25 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   const int64_t leftover_wgs = 2048 / a.H > 256 ? 2048 / a.H : 256;
   if (skip_tiled && nwg > leftover_wgs) nwg = leftover_wgs;
   const dim3 grid((unsigned)nwg, (unsigned)a.H);
-  if (!skip_tiled) profile_mark_begin(a.stream, "gather_csr_kernel");
+  // the benchmark hook brackets the kernel that does the work: the row kernel, or the chunk
+  // kernel where a prepared graph has found every row left to it split
+  const bool mark = !skip_tiled || (a.prepared && a.plan_no_tiles);
+  const bool mark_chunks = mark && a.prepared && a.plan_long_rows > 0;
+  if (mark && !mark_chunks) profile_mark_begin(a.stream, "gather_csr_kernel");
   hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
                      a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
                      skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
-  if (!skip_tiled) profile_mark_end(a.stream);
+  if (mark && !mark_chunks) profile_mark_end(a.stream);
   if (split && (!a.prepared || a.plan_long_rows > 0)) {
+    if (mark_chunks) profile_mark_begin(a.stream, "gather_chunk_kernel");
     hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled && a.H >= 8 ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
-    hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3(64, (unsigned)a.H), dim3(256), 0, a.stream, O,
+    if (mark_chunks) profile_mark_end(a.stream);
+    // one wavefront per long row and head; a prepared graph knows how many there are
+    int64_t merge_wgs = a.prepared ? ((int64_t)a.plan_long_rows + 3) / 4 : (a.L + 3) / 4;
+    const int64_t merge_cap = 4096 / a.H > 64 ? 4096 / a.H : 64;
+    if (merge_wgs > merge_cap) merge_wgs = merge_cap;
+    hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3((unsigned)merge_wgs, (unsigned)a.H), dim3(256), 0, a.stream, O,
                        a.lse, a.row_ptr, a.L, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
   }
   return hip_status(hipGetLastError());

@@ -1553,6 +1553,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
     const int c_last = pos < end ? col_idx[end - 1] : -1;
     int nblk = 0;
     bool overflow = false;
+    int consumed = 0;                   // edges of this lane's row in the blocks written so far
     while (true) {
       int cur = INT32_MAX;
       if (!arith && pos < end) {
@@ -1648,6 +1649,20 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
       if (lane < kTile) pair_mask[(slot0 + nblk) * kTile + lane] = word;
       if (lane == 0) pair_blk[slot0 + nblk] = b | (full ? kFullBit : 0);
       ++nblk;
+      consumed += __builtin_popcount(word);
+      if (nblk == kProbeBlocks) {
+        // A list that averages under kProbeEdges edges per block over its first kProbeBlocks blocks
+        // is given up at once (scattered columns: the rows go to the per-row kernels) instead
+        // of being walked until its slots run out.  Like the slot rule this depends on the mask
+        // alone.
+        int total = lane < kTile ? consumed : 0;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off, kWave);
+        if (total < kProbeBlocks * kProbeEdges) {
+          overflow = true;
+          break;
+        }
+      }
     }
     if (lane == 0) {
       TileItem it;
@@ -2621,8 +2636,11 @@ void launch_tile_analyze(const AttnArgs& a) {
 
 sga_status launch_tile_explicit(const AttnArgs& a) {
   if (!a.ws || a.ws_bytes < 256) return launch_gather_explicit(a, false, false);
-  sga_status st = a.dtype == SGA_F32 ? run_tile_explicit<float>(a) : run_tile_explicit<__half>(a);
-  if (st != SGA_OK) return st;
+  // (a prepared graph in which no tile qualified goes straight to the per-row kernels)
+  if (!(a.prepared && a.plan_no_tiles)) {
+    const sga_status st = a.dtype == SGA_F32 ? run_tile_explicit<float>(a) : run_tile_explicit<__half>(a);
+    if (st != SGA_OK) return st;
+  }
   if (a.prepared && a.plan_tiles_cover_all) return SGA_OK;
   // rows of tiles that did not qualify (or everything, if the workspace is too small)
   return launch_gather_explicit(a, true, true);

@@ -18,6 +18,23 @@ constexpr int kSplitThreshold = 2048; // rows with more neighbours are split
 constexpr int kSplitChunk = 2048;     // target edges per chunk
 constexpr int kSplitChunkMin = 256;   // ... of a call with little work in total (split_chunk)
 constexpr int kMaxSplit = 64;         // at most this many chunks per row
+// Keys whose K and V rows do not fit one L2 (each of the 8 XCDs has its own 4 MB): rows of at
+// least kL2ChunkEdges * n neighbours are then cut into n = l2_chunks() chunks, a multiple of 8, and
+// chunk c of every row runs on XCD c % 8.  A chunk of a row's sorted neighbour list covers a
+// range of keys, so each L2 then serves about an n-th of K and V instead of all of it (for a
+// uniformly random mask exactly that; any other mask is split the same way, only with less to
+// gain).  The partial states of this finer split may take up to kL2PartialBudget bytes; a call
+// that could need more keeps the coarser split by edge count.
+constexpr int64_t kL2FitBytes = int64_t(3) << 20;
+constexpr int64_t kL2ShareBytes = int64_t(2) << 20;       // K and V bytes per chunk and XCD aimed at
+constexpr int kL2ChunkEdges = 128;
+constexpr int64_t kL2PartialBudget = int64_t(64) << 20;
+__host__ __device__ inline int l2_chunks(int64_t L, int32_t d, int32_t dtype) {
+  const int64_t kv = 2 * L * d * (dtype == SGA_F32 ? 4 : 2);
+  if (kv <= kL2FitBytes) return 0;
+  int64_t n = 8 * ((kv + 8 * kL2ShareBytes - 1) / (8 * kL2ShareBytes));
+  return (int)(n > kMaxSplit ? kMaxSplit : n);
+}
 constexpr int kMaxImplicitGlobal = 64;  // global rows the implicit non-local kernels can split
 // Implicit window masks on few tiles (a short sequence, one head): a tile's key blocks are cut
 // into up to kMaxWindowSplit ranges that separate wavefronts reduce to partial states, so that
@@ -30,6 +47,8 @@ constexpr int kWindowSplitTiles = 4096;
 constexpr int kTile = 32;                 // query rows per tile = keys per block
 constexpr int kCutEdges = 16384;          // tiles with fewer edges are never cut into segments
 constexpr int kPairEdges = 128;           // a tile qualifies if it averages >= this many edges per block
+constexpr int kProbeBlocks = 16;          // ... and a list is given up early if its first kProbeBlocks blocks
+constexpr int kProbeEdges = 112;          //     average fewer than kProbeEdges edges (kPairEdges less a margin)
 constexpr int kMaxTilePartials = 32768;   // partial states of split tiles per call
 constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32], l[32]
 
@@ -61,8 +80,7 @@ __host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) 
 
 // ---- workspace layout -------------------------------------------------------
 // [0, 256)            counters (uint32): see WsCounter
-// items               cap_items x int2 {row, chunk}                    (gather split)
-// long_rows           cap_items x int4 {row, base, nchunks, chunk_len}
+// long_rows           cap_items x int4 {row, first partial slot, nchunks, chunk_len}   (gather split)
 // partials            cap_items x H x kPartialStride floats {acc[d], m, l}
 //                     (implicit non-local mask: kMaxImplicitGlobal rows x kMaxSplit chunks)
 // items_rec           n_work x TileItem: the work items of the tile path
@@ -77,7 +95,7 @@ __host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) 
 //                     then H x uint32: wavefronts (workgroups) of the head that found no item left
 enum WsCounter : int {
   kCtrChunksNeeded = 0,   // sum of chunk counts of all long rows
-  kCtrItemsAlloc = 1,     // bump allocator over items
+  kCtrItemsAlloc = 1,     // bump allocator over the partial slots of split rows
   kCtrLongRows = 2,       // number of long rows recorded
   kCtrTilePartsNeeded = 3,  // sum of segment counts of all multi-segment tiles
   kCtrTilePartsAlloc = 4,   // bump allocator over tile partial slots
@@ -100,7 +118,7 @@ struct alignas(32) TileItem {
 struct WorkspacePlan {
   // gather split
   int64_t cap_items;
-  size_t off_items, off_long, off_partials;
+  size_t off_long, off_partials;
   // tile path
   int64_t n_tiles;        // ceil(L / 32)
   int64_t n_work;         // tile work items (segments)
@@ -108,6 +126,7 @@ struct WorkspacePlan {
   int64_t cap_tparts;     // capacity of tile partial states
   int seg_shift;          // log2 of S, the edges per work item of the tile path
   int split_chunk;        // target edges per chunk of a split row
+  int l2_chunks;          // != 0: rows of >= kL2ChunkEdges * l2_chunks neighbours are cut into this many chunks
   size_t off_items_rec, off_tile_bad, off_tile_pbase, off_multi_tiles, off_pair_blk, off_pair_mask,
       off_tpartials, off_work_next, off_wparts;
   int64_t cap_wparts;     // (tile, head) pairs whose window partials fit (implicit masks)
@@ -132,11 +151,17 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   if (n_long > L) n_long = L;
   int64_t cap = e / p.split_chunk + n_long;
   if (cap > (int64_t)kMaxSplit * n_long) cap = (int64_t)kMaxSplit * n_long;
+  p.l2_chunks = nnz < 0 ? 0 : l2_chunks(L, d, dtype);
+  if (p.l2_chunks) {
+    int64_t rows = e / ((int64_t)kL2ChunkEdges * p.l2_chunks);      // rows that can qualify
+    if (rows > L) rows = L;
+    const int64_t cap_l2 = rows * p.l2_chunks;
+    if (cap_l2 * H * (d + 4) * (int64_t)sizeof(float) > kL2PartialBudget) p.l2_chunks = 0;
+    else if (cap_l2 > cap) cap = cap_l2;
+  }
   // implicit masks: only the dense rows of the global (non-local) mask are split
   if (nnz < 0) cap = (int64_t)kMaxImplicitGlobal * kMaxSplit;
   p.cap_items = cap;
-  p.off_items = off;
-  off = (off + (size_t)cap * 8 + 255) & ~size_t(255);
   p.off_long = off;
   off = (off + (size_t)cap * 16 + 255) & ~size_t(255);
   p.off_partials = off;
@@ -176,6 +201,27 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
         ~size_t(255);
   p.total_bytes = off;
   return p;
+}
+
+// Rows the per-row kernels split into chunks (partial states + ordered merge): more than
+// kSplitThreshold neighbours, or enough of them for the split by L2 share (see l2_chunks).
+__host__ __device__ inline bool row_is_split(int64_t deg, const WorkspacePlan& p) {
+  return deg > kSplitThreshold || (p.l2_chunks && deg >= (int64_t)kL2ChunkEdges * p.l2_chunks);
+}
+// ... into nchunks chunks of len edges (the last one shorter), len a multiple of 32.
+__host__ __device__ inline void row_split_shape(int64_t deg, const WorkspacePlan& p, int32_t& nchunks,
+                                                int32_t& len) {
+  int64_t n;
+  if (p.l2_chunks && deg >= (int64_t)kL2ChunkEdges * p.l2_chunks) {
+    n = p.l2_chunks;
+  } else {
+    n = (deg + p.split_chunk - 1) / p.split_chunk;
+    if (n > kMaxSplit) n = kMaxSplit;
+  }
+  int64_t l = (deg + n - 1) / n;
+  l = (l + 31) / 32 * 32;
+  len = (int32_t)l;
+  nchunks = (int32_t)((deg + l - 1) / l);
 }
 
 // First work item of tile t: f(t) = t + row_ptr[min(32t, L)] / S.
@@ -249,6 +295,7 @@ struct AttnArgs {
   bool prepared;
   uint32_t plan_multi_tiles;   // multi-segment tiles whose partial states fit (0: no merge launch)
   bool plan_tiles_cover_all;   // no row is left to the per-row kernels
+  bool plan_no_tiles;          // no tile qualified: the tile kernels have nothing to do
   uint32_t plan_long_rows;     // split rows among the leftover rows whose chunk items fit
 };
 

@@ -2,7 +2,7 @@
 from dataclasses import dataclass, replace
 from typing import Dict, List
 
-from .masks import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
+from .masks import (MaskSpec, RandomMaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL,
                     KIND_BIGBIRD)
 
 BASE_SEED = 20250201
@@ -75,6 +75,19 @@ TABLE3_WORKLOADS: Dict[str, Workload] = {
     "table3_16m": _table3("table3_16m", 16_000_000, 0.00017),
     "table3_160m": _table3("table3_160m", 160_000_000, 0.00001),
 }
+
+
+def _e2_random(L, density, dtype="f32", d=64):
+    tag = f"e2_random_{L // 1024}k_sf{int(round(density * 1000)):04d}_{dtype}"
+    return tag, Workload(tag, H=1, L=L, d=d, dtype=dtype, sigma=1.0 if dtype == "f32" else 0.5,
+                         mask=RandomMaskSpec(L, density, BASE_SEED + 7), explicit=True)
+
+
+# Random CSR masks of the microbenchmark grid (Section V-C): one head, d = 64, the longest of its
+# three sequence lengths, sparsity factors 0.01 and 0.1, both storage types.  These run on the
+# per-row (general CSR) kernels: scattered columns fill no 32 x 32 tile.
+E2_RANDOM_WORKLOADS: Dict[str, Workload] = dict(
+    _e2_random(24576, sf, dt) for sf in (0.01, 0.1) for dt in ("f32", "f16"))
 
 
 def small_variants() -> List[Workload]:

@@ -54,3 +54,18 @@ class MaskSpec:
     @property
     def name(self) -> str:
         return KIND_NAMES[self.kind]
+
+
+@dataclass(frozen=True)
+class RandomMaskSpec:
+    """A uniformly random mask (the "uniform random" pattern of Section II-C and the random CSR
+    runs of the microbenchmark, Section V-C): every (i, j) pair is an edge with probability
+    `density`, drawn on the device from `seed` (sga_inputs.tensors.torch_random_csr).  It has no
+    closed form: both sides consume the drawn CSR arrays."""
+    L: int
+    density: float
+    seed: int = 0
+
+    @property
+    def name(self) -> str:
+        return "random"

@@ -60,3 +60,24 @@ def torch_qkv(H, L, d, dtype, sigma, seed, device):
             x[r0:r1].copy_(c)
         out.append(x.view(H, L, d))
     return tuple(out)
+
+
+def torch_random_csr(spec, device):
+    """CSR (row_ptr int64 [L+1], col_idx int32 [nnz]) of a RandomMaskSpec on `device`: the mask
+    is drawn row block by row block (fixed blocks of 2048 rows: part of the recipe) as
+    rand(rows, L) < density from a generator seeded with spec.seed."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(spec.seed)
+    L = spec.L
+    counts, cols = [], []
+    for r0 in range(0, L, 2048):
+        r1 = min(L, r0 + 2048)
+        dense = torch.rand((r1 - r0, L), generator=g, device=device) < spec.density
+        counts.append(dense.sum(dim=1))
+        cols.append(dense.nonzero()[:, 1].to(torch.int32))
+        del dense
+    row_ptr = torch.zeros(L + 1, dtype=torch.int64, device=device)
+    row_ptr[1:] = torch.cat(counts).cumsum(0)
+    col_idx = torch.cat(cols).contiguous()
+    return row_ptr, col_idx

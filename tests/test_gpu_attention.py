@@ -290,6 +290,40 @@ def test_split_rows_high_degree(dtype, path):
     assert np.array_equal(O, O_b)
 
 
+@pytest.mark.parametrize("dtype,L,p", [("f32", 7000, 0.2), ("f16", 13000, 0.11)])
+def test_rows_split_by_l2_share(dtype, L, p):
+    """Keys whose K and V do not fit one L2: rows of a uniformly random mask with 1,000 to 2,000
+    neighbours (below the ordinary split threshold) are cut into 8 chunks that run on the 8
+    XCDs, beside shorter rows that stay whole and two dense rows.  Sampled rows against the dense
+    oracle on every path, and a rerun is bit-identical."""
+    print("case l2 split", dtype, L, flush=True)
+    H, d = 2, 64
+    rng = np.random.default_rng(77)
+    mask = rng.random((L, L)) < p                    # about 1,400 neighbours per row
+    mask[1::3] &= rng.random((L // 3 + 1, L))[: len(mask[1::3])] < 0.3      # every third row: about 420
+    mask[5] = True
+    mask[L - 2] = True
+    mask[40] = False                                 # an empty row
+    rp, ci = R.csr_from_dense(mask)
+    deg = np.diff(rp)
+    assert (deg[0::3][3:] >= 8 * 128).all() and (deg[0::3] <= 2048).all() and (deg[1::3].max() < 8 * 128)
+    Q, K, V = numpy_qkv(H, L, d, dtype, 0.6, 31)
+    dQ, dK, dV = to_device(Q, K, V)
+    drp, dci = to_device(rp, ci)
+    ws = sga.alloc_workspace(L, H, d, dtype, int(rp[-1]))
+    rows = np.unique(np.concatenate([np.arange(0, 60), [L - 2, L - 1], rng.integers(0, L, 80)]))
+    refs = [R.attention_dense(Q[h][rows].astype(np.float64), K[h].astype(np.float64),
+                              V[h].astype(np.float64), mask[rows], 0.125) for h in range(H)]
+    for path in (sga.PATH_GATHER, sga.PATH_AUTO):
+        O, lse = sga.attention_forward(dQ, dK, dV, drp, dci, 0.125, workspace=ws, path=path, want_lse=True)
+        O2 = sga.attention_forward(dQ, dK, dV, drp, dci, 0.125, workspace=ws, path=path)
+        import torch
+        torch.cuda.synchronize()
+        assert torch.equal(O, O2)
+        for h in range(H):
+            _close(O[h].cpu().numpy()[rows], lse[h].cpu().numpy()[rows], refs[h][0], refs[h][1], dtype)
+
+
 def test_explicit_and_implicit_paths_agree():
     """The same mask through the CSR entry point and the implicit entry point (the paper's
     own cross-check between its CSR and ordered-sparsity kernels, Section V-F)."""
