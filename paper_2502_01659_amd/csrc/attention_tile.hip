@@ -80,13 +80,15 @@ __device__ __forceinline__ void wait_loads_except() {
   __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-// Waits until at most `keep` of the most recently issued vector memory operations are still in
-// flight; keep is wave-uniform and one of 0, 4, 8, 9 (any other value: no wait).
-__device__ __forceinline__ void wait_loads_keep(int keep) {
-  if (keep == 0) wait_loads_except<0>();
-  else if (keep == 4) wait_loads_except<4>();
-  else if (keep == 8) wait_loads_except<8>();
-  else if (keep == 9) wait_loads_except<9>();
+// Wait ahead of the reads of a staged V block: with further copies behind it (more), all but
+// the kKeepMore most recently issued vector memory operations must have completed; without, all
+// of them.  kKeepMore = -1: the block is known to be complete, no wait.
+template <int kKeepMore>
+__device__ __forceinline__ void wait_staged_v(bool more) {
+  static_assert(kKeepMore >= -1 && kKeepMore <= 63, "a count the vmcnt field can hold, or -1");
+  if constexpr (kKeepMore >= 0) {
+    if (more) wait_loads_except<kKeepMore>(); else wait_loads_except<0>();
+  }
 }
 
 // K-ready wait of the LDS pipelines: the K copies of block k are older than the kCopies V copies
@@ -377,12 +379,41 @@ __device__ __forceinline__ void numerators_h(const floatx16& sv, float c, TileSt
   }
   st.l = l;
 }
+// The running max of fp16 tiles is raised on demand: the numerators are first taken against the
+// m the state already has, and only if one of them leaves the fp16 range (it rounds to +inf, and
+// so does the sum it enters; the first block of a tile, whose m is still the initial one, always
+// does) is the block's maximum computed, m raised and the numerators taken again.  A numerator is
+// then at most 2^16 instead of 2^kRescaleSlack, which fp16 holds at the same relative precision,
+// and the common block pays neither for the maximum nor for waiting on it.
+constexpr float kSumOverflow = 3.0e38f;
+__device__ __forceinline__ bool sum_overflowed(const TileState& st) { return !(st.l < kSumOverflow); }
 __device__ __forceinline__ void softmax_block_h(floatx16 sv, float c, bool full, uint32_t word, int h,
                                                 TileState& st, half8 (&ph)[2]) {
   if (!full) mask_scores(sv, word, h);
-  const float bm = block_max(sv, c, h);
-  if (__any(needs_rescale(st, bm))) rescale_state(st, bm);
+  const float l_before = st.l;
   numerators_h(sv, c, st, ph);
+  if (__any(sum_overflowed(st))) {
+    st.l = l_before;
+    rescale_state(st, block_max(sv, c, h));
+    numerators_h(sv, c, st, ph);
+  }
+}
+// The same for two sub-tiles whose blocks are both unmasked, as one stretch of code with one
+// (rare) branch.
+__device__ __forceinline__ void softmax_pair_h(const floatx16& s_a, const floatx16& s_b, float c, int h,
+                                               TileState& sta, TileState& stb, half8 (&pha)[2],
+                                               half8 (&phb)[2]) {
+  const float la = sta.l, lb = stb.l;
+  numerators_h(s_a, c, sta, pha);
+  numerators_h(s_b, c, stb, phb);
+  if (__any(sum_overflowed(sta) || sum_overflowed(stb))) {
+    sta.l = la;
+    stb.l = lb;
+    rescale_state(sta, block_max(s_a, c, h));
+    rescale_state(stb, block_max(s_b, c, h));
+    numerators_h(s_a, c, sta, pha);
+    numerators_h(s_b, c, stb, phb);
+  }
 }
 
 // Source addresses of the global -> LDS block copies.  A block's rows are row0 + j*stride
@@ -528,7 +559,10 @@ struct CoreF32T {
   }
 
   // kf[t] = K[key n of the block][h*32 + t], straight from global memory: 128 contiguous bytes
-  // per lane.  lane_off = byte offset of the lane's key row and half inside a whole block.
+  // per lane, i.e. kFragLoads loads of 16 bytes (the widest load there is; the counted waits of
+  // run_regk rely on this number).  lane_off = byte offset of the lane's key row and half inside
+  // a whole block.
+  static constexpr int kFragLoads = 32 * (int)sizeof(float) / 16;
   __device__ static void load_k(const float* __restrict__ Kh, const BlockInfo& b, int64_t stride_bytes,
                                 uint32_t lane_off, int n, int h, float (&kf)[32]) {
     const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * Stage::kGlobalRowBytes;
@@ -563,9 +597,10 @@ struct CoreF32T {
   }
 
   // S^T = K_blk Q^T, softmax, O^T += V_blk^T P^T for one block whose V rows are staged at ldsv.
-  // (v_keep: the staged V block is complete once at most this many later copies are in flight)
+  // (kKeepMore, more: see wait_staged_v)
+  template <int kKeepMore>
   __device__ void block_math(const float (&kf)[32], const BlockInfo& b, float c, int n, int h,
-                             TileState& st, const char* ldsv, int v_keep) {
+                             TileState& st, const char* ldsv, bool more) {
     floatx16 s = {0};
 #pragma unroll
     for (int t = 0; t < 32; ++t)
@@ -573,7 +608,7 @@ struct CoreF32T {
     if (kD > kHeadDim) xchg.sum_slices(s, 32 * h + n);
     float p[16];
     softmax_block(s, c, b, h, st, p);
-    wait_loads_keep(v_keep);
+    wait_staged_v<kKeepMore>(more);
     __builtin_amdgcn_wave_barrier();
     const float* vread = reinterpret_cast<const float*>(ldsv) + h * 4 * kHeadDim + n;
     if (b.full) {
@@ -637,7 +672,7 @@ struct CoreF32T {
       __builtin_amdgcn_wave_barrier();
       if (more) sm.stage_k(Kh, b1, lane, ldsk);
       // V block k is older than the 8 K copies issued above (if any)
-      block_math(kf, b, c, n, h, st, ldsv, more ? 8 : 0);
+      block_math<8>(kf, b, c, n, h, st, ldsv, more);
       b = b1;
       b1 = b2;
     }
@@ -668,7 +703,7 @@ struct CoreF32T {
       sm.stage_v(Vh, b, lane, lds);
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.get(k + 2, n);
-      block_math(kf, b, c, n, h, st, lds, 0);
+      block_math<0>(kf, b, c, n, h, st, lds, false);
       b = b1;
       b1 = b2;
     };
@@ -714,12 +749,13 @@ struct CoreF32T {
       }
       BlockInfo b2 = b1;
       if (k + 2 < k1) b2 = src.block(k + 2);
-      // the words and the K fragment of block k are older than the 8 (+ 1 + 8) operations above
-      if (more) wait_loads_except<17>(); else wait_loads_except<8>();
+      // the words and the K fragment of block k are older than the operations above: the V copies
+      // and, if a block follows, its word copy and fragment loads
+      if (more) wait_loads_except<Stage::kCopies + 1 + kFragLoads>(); else wait_loads_except<Stage::kCopies>();
       __builtin_amdgcn_wave_barrier();
       b.word = *reinterpret_cast<const uint32_t*>(ldsw + (k & 1) * 256 + lane * 4);
-      // V block k is older than the word copy and the 8 fragment loads (if any)
-      block_math(kf, b, c, n, h, st, lds, more ? 9 : 0);
+      // V block k is older than the word copy and the fragment loads (if any)
+      block_math<1 + kFragLoads>(kf, b, c, n, h, st, lds, more);
       b = b1;
       b1 = b2;
     };
@@ -820,13 +856,13 @@ struct CoreF16T {
     return __builtin_bit_cast(half4, raw);
   }
 
-  // (v_keep: the staged V block is complete once at most this many later copies are in flight;
-  // negative: it is known to be complete)
+  // (kKeepMore, more: see wait_staged_v)
+  template <int kKeepMore>
   __device__ void block_math(const half8 (&kf)[4], const BlockInfo& b, float c, int lane, int h,
-                             TileState& st, const char* ldsv, int v_keep) {
+                             TileState& st, const char* ldsv, bool more) {
     half8 ph[2];
     scores(kf, b, c, lane, h, st, ph);
-    wait_loads_keep(v_keep);
+    wait_staged_v<kKeepMore>(more);
     __builtin_amdgcn_wave_barrier();
     accumulate(ph, lane, h, st, ldsv);
   }
@@ -898,118 +934,10 @@ struct CoreF16T {
       __builtin_amdgcn_wave_barrier();
       if (more) sm.stage_k(Kh, b1, lane, ldsk);
       // V block k (and any record load after it) is older than the 4 K copies issued above (if any)
-      block_math(kf, b, c, lane, h, st, ldsv, more ? 4 : 0);
+      block_math<4>(kf, b, c, lane, h, st, ldsv, more);
       b = b1;
       b1 = b2;
     }
-  }
-
-  // Two neighbouring 32-query sub-tiles in one wavefront (this->qf holds the first, qb the
-  // second): every staged K and V block, the K fragment read and the V^T operand reads serve
-  // both, and the two chains of products are independent of each other.  The block lists of
-  // the two sub-tiles (sa, sb) must start at the same key.  Every block is classified per
-  // sub-tile from wave-uniform quantities (WindowBlocks::classify): a block outside a sub-tile's
-  // window is skipped for it, an interior block runs without mask words, and only the few
-  // blocks on the window's edges pay for the per-lane mask arithmetic.  Pipeline as in run_ldsk.
-  __device__ void run_pair(const half8 (&qb)[4], const __half* __restrict__ Kh,
-                           const __half* __restrict__ Vh, const WindowBlocks& sa, const WindowBlocks& sb,
-                           int k1, float c, int lane, TileState& sta, TileState& stb, char* lds) {
-    if (k1 <= 0) return;
-    const int n = lane & 31, h = lane >> 5;
-    Stage sm;
-    sm.init(sa.key_stride(), lane);
-    char* ldsk = lds;
-    char* ldsv = lds + kBlockBytes;
-    BlockInfo cur = sa.place(0);
-    __builtin_amdgcn_wave_barrier();     // reads of both buffers by an earlier work item are done
-    sm.stage_k(Kh, cur, lane, ldsk);
-    const char* vt = vt_base(ldsv, lane, h);
-    // One block step; kInterior: the block is interior to both sub-tiles.  The pipeline state
-    // (cur, the staged K block) passes from step to step whatever their kind.
-    auto step = [&](int k, auto interior) {
-      constexpr bool kInterior = decltype(interior)::value;
-      const bool more = k + 1 < k1;      // wave-uniform
-      wait_lds_reads();                  // the previous block's reads of the staged V are done
-      __builtin_amdgcn_wave_barrier();
-      sm.stage_v(Vh, cur, lane, ldsv);
-      const BlockInfo nxt = sa.place(more ? k + 1 : k);
-      wait_loads_except<4>();            // K block k is older than the 4 V copies just issued
-      __builtin_amdgcn_wave_barrier();
-      half8 kf[4];
-      read_k(ldsk, n, h, kf);
-      wait_lds_reads();                  // the K buffer may be overwritten now
-      __builtin_amdgcn_wave_barrier();
-      if (more) sm.stage_k(Kh, nxt, lane, ldsk);
-      half8 pha[2], phb[2];
-      if constexpr (kInterior) {
-        // One stretch of straight-line code: the products of one sub-tile run on the matrix cores
-        // while the vector unit works on the other's softmax, and the V^T operand reads are all
-        // in flight before the first PV product.
-        floatx16 s_a = {0}, s_b = {0};
-#pragma unroll
-        for (int t = 0; t < 4; ++t) s_a = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qf[t], s_a, 0, 0, 0);
-#pragma unroll
-        for (int t = 0; t < 4; ++t) s_b = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qb[t], s_b, 0, 0, 0);
-        const float bm_a = block_max(s_a, c, h), bm_b = block_max(s_b, c, h);
-        if (__any(needs_rescale(sta, bm_a) || needs_rescale(stb, bm_b))) {
-          rescale_state(sta, bm_a);
-          rescale_state(stb, bm_b);
-        }
-        numerators_h(s_a, c, sta, pha);
-        numerators_h(s_b, c, stb, phb);
-        // V block k is older than the 4 K copies issued above (if any)
-        if (more) wait_loads_except<4>(); else wait_loads_except<0>();
-        __builtin_amdgcn_wave_barrier();
-        half8 va[2][2];
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int cb = 0; cb < 2; ++cb) va[u][cb] = read_va(vt, u, cb);
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int cb = 0; cb < 2; ++cb) {
-            sta.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[u][cb], pha[u], sta.o[cb], 0, 0, 0);
-            stb.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va[u][cb], phb[u], stb.o[cb], 0, 0, 0);
-          }
-      } else {
-        const int class_a = sa.classify(k), class_b = sb.classify(k);     // wave-uniform
-        if (class_a) {
-          floatx16 sacc = {0};
-#pragma unroll
-          for (int t = 0; t < 4; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qf[t], sacc, 0, 0, 0);
-          const uint32_t word = class_a == 2 ? ~0u : sa.get(k, n).word;
-          softmax_block_h(sacc, c, class_a == 2, word, h, sta, pha);
-        }
-        if (class_b) {
-          floatx16 sacc = {0};
-#pragma unroll
-          for (int t = 0; t < 4; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], qb[t], sacc, 0, 0, 0);
-          const uint32_t word = class_b == 2 ? ~0u : sb.get(k, n).word;
-          softmax_block_h(sacc, c, class_b == 2, word, h, stb, phb);
-        }
-        if (more) wait_loads_except<4>(); else wait_loads_except<0>();
-        __builtin_amdgcn_wave_barrier();
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-          for (int cb = 0; cb < 2; ++cb) {
-            const half8 va = read_va(vt, u, cb);
-            if (class_a) sta.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pha[u], sta.o[cb], 0, 0, 0);
-            if (class_b) stb.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, phb[u], stb.o[cb], 0, 0, 0);
-          }
-      }
-      cur = nxt;
-    };
-    // The blocks interior to both sub-tiles form one range [k_lo, k_hi): a few edge blocks, the
-    // interior in a loop of its own (no branch on the block's kind inside it), a few edge blocks.
-    int k_lo = 0, k_hi = k1;
-    while (k_lo < k1 && !(sa.classify(k_lo) == 2 && sb.classify(k_lo) == 2)) ++k_lo;
-    while (k_hi > k_lo && !(sa.classify(k_hi - 1) == 2 && sb.classify(k_hi - 1) == 2)) --k_hi;
-    int k = 0;
-    for (; k < k_lo; ++k) step(k, std::false_type{});
-    for (; k < k_hi; ++k) step(k, std::true_type{});
-    for (; k < k1; ++k) step(k, std::false_type{});
   }
 
   // Explicit block lists: as run_ldsk, with no vector load into registers inside the loop.  Block
@@ -2214,57 +2142,199 @@ __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
                           accumulate != 0);
 }
 
-// fp16 window masks, 64 queries per wavefront: two neighbouring 32-query sub-tiles share every
-// K and V block they both need (CoreF16::run_pair), which roughly halves the staging, the LDS
-// operand reads and the per-tile set-up per query.  Same grid mapping as tile_window_kernel
-// with 256 queries per workgroup.
-__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_pair_kernel(
+// fp16 window masks, wide bands: a workgroup owns 256 consecutive queries of a class (64 per
+// wavefront: two 32-query sub-tiles that share every K fragment and V^T operand read, with two
+// independent chains of products) and walks the key blocks of its
+// whole window once, in step: every K and V block is copied global -> LDS once per workgroup
+// (each wavefront moves one 1 KB copy of K and one of V per block instead of all eight), into a
+// ring of kBandSlots blocks that runs kBandAhead blocks ahead of the block being computed.  One
+// workgroup barrier per block both publishes the block (every wavefront has waited for its own
+// two copies) and retires the block before it (its slot is the next one to be overwritten).
+// A wavefront computes a block only where it lies inside its own window (its queries start 64w
+// keys into the workgroup's range, so it idles for two blocks per wavefront index at one end or
+// the other).  The copies are issued untracked: every wavefront issues exactly two per block, so
+// a counted wait names the block that must have landed; past the last block the copies repeat
+// the last block into a slot nobody reads any more, which keeps the count constant to the end.
+constexpr int kBandSlots = 8;
+constexpr int kBandAhead = 6;      // <= kBandSlots - 2: the slot written holds a block retired a barrier ago
+
+__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_band_kernel(
     const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
     __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
     float scale, int accumulate, int64_t seg_len) {
-  constexpr int kLds = 2 * CoreF16::kBlockBytes;
-  __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
+  constexpr int kSlotBytes = 2 * CoreF16::kBlockBytes;       // K block, then V block
+  __shared__ __attribute__((aligned(16))) char ring[kBandSlots * kSlotBytes];
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int n = lane & 31, h = lane >> 5;
-  char* lds = lds_all + wave * kLds;
   const int64_t chunk = gridDim.x / 8;
   const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
   WindowSlot slot;
-  if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;
+  if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;      // (the whole workgroup leaves)
   const int64_t p = slot.p, Lc = slot.Lc;
-  const int64_t u0 = (slot.grp * 4 + wave) * (2 * kTile);
-  if (u0 >= Lc) return;
+  const int64_t q0 = slot.grp * (8 * kTile);
+  if (q0 >= Lc) return;
   const int64_t hd = blockIdx.y;
   const int64_t hoff = hd * L * kHeadDim;
-  const int64_t vlo = u0 - W > 0 ? u0 - W : 0;
-  const int64_t vhi = u0 + 2 * kTile - 1 + W < Lc - 1 ? u0 + 2 * kTile - 1 + W : Lc - 1;
-  const WindowBlocks sa{vlo, Lc, s, p, u0, W}, sb{vlo, Lc, s, p, u0 + kTile, W};
-  const int nblk = (int)((vhi - vlo) / kTile + 1);
+  const int64_t u0 = q0 + (int64_t)wave * (2 * kTile);
+  const int64_t vfirst = q0 - W > 0 ? q0 - W : 0;
+  const int64_t vlast = q0 + 8 * kTile - 1 + W < Lc - 1 ? q0 + 8 * kTile - 1 + W : Lc - 1;
+  const int nblk = (int)((vlast - vfirst) / kTile + 1);
+  // a wavefront whose queries lie past the end of the class (u0 >= Lc) still copies and meets the
+  // barriers; classify() then reports no block as its own
+  const WindowBlocks sa{vfirst, Lc, s, p, u0, W}, sb{vfirst, Lc, s, p, u0 + kTile, W};
   const int64_t ua = u0 + n, ub = u0 + kTile + n;
   const bool exists_a = ua < Lc, exists_b = ub < Lc;
   const int64_t qrow_a = s * (exists_a ? ua : Lc - 1) + p, qrow_b = s * (exists_b ? ub : Lc - 1) + p;
   CoreF16 core, core_b;
   core.load_q(Q + hoff + qrow_a * kHeadDim, h, scale < 0.f);
   core_b.load_q(Q + hoff + qrow_b * kHeadDim, h, scale < 0.f);
+  wait_loads_except<0>();            // Q has arrived: from here on only the ring's copies are counted
+  core.q_arrived();
+  core_b.q_arrived();
+  // this wavefront's share of a block: keys 8w .. 8w+7, eight lanes of 16 bytes per 128-byte row
+  // (the K chunks swizzled as CoreF16::read_k expects)
+  const int r_own = 8 * wave + (lane >> 3), c_own = lane & 7;
+  const char* Kb = reinterpret_cast<const char*>(K + hoff);
+  const char* Vb = reinterpret_cast<const char*>(V + hoff);
+  auto issue = [&](int kb) {
+    const int kc = kb < nblk ? kb : nblk - 1;
+    int64_t v = vfirst + (int64_t)kc * kTile + r_own;
+    v = v < Lc ? v : Lc - 1;                               // keys past the end re-read the last one (masked off)
+    const int64_t row_bytes = (s * v + p) * (kHeadDim * 2);
+    char* dst = ring + (kb % kBandSlots) * kSlotBytes + wave * 1024;
+    copy16_to_lds_untracked(Kb + row_bytes + ((c_own ^ (r_own & 7)) * 16), dst);
+    copy16_to_lds_untracked(Vb + row_bytes + c_own * 16, dst + CoreF16::kBlockBytes);
+  };
   TileState sta, stb;
   sta.init();
   stb.init();
-  wait_loads_except<0>();     // Q has arrived: the block loop counts only its own copies
-  core.q_arrived();
-  core_b.q_arrived();
-  core.run_pair(core_b.qf, K + hoff, V + hoff, sa, sb, nblk, softmax_factor(scale), lane, sta, stb, lds);
+  const float c = softmax_factor(scale);
+  const char* vt0 = CoreF16::vt_base(ring + CoreF16::kBlockBytes, lane, h);
+  // The barrier that opens block kb: every wavefront has waited for its own copies of blocks kb
+  // and kb+1 (so after it both are whole: the interior steps read K of block kb+1 for the score
+  // products they issue one block ahead), and everyone is done with block kb-1; then the copy
+  // kBandAhead blocks on is started, into the slot of block kb-2.
+  auto publish = [&](int kb) {
+    wait_loads_except<2 * (kBandAhead - 2)>();
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    issue(kb + kBandAhead);
+  };
+  // One block on the edge of (or outside) this wavefront's windows: publish it, compute what
+  // falls inside.
+  auto step = [&](int kb) {
+    publish(kb);
+    const char* ldsk = ring + (kb % kBandSlots) * kSlotBytes;
+    const char* vt = vt0 + (kb % kBandSlots) * kSlotBytes;
+    half8 pha[2], phb[2];
+    {
+      const int class_a = sa.classify(kb), class_b = sb.classify(kb);     // wave-uniform
+      if (class_a | class_b) {
+        half8 kf[4];
+        CoreF16::read_k(ldsk, n, h, kf);
+        if (class_a) {
+          floatx16 sacc = {0};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], core.qf[t], sacc, 0, 0, 0);
+          const uint32_t word = class_a == 2 ? ~0u : sa.get(kb, n).word;
+          softmax_block_h(sacc, c, class_a == 2, word, h, sta, pha);
+        }
+        if (class_b) {
+          floatx16 sacc = {0};
+#pragma unroll
+          for (int t = 0; t < 4; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], core_b.qf[t], sacc, 0, 0, 0);
+          const uint32_t word = class_b == 2 ? ~0u : sb.get(kb, n).word;
+          softmax_block_h(sacc, c, class_b == 2, word, h, stb, phb);
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+          for (int cb = 0; cb < 2; ++cb) {
+            const half8 va = CoreF16::read_va(vt, u, cb);
+            if (class_a) sta.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, pha[u], sta.o[cb], 0, 0, 0);
+            if (class_b) stb.o[cb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va, phb[u], stb.o[cb], 0, 0, 0);
+          }
+      }
+    }
+  };
+  // the blocks interior to both of this wavefront's sub-tiles form one range [k_lo, k_hi)
+  int k_lo = 0, k_hi = nblk;
+  while (k_lo < nblk && !(sa.classify(k_lo) == 2 && sb.classify(k_lo) == 2)) ++k_lo;
+  while (k_hi > k_lo && !(sa.classify(k_hi - 1) == 2 && sb.classify(k_hi - 1) == 2)) --k_hi;
+  // Interior blocks, software-pipelined: the score products of block kb+1 are issued ahead of the
+  // exponentials and the PV products of block kb, so that the matrix cores and the vector unit
+  // have independent work side by side.  cur_* hold the scores of block kb on entry (kFirst: the
+  // step computes them itself), nxt_* receive those of block kb+1 (kNext: it is interior too);
+  // successive steps swap the two pairs, so no accumulator is ever copied.
+  auto products = [&](int kb, floatx16& da, floatx16& db) {
+    half8 kf[4];
+    CoreF16::read_k(ring + (kb % kBandSlots) * kSlotBytes, n, h, kf);
+    da = floatx16{0};
+    db = floatx16{0};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) da = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], core.qf[t], da, 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) db = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], core_b.qf[t], db, 0, 0, 0);
+  };
+  auto piped = [&](int kb, floatx16& cur_a, floatx16& cur_b, floatx16& nxt_a, floatx16& nxt_b, auto first,
+                   auto next) {
+    publish(kb);
+    if constexpr (decltype(first)::value) products(kb, cur_a, cur_b);
+    if constexpr (decltype(next)::value) products(kb + 1, nxt_a, nxt_b);
+    half8 pha[2], phb[2];
+    softmax_pair_h(cur_a, cur_b, c, h, sta, stb, pha, phb);
+    const char* vt = vt0 + (kb % kBandSlots) * kSlotBytes;
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+      const half8 va0 = CoreF16::read_va(vt, u, 0), va1 = CoreF16::read_va(vt, u, 1);
+      sta.o[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va0, pha[u], sta.o[0], 0, 0, 0);
+      stb.o[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va0, phb[u], stb.o[0], 0, 0, 0);
+      sta.o[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va1, pha[u], sta.o[1], 0, 0, 0);
+      stb.o[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(va1, phb[u], stb.o[1], 0, 0, 0);
+    }
+  };
+  for (int kb = 0; kb < kBandAhead; ++kb) issue(kb);
+  int kb = 0;
+  for (; kb < k_lo; ++kb) step(kb);
+  if (kb < k_hi) {
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    floatx16 s_a, s_b, t_a, t_b;
+    if (kb + 1 < k_hi) {
+      piped(kb, s_a, s_b, t_a, t_b, yes, yes);
+      ++kb;                                              // the scores of block kb are in t_*
+      for (; kb + 2 < k_hi; kb += 2) {
+        piped(kb, t_a, t_b, s_a, s_b, no, yes);
+        piped(kb + 1, s_a, s_b, t_a, t_b, no, yes);
+      }
+      if (kb + 1 < k_hi) {
+        piped(kb, t_a, t_b, s_a, s_b, no, yes);
+        piped(kb + 1, s_a, s_b, t_a, t_b, no, no);
+      } else {
+        piped(kb, t_a, t_b, s_a, s_b, no, no);
+      }
+    } else {
+      piped(kb, s_a, s_b, t_a, t_b, yes, no);
+    }
+    kb = k_hi;
+  }
+  for (; kb < nblk; ++kb) step(kb);
+  // every copy has landed and every wavefront is done with the ring: its space takes the output tiles
+  wait_loads_except<0>();
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  if (u0 >= Lc) return;
   float* lse_h = lse ? lse + hd * L : nullptr;
   if (accumulate) {
     finish_tile<__half>(O + hoff, lse_h, qrow_a, qrow_a, exists_a, sta, h, true);
     finish_tile<__half>(O + hoff, lse_h, qrow_b, qrow_b, exists_b, stb, h, true);
   } else {
-    static_assert(CoreF16::kTileBytes <= kLds, "output tile fits the wavefront's LDS");
+    char* lds = ring + wave * (2 * CoreF16::kTileBytes);
     const int64_t left = Lc - u0;
     finish_tile_rows<__half>(O + hoff, lse_h, s * u0 + p, s, left < kTile ? (int)left : kTile, sta, lane, lds);
     if (left > kTile)
       finish_tile_rows<__half>(O + hoff, lse_h, s * (u0 + kTile) + p, s,
-                               left < 2 * kTile ? (int)(left - kTile) : kTile, stb, lane, lds);
+                               left < 2 * kTile ? (int)(left - kTile) : kTile, stb, lane,
+                               lds + CoreF16::kTileBytes);
   }
 }
 
@@ -2360,7 +2430,7 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
       const BlockInfo b = src.get(k, n);
       half8 kf[4];
       CoreF16::read_k(lds_k + k * CoreF16::kBlockBytes, n, h, kf);
-      core.block_math(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, -1);
+      core.template block_math<-1>(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, false);
     }
   };
   if (vlast - vfirst + 1 == kWgBlocks * kTile) {
@@ -2584,7 +2654,7 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const dim3 grid((unsigned)n_wg, (unsigned)a.H);
   const int acc = a.accumulate ? 1 : 0;
   if (a.dtype == SGA_F32) clear_unselected_rows<float>(a); else clear_unselected_rows<__half>(a);
-  profile_mark_begin(a.stream, wg ? "tile_window_wg_kernel" : pair ? "tile_window_pair_kernel" : "tile_window_kernel");
+  profile_mark_begin(a.stream, wg ? "tile_window_wg_kernel" : pair ? "tile_window_band_kernel" : "tile_window_kernel");
   if (wg) {
     const int nb_max = (int)((4 * kTile - 1 + 2 * (int64_t)a.window) / kTile + 1);
     int64_t Lq = a.L / s, Lr = a.L % s;             // class lengths, see the kernel
@@ -2598,7 +2668,7 @@ sga_status run_tile_implicit(const AttnArgs& a) {
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
                        (int64_t)a.window, s, n_groups, a.scale, acc, nb_max, shape.seg_len, Lq, Lr);
   } else if (pair) {
-    hipLaunchKernelGGL(tile_window_pair_kernel, grid, dim3(256), 0, a.stream,
+    hipLaunchKernelGGL(tile_window_band_kernel, grid, dim3(256), 0, a.stream,
                        static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
                        static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
                        (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len);
