@@ -593,6 +593,9 @@ def main():
                     help="explicit workloads: build the mask and prepare its tile graph once, "
                          "then time sga_attention_forward_prepared alone (the steady state that "
                          "the default line reports under steady_state)")
+    ap.add_argument("--no-steady", action="store_true",
+                    help="explicit workloads: skip the steady-state leg (prepared graph), so that a "
+                         "profile of the run holds unprepared forwards only")
     ap.add_argument("--traffic-summary", default=None, metavar="DIR",
                     help="no GPU work: read the rocprofv3 --pmc csv files under DIR (see "
                          "traffic_summary) for --workload [--prepared], print the per-kernel HBM "
@@ -661,7 +664,7 @@ def main():
         cf, ck = run.cold()
         out["cold_cache"] = {"forward_ms": cf, "kernel_ms": ck,
                              "how": "1 GiB scratch buffer overwritten before every launch, 5 launches"}
-    if wl.explicit and not run.prepared:
+    if wl.explicit and not run.prepared and not args.no_steady:
         out["steady_state"] = steady_state(run, args.steps, args.warmup, args.path)
     if not args.no_cpu and not run.random:      # (the row-scan oracle takes mask predicates, not drawn CSR arrays)
         out["cpu_baseline"] = cpu_baseline(wl, run)
