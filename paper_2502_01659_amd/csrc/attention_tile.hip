@@ -1436,10 +1436,28 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
   for (int64_t w = (int64_t)blockIdx.x * waves + threadIdx.x / kWave; w < pl.n_work;
        w += (int64_t)gridDim.x * waves) {
-    const WorkId id = locate_work(row_ptr, L, pl.seg_shift, pl.n_tiles, pl.n_work, w, lane);
+    WorkId id = locate_work(row_ptr, L, pl.seg_shift, pl.n_tiles, pl.n_work, w, lane);
     if (id.seg >= id.nseg) {          // spare item of a tile whose edge range crosses a multiple of S
       if (lane == 0) items[w].tile = -1;
       continue;
+    }
+    if (id.nseg > 1) {
+      // Four neighbouring tiles that are all cut into the same number of segments (rows of global
+      // tokens: every tile spans the whole key range) trade segments among their items so that
+      // consecutive items hold the same segment of the four tiles.  The items of a workgroup
+      // of the static schedule then stream the same K and V blocks at the same time, instead of
+      // each tile passing over all keys on its own (workload 4: the four global tiles of a head
+      // otherwise fetch K and V four times).  The j-th (tile, segment) pair of the quad in
+      // tile-major order computes pair number j in segment-major order: a permutation of the
+      // same 4 * nseg pairs, a function of the mask alone.
+      const int64_t g = id.tile & ~int64_t(3);
+      bool same = g + 3 < pl.n_tiles;
+      for (int64_t q = g; same && q < g + 4; ++q) same = tile_segments(row_ptr, L, pl.seg_shift, q) == id.nseg;
+      if (same) {
+        const int64_t j = (id.tile - g) * id.nseg + id.seg;
+        id.tile = g + (j & 3);
+        id.seg = (int32_t)(j >> 2);
+      }
     }
     const int64_t t = id.tile;
     const int64_t row_first = t * kTile;
