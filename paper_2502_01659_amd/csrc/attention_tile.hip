@@ -467,18 +467,6 @@ struct StageMap {
       }
     }
   }
-  // stage_k and stage_v of a whole block with untracked copies
-  __device__ void stage_whole_untracked(const T* __restrict__ Kh, const T* __restrict__ Vh, int64_t row0,
-                                        char* dst_k, char* dst_v) const {
-    const char* kb = reinterpret_cast<const char*>(Kh) + row0 * kGlobalRowBytes;
-    const char* vb = reinterpret_cast<const char*>(Vh) + row0 * kGlobalRowBytes;
-#pragma unroll
-    for (int i = 0; i < kCopies; ++i)
-      copy16_to_lds_untracked(kb + i * kRows * stride_bytes + koff[kLanes == 8 ? 0 : i % 4], dst_k + i * 1024);
-#pragma unroll
-    for (int i = 0; i < kCopies; ++i)
-      copy16_to_lds_untracked(vb + i * kRows * stride_bytes + voff, dst_v + i * 1024);
-  }
   __device__ void stage_k(const T* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) const {
     if (b.nvalid == kTile) {
       const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * kGlobalRowBytes;
@@ -2357,7 +2345,8 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
 }
 
 // fp16 window masks narrow enough that the keys of 128 consecutive queries fit the LDS
-// (128 + 2W <= 256 keys: K and V blocks of 8 x 32 keys, 64 KB).  A workgroup owns 128 queries
+// (128 + 2W <= 256 keys: 8 key blocks; this kernel takes the windows of up to 6 blocks, K and V
+// side by side in 48 KB at most, tile_window_kv_kernel those of 7 and 8).  A workgroup owns 128 queries
 // of one residue class: its four wavefronts first copy every K and V block the workgroup
 // needs global -> LDS, once (wavefront w copies blocks w, w+4), and after one barrier each
 // wavefront runs its own 32-query sub-tile entirely out of LDS.  Compared with one wavefront
@@ -2451,34 +2440,10 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
       core.template block_math<-1>(kf, b, c, lane, h, st, lds_v + k * CoreF16::kBlockBytes, false);
     }
   };
-  if (vlast - vfirst + 1 == kWgBlocks * kTile) {
-    // A full window of whole blocks, every wavefront copies two of them: the four middle blocks
-    // (2..5; wavefront w needs blocks w..w+4, so each has three or four of them to work on) are
-    // computed on while blocks 0, 1, 6 and 7 are still on their way.  The copies are issued untracked
-    // (see copy16_to_lds_untracked), the second round once Q and the first have arrived (the
-    // waits ask for every operation in flight: no order between loads into registers and
-    // copies to LDS is assumed), and the first barrier is a plain one: __syncthreads() would
-    // wait for every copy.
-    auto stage_whole = [&](int j) {
-      sm.stage_whole_untracked(K + hoff, V + hoff, s * (vfirst + (int64_t)j * kTile) + p,
-                               lds_k + j * CoreF16::kBlockBytes, lds_v + j * CoreF16::kBlockBytes);
-    };
-    stage_whole(2 + wave);
-    wait_loads_except<0>();
-    core.q_arrived();
-    stage_whole(wave < 2 ? wave : wave + 4);
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    blocks(k_lo > 2 ? k_lo : 2, k_hi < 5 ? k_hi : 5);
-    wait_loads_except<0>();
-    __syncthreads();
-    blocks(k_lo, k_hi < 1 ? k_hi : 1);
-    blocks(k_lo > 6 ? k_lo : 6, k_hi);
-  } else {
-    for (int j = wave; j < nb; j += 4) stage(j);
-    wait_loads_except<0>();
-    __syncthreads();
-    blocks(k_lo, k_hi);
-  }
+  for (int j = wave; j < nb; j += 4) stage(j);
+  wait_loads_except<0>();
+  __syncthreads();
+  blocks(k_lo, k_hi);
   float* lse_h = lse ? lse + hd * L : nullptr;
   if (accumulate) {
     if (active) finish_tile<__half>(O + hoff, lse_h, qrow, qrow, exists, st, h, true);
@@ -2486,6 +2451,156 @@ __global__ __launch_bounds__(256) void tile_window_wg_kernel(
   }
   // every wavefront is done with the staged blocks: their space takes the four output tiles
   // (at least 4 K and 4 V blocks are allocated, 32 KB)
+  __syncthreads();
+  if (active)
+    finish_tile_rows<__half>(O + hoff, lse_h, s * u0 + p, s, Lc - u0 < kTile ? (int)(Lc - u0) : kTile, st,
+                             lane, lds_wg + wave * CoreF16::kTileBytes);
+}
+
+// softmax_block_h for a caller that accumulates the PV products later: only m and l are kept
+// here (st.o is not touched); the numerators of the block are taken against the m the block leaves
+// behind, which the caller records.
+__device__ __forceinline__ void softmax_block_deferred(floatx16 sv, float c, bool full, uint32_t word,
+                                                       int h, TileState& st, half8 (&ph)[2]) {
+  if (!full) mask_scores(sv, word, h);
+  const float l_before = st.l;
+  numerators_h(sv, c, st, ph);
+  if (__any(sum_overflowed(st))) {
+    const float bm = block_max(sv, c, h);
+    const float m_new = needs_rescale(st, bm) ? bm : st.m;
+    st.l = l_before * __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+    numerators_h(sv, c, st, ph);
+  }
+}
+
+// The same windows as tile_window_wg_kernel at their widest (7 or 8 key blocks per workgroup),
+// with K and V taking turns in ONE set of LDS blocks: the workgroup copies its K blocks, every
+// wavefront takes the scores and softmax numerators of its sub-tile against them (numerators and
+// the running max each block left behind stay in registers: at most kKvWaveBlocks blocks meet a
+// 32-query sub-tile), and after a barrier the V blocks are copied over the K blocks and the PV
+// products follow, O rescaled where the recorded max changes, exactly as the online form does.
+// Half the LDS (32 KB for 8 blocks) and under 128 registers: four workgroups per CU instead of
+// two, so that the copies of one workgroup overlap the arithmetic of three others.
+// (blocks start at the workgroup's first key, W below it: sub-tile w covers blocks w .. w + (31 + 2W) / 32
+// of them, and in the first workgroup of a class, where the window is cut at key 0, at most
+// 2 * ceil(W / 32) + 1: five blocks at most for W <= 64)
+constexpr int kKvWaveBlocks = 5;
+constexpr int kKvMinBlocks = 7;     // windows of this many blocks per workgroup take this kernel
+
+__global__ __launch_bounds__(256) void tile_window_kv_kernel(
+    const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
+    __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
+    float scale, int accumulate, int nb_max, int64_t seg_len, int64_t Lq, int64_t Lr) {
+  extern __shared__ __attribute__((aligned(16))) char lds_wg[];      // max(nb_max, 5) blocks
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  // (placement of the workgroup among the window tiles: see tile_window_wg_kernel)
+  const uint32_t chunk = gridDim.x / 8;
+  const uint32_t bid = (blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  int64_t p, Lc, q0;
+  if (seg_len > 0) {
+    const uint32_t ng32 = (uint32_t)n_groups;
+    const uint32_t seg = bid / ng32;
+    p = (int64_t)seg * seg_len;
+    if (p >= L) return;
+    Lc = p + seg_len <= L ? Lq : Lr;
+    q0 = (int64_t)(bid - seg * ng32) * (4 * kTile);
+  } else {
+    if ((int64_t)bid >= n_groups * s) return;
+    const uint32_t s32 = (uint32_t)s;
+    const uint32_t grp = bid / s32;
+    p = bid - grp * s32;
+    Lc = Lq + (p < Lr ? 1 : 0);
+    q0 = (int64_t)grp * (4 * kTile);
+  }
+  p = uniform64(p);
+  Lc = uniform64(Lc);
+  q0 = uniform64(q0);
+  if (q0 >= Lc) return;                            // (the whole workgroup leaves: no barrier is missed)
+  const int64_t hd = blockIdx.y;
+  const int64_t hoff = hd * L * kHeadDim;
+  const int64_t vfirst = q0 - W > 0 ? q0 - W : 0;
+  const int64_t vlast = q0 + 4 * kTile - 1 + W < Lc - 1 ? q0 + 4 * kTile - 1 + W : Lc - 1;
+  const int nb = (int)((vlast - vfirst) / kTile + 1);          // <= kWgBlocks
+  const int64_t u0 = q0 + (int64_t)wave * kTile;
+  const int64_t u = u0 + n;
+  const bool exists = u < Lc;
+  const int64_t qrow = s * (exists ? u : Lc - 1) + p;
+  CoreF16 core;
+  core.load_q(Q + hoff + qrow * kHeadDim, h, scale < 0.f);
+  CoreF16::Stage sm;
+  sm.init(s, lane);
+  auto block_at = [&](int j) {
+    BlockInfo b;
+    const int64_t v0 = vfirst + (int64_t)j * kTile;
+    b.raw = 0;
+    b.row0 = s * v0 + p;
+    b.nvalid = Lc - v0 < kTile ? (int)(Lc - v0) : kTile;
+    b.word = 0;
+    b.full = false;
+    return b;
+  };
+  const bool active = u0 < Lc;                     // (a wavefront without queries still meets the barriers below)
+  const int64_t rem64 = Lc - vfirst, nq64 = Lc - u0;
+  const WindowWordsNear src{(int)(u0 - vfirst), (int)W, (int)(nq64 > 64 ? 64 : (nq64 > 0 ? nq64 : 0)),
+                            (int)(rem64 > (1 << 20) ? (1 << 20) : rem64)};
+  const int64_t lo_key = u0 - W > vfirst ? u0 - W : vfirst;
+  const int64_t hi_key = u0 + kTile - 1 + W < vlast ? u0 + kTile - 1 + W : vlast;
+  const int k_lo = (int)((lo_key - vfirst) / kTile);
+  const int k_hi = active ? (int)((hi_key - vfirst) / kTile) : k_lo - 1;     // k_hi - k_lo < kKvWaveBlocks
+  const float c = softmax_factor(scale);
+  // K blocks of the workgroup, then this sub-tile's scores and numerators
+  for (int j = wave; j < nb; j += 4) sm.stage_k(K + hoff, block_at(j), lane, lds_wg + j * CoreF16::kBlockBytes);
+  wait_loads_except<0>();
+  __syncthreads();
+  TileState st;
+  st.init();
+  half8 ph[kKvWaveBlocks][2];
+  float m_after[kKvWaveBlocks];
+#pragma unroll
+  for (int j = 0; j < kKvWaveBlocks; ++j) {
+    const int k = k_lo + j;
+    m_after[j] = st.m;
+    if (k <= k_hi) {
+      const BlockInfo b = src.get(k, n);
+      half8 kf[4];
+      CoreF16::read_k(lds_wg + k * CoreF16::kBlockBytes, n, h, kf);
+      floatx16 sacc = {0};
+#pragma unroll
+      for (int t = 0; t < 4; ++t) sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], core.qf[t], sacc, 0, 0, 0);
+      softmax_block_deferred(sacc, c, b.full != 0, b.word, h, st, ph[j]);
+      m_after[j] = st.m;
+    }
+  }
+  __syncthreads();                                 // every wavefront has read its K blocks
+  for (int j = wave; j < nb; j += 4) sm.stage_v(V + hoff, block_at(j), lane, lds_wg + j * CoreF16::kBlockBytes);
+  wait_loads_except<0>();
+  __syncthreads();
+  float m_run = m_after[0];
+#pragma unroll
+  for (int j = 0; j < kKvWaveBlocks; ++j) {
+    const int k = k_lo + j;
+    if (k <= k_hi) {
+      if (__any(m_after[j] != m_run)) {
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_after[j]);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          st.o[0][r] *= alpha;
+          st.o[1][r] *= alpha;
+        }
+        m_run = m_after[j];
+      }
+      CoreF16::accumulate(ph[j], lane, h, st, lds_wg + k * CoreF16::kBlockBytes);
+    }
+  }
+  float* lse_h = lse ? lse + hd * L : nullptr;
+  if (accumulate) {
+    if (active) finish_tile<__half>(O + hoff, lse_h, qrow, qrow, exists, st, h, true);
+    return;
+  }
+  // every wavefront is done with the staged blocks: their space takes the four output tiles
   __syncthreads();
   if (active)
     finish_tile_rows<__half>(O + hoff, lse_h, s * u0 + p, s, Lc - u0 < kTile ? (int)(Lc - u0) : kTile, st,
@@ -2672,19 +2787,27 @@ sga_status run_tile_implicit(const AttnArgs& a) {
   const dim3 grid((unsigned)n_wg, (unsigned)a.H);
   const int acc = a.accumulate ? 1 : 0;
   if (a.dtype == SGA_F32) clear_unselected_rows<float>(a); else clear_unselected_rows<__half>(a);
-  profile_mark_begin(a.stream, wg ? "tile_window_wg_kernel" : pair ? "tile_window_band_kernel" : "tile_window_kernel");
+  const int nb_max = (int)((4 * kTile - 1 + 2 * (int64_t)a.window) / kTile + 1);   // key blocks of 128 queries
+  const bool kv = wg && nb_max >= kKvMinBlocks;
+  profile_mark_begin(a.stream, kv ? "tile_window_kv_kernel" : wg ? "tile_window_wg_kernel"
+                               : pair ? "tile_window_band_kernel" : "tile_window_kernel");
   if (wg) {
-    const int nb_max = (int)((4 * kTile - 1 + 2 * (int64_t)a.window) / kTile + 1);
     int64_t Lq = a.L / s, Lr = a.L % s;             // class lengths, see the kernel
     if (shape.seg_len > 0) {
       const int64_t last_len = a.L - (a.L - 1) / shape.seg_len * shape.seg_len;
       Lq = (shape.seg_len + s - 1) / s;
       Lr = (last_len + s - 1) / s;
     }
-    hipLaunchKernelGGL(tile_window_wg_kernel, grid, dim3(256), (size_t)nb_max * 2 * CoreF16::kBlockBytes,
-                       a.stream, static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
-                       static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
-                       (int64_t)a.window, s, n_groups, a.scale, acc, nb_max, shape.seg_len, Lq, Lr);
+    if (kv)
+      hipLaunchKernelGGL(tile_window_kv_kernel, grid, dim3(256), (size_t)(nb_max > 5 ? nb_max : 5) * CoreF16::kBlockBytes,
+                         a.stream, static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
+                         static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
+                         (int64_t)a.window, s, n_groups, a.scale, acc, nb_max, shape.seg_len, Lq, Lr);
+    else
+      hipLaunchKernelGGL(tile_window_wg_kernel, grid, dim3(256), (size_t)nb_max * 2 * CoreF16::kBlockBytes,
+                         a.stream, static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
+                         static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
+                         (int64_t)a.window, s, n_groups, a.scale, acc, nb_max, shape.seg_len, Lq, Lr);
   } else if (pair) {
     hipLaunchKernelGGL(tile_window_band_kernel, grid, dim3(256), 0, a.stream,
                        static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),

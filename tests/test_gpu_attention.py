@@ -384,7 +384,11 @@ def _close(O, lse, O_ref, lse_ref, dtype, factor=1.0):
     MaskSpec(KIND_DILATED_2D, 640, block=64, stride=2),
     MaskSpec(KIND_DILATED_2D, 1000, block=96, stride=3),
     MaskSpec(KIND_DILATED_2D, 333, block=40, stride=1),
-], ids=lambda s: f"{s.name}-L{s.L}")
+    # classes of 60 and of 64 tokens per block: every key of the class is within 7 or 8 key
+    # blocks of 128 queries (fp16: K and V take turns in the workgroup's LDS blocks)
+    MaskSpec(KIND_DILATED_2D, 1300, block=120, stride=2),
+    MaskSpec(KIND_DILATED_2D, 900, block=64, stride=1),
+], ids=lambda s: f"{s.name}-L{s.L}-b{s.block}")
 def test_nonlocal_and_dilated_2d_masks(spec, dtype):
     """Explicit CSR (every path) and the implicit generators of the global (non-local) and
     2-D dilated masks against the dense oracle; rows without neighbours are the initial state."""
