@@ -678,7 +678,7 @@ def main():
                 continue
             try:
                 r = Runner(w, path)
-                ms, f, b, km = r.timed(5, 2)
+                ms, f, b, km = r.timed(20, 5)      # (each of these steps takes 0.05 to 2.5 ms)
                 e = r.nnz * w.H
                 sweep.append({"workload": name, "L": w.L, "H": w.H, "dtype": w.dtype,
                               "edges_per_step": e, "ms_per_step": ms, "forward_ms": f,
@@ -690,7 +690,7 @@ def main():
                     cf, ck = r.cold()
                     sweep[-1]["cold_cache"] = {"forward_ms": cf, "kernel_ms": ck}
                 if w.explicit:
-                    sweep[-1]["steady_state"] = steady_state(r, 5, 2, args.path)
+                    sweep[-1]["steady_state"] = steady_state(r, 20, 5, args.path)
                 del r
             except Exception as ex:    # a sweep entry must not lose the headline line
                 sweep.append({"workload": name, "error": repr(ex)})
@@ -702,7 +702,7 @@ def main():
             # matrix-core products per product): reported beside the true-fp32 figures, never as them
             try:
                 r = Runner(w2, 3)
-                ms, f, b, km = r.timed(5, 2)
+                ms, f, b, km = r.timed(20, 5)
                 out["split_precision"] = {"workload": w2.name, "path": "tile_split", "ms_per_step": ms,
                                           "forward_ms": f, "build_mask_ms": b,
                                           "forward_edges_per_s": r.nnz * w2.H / (f * 1e-3),
