@@ -1042,7 +1042,9 @@ struct CoreF16T {
       const int r = (lane >> 3) + 8 * i;
       const uint4 v = *reinterpret_cast<const uint4*>(lds + r * kTilePitch + (lane & 7) * 16);
       if (r < n_rows)
-        *reinterpret_cast<uint4*>(Oh + (row0 + r * row_step) * kHeadDim + (lane & 7) * 8) = v;
+        // (written once and not read again by this call: a streaming store keeps the L2 for K and V)
+        __builtin_nontemporal_store(__builtin_bit_cast(half8, v),
+                                    reinterpret_cast<half8*>(Oh + (row0 + r * row_step) * kHeadDim + (lane & 7) * 8));
     }
   }
 };

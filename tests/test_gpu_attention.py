@@ -98,6 +98,8 @@ def test_ragged_and_degenerate_shapes(spec, dtype, path):
     MaskSpec(KIND_SLIDING, 513, window=63),
     MaskSpec(KIND_SLIDING, 513, window=65),      # one key past the workgroup kernel's window
     MaskSpec(KIND_SLIDING, 131, window=16),
+    MaskSpec(KIND_SLIDING, 700, window=32),      # 6 key blocks per workgroup: the widest with K and V side by side
+    MaskSpec(KIND_SLIDING, 700, window=33),      # 7: the narrowest with K, then V, in one set of blocks
     MaskSpec(KIND_SLIDING, 900, window=32),      # 6 whole blocks per interior workgroup
     MaskSpec(KIND_SLIDING, 901, window=48),      # 7
     MaskSpec(KIND_DILATED, 1801, window=40, stride=2),
@@ -105,9 +107,10 @@ def test_ragged_and_degenerate_shapes(spec, dtype, path):
     MaskSpec(KIND_DILATED, 769, window=48, stride=2),
 ], ids=lambda s: f"{s.name}-L{s.L}-w{s.window}")
 def test_window_staging_boundaries(spec, dtype):
-    """Implicit windows on the tile path at the sizes where the staging of the fp16 workgroup
-    kernel changes shape: full 8-block windows (staged in two rounds) next to ragged ones, the
-    widest window that kernel takes and the first one it does not, short sequences."""
+    """Implicit windows on the tile path at the sizes where the fp16 workgroup kernels change
+    shape: windows of 6 key blocks (K and V side by side in LDS) against 7 and 8 (K, then V over
+    it), full 8-block windows next to ragged ones, the widest window the workgroup kernels take
+    and the first one they do not, short sequences."""
     print("case", spec, dtype, flush=True)
     wl = Workload("t", H=2, L=spec.L, d=64, dtype=dtype, sigma=0.8, mask=spec, explicit=False, seed=123)
     Q, K, V = small_inputs(wl)
