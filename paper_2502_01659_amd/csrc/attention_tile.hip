@@ -153,6 +153,14 @@ struct ExplicitBlocks {
     const int64_t left = L - b.row0;
     b.nvalid = left < kTile ? (int)left : kTile;
   }
+  // resolve() for a block that is not the last of its list: lists ascend, so only the last
+  // block of a list can be the one the end of the sequence cuts short.
+  __device__ void resolve_whole(BlockInfo& b) const {
+    const int id = __builtin_amdgcn_readfirstlane(b.raw);
+    b.full = (id & kFullBit) != 0;
+    b.row0 = (int64_t)(id & ~kFullBit) * kTile;
+    b.nvalid = kTile;
+  }
   // Block k without its mask word, read through the scalar (constant) path: the list is only
   // written by an earlier kernel, and a scalar load neither occupies a vector register nor counts
   // among the vector memory operations, so the pipelines' counted waits stay exact.
@@ -450,12 +458,21 @@ struct StageMap {
       for (int i = 0; i < 4; ++i) koff[i] = rowoff + ((lc ^ ((4 * i + lr) & 15)) * 16);
     }
   }
+  // (a block all of whose 32 keys exist)
+  __device__ void stage_v_whole(const T* __restrict__ Vh, int64_t row0, char* dst) const {
+    const char* base = reinterpret_cast<const char*>(Vh) + row0 * kGlobalRowBytes;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i) copy16_to_lds(base + i * kRows * stride_bytes + voff, dst + i * 1024);
+  }
+  __device__ void stage_k_whole(const T* __restrict__ Kh, int64_t row0, char* dst) const {
+    const char* base = reinterpret_cast<const char*>(Kh) + row0 * kGlobalRowBytes;
+#pragma unroll
+    for (int i = 0; i < kCopies; ++i)
+      copy16_to_lds(base + i * kRows * stride_bytes + koff[kLanes == 8 ? 0 : i % 4], dst + i * 1024);
+  }
   __device__ void stage_v(const T* __restrict__ Vh, const BlockInfo& b, int lane, char* dst) const {
     if (b.nvalid == kTile) {
-      const char* base = reinterpret_cast<const char*>(Vh) + b.row0 * kGlobalRowBytes;
-#pragma unroll
-      for (int i = 0; i < kCopies; ++i)
-        copy16_to_lds(base + i * kRows * stride_bytes + voff, dst + i * 1024);
+      stage_v_whole(Vh, b.row0, dst);
     } else {
 #pragma unroll
       for (int i = 0; i < kCopies; ++i) {
@@ -469,10 +486,7 @@ struct StageMap {
   }
   __device__ void stage_k(const T* __restrict__ Kh, const BlockInfo& b, int lane, char* dst) const {
     if (b.nvalid == kTile) {
-      const char* base = reinterpret_cast<const char*>(Kh) + b.row0 * kGlobalRowBytes;
-#pragma unroll
-      for (int i = 0; i < kCopies; ++i)
-        copy16_to_lds(base + i * kRows * stride_bytes + koff[kLanes == 8 ? 0 : i % 4], dst + i * 1024);
+      stage_k_whole(Kh, b.row0, dst);
     } else {
 #pragma unroll
       for (int i = 0; i < kCopies; ++i) {
@@ -951,14 +965,18 @@ struct CoreF16T {
     __builtin_amdgcn_wave_barrier();     // reads of the buffers by an earlier work item are done
     copy4_to_lds(wsrc + (int64_t)k0 * kTile, ldsw + (k0 & 1) * 256);
     sm.stage_k(Kh, b, lane, ldsk);
-    for (int k = k0; k < k1; ++k) {
-      const bool more = k + 1 < k1;      // wave-uniform
-      src.resolve(b1);
+    // One block step.  kInner: blocks k+1 and k+2 exist and blocks k and k+1 are whole (true up
+    // to the list's last two blocks), which leaves no branch on the position in the list and
+    // none on a block cut short by the end of the sequence.
+    auto step = [&](int k, auto inner) {
+      constexpr bool kInner = decltype(inner)::value;
+      const bool more = kInner || k + 1 < k1;      // wave-uniform
+      if (kInner) src.resolve_whole(b1); else src.resolve(b1);
       __builtin_amdgcn_wave_barrier();   // the previous block's reads of V and of the other word slot are done
       if (more) copy4_to_lds(wsrc + (int64_t)(k + 1) * kTile, ldsw + ((k + 1) & 1) * 256);
-      sm.stage_v(Vh, b, lane, ldsv);
+      if (kInner) sm.stage_v_whole(Vh, b.row0, ldsv); else sm.stage_v(Vh, b, lane, ldsv);
       BlockInfo b2 = b1;
-      if (k + 2 < k1) b2 = src.block(k + 2);
+      if (kInner || k + 2 < k1) b2 = src.block(k + 2);
       // K block k and the words of block k are older than the copies issued in this step
       if (more) wait_loads_except<5>(); else wait_loads_except<4>();
       __builtin_amdgcn_wave_barrier();
@@ -967,7 +985,7 @@ struct CoreF16T {
       b.word = *reinterpret_cast<const uint32_t*>(ldsw + (k & 1) * 256 + lane * 4);
       wait_lds_reads();                  // the K buffer may be overwritten now
       __builtin_amdgcn_wave_barrier();
-      if (more) sm.stage_k(Kh, b1, lane, ldsk);
+      if (kInner) sm.stage_k_whole(Kh, b1.row0, ldsk); else if (more) sm.stage_k(Kh, b1, lane, ldsk);
       half8 ph[2];
       scores(kf, b, c, lane, h, st, ph);
       // V block k (and the words of block k+1) are older than the 4 K copies issued above (if any)
@@ -976,7 +994,10 @@ struct CoreF16T {
       accumulate(ph, lane, h, st, ldsv);
       b = b1;
       b1 = b2;
-    }
+    };
+    int k = k0;
+    for (; k + 2 < k1; ++k) step(k, std::true_type{});
+    for (; k < k1; ++k) step(k, std::false_type{});
   }
 
   template <int kPipe>
@@ -1647,7 +1668,7 @@ constexpr uint32_t kXcdRun = 4;   // consecutive workgroups of the static schedu
 // order balances the load and no workgroup has to be re-launched between items).  A segment
 // of a multi-segment tile leaves a partial state.
 template <typename T, int kPipe>
-__global__ __launch_bounds__(256) void tile_attend_kernel(
+__device__ __forceinline__ void tile_attend_body(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
     size_t ws_bytes, int accumulate) {
@@ -1738,6 +1759,24 @@ __global__ __launch_bounds__(256) void tile_attend_kernel(
                           left < kTile ? (int)left : kTile, st, lane, lds);
     }
   }
+}
+
+template <typename T, int kPipe>
+__global__ __launch_bounds__(256) void tile_attend_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L, float scale, void* ws,
+    size_t ws_bytes, int accumulate) {
+  tile_attend_body<T, kPipe>(Q, K, V, O, lse, row_ptr, L, scale, ws, ws_bytes, accumulate);
+}
+
+// fp16 storage: the same body held to the registers of four wavefronts per SIMD (the fp16 items
+// are short and bound by the memory path: the fourth wavefront is worth more than the two
+// registers the allocator would otherwise take beyond 128).
+__global__ __attribute__((amdgpu_waves_per_eu(4, 4))) __launch_bounds__(256) void tile_attend_f16_kernel(
+    const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
+    __half* __restrict__ O, float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L,
+    float scale, void* ws, size_t ws_bytes, int accumulate) {
+  tile_attend_body<__half, kPipeLdsK>(Q, K, V, O, lse, row_ptr, L, scale, ws, ws_bytes, accumulate);
 }
 
 // Head dimensions 128 and 256: one workgroup of kD / 64 wavefronts per work item, wavefront w
@@ -2633,13 +2672,18 @@ sga_status run_tile_explicit(const AttnArgs& a) {
     if (per_head < 1) per_head = 1;
     if (per_head > nwg) per_head = nwg;
   }
-  profile_mark_begin(a.stream, "tile_attend_kernel");
   // fp32 tiles keep the K fragment in registers; fp16 tiles stage K in LDS (measured best)
-  constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
-  constexpr int kPipeAlt = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeSplit;
-  auto kernel = a.split ? tile_attend_kernel<T, kPipeAlt> : tile_attend_kernel<T, kPipe>;
-  hipLaunchKernelGGL(kernel, dim3((unsigned)a.H, (unsigned)per_head), dim3(256), 0, a.stream, Q, K, V, O,
-                     a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
+  const dim3 grid((unsigned)a.H, (unsigned)per_head);
+  if constexpr (DtypeOf<T>::code == SGA_F16) {
+    profile_mark_begin(a.stream, "tile_attend_f16_kernel");
+    hipLaunchKernelGGL(tile_attend_f16_kernel, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.row_ptr,
+                       a.L, a.scale, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
+  } else {
+    profile_mark_begin(a.stream, "tile_attend_kernel");
+    auto kernel = a.split ? tile_attend_kernel<T, kPipeSplit> : tile_attend_kernel<T, kPipeRegK>;
+    hipLaunchKernelGGL(kernel, grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws,
+                       a.ws_bytes, a.accumulate ? 1 : 0);
+  }
   profile_mark_end(a.stream);
   // (a prepared graph knows whether any tile was cut into segments)
   if (!a.prepared || a.plan_multi_tiles > 0)
