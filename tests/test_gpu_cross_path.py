@@ -1,0 +1,105 @@
+"""The tile kernels against the per-row kernels on seeded random shapes.
+
+The two families share no kernel code (matrix-core tiles with block masks against one wavefront
+per row walking the neighbour list), so their agreement on shapes nobody chose by hand (sequence
+lengths that cut tiles, windows on both sides of every kernel switch, random block patterns)
+is a property that holds at sizes the dense oracle does not reach.  Each path is compared with
+the oracle itself in test_gpu_attention.py; here the bar is twice the oracle tolerance, relative
+to 1 + |O|, and the lse of every row must agree, -inf included.  Prepared graphs must reproduce
+the unprepared result bit for bit.
+"""
+import random
+
+import pytest
+
+import paper_2502_01659_amd as sga
+from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD, KIND_NONLOCAL,
+                        KIND_DILATED_2D, torch_qkv)
+from gpu_util import TOL, LSE_TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def _agree(O1, l1, O2, l2, dtype, amp=1.0):
+    import torch
+    assert torch.isfinite(O1.float()).all() and torch.isfinite(O2.float()).all()
+    err = ((O1.float() - O2.float()).abs() / (1.0 + O2.float().abs())).max().item()
+    assert err <= 2 * TOL[dtype] * amp, err
+    inf1, inf2 = ~torch.isfinite(l1), ~torch.isfinite(l2)
+    assert torch.equal(inf1, inf2)
+    if (~inf1).any():
+        assert (l1[~inf1] - l2[~inf1]).abs().max().item() <= 2.5 * LSE_TOL[dtype] * amp
+
+
+def _window_spec(rng):
+    kind = rng.choice([KIND_SLIDING, KIND_DILATED, KIND_DILATED_2D])
+    L = rng.choice([rng.randint(1, 300), rng.randint(300, 3000), rng.randint(3000, 20000)])
+    if kind == KIND_DILATED_2D:
+        stride = rng.randint(1, 4)
+        block = rng.choice([rng.randint(1, 80), rng.randint(80, 300), rng.randint(30, 70) * stride])
+        return MaskSpec(kind, L, block=block, stride=stride)
+    stride = 1 if kind == KIND_SLIDING else rng.randint(2, 4)
+    # both sides of the kernel switches at 32 (6 -> 7 key blocks per workgroup) and 64 (band kernel)
+    W = rng.choice([rng.randint(0, 16), rng.randint(17, 32), rng.randint(33, 64), rng.randint(65, 200)])
+    return MaskSpec(kind, L, window=W, stride=stride)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_implicit_tiles_agree_with_row_kernels(seed):
+    import torch
+    rng = random.Random(1000 + seed)
+    spec = _window_spec(rng)
+    dtype = rng.choice(["f16", "f16", "f32"])
+    H = rng.choice([1, 2, 3])
+    sigma = rng.choice([0.3, 1.0, 3.0])
+    scale = rng.choice([0.125, -0.125, 0.5])
+    amp = max(1.0, sigma * sigma * abs(scale) * 8)      # rounding of the scores grows with their size
+    print("case", seed, spec, dtype, "H", H, "sigma", sigma, "scale", scale, flush=True)
+    Q, K, V = torch_qkv(H, spec.L, 64, dtype, sigma, seed, "cuda:0")
+    O1, l1 = sga.attention_forward_implicit(Q, K, V, spec, scale, path=sga.PATH_TILE, want_lse=True)
+    O2, l2 = sga.attention_forward_implicit(Q, K, V, spec, scale, path=sga.PATH_GATHER, want_lse=True)
+    torch.cuda.synchronize()
+    _agree(O1, l1, O2, l2, dtype, amp)
+
+
+def _explicit_spec(rng, seed):
+    kind = rng.choice([KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD, KIND_NONLOCAL, KIND_DILATED_2D])
+    L = rng.choice([rng.randint(1, 300), rng.randint(300, 3000), rng.randint(3000, 30000)])
+    if kind == KIND_BIGBIRD:
+        block = rng.choice([16, 32, 64, 128])
+        nb = max(8, L // block)
+        wb, ng = rng.randint(0, 2), rng.randint(0, 2)
+        nr = rng.randint(0, max(0, min(3, nb - (2 * wb + 1) - ng - 1)))
+        return MaskSpec(kind, nb * block, block=block, window_blocks=wb, n_global_blocks=ng, n_random_blocks=nr,
+                        seed=seed)
+    if kind == KIND_DILATED_2D:
+        return MaskSpec(kind, L, block=rng.randint(1, 400), stride=rng.randint(1, 4))
+    if kind in (KIND_GLOBAL_LOCAL, KIND_NONLOCAL):
+        return MaskSpec(kind, L, window=rng.randint(0, 200), n_global=rng.randint(0, min(L, 70)))
+    return MaskSpec(kind, L, window=rng.randint(0, 300), stride=1 if kind == KIND_SLIDING else rng.randint(2, 4))
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_explicit_tiles_agree_with_row_kernels_and_prepared_graphs(seed):
+    import torch
+    rng = random.Random(2000 + seed)
+    spec = _explicit_spec(rng, seed)
+    dtype = rng.choice(["f16", "f32"])
+    H = rng.choice([1, 2, 4])
+    sigma = rng.choice([0.3, 1.0])
+    scale = rng.choice([0.125, -0.125, 0.3])
+    print("case", seed, spec, dtype, "H", H, "sigma", sigma, "scale", scale, flush=True)
+    L = spec.L
+    Q, K, V = torch_qkv(H, L, 64, dtype, sigma, seed, "cuda:0")
+    rp, ci = sga.build_mask(spec)
+    nnz = int(rp[-1])
+    ws = sga.alloc_workspace(L, H, 64, dtype, nnz)
+    O1, l1 = sga.attention_forward(Q, K, V, rp, ci, scale, workspace=ws, path=sga.PATH_TILE, want_lse=True)
+    O2, l2 = sga.attention_forward(Q, K, V, rp, ci, scale, path=sga.PATH_GATHER, want_lse=True)
+    ws2 = sga.alloc_workspace(L, H, 64, dtype, nnz)
+    ws2.fill_(0x5A)
+    plan = sga.graph_prepare(rp, ci, H, 64, dtype, ws2)
+    O3, l3 = sga.attention_forward_prepared(Q, K, V, rp, ci, scale, plan, ws2, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O3) and torch.equal(l1, l3)
+    _agree(O1, l1, O2, l2, dtype)
