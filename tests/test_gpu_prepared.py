@@ -10,7 +10,7 @@ import numpy as np
 import pytest
 
 import paper_2502_01659_amd as sga
-from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_GLOBAL_LOCAL, KIND_BIGBIRD, KIND_NONLOCAL,
+from sga_inputs import (MaskSpec, KIND_SLIDING, KIND_DILATED, KIND_GLOBAL_LOCAL, KIND_BIGBIRD, KIND_NONLOCAL,
                         numpy_qkv, Workload)
 from oracle import reference as R
 from gpu_util import TOL, to_device, max_err
@@ -151,6 +151,54 @@ def test_prepared_forward_replays_from_a_hip_graph():
 
     def step():
         sga.attention_forward_prepared(Q, K, V, rp, ci, 0.125, plan, ws, O=O, lse=lse)
+
+    fill(1)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for seed in (2, 3, 4):
+        fill(seed)
+        step()
+        torch.cuda.synchronize()
+        want = (O.clone(), lse.clone())
+        O.zero_()
+        lse.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(O, want[0]) and torch.equal(lse, want[1]), seed
+
+
+@pytest.mark.parametrize("spec,dtype", [
+    (MaskSpec(KIND_DILATED, 5000, window=64, stride=2), "f16"),      # K, then V, in one set of LDS blocks
+    (MaskSpec(KIND_SLIDING, 5000, window=16), "f16"),                # K and V side by side
+    (MaskSpec(KIND_SLIDING, 5000, window=300), "f16"),               # ring of blocks per workgroup
+    (MaskSpec(KIND_SLIDING, 3000, window=100), "f32"),
+], ids=lambda v: v if isinstance(v, str) else f"{v.name}-w{v.window}")
+def test_implicit_forward_replays_from_a_hip_graph(spec, dtype):
+    """The implicit forward needs no workspace and queues kernels only: captured once, every
+    replay (new inputs and eager work in between) equals the eager result bit for bit."""
+    import torch
+    L, H, d = spec.L, 2, 64
+    dev = "cuda:0"
+    tdt = torch.float16 if dtype == "f16" else torch.float32
+    Q = torch.empty((H, L, d), dtype=tdt, device=dev)
+    K, V, O = torch.empty_like(Q), torch.empty_like(Q), torch.empty_like(Q)
+    lse = torch.empty((H, L), dtype=torch.float32, device=dev)
+
+    def fill(seed):
+        q, k, v = numpy_qkv(H, L, d, dtype, 0.7, seed)
+        Q.copy_(torch.from_numpy(q).to(dev))
+        K.copy_(torch.from_numpy(k).to(dev))
+        V.copy_(torch.from_numpy(v).to(dev))
+
+    def step():
+        sga.attention_forward_implicit(Q, K, V, spec, 0.125, O=O, lse=lse)
 
     fill(1)
     side = torch.cuda.Stream()
