@@ -346,8 +346,11 @@ def test_scale_sign_zero_and_non_power_of_two(scale, dtype, path):
     neighbours, zero gives uniform weights, and a value that is no power of two is not exact in
     fp16 (the scale must not be folded into the stored inputs)."""
     print("case scale", scale, dtype, path, flush=True)
+    # (the three windows run on the three fp16 window kernels of the tile path)
     for spec, implicit in [(MaskSpec(KIND_GLOBAL_LOCAL, 333, window=20, n_global=3), False),
-                           (MaskSpec(KIND_DILATED, 333, window=9, stride=2), True)]:
+                           (MaskSpec(KIND_DILATED, 333, window=9, stride=2), True),
+                           (MaskSpec(KIND_DILATED, 700, window=60, stride=2), True),
+                           (MaskSpec(KIND_SLIDING, 500, window=100), True)]:
         wl = Workload("t", H=2, L=spec.L, d=64, dtype=dtype, sigma=1.0, mask=spec, explicit=True, seed=5)
         Q, K, V = small_inputs(wl)
         dQ, dK, dV = to_device(Q, K, V)
