@@ -257,6 +257,7 @@ sga_status run_implicit_call(const void* Q, const void* K, const void* V, const 
   a.ws = workspace; a.ws_bytes = workspace_bytes;
   a.accumulate = accumulate;
   a.split = path == SGA_PATH_TILE_SPLIT;
+  a.tiles_allowed = path != SGA_PATH_GATHER;
   (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
   if (kind == SGA_MASK_NONLOCAL) {
     const int64_t g = desc->n_global < L ? desc->n_global : L;

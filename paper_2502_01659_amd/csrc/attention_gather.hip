@@ -514,18 +514,47 @@ __global__ __launch_bounds__(64) void nonlocal_chunk_kernel(
   }
 }
 
-// ... and one wavefront per (global row, head) combines the row's partials in chunk order
-// (deterministic).
+// ... and one workgroup per (global row, head) combines the row's partials: each of its four
+// wavefronts reduces a quarter of the chunks, in chunk order, to one partial state in LDS, and
+// the first wavefront combines the four in wavefront order and writes the row (a fixed order:
+// deterministic).
 template <typename T, int D>
-__global__ __launch_bounds__(64) void nonlocal_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
-                                                            int64_t L, int32_t n_chunks,
-                                                            const float* __restrict__ partials,
-                                                            int accumulate) {
-  const int lane = threadIdx.x;
+__global__ __launch_bounds__(256) void nonlocal_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
+                                                             int64_t L, int32_t n_chunks,
+                                                             const float* __restrict__ partials,
+                                                             int accumulate) {
+  constexpr int kCh = (D + kWave - 1) / kWave;
+  __shared__ float quarter[4][D + 4];
+  const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
   const int64_t i = blockIdx.x, h = blockIdx.y, H = gridDim.y;
-  const float* p0 = partials + ((i * n_chunks) * H + h) * (D + 4);
-  merge_row_partials<T, D>(p0, H * (D + 4), n_chunks, O + h * L * D + i * D,
-                           lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
+  const int64_t step = H * (D + 4);
+  const int per = (n_chunks + 3) / 4;
+  const int c0 = wave * per < n_chunks ? wave * per : n_chunks;
+  const int c1 = c0 + per < n_chunks ? c0 + per : n_chunks;
+  const float* p0 = partials + ((i * n_chunks + c0) * H + h) * (D + 4);
+  float M = kMinusHuge;
+  for (int c = 0; c < c1 - c0; ++c) M = fmaxf(M, p0[c * step + D]);
+  float l = 0.f, acc[kCh];
+#pragma unroll
+  for (int k = 0; k < kCh; ++k) acc[k] = 0.f;
+  for (int c = 0; c < c1 - c0; ++c) {
+    const float w = __builtin_amdgcn_exp2f(p0[c * step + D] - M);
+    l = __builtin_fmaf(p0[c * step + D + 1], w, l);
+#pragma unroll
+    for (int k = 0; k < kCh; ++k)
+      if (lane + k * kWave < D) acc[k] = __builtin_fmaf(p0[c * step + lane + k * kWave], w, acc[k]);
+  }
+#pragma unroll
+  for (int k = 0; k < kCh; ++k)
+    if (lane + k * kWave < D) quarter[wave][lane + k * kWave] = acc[k];
+  if (lane == 0) {
+    quarter[wave][D] = M;
+    quarter[wave][D + 1] = l;
+  }
+  __syncthreads();
+  if (wave == 0)
+    merge_row_partials<T, D>(&quarter[0][0], D + 4, 4, O + h * L * D + i * D, lse ? lse + h * L + i : nullptr, lane,
+                             accumulate != 0);
 }
 
 // One wavefront per (chunk of a long row, head): partial state of a slice of the row.  Chunk c
@@ -698,6 +727,22 @@ static sga_status run_implicit(const AttnArgs& a) {
   // rows that are one arithmetic run: all rows of the 2-D dilated mask, rows >= g of the
   // non-local mask
   const int64_t g = a.mask_kind == SGA_MASK_NONLOCAL ? (a.n_global < a.L ? a.n_global : a.L) : 0;
+  if constexpr (D == kHeadDim) {
+    if (a.mask_kind == SGA_MASK_NONLOCAL && a.tiles_allowed) {
+      // matrix-core tiles: 32 rows >= g at a time against the one or two key blocks that hold the
+      // global tokens; the g global rows as one or two tiles over ranges of all key blocks, with
+      // partial states that the merge below combines in range order
+      float* partials = g > 0 ? reinterpret_cast<float*>(static_cast<char*>(a.ws) +
+                                                         plan_workspace(a.L, a.H, -1, a.dtype, D).off_partials)
+                              : nullptr;
+      int32_t n_chunks = 0;
+      launch_tile_nonlocal(a, g, partials, &n_chunks);
+      if (g > 0)
+        hipLaunchKernelGGL((nonlocal_merge_kernel<T, D>), dim3((unsigned)g, (unsigned)a.H), dim3(256), 0, a.stream,
+                           O, a.lse, a.L, n_chunks, partials, acc);
+      return hip_status(hipGetLastError());
+    }
+  }
   if (a.L > g) {
     const dim3 grid((unsigned)((a.L - g + 3) / 4), (unsigned)a.H);
     profile_mark_begin(a.stream, "gather_runs_kernel");
@@ -715,7 +760,7 @@ static sga_status run_implicit(const AttnArgs& a) {
     hipLaunchKernelGGL((nonlocal_chunk_kernel<T, D>), dim3((unsigned)n_chunks, (unsigned)g, (unsigned)a.H),
                        dim3(64), 0, a.stream, Q, K, V, a.L, (int64_t)a.window, (int64_t)len, a.scale,
                        partials);
-    hipLaunchKernelGGL((nonlocal_merge_kernel<T, D>), dim3((unsigned)g, (unsigned)a.H), dim3(64), 0, a.stream,
+    hipLaunchKernelGGL((nonlocal_merge_kernel<T, D>), dim3((unsigned)g, (unsigned)a.H), dim3(256), 0, a.stream,
                        O, a.lse, a.L, n_chunks, partials, acc);
   }
   return hip_status(hipGetLastError());

@@ -2058,6 +2058,118 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   }
 }
 
+// Key blocks of the non-local mask (global tokens 0..g-1 without the window, Section IV-B
+// "Global (non-local)") against the 32 queries that start at row0, by index arithmetic.
+// kGlobalRows: the queries i < g, which see every key outside their window, blocks kb0, kb0+1, ...;
+// otherwise the queries i >= g, which see the global keys j < min(g, i - W).  Queries of the
+// other kind (and past the end) get empty words.
+template <bool kGlobalRows>
+struct NonlocalBlocks {
+  int64_t L, g, W, row0;
+  int64_t kb0;
+  static constexpr int kGetLoads = 0;
+  __device__ int64_t key_stride() const { return 1; }
+  __device__ void resolve(BlockInfo&) const {}
+  __device__ BlockInfo get(int k, int n) const {
+    BlockInfo b;
+    b.raw = 0;
+    const int64_t v0 = (kb0 + k) * kTile;
+    b.row0 = v0;
+    const int64_t left = L - v0;
+    b.nvalid = left < kTile ? (int)left : kTile;
+    const uint32_t valid = b.nvalid == kTile ? ~0u : ((1u << b.nvalid) - 1u);
+    const int64_t i = row0 + n;
+    if (kGlobalRows) {
+      // keys of the block inside the window [i - W, i + W] are no neighbours
+      int64_t lo = i - W - v0, hi = i + W - v0;
+      uint32_t inside = 0;
+      if (hi >= 0 && lo <= kTile - 1) {
+        lo = lo < 0 ? 0 : lo;
+        hi = hi > kTile - 1 ? kTile - 1 : hi;
+        inside = (~0u >> (31 - (int)hi)) & (~0u << (int)lo);
+      }
+      b.word = i < g ? (valid & ~inside) : 0u;
+      // (wave-uniform) every query of the tile is a global row and no window reaches the block
+      b.full = b.nvalid == kTile && row0 + kTile <= g && (row0 + kTile - 1 + W < v0 || row0 - W > v0 + kTile - 1);
+    } else {
+      const int64_t end = (g < i - W ? g : i - W) - v0;       // keys [0, end) of the block are neighbours
+      const uint32_t below = end <= 0 ? 0u : (end >= kTile ? ~0u : ((1u << (int)end) - 1u));
+      b.word = (i >= g && i < L) ? (valid & below) : 0u;
+      const int64_t end0 = (g < row0 - W ? g : row0 - W) - v0;      // of the tile's first query
+      b.full = b.nvalid == kTile && row0 >= g && row0 + kTile <= L && end0 >= kTile;
+    }
+    return b;
+  }
+};
+
+// Implicit non-local mask, queries i >= g: one wavefront per 32 rows against the (g + 31) / 32
+// key blocks that hold the global tokens.
+template <typename T, int kPipe>
+__global__ __launch_bounds__(256) void tile_nonlocal_cols_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, int64_t L, int64_t W, int64_t g, float scale, int accumulate) {
+  constexpr int kLds = CoreFor<T, kPipe>::type::template lds_bytes<kPipe>();
+  __shared__ __attribute__((aligned(16))) char lds_all[4 * kLds];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  char* lds = lds_all + wave * kLds;
+  const int64_t row0 = (g / kTile + (int64_t)blockIdx.x * 4 + wave) * kTile;      // the first tile may start below g
+  if (row0 >= L) return;
+  const int64_t hd = blockIdx.y;
+  const int64_t hoff = hd * L * kHeadDim;
+  const NonlocalBlocks<false> src{L, g, W, row0, 0};
+  const int nblk = (int)((g + kTile - 1) / kTile);
+  const int64_t i = row0 + n;
+  const bool mine = i >= g && i < L;
+  typename CoreFor<T, kPipe>::type core;
+  core.load_q(Q + hoff + (i < L ? i : L - 1) * kHeadDim, h, scale < 0.f);
+  TileState st;
+  st.init();
+  core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st, lds);
+  finish_tile<T>(O + hoff, lse ? lse + hd * L : nullptr, i, i, mine, st, h, accumulate != 0);
+}
+
+// Implicit non-local mask, the g global rows: grid = (ranges of key blocks, tiles of global rows,
+// heads), one wavefront each, which leaves the partial state of its rows over its range in the
+// layout nonlocal_merge_kernel reads (row-major: D accumulators, m, l per (row, range, head)).
+template <typename T, int kPipe>
+__global__ __launch_bounds__(64) void tile_nonlocal_rows_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, int64_t L, int64_t W,
+    int64_t g, int64_t blocks_per_range, float scale, float* __restrict__ partials) {
+  constexpr int kLds = CoreFor<T, kPipe>::type::template lds_bytes<kPipe>();
+  __shared__ __attribute__((aligned(16))) char lds[kLds];
+  const int lane = threadIdx.x;
+  const int n = lane & 31, h = lane >> 5;
+  const int64_t c = blockIdx.x, n_ranges = gridDim.x, hd = blockIdx.z, H = gridDim.z;
+  const int64_t row0 = (int64_t)blockIdx.y * kTile;
+  const int64_t hoff = hd * L * kHeadDim;
+  const int64_t nb_total = (L + kTile - 1) / kTile;
+  const int64_t kb0 = c * blocks_per_range;
+  const int64_t kb1 = kb0 + blocks_per_range < nb_total ? kb0 + blocks_per_range : nb_total;
+  const NonlocalBlocks<true> src{L, g, W, row0, kb0};
+  const int64_t i = row0 + n;
+  typename CoreFor<T, kPipe>::type core;
+  core.load_q(Q + hoff + (i < L ? i : L - 1) * kHeadDim, h, scale < 0.f);
+  TileState st;
+  st.init();
+  core.template run<kPipe>(K + hoff, V + hoff, src, 0, (int)(kb1 > kb0 ? kb1 - kb0 : 0), softmax_factor(scale),
+                           lane, st, lds);
+  if (i >= g) return;
+  const float l = st.l + other_half(st.l, h);
+  float* p = partials + ((i * n_ranges + c) * H + hd) * (kHeadDim + 4);
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<float4*>(p + cb * 32 + 8 * q + 4 * h) =
+          make_float4(st.o[cb][4 * q], st.o[cb][4 * q + 1], st.o[cb][4 * q + 2], st.o[cb][4 * q + 3]);
+  if (h == 0) {
+    p[kHeadDim] = st.m;
+    p[kHeadDim + 1] = l;
+  }
+}
+
 __device__ __forceinline__ float lane_value(float v, int src_lane) {     // v of lane src_lane (uniform index)
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), src_lane));
 }
@@ -2901,6 +3013,45 @@ sga_status launch_tile_explicit(const AttnArgs& a) {
   if (a.prepared && a.plan_tiles_cover_all) return SGA_OK;
   // rows of tiles that did not qualify (or everything, if the workspace is too small)
   return launch_gather_explicit(a, true, true);
+}
+
+namespace {
+template <typename T>
+void run_tile_nonlocal(const AttnArgs& a, int64_t g, float* partials, int32_t* n_chunks) {
+  constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
+  const T* Q = static_cast<const T*>(a.Q);
+  const T* K = static_cast<const T*>(a.K);
+  const T* V = static_cast<const T*>(a.V);
+  const int acc = a.accumulate ? 1 : 0;
+  const int64_t first_tile = g / kTile, n_tiles = (a.L + kTile - 1) / kTile;
+  if (n_tiles > first_tile && a.L > g) {
+    profile_mark_begin(a.stream, "tile_nonlocal_cols_kernel");
+    hipLaunchKernelGGL((tile_nonlocal_cols_kernel<T, kPipe>), dim3((unsigned)((n_tiles - first_tile + 3) / 4), (unsigned)a.H),
+                       dim3(256), 0, a.stream, Q, K, V, static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, g,
+                       a.scale, acc);
+    profile_mark_end(a.stream);
+  }
+  *n_chunks = 0;
+  if (g > 0) {
+    // ranges of at least 8 key blocks, as many as the partial states of the workspace allow
+    // (kMaxImplicitGlobal rows x kMaxSplit ranges in all: fewer global rows, more ranges each)
+    const int64_t g_rows = (g + kTile - 1) / kTile * kTile;
+    int64_t max_ranges = (int64_t)kMaxImplicitGlobal * kMaxSplit / g_rows;
+    if (max_ranges > 256) max_ranges = 256;
+    int64_t per = (n_tiles + max_ranges - 1) / max_ranges;
+    if (per < 8) per = 8;
+    const int64_t ranges = (n_tiles + per - 1) / per;
+    *n_chunks = (int32_t)ranges;
+    hipLaunchKernelGGL((tile_nonlocal_rows_kernel<T, kPipe>),
+                       dim3((unsigned)ranges, (unsigned)((g + kTile - 1) / kTile), (unsigned)a.H), dim3(64), 0, a.stream,
+                       Q, K, V, a.L, (int64_t)a.window, g, per, a.scale, partials);
+  }
+}
+}  // namespace
+
+void launch_tile_nonlocal(const AttnArgs& a, int64_t g, float* partials, int32_t* n_chunks) {
+  if (a.dtype == SGA_F32) run_tile_nonlocal<float>(a, g, partials, n_chunks);
+  else run_tile_nonlocal<__half>(a, g, partials, n_chunks);
 }
 
 sga_status launch_tile_implicit(const AttnArgs& a) {

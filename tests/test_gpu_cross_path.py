@@ -103,3 +103,35 @@ def test_explicit_tiles_agree_with_row_kernels_and_prepared_graphs(seed):
     torch.cuda.synchronize()
     assert torch.equal(O1, O3) and torch.equal(l1, l3)
     _agree(O1, l1, O2, l2, dtype)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_implicit_nonlocal_tiles_agree_with_row_kernels(seed):
+    """The implicit non-local mask (global tokens without their window): rows >= g and the g dense
+    rows on the tile kernels against the per-row kernels, as a fresh call and continuing the state
+    a local call left (the composition of Section V-F)."""
+    import torch
+    rng = random.Random(3000 + seed)
+    L = rng.choice([rng.randint(1, 300), rng.randint(300, 3000), rng.randint(3000, 20000)])
+    g = rng.choice([0, 1, rng.randint(1, 16), rng.randint(17, 32), rng.randint(33, 64)])
+    W = rng.choice([0, rng.randint(1, 40), rng.randint(41, 200)])
+    dtype = rng.choice(["f16", "f32"])
+    H = rng.choice([1, 2, 3])
+    scale = rng.choice([0.125, -0.125, 0.3])
+    nl = MaskSpec(KIND_NONLOCAL, L, window=W, n_global=min(g, L))
+    loc = MaskSpec(KIND_SLIDING, L, window=W)
+    print("case", seed, nl, dtype, "H", H, "scale", scale, flush=True)
+    Q, K, V = torch_qkv(H, L, 64, dtype, 0.8, seed, "cuda:0")
+    ws = sga.alloc_workspace(L, H, 64, dtype, -1)
+    O1, l1 = sga.attention_forward_implicit(Q, K, V, nl, scale, workspace=ws, path=sga.PATH_TILE, want_lse=True)
+    O2, l2 = sga.attention_forward_implicit(Q, K, V, nl, scale, workspace=ws, path=sga.PATH_GATHER, want_lse=True)
+    torch.cuda.synchronize()
+    _agree(O1, l1, O2, l2, dtype)
+    # local first, then the non-local edges on the same state: both kernel families
+    outs = []
+    for path in (sga.PATH_TILE, sga.PATH_GATHER):
+        O, lse = sga.attention_forward_implicit(Q, K, V, loc, scale, workspace=ws, path=path, want_lse=True)
+        sga.attention_accumulate_implicit(Q, K, V, nl, scale, O, lse, workspace=ws, path=path)
+        outs.append((O, lse))
+    torch.cuda.synchronize()
+    _agree(outs[0][0], outs[0][1], outs[1][0], outs[1][1], dtype, 2.0)
