@@ -712,7 +712,11 @@ def main():
                 out["split_precision"] = {"error": repr(ex)}
             torch.cuda.empty_cache()
             try:
-                out["composition"] = composition_times(w2, path)
+                out["composition"] = composition_times(w2, path, steps=20, warmup=5)
+                # the same mask with fp16 storage (there the implicit pair is the faster one)
+                import dataclasses
+                out["composition_f16"] = composition_times(dataclasses.replace(w2, dtype="f16", sigma=0.5), path,
+                                                           steps=20, warmup=5)
             except Exception as ex:
                 out["composition"] = {"error": repr(ex)}
     print(json.dumps(out))
