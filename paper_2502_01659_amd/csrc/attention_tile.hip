@@ -1636,10 +1636,12 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
         // multi-segment tile goes to the gather path (all-or-nothing keeps runs reproducible)
         atomicAdd(&ctr[kCtrTilePartsNeeded], (uint32_t)id.nseg);
         const uint32_t first = atomicAdd(&ctr[kCtrTilePartsAlloc], (uint32_t)id.nseg);
-        tile_pbase[t] = (int64_t)first + id.nseg <= pl.cap_tparts ? (int32_t)first : -1;
+        const int32_t pbase = (int64_t)first + id.nseg <= pl.cap_tparts ? (int32_t)first : -1;
+        tile_pbase[t] = pbase;
+        // the merge reads one record per tile instead of a chain of dependent loads
         const uint32_t mi = atomicAdd(&ctr[kCtrMultiTiles], 1u);
         if ((int64_t)mi < pl.cap_tparts)
-          reinterpret_cast<int32_t*>(base_ws + pl.off_multi_tiles)[mi] = (int32_t)t;
+          reinterpret_cast<int4*>(base_ws + pl.off_multi_tiles)[mi] = make_int4((int32_t)t, pbase, id.nseg, 0);
       }
     }
   }
@@ -1877,18 +1879,18 @@ __global__ __launch_bounds__(256) void tile_merge_kernel(T* __restrict__ O, floa
   if (pl.total_bytes > ws_bytes || !tile_parts_fit(pl, ws)) return;
   char* base_ws = static_cast<char*>(ws);
   const uint32_t n_multi = reinterpret_cast<const uint32_t*>(ws)[kCtrMultiTiles];
-  const int32_t* multi = reinterpret_cast<const int32_t*>(base_ws + pl.off_multi_tiles);
+  const int4* multi = reinterpret_cast<const int4*>(base_ws + pl.off_multi_tiles);     // {tile, first partial slot, segments, -}
   const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
-  const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
   const float* parts = reinterpret_cast<const float*>(base_ws + pl.off_tpartials);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
   const int64_t hd = blockIdx.y;
   for (uint32_t i = blockIdx.x; i < n_multi; i += gridDim.x) {
-    const int64_t t = multi[i];
+    const int4 rec = multi[i];
+    const int64_t t = rec.x;
     if (tile_bad[t]) continue;
-    const int nseg = tile_segments(row_ptr, L, pl.seg_shift, t);
-    const float* p0 = parts + ((int64_t)tile_pbase[t] * H + hd) * (kSlices * kTilePartialFloats);
+    const int nseg = rec.z;
+    const float* p0 = parts + ((int64_t)rec.y * H + hd) * (kSlices * kTilePartialFloats);
     const int64_t step = (int64_t)H * (kSlices * kTilePartialFloats);
     const int rows_per_wg = kTile / (int)gridDim.z;
     for (int r = blockIdx.z * rows_per_wg; r < (int)(blockIdx.z + 1) * rows_per_wg; ++r) {

@@ -86,7 +86,7 @@ __host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) 
 // items_rec           n_work x TileItem: the work items of the tile path
 // tile_bad            n_tiles x int32: != 0 -> tile is left to the gather path
 // tile_pbase          n_tiles x int32: first partial slot of a multi-segment tile
-// multi_tiles         cap_tparts x int32: ids of the multi-segment tiles (merge list, any order)
+// multi_tiles         cap_tparts x {tile, first partial slot, segments, -}: the multi-segment tiles (merge list, any order)
 // pair_blk            cap_pairs x int32: key block id (| full flag); tile t owns slots
 //                     [row_ptr[32t]/128, row_ptr[32(t+1)]/128), split evenly among its segments
 // pair_mask           cap_pairs x 32 x uint32: bit j of word r = edge (row 32t+r, key 32b+j)
@@ -180,7 +180,7 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   p.off_tile_pbase = off;
   off = (off + (size_t)p.n_tiles * 4 + 255) & ~size_t(255);
   p.off_multi_tiles = off;
-  off = (off + (size_t)p.cap_tparts * 4 + 255) & ~size_t(255);
+  off = (off + (size_t)p.cap_tparts * 16 + 255) & ~size_t(255);     // {tile, first partial slot, segments, -}
   p.off_pair_blk = off;
   off = (off + (size_t)p.cap_pairs * sizeof(int32_t) + 255) & ~size_t(255);
   p.off_pair_mask = off;
