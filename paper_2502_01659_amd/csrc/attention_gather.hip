@@ -727,7 +727,7 @@ static sga_status run_implicit(const AttnArgs& a) {
   // rows that are one arithmetic run: all rows of the 2-D dilated mask, rows >= g of the
   // non-local mask
   const int64_t g = a.mask_kind == SGA_MASK_NONLOCAL ? (a.n_global < a.L ? a.n_global : a.L) : 0;
-  if constexpr (D == kHeadDim) {
+  if constexpr (D >= kHeadDim) {
     if (a.mask_kind == SGA_MASK_NONLOCAL && a.tiles_allowed) {
       // matrix-core tiles: 32 rows >= g at a time against the one or two key blocks that hold the
       // global tokens; the g global rows as one or two tiles over ranges of all key blocks, with

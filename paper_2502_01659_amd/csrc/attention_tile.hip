@@ -2303,6 +2303,79 @@ __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
                           accumulate != 0);
 }
 
+// The implicit non-local mask at head dimensions 128 and 256: the two kernels of the 64-channel
+// form (tile_nonlocal_cols_kernel, tile_nonlocal_rows_kernel) with one workgroup of kD / 64
+// wavefronts per tile, each on its 64-channel slice (see tile_attend_wide_kernel).
+template <typename T, int kD, int kPipe>
+__global__ __launch_bounds__(kD) void tile_nonlocal_cols_wide_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, int64_t L, int64_t W, int64_t g, float scale, int accumulate) {
+  using Core = typename WideCoreOf<T, kD>::type;
+  constexpr int kSlices = kD / kHeadDim;
+  constexpr int kLds = Core::template lds_bytes<kPipe>();
+  __shared__ __attribute__((aligned(16))) char lds_all[kSlices * kLds + SliceExchange<kD>::kBytes];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  const int64_t row0 = (g / kTile + (int64_t)blockIdx.x) * kTile;
+  if (row0 >= L) return;                           // (the same for every wavefront of the workgroup)
+  const int64_t hd = blockIdx.y;
+  const int64_t hoff = hd * L * kD + slice * kHeadDim;
+  const NonlocalBlocks<false> src{L, g, W, row0, 0};
+  const int nblk = (int)((g + kTile - 1) / kTile);
+  const int64_t i = row0 + n;
+  Core core;
+  core.xchg.init(lds_all + kSlices * kLds, slice);
+  core.load_q(Q + hoff + (i < L ? i : L - 1) * kD, h, scale < 0.f);
+  TileState st;
+  st.init();
+  core.template run<kPipe>(K + hoff, V + hoff, src, 0, nblk, softmax_factor(scale), lane, st,
+                           lds_all + slice * kLds);
+  finish_tile_wide<T, kD>(O + hoff, lse ? lse + hd * L : nullptr, i < L ? i : L - 1, i >= g && i < L, st, h, slice,
+                          accumulate != 0);
+}
+
+template <typename T, int kD, int kPipe>
+__global__ __launch_bounds__(kD) void tile_nonlocal_rows_wide_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, int64_t L, int64_t W,
+    int64_t g, int64_t blocks_per_range, float scale, float* __restrict__ partials) {
+  using Core = typename WideCoreOf<T, kD>::type;
+  constexpr int kSlices = kD / kHeadDim;
+  constexpr int kLds = Core::template lds_bytes<kPipe>();
+  __shared__ __attribute__((aligned(16))) char lds_all[kSlices * kLds + SliceExchange<kD>::kBytes];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int slice = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  const int64_t c = blockIdx.x, n_ranges = gridDim.x, hd = blockIdx.z, H = gridDim.z;
+  const int64_t row0 = (int64_t)blockIdx.y * kTile;
+  const int64_t hoff = hd * L * kD + slice * kHeadDim;
+  const int64_t nb_total = (L + kTile - 1) / kTile;
+  const int64_t kb0 = c * blocks_per_range;
+  const int64_t kb1 = kb0 + blocks_per_range < nb_total ? kb0 + blocks_per_range : nb_total;
+  const NonlocalBlocks<true> src{L, g, W, row0, kb0};
+  const int64_t i = row0 + n;
+  Core core;
+  core.xchg.init(lds_all + kSlices * kLds, slice);
+  core.load_q(Q + hoff + (i < L ? i : L - 1) * kD, h, scale < 0.f);
+  TileState st;
+  st.init();
+  core.template run<kPipe>(K + hoff, V + hoff, src, 0, (int)(kb1 > kb0 ? kb1 - kb0 : 0), softmax_factor(scale),
+                           lane, st, lds_all + slice * kLds);
+  if (i >= g) return;
+  const float l = st.l + other_half(st.l, h);
+  float* p = partials + ((i * n_ranges + c) * H + hd) * (kD + 4);
+#pragma unroll
+  for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+      *reinterpret_cast<float4*>(p + slice * kHeadDim + cb * 32 + 8 * q + 4 * h) =
+          make_float4(st.o[cb][4 * q], st.o[cb][4 * q + 1], st.o[cb][4 * q + 2], st.o[cb][4 * q + 3]);
+  if (h == 0 && slice == 0) {
+    p[kD] = st.m;
+    p[kD + 1] = l;
+  }
+}
+
 // fp16 window masks, wide bands: a workgroup owns 256 consecutive queries of a class (64 per
 // wavefront: two 32-query sub-tiles that share every K fragment and V^T operand read, with two
 // independent chains of products) and walks the key blocks of its
@@ -3051,9 +3124,49 @@ void run_tile_nonlocal(const AttnArgs& a, int64_t g, float* partials, int32_t* n
 }
 }  // namespace
 
+namespace {
+template <typename T, int kD>
+void run_tile_nonlocal_wide(const AttnArgs& a, int64_t g, float* partials, int32_t* n_chunks) {
+  constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
+  const T* Q = static_cast<const T*>(a.Q);
+  const T* K = static_cast<const T*>(a.K);
+  const T* V = static_cast<const T*>(a.V);
+  const int acc = a.accumulate ? 1 : 0;
+  const int64_t first_tile = g / kTile, n_tiles = (a.L + kTile - 1) / kTile;
+  if (n_tiles > first_tile && a.L > g) {
+    profile_mark_begin(a.stream, "tile_nonlocal_cols_wide_kernel");
+    hipLaunchKernelGGL((tile_nonlocal_cols_wide_kernel<T, kD, kPipe>), dim3((unsigned)(n_tiles - first_tile), (unsigned)a.H),
+                       dim3(kD), 0, a.stream, Q, K, V, static_cast<T*>(a.O), a.lse, a.L, (int64_t)a.window, g, a.scale,
+                       acc);
+    profile_mark_end(a.stream);
+  }
+  *n_chunks = 0;
+  if (g > 0) {
+    const int64_t g_rows = (g + kTile - 1) / kTile * kTile;
+    int64_t max_ranges = (int64_t)kMaxImplicitGlobal * kMaxSplit / g_rows;
+    if (max_ranges > 256) max_ranges = 256;
+    int64_t per = (n_tiles + max_ranges - 1) / max_ranges;
+    if (per < 8) per = 8;
+    const int64_t ranges = (n_tiles + per - 1) / per;
+    *n_chunks = (int32_t)ranges;
+    hipLaunchKernelGGL((tile_nonlocal_rows_wide_kernel<T, kD, kPipe>),
+                       dim3((unsigned)ranges, (unsigned)((g + kTile - 1) / kTile), (unsigned)a.H), dim3(kD), 0, a.stream,
+                       Q, K, V, a.L, (int64_t)a.window, g, per, a.scale, partials);
+  }
+}
+}  // namespace
+
 void launch_tile_nonlocal(const AttnArgs& a, int64_t g, float* partials, int32_t* n_chunks) {
-  if (a.dtype == SGA_F32) run_tile_nonlocal<float>(a, g, partials, n_chunks);
-  else run_tile_nonlocal<__half>(a, g, partials, n_chunks);
+  if (a.d == 128) {
+    if (a.dtype == SGA_F32) run_tile_nonlocal_wide<float, 128>(a, g, partials, n_chunks);
+    else run_tile_nonlocal_wide<__half, 128>(a, g, partials, n_chunks);
+  } else if (a.d == 256) {
+    if (a.dtype == SGA_F32) run_tile_nonlocal_wide<float, 256>(a, g, partials, n_chunks);
+    else run_tile_nonlocal_wide<__half, 256>(a, g, partials, n_chunks);
+  } else {
+    if (a.dtype == SGA_F32) run_tile_nonlocal<float>(a, g, partials, n_chunks);
+    else run_tile_nonlocal<__half>(a, g, partials, n_chunks);
+  }
 }
 
 sga_status launch_tile_implicit(const AttnArgs& a) {

@@ -287,8 +287,8 @@ struct AttnArgs {
   bool accumulate;
   // fp32 storage: products as three fp16 matrix-core terms instead of fp32 MFMA (tile path)
   bool split;
-  // implicit non-local mask: the 64-channel tile kernels may be used (the caller did not ask
-  // for the per-row kernels)
+  // implicit non-local mask: the tile kernels may be used (the caller did not ask for the
+  // per-row kernels)
   bool tiles_allowed;
   // workspace
   void* ws;
@@ -317,7 +317,7 @@ void launch_tile_analyze(const AttnArgs& a);
 // reservation of the chunk items of the split rows the tile path leaves over (sga_graph_prepare)
 void launch_split_prepass(const AttnArgs& a, bool skip_tiled);
 sga_status launch_tile_implicit(const AttnArgs& a);
-// Implicit non-local mask on the 64-channel tile kernels: the rows >= g against the global keys,
+// Implicit non-local mask on the tile kernels (d = 64, 128, 256): the rows >= g against the global keys,
 // and the partial states of the g global rows over *n_chunks ranges of the key blocks, in the
 // layout nonlocal_merge_kernel reads (the caller launches that merge).
 void launch_tile_nonlocal(const AttnArgs& a, int64_t g, float* partials, int32_t* n_chunks);

@@ -105,7 +105,7 @@ def test_explicit_tiles_agree_with_row_kernels_and_prepared_graphs(seed):
     _agree(O1, l1, O2, l2, dtype)
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(36))
 def test_implicit_nonlocal_tiles_agree_with_row_kernels(seed):
     """The implicit non-local mask (global tokens without their window): rows >= g and the g dense
     rows on the tile kernels against the per-row kernels, as a fresh call and continuing the state
@@ -117,12 +117,13 @@ def test_implicit_nonlocal_tiles_agree_with_row_kernels(seed):
     W = rng.choice([0, rng.randint(1, 40), rng.randint(41, 200)])
     dtype = rng.choice(["f16", "f32"])
     H = rng.choice([1, 2, 3])
-    scale = rng.choice([0.125, -0.125, 0.3])
+    d = rng.choice([64, 64, 128, 256])        # (128 and 256: one workgroup of d / 64 wavefronts per tile)
+    scale = rng.choice([0.125, -0.125, 0.3]) * (64 / d) ** 0.5
     nl = MaskSpec(KIND_NONLOCAL, L, window=W, n_global=min(g, L))
     loc = MaskSpec(KIND_SLIDING, L, window=W)
-    print("case", seed, nl, dtype, "H", H, "scale", scale, flush=True)
-    Q, K, V = torch_qkv(H, L, 64, dtype, 0.8, seed, "cuda:0")
-    ws = sga.alloc_workspace(L, H, 64, dtype, -1)
+    print("case", seed, nl, dtype, "H", H, "d", d, "scale", scale, flush=True)
+    Q, K, V = torch_qkv(H, L, d, dtype, 0.8, seed, "cuda:0")
+    ws = sga.alloc_workspace(L, H, d, dtype, -1)
     O1, l1 = sga.attention_forward_implicit(Q, K, V, nl, scale, workspace=ws, path=sga.PATH_TILE, want_lse=True)
     O2, l2 = sga.attention_forward_implicit(Q, K, V, nl, scale, workspace=ws, path=sga.PATH_GATHER, want_lse=True)
     torch.cuda.synchronize()
