@@ -136,3 +136,27 @@ def test_implicit_nonlocal_tiles_agree_with_row_kernels(seed):
         outs.append((O, lse))
     torch.cuda.synchronize()
     _agree(outs[0][0], outs[0][1], outs[1][0], outs[1][1], dtype, 2.0)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "f32"])
+def test_implicit_nonlocal_tiles_at_length(dtype):
+    """The same agreement where the g global rows span thousands of key blocks (128 ranges of 74
+    blocks each) and row offsets pass 2^24."""
+    import torch
+    L, H, g, W = 300001, 2, 40, 77
+    nl = MaskSpec(KIND_NONLOCAL, L, window=W, n_global=g)
+    Q, K, V = torch_qkv(H, L, 64, dtype, 0.8, 5, "cuda:0")
+    ws = sga.alloc_workspace(L, H, 64, dtype, -1)
+    O1, l1 = sga.attention_forward_implicit(Q, K, V, nl, 0.125, workspace=ws, path=sga.PATH_TILE, want_lse=True)
+    O2, l2 = sga.attention_forward_implicit(Q, K, V, nl, 0.125, workspace=ws, path=sga.PATH_GATHER, want_lse=True)
+    torch.cuda.synchronize()
+    _agree(O1, l1, O2, l2, dtype)
+    # V = ones: every row with a neighbour returns exactly 1, the others the initial state
+    ones = torch.ones_like(V)
+    O3, l3 = sga.attention_forward_implicit(Q, K, ones, nl, 0.125, workspace=ws, path=sga.PATH_TILE, want_lse=True)
+    torch.cuda.synchronize()
+    has = torch.isfinite(l3)
+    assert torch.equal(has, torch.isfinite(l2))
+    tol = 1e-6 if dtype == "f32" else 1e-3
+    assert (O3[has].float() - 1.0).abs().max().item() <= tol
+    assert (O3[~has].float() == 0).all()
