@@ -1630,7 +1630,11 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
       it.slot0 = slot0;
       it.pad = 0;
       items[w] = it;
-      if (overflow && atomicOr(&tile_bad[t], 1) == 0) atomicAdd(&ctr[kCtrTilesBad], 1u);
+      if (overflow && atomicOr(&tile_bad[t], 1) == 0) {
+        // (the per-row kernels walk this list instead of testing every row of the sequence)
+        const uint32_t bi = atomicAdd(&ctr[kCtrTilesBad], 1u);
+        reinterpret_cast<int32_t*>(base_ws + pl.off_bad_list)[bi] = (int32_t)t;
+      }
       if (id.seg == 0 && id.nseg > 1) {
         // reserve the tile's partial slots; if the call needs more than exist, every
         // multi-segment tile goes to the gather path (all-or-nothing keeps runs reproducible)

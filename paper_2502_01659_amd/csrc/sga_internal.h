@@ -58,10 +58,17 @@ constexpr int kTilePartialFloats = kTile * 64 + 2 * kTile;   // o[32][64], m[32]
 // The mapping follows from row_ptr alone and needs neither a scan nor atomics.  A dense
 // 32x32 block is 1024 edges: S is 32 dense blocks of fp32 MFMA work or 256 of fp16 work.
 // S is a power of two (the kernels divide edge counts by it with a shift): 2^15 or 2^18 edges.
-// A call with little work in total (nnz * H edges) gets shorter items, down to 2^12 or 2^15
-// edges, until it has about 1024 of them: otherwise a small call with a few dense rows would
-// leave its few long items to a handful of wavefronts while the rest of the chip idles.
-// (Microbenchmark grid, one head, a few global tokens at L = 8192: 0.76 -> 0.14 ms.)
+// A call with less work in total (nnz * H edges) gets shorter items, down to 2^12 or 2^15
+// edges, until it has about 1024 (fp32) or 4096 (fp16) of them: otherwise a call with a few
+// dense rows leaves its few long items to a handful of wavefronts while the rest of the chip
+// idles.  An item of S edges takes a wavefront S / (nnz * H / 4096) of the time the whole chip
+// needs for the call, and the tiles that are cut at all (rows of global tokens) are half empty,
+// which doubles that.  (Microbenchmark grid, fp32, one head, a few global tokens at L = 8192:
+// 0.76 -> 0.14 ms with 1024 items; the longformer mask with fp16 storage, L = 65,536, H = 8:
+// 0.28 -> 0.16 ms with 4096 instead of 1024, L = 262,144, H = 4: 0.65 -> 0.32 ms.  fp32 items
+// pay about 5 microseconds between the claim and the first block, as much as 3 blocks of
+// matrix work: 4096 items made the global masks of the microbenchmark grid up to 1.5 times
+// slower, and 8192 cost workload 2 1.4 %.)
 // Edges per chunk of a split row: kSplitChunk, halved down to kSplitChunkMin while the call
 // (nnz * H edges) has fewer than about 1024 such chunks, for the same reason as seg_shift.
 __host__ __device__ inline int split_chunk(int64_t nnz, int32_t H) {
@@ -74,7 +81,7 @@ __host__ __device__ inline int seg_shift_min(int32_t dtype) { return dtype == SG
 __host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) {
   int sh = dtype == SGA_F32 ? 15 : 18;
   const int64_t e = (nnz < 0 ? 0 : nnz) * (int64_t)H;
-  while (sh > seg_shift_min(dtype) && (e >> sh) < 1024) --sh;
+  while (sh > seg_shift_min(dtype) && (e >> sh) < (dtype == SGA_F32 ? 1024 : 4096)) --sh;
   return sh;
 }
 
@@ -85,6 +92,7 @@ __host__ __device__ inline int seg_shift(int32_t dtype, int64_t nnz, int32_t H) 
 //                     (implicit non-local mask: kMaxImplicitGlobal rows x kMaxSplit chunks)
 // items_rec           n_work x TileItem: the work items of the tile path
 // tile_bad            n_tiles x int32: != 0 -> tile is left to the gather path
+// bad_list            n_tiles x int32: the tiles with tile_bad != 0, in any order (kCtrTilesBad of them)
 // tile_pbase          n_tiles x int32: first partial slot of a multi-segment tile
 // multi_tiles         cap_tparts x {tile, first partial slot, segments, -}: the multi-segment tiles (merge list, any order)
 // pair_blk            cap_pairs x int32: key block id (| full flag); tile t owns slots
@@ -127,7 +135,7 @@ struct WorkspacePlan {
   int seg_shift;          // log2 of S, the edges per work item of the tile path
   int split_chunk;        // target edges per chunk of a split row
   int l2_chunks;          // != 0: rows of >= kL2ChunkEdges * l2_chunks neighbours are cut into this many chunks
-  size_t off_items_rec, off_tile_bad, off_tile_pbase, off_multi_tiles, off_pair_blk, off_pair_mask,
+  size_t off_items_rec, off_tile_bad, off_bad_list, off_tile_pbase, off_multi_tiles, off_pair_blk, off_pair_mask,
       off_tpartials, off_work_next, off_wparts;
   int64_t cap_wparts;     // (tile, head) pairs whose window partials fit (implicit masks)
   size_t total_bytes;
@@ -176,6 +184,8 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   p.off_items_rec = off;
   off = (off + (size_t)p.n_work * sizeof(TileItem) + 255) & ~size_t(255);
   p.off_tile_bad = off;
+  off = (off + (size_t)p.n_tiles * 4 + 255) & ~size_t(255);
+  p.off_bad_list = off;
   off = (off + (size_t)p.n_tiles * 4 + 255) & ~size_t(255);
   p.off_tile_pbase = off;
   off = (off + (size_t)p.n_tiles * 4 + 255) & ~size_t(255);
