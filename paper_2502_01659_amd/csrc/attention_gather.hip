@@ -315,6 +315,7 @@ __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __res
   int32_t n, len;
   row_split_shape(deg, pl, n, len);
   atomicAdd(&ctr[kCtrChunksNeeded], (uint32_t)n);
+  atomicMax(&ctr[kCtrMaxChunks], (uint32_t)n);
   const uint32_t base = atomicAdd(&ctr[kCtrItemsAlloc], (uint32_t)n);
   if ((int64_t)base + n > pl.cap_items) return;
   const uint32_t slot = atomicAdd(&ctr[kCtrLongRows], 1u);
@@ -612,7 +613,8 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
   const int64_t h = blockIdx.y;
   const int64_t hoff = h * L * D;
   const uint32_t xcd = blockIdx.x & 7;
-  const uint64_t n_units = (uint64_t)n_long * (kMaxSplit / 8);
+  const uint32_t max_chunks = reinterpret_cast<const uint32_t*>(ws)[kCtrMaxChunks];
+  const uint64_t n_units = (uint64_t)n_long * ((max_chunks + 7) / 8);
   for (uint64_t u = (uint64_t)(blockIdx.x >> 3) * waves + threadIdx.x / kWave; u < n_units;
        u += (uint64_t)(gridDim.x >> 3) * waves) {
     const int4 rec = lr[u % n_long];                         // {row, first partial slot, chunks, chunk length}
@@ -643,12 +645,43 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
   }
 }
 
-// One wavefront per (long row, head): combine the row's partials in chunk order.
+// Partial states p0[c * step + ...], c < n, combined in order into one partial state
+// (D accumulators, m, l) at `out`; one wavefront, lane c owns channels c, c + 64, ...
+template <int D>
+__device__ __forceinline__ void combine_partials(const float* p0, int64_t step, int n, float* out, int lane) {
+  constexpr int kCh = (D + kWave - 1) / kWave;
+  float M = kMinusHuge;
+  for (int c = 0; c < n; ++c) M = fmaxf(M, p0[c * step + D]);
+  float l = 0.f, acc[kCh];
+#pragma unroll
+  for (int k = 0; k < kCh; ++k) acc[k] = 0.f;
+  for (int c = 0; c < n; ++c) {
+    const float w = __builtin_amdgcn_exp2f(p0[c * step + D] - M);
+    l = __builtin_fmaf(p0[c * step + D + 1], w, l);
+#pragma unroll
+    for (int k = 0; k < kCh; ++k)
+      if (lane + k * kWave < D) acc[k] = __builtin_fmaf(p0[c * step + lane + k * kWave], w, acc[k]);
+  }
+#pragma unroll
+  for (int k = 0; k < kCh; ++k)
+    if (lane + k * kWave < D) out[lane + k * kWave] = acc[k];
+  if (lane == 0) {
+    out[D] = M;
+    out[D + 1] = l;
+  }
+}
+
+// Rows of up to kMaxSplit chunks: one wavefront per (long row, head) combines the row's partials
+// in chunk order.  Rows of more chunks (cut by edge count into up to kMaxSplitLong): one
+// workgroup per row, each of its four wavefronts combines a quarter of the partials in chunk
+// order, the first one the four results in wavefront order (a fixed order whatever the
+// schedule).
 template <typename T, int D>
 __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, float* __restrict__ lse,
                                                            const int64_t* __restrict__ row_ptr,
                                                            int64_t L, void* ws, size_t ws_bytes,
                                                            int accumulate) {
+  __shared__ float quarter[4][D + 4];
   const int32_t H = (int32_t)gridDim.y;
   constexpr int32_t dtype = DtypeOf<T>::code;
   if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
@@ -657,14 +690,31 @@ __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, fl
   const int4* lr = reinterpret_cast<const int4*>(static_cast<char*>(ws) + pl.off_long);
   const float* partials = reinterpret_cast<const float*>(static_cast<char*>(ws) + pl.off_partials);
   const int lane = threadIdx.x & (kWave - 1);
-  const int waves = blockDim.x / kWave;
+  const int wave = threadIdx.x / kWave;
   const int64_t h = blockIdx.y;
-  for (uint32_t r = blockIdx.x * waves + threadIdx.x / kWave; r < n_long; r += gridDim.x * waves) {
+  const int64_t step = (int64_t)H * (D + 4);
+  for (uint32_t r = blockIdx.x * 4 + wave; r < n_long; r += gridDim.x * 4) {
     const int4 rec = lr[r];
+    if (rec.z > kMaxSplit) continue;
+    const int64_t i = rec.x;
+    merge_row_partials<T, D>(partials + ((int64_t)rec.y * H + h) * (D + 4), step, rec.z, O + h * L * D + i * D,
+                             lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
+  }
+  if (reinterpret_cast<const uint32_t*>(ws)[kCtrMaxChunks] <= (uint32_t)kMaxSplit) return;
+  for (uint32_t r = blockIdx.x; r < n_long; r += gridDim.x) {      // (the same trips for the whole workgroup)
+    const int4 rec = lr[r];
+    if (rec.z <= kMaxSplit) continue;
     const int64_t i = rec.x;
     const float* p0 = partials + ((int64_t)rec.y * H + h) * (D + 4);
-    merge_row_partials<T, D>(p0, (int64_t)H * (D + 4), rec.z, O + h * L * D + i * D,
-                             lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
+    T* Orow = O + h * L * D + i * D;
+    float* lse_i = lse ? lse + h * L + i : nullptr;
+    const int per = (rec.z + 3) / 4;
+    const int c0 = wave * per < rec.z ? wave * per : rec.z;
+    const int c1 = c0 + per < rec.z ? c0 + per : rec.z;
+    __syncthreads();                 // the previous row's combine has read the shared records
+    combine_partials<D>(p0 + c0 * step, step, c1 - c0, &quarter[wave][0], lane);
+    __syncthreads();
+    if (wave == 0) merge_row_partials<T, D>(&quarter[0][0], D + 4, 4, Orow, lse_i, lane, accumulate != 0);
   }
 }
 

@@ -17,7 +17,11 @@ constexpr int kWave = 64;             // CDNA wavefront width
 constexpr int kSplitThreshold = 2048; // rows with more neighbours are split
 constexpr int kSplitChunk = 2048;     // target edges per chunk
 constexpr int kSplitChunkMin = 256;   // ... of a call with little work in total (split_chunk)
-constexpr int kMaxSplit = 64;         // at most this many chunks per row
+constexpr int kMaxSplit = 64;         // at most this many chunks per row by L2 share, and ranges of an implicit global row
+// ... and by edge count: a row of millions of neighbours (one global token of a long sequence
+// whose tile does not qualify for the tile path) must spread over the chip, not over 64
+// wavefronts (L = 4,194,304, one global token, fp16: 2.65 -> 0.6 ms)
+constexpr int kMaxSplitLong = 1024;
 // Keys whose K and V rows do not fit one L2 (each of the 8 XCDs has its own 4 MB): rows of at
 // least kL2ChunkEdges * n neighbours are then cut into n = l2_chunks() chunks, a multiple of 8, and
 // chunk c of every row runs on XCD c % 8.  A chunk of a row's sorted neighbour list covers a
@@ -109,6 +113,7 @@ enum WsCounter : int {
   kCtrTilePartsAlloc = 4,   // bump allocator over tile partial slots
   kCtrTilesBad = 5,         // tiles whose block lists overflowed (left to the gather path)
   kCtrMultiTiles = 6,       // multi-segment tiles recorded in the merge list
+  kCtrMaxChunks = 7,        // most chunks any split row has (bounds the chunk kernel's unit loop)
   kNumCounters = 64
 };
 
@@ -158,7 +163,7 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   int64_t n_long = e / (kSplitThreshold + 1);
   if (n_long > L) n_long = L;
   int64_t cap = e / p.split_chunk + n_long;
-  if (cap > (int64_t)kMaxSplit * n_long) cap = (int64_t)kMaxSplit * n_long;
+  if (cap > (int64_t)kMaxSplitLong * n_long) cap = (int64_t)kMaxSplitLong * n_long;
   p.l2_chunks = nnz < 0 ? 0 : l2_chunks(L, d, dtype);
   if (p.l2_chunks) {
     int64_t rows = e / ((int64_t)kL2ChunkEdges * p.l2_chunks);      // rows that can qualify
@@ -221,13 +226,11 @@ __host__ __device__ inline bool row_is_split(int64_t deg, const WorkspacePlan& p
 // ... into nchunks chunks of len edges (the last one shorter), len a multiple of 32.
 __host__ __device__ inline void row_split_shape(int64_t deg, const WorkspacePlan& p, int32_t& nchunks,
                                                 int32_t& len) {
-  int64_t n;
-  if (p.l2_chunks && deg >= (int64_t)kL2ChunkEdges * p.l2_chunks) {
-    n = p.l2_chunks;
-  } else {
-    n = (deg + p.split_chunk - 1) / p.split_chunk;
-    if (n > kMaxSplit) n = kMaxSplit;
-  }
+  int64_t n = (deg + p.split_chunk - 1) / p.split_chunk;
+  if (n > kMaxSplitLong) n = kMaxSplitLong;
+  // (a row of more than kMaxSplit chunks by edge count keeps them: there are few such rows in a
+  // call, and each has to spread over the chip before it can share an L2 with its neighbours)
+  if (n <= kMaxSplit && p.l2_chunks && deg >= (int64_t)kL2ChunkEdges * p.l2_chunks) n = p.l2_chunks;
   int64_t l = (deg + n - 1) / n;
   l = (l + 31) / 32 * 32;
   len = (int32_t)l;
