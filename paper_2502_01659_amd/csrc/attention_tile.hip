@@ -44,6 +44,9 @@ constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kMinusHuge = -1.0e30f;
 constexpr int kFullBit = 1 << 30;
+constexpr int kBitmapBlocks = 32;   // key blocks per window of the CSR -> tile pass's bitmap walk
+constexpr int kBitmapAfter = 4;     // ... which takes over after this many blocks if all but one had scattered columns
+constexpr int kBitmapUnits = 2;     // ... each lane taking this many units of 16 columns at a time
 
 // Key (within a 32-key block) held in accumulator register r of half-wave h after an
 // MFMA 32x32 whose M index is the key: rows 8*(r/4) + 4*h + r%4.
@@ -1436,8 +1439,13 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
                                                            int32_t d, void* ws, size_t ws_bytes) {
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, d);
   if (pl.total_bytes > ws_bytes) return;
+  // per wavefront: the bit words of kBitmapBlocks key blocks, then of the 32 rows the first
+  // unit of the window in one numbering, their positions in col_idx (low, high word) and their
+  // numbers of columns inside the window
+  __shared__ __attribute__((aligned(16))) uint32_t bitmap_all[4][kBitmapBlocks * kTile + 4 * kTile];
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
+  uint32_t* bm = bitmap_all[__builtin_amdgcn_readfirstlane(threadIdx.x / kWave)];
   char* base_ws = static_cast<char*>(ws);
   TileItem* items = reinterpret_cast<TileItem*>(base_ws + pl.off_items_rec);
   int32_t* tile_bad = reinterpret_cast<int32_t*>(base_ws + pl.off_tile_bad);
@@ -1511,6 +1519,8 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
     int nblk = 0;
     bool overflow = false;
     int consumed = 0;                   // edges of this lane's row in the blocks written so far
+    int scattered = 0;                  // blocks so far in which some row's columns were read one by one
+    bool by_bitmap = false;
     while (true) {
       int cur = INT32_MAX;
       if (!arith && pos < end) {
@@ -1559,6 +1569,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
         break;
       }
       uint32_t word = 0;
+      bool one_by_one = false;
       if (cur == b) {
         if (arith) {
           const int lo = run_lo & 31;
@@ -1579,6 +1590,7 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
           } else {
             // the row's columns inside block b are the next entries of its sorted list: take
             // them four per load while four remain, then one by one
+            one_by_one = true;
             bool more = true;
             while (more && pos + 4 <= end) {
               int cc[4];
@@ -1607,6 +1619,14 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
       if (lane == 0) pair_blk[slot0 + nblk] = b | (full ? kFullBit : 0);
       ++nblk;
       consumed += __builtin_popcount(word);
+      if (__any(one_by_one)) ++scattered;
+      // Scattered columns in nearly all of the first blocks: the rest of the list is made by
+      // the bitmap walk below (the same blocks and words, from coalesced loads, many in flight,
+      // instead of a chain of dependent ones per row).
+      if (nblk == kBitmapAfter && scattered >= kBitmapAfter - 1) {
+        by_bitmap = true;
+        break;
+      }
       if (nblk == kProbeBlocks) {
         // A list that averages under kProbeEdges edges per block over its first kProbeBlocks blocks
         // is given up at once (scattered columns: the rows go to the per-row kernels) instead
@@ -1619,6 +1639,114 @@ __global__ __launch_bounds__(256) void tile_analyze_kernel(const int64_t* __rest
           overflow = true;
           break;
         }
+      }
+    }
+    if (by_bitmap) {
+      // (a row walked arithmetically goes back to its position in the column list)
+      if (arith) pos = end - (run_lo <= run_hi ? run_hi - run_lo + 1 : 0);
+      uint32_t* first = bm + kBitmapBlocks * kTile;
+      uint32_t* at_lo = first + kTile;
+      uint32_t* at_hi = at_lo + kTile;
+      uint32_t* count = at_hi + kTile;
+      const int64_t nnz = row_ptr[L];
+      while (true) {
+        const int cur = pos < end ? col_idx[pos] >> 5 : INT32_MAX;
+        const int b0 = first_half_min(cur);              // the window: key blocks b0 .. b0 + kBitmapBlocks - 1
+        if (b0 == INT32_MAX) break;
+#pragma unroll
+        for (int k = 0; k < kBitmapBlocks * kTile / (4 * kWave); ++k)
+          reinterpret_cast<uint4*>(bm)[k * kWave + lane] = uint4{0u, 0u, 0u, 0u};
+        // where each row's columns inside the window end (at most one column per key)
+        const int64_t reach = end - pos > kBitmapBlocks * kTile ? pos + kBitmapBlocks * kTile : end;
+        const int64_t q = lower_bound_col(col_idx, pos, reach, ((int64_t)b0 + kBitmapBlocks) * kTile);
+        const int cnt = (int)(q - pos);
+        // The window's columns in units of 16 consecutive entries of one row, all units of the 32
+        // rows in one numbering: a lane takes a unit with four 16-byte loads, combines the bits
+        // that fall into the same word in registers, and adds each word to the bitmap with one
+        // LDS atomic (neighbouring lanes hold different words, or at worst the same one).
+        const int units = (cnt + 15) >> 4;
+        int incl = units;
+#pragma unroll
+        for (int off = 1; off < kTile; off <<= 1) {
+          const int up = __shfl_up(incl, off, kWave);
+          if (lane >= off) incl += up;
+        }
+        const int total = __shfl(incl, kTile - 1, kWave);
+        if (total == 0) break;                           // (cannot happen: the row that gave b0 has a column in the window)
+        if (lane < kTile) {
+          first[lane] = (uint32_t)(incl - units);
+          at_lo[lane] = (uint32_t)pos;
+          at_hi[lane] = (uint32_t)((uint64_t)pos >> 32);
+          count[lane] = (uint32_t)cnt;
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");      // (one wavefront: its LDS operations complete in order)
+        for (int u0 = 0; u0 < total; u0 += kBitmapUnits * kWave) {
+          int rr[kBitmapUnits], nn[kBitmapUnits];
+          int cc[kBitmapUnits][16];
+#pragma unroll
+          for (int v = 0; v < kBitmapUnits; ++v) {
+            const int unit = u0 + v * kWave + lane;
+            const int uu = unit < total ? unit : total - 1;
+            int r = 0;
+#pragma unroll
+            for (int st = kTile / 2; st > 0; st >>= 1)
+              if ((int)first[r + st] <= uu) r += st;
+            const int j = uu - (int)first[r];
+            const int64_t at = (int64_t)(((uint64_t)at_hi[r] << 32) | at_lo[r]) + 16 * j;
+            const int left = (int)count[r] - 16 * j;
+            rr[v] = r;
+            nn[v] = unit < total ? (left < 16 ? left : 16) : 0;
+            if (at + 16 <= nnz) {
+              __builtin_memcpy(cc[v], col_idx + at, 64);
+            } else {
+#pragma unroll
+              for (int t = 0; t < 16; ++t) cc[v][t] = at + t < nnz ? col_idx[at + t] : 0;
+            }
+          }
+#pragma unroll
+          for (int v = 0; v < kBitmapUnits; ++v) {
+            int held = -1;
+            uint32_t word = 0;
+#pragma unroll
+            for (int t = 0; t < 16; ++t) {
+              if (t < nn[v]) {
+                const int k = (cc[v][t] >> 5) - b0;
+                if (k != held) {
+                  if (held >= 0) atomicOr(&bm[held * kTile + rr[v]], word);
+                  held = k;
+                  word = 0;
+                }
+                word |= 1u << (cc[v][t] & 31);
+              }
+            }
+            if (held >= 0) atomicOr(&bm[held * kTile + rr[v]], word);
+          }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        for (int k = 0; k < kBitmapBlocks; ++k) {
+          const uint32_t word = lane < kTile ? bm[k * kTile + lane] : 0u;
+          if (!__any(word != 0u)) continue;
+          if (nblk >= cap) {
+            overflow = true;
+            break;
+          }
+          const bool full = __all(lane >= kTile || word == ~0u);
+          if (lane < kTile) pair_mask[(slot0 + nblk) * kTile + lane] = word;
+          if (lane == 0) pair_blk[slot0 + nblk] = (b0 + k) | (full ? kFullBit : 0);
+          ++nblk;
+          consumed += __builtin_popcount(word);
+          if (nblk == kProbeBlocks) {                    // (the same test as in the walk above)
+            int sum = consumed;
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) sum += __shfl_xor(sum, off, kWave);
+            if (sum < kProbeBlocks * kProbeEdges) {
+              overflow = true;
+              break;
+            }
+          }
+        }
+        if (overflow) break;
+        pos = q;
       }
     }
     if (lane == 0) {
@@ -3077,6 +3205,7 @@ sga_status run_tile_implicit(const AttnArgs& a) {
 void launch_tile_analyze(const AttnArgs& a) {
   const int64_t n_tiles = (a.L + kTile - 1) / kTile;
   int64_t nwg_analyze = n_tiles + 64;
+  if (nwg_analyze < 2048) nwg_analyze = 2048;
   if (nwg_analyze > 16384) nwg_analyze = 16384;
   hipLaunchKernelGGL(tile_analyze_kernel, dim3((unsigned)nwg_analyze), dim3(256), 0, a.stream, a.row_ptr,
                      a.col_idx, a.L, a.H, a.dtype, a.d, a.ws, a.ws_bytes);

@@ -181,6 +181,62 @@ def test_verification_protocol_bernoulli_masks(sf, path):
         assert max_err(lse[h][~empty], lse_ref[~empty]) <= LSE_TOL["f32"]
 
 
+def _scattered_masks(L):
+    """Dense masks with scattered columns at block fills that keep them on the tile path, long
+    enough that a tile's key-block list spans several windows of the CSR -> tile pass's bitmap
+    walk (32 key blocks each): even fill, fill that falls off along the row (so the late windows
+    are sparse), wide empty stretches between scattered ones, scattered columns next to rows that
+    are one run (a dense row, a band) or empty, and a scattered start followed by whole runs."""
+    rng = np.random.default_rng(23)
+    i = np.arange(L)[:, None]
+    j = np.arange(L)[None, :]
+    u = rng.random((L, L))
+    out = {}
+    out["even_0.3"] = u < 0.3
+    out["even_0.7"] = u < 0.7
+    out["falling"] = u < 0.9 * (1.0 - j / L) ** 2
+    out["gaps"] = (u < 0.5) & ((j // 700) % 2 == 0)
+    mixed = u < 0.4
+    mixed[5] = True
+    mixed[40:50] = False
+    mixed[64:96] = (np.abs(i - j) <= 40)[64:96]
+    mixed[96:128, :] = (u < 0.4)[96:128, :] | (j >= L - 200)
+    out["mixed_rows"] = mixed
+    out["scattered_then_runs"] = ((u < 0.5) & (j < 900)) | ((j >= 1500) & (j < 1500 + 64 + i % 200))
+    return out
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+@pytest.mark.parametrize("name", ["even_0.3", "even_0.7", "falling", "gaps", "mixed_rows", "scattered_then_runs"])
+def test_scattered_masks_every_path(name, dtype):
+    import torch
+    L, d, H = 3301, 64, 2
+    mask = _scattered_masks(L)[name]
+    Q, K, V = numpy_qkv(H, L, d, dtype, 0.7, 910)
+    rp, ci = R.csr_from_dense(mask)
+    dQ, dK, dV = to_device(Q, K, V)
+    drp, dci = to_device(rp, ci)
+    refs = [R.attention_dense(Q[h], K[h], V[h], mask, 0.125) for h in range(H)]
+    empty = ~mask.any(axis=1)
+    ws = sga.alloc_workspace(L, H, d, dtype, int(rp[-1]))
+    for path in PATHS:
+        O, lse = sga.attention_forward(dQ, dK, dV, drp, dci, 0.125, workspace=ws, path=path, want_lse=True)
+        O, lse = O.cpu().numpy(), lse.cpu().numpy()
+        for h in range(H):
+            assert max_err(O[h], refs[h][0]) <= TOL[dtype], (path, h)
+            assert (O[h][empty] == 0).all() and np.isneginf(lse[h][empty]).all()
+            assert max_err(lse[h][~empty], refs[h][1][~empty]) <= LSE_TOL[dtype], (path, h)
+    # the graph made once reproduces the call that makes it every time
+    O1, l1 = sga.attention_forward(dQ, dK, dV, drp, dci, 0.125, workspace=ws, path=sga.PATH_TILE, want_lse=True)
+    ws2 = sga.alloc_workspace(L, H, d, dtype, int(rp[-1]))
+    ws2.fill_(0x5A)
+    plan = sga.graph_prepare(drp, dci, H, d, dtype, ws2)
+    O2, l2 = sga.attention_forward_prepared(dQ, dK, dV, drp, dci, 0.125, plan, ws2, want_lse=True)
+    torch.cuda.synchronize()
+    assert plan.tiles_left < (L + 31) // 32          # (the tile path took part in it)
+    assert torch.equal(O1, O2) and torch.equal(l1, l2)
+
+
 def _run_masks(L):
     """Dense masks whose rows are made of runs of consecutive columns, one shape per branch of the
     CSR -> tile conversion: every row one run with touching block ranges (the loop without
