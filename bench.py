@@ -307,6 +307,15 @@ def cpu_baseline(wl, runner, budget_s=12.0, target_s=1.5):
     n = int(min(wl.L, max(len(probe), budget_s / per_row)))
     rows = np.sort(rng.choice(wl.L, size=n, replace=False)).astype(np.int64)
     t, edges = run(0, rows)
+    for _ in range(2):          # the probe rows pay for the first touches: top the sample up to the budget
+        if n == wl.L or t >= 0.8 * budget_s:
+            break
+        more = np.setdiff1d(rng.choice(wl.L, size=min(wl.L, int(n * (budget_s - t) / t) + 1), replace=False), rows)
+        if len(more) == 0:
+            break
+        dt, de = run(0, more.astype(np.int64))
+        rows = np.union1d(rows, more).astype(np.int64)
+        t, edges, n = t + dt, edges + de, len(rows)
     heads, n_rows = 1, n
     while n == wl.L and t < target_s and heads < wl.H:      # whole heads were cheap: take more
         dt, de = run(heads, rows)

@@ -312,15 +312,33 @@ __global__ __launch_bounds__(256) void split_prepass_kernel(const int64_t* __res
   if (skip_tiled && (tiles_cover_everything(pl, ws) || tile_handled(pl, ws, row_ptr, L, dtype, i / kTile)))
     return;
   uint32_t* ctr = reinterpret_cast<uint32_t*>(ws);
-  int32_t n, len;
-  row_split_shape(deg, pl, n, len);
+  int32_t n, len, nf, lenf;
+  row_split_shape(deg, pl, false, n, len);
+  row_split_shape(deg, pl, true, nf, lenf);
+  if (nf <= n) {
+    nf = n;
+    lenf = len;
+  }
   atomicAdd(&ctr[kCtrChunksNeeded], (uint32_t)n);
   atomicMax(&ctr[kCtrMaxChunks], (uint32_t)n);
+  atomicAdd(&ctr[kCtrFineNeeded], (uint32_t)nf);
+  atomicMax(&ctr[kCtrMaxChunksFine], (uint32_t)nf);
   const uint32_t base = atomicAdd(&ctr[kCtrItemsAlloc], (uint32_t)n);
+  const uint32_t basef = atomicAdd(&ctr[kCtrFineAlloc], (uint32_t)nf);
   if ((int64_t)base + n > pl.cap_items) return;
   const uint32_t slot = atomicAdd(&ctr[kCtrLongRows], 1u);
   int4* lr = reinterpret_cast<int4*>(static_cast<char*>(ws) + pl.off_long);
   lr[slot] = make_int4((int)i, (int)base, n, len);
+  // (read only if the finer chunks of every row fit, and then basef + nf <= cap_items)
+  lr[pl.cap_items + slot] = make_int4((int)i, (int)basef, nf, lenf);
+}
+
+// The list of long rows that this call uses: the finer split if all its chunks fit.
+__device__ __forceinline__ const int4* long_rows(const WorkspacePlan& pl, const void* ws, uint32_t& max_chunks) {
+  const uint32_t* ctr = reinterpret_cast<const uint32_t*>(ws);
+  const bool fine = (int64_t)ctr[kCtrFineNeeded] <= pl.cap_items;
+  max_chunks = ctr[fine ? kCtrMaxChunksFine : kCtrMaxChunks];
+  return reinterpret_cast<const int4*>(static_cast<const char*>(ws) + pl.off_long) + (fine ? pl.cap_items : 0);
 }
 
 // True when the long rows of this call are handled by the chunk kernels.
@@ -606,14 +624,14 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
   if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, D);
   const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrLongRows];
-  const int4* lr = reinterpret_cast<const int4*>(static_cast<char*>(ws) + pl.off_long);
+  uint32_t max_chunks;
+  const int4* lr = long_rows(pl, ws, max_chunks);
   float* partials = reinterpret_cast<float*>(static_cast<char*>(ws) + pl.off_partials);
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
   const int64_t hoff = h * L * D;
   const uint32_t xcd = blockIdx.x & 7;
-  const uint32_t max_chunks = reinterpret_cast<const uint32_t*>(ws)[kCtrMaxChunks];
   const uint64_t n_units = (uint64_t)n_long * ((max_chunks + 7) / 8);
   for (uint64_t u = (uint64_t)(blockIdx.x >> 3) * waves + threadIdx.x / kWave; u < n_units;
        u += (uint64_t)(gridDim.x >> 3) * waves) {
@@ -646,21 +664,40 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
 }
 
 // Partial states p0[c * step + ...], c < n, combined in order into one partial state
-// (D accumulators, m, l) at `out`; one wavefront, lane c owns channels c, c + 64, ...
+// (D accumulators, m, l) at `out`; one wavefront, lane c owns channels c, c + 64, ...  The
+// maxima are read 64 partials at a time and the states eight at a time, so that a row of a
+// thousand chunks does not wait for a thousand loads one after the other; the sums run in
+// chunk order all the same.
 template <int D>
 __device__ __forceinline__ void combine_partials(const float* p0, int64_t step, int n, float* out, int lane) {
   constexpr int kCh = (D + kWave - 1) / kWave;
+  constexpr int kAhead = 8;
   float M = kMinusHuge;
-  for (int c = 0; c < n; ++c) M = fmaxf(M, p0[c * step + D]);
+  for (int c = lane; c < n; c += kWave) M = fmaxf(M, p0[c * step + D]);
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) M = fmaxf(M, __shfl_xor(M, off, kWave));
   float l = 0.f, acc[kCh];
 #pragma unroll
   for (int k = 0; k < kCh; ++k) acc[k] = 0.f;
-  for (int c = 0; c < n; ++c) {
-    const float w = __builtin_amdgcn_exp2f(p0[c * step + D] - M);
-    l = __builtin_fmaf(p0[c * step + D + 1], w, l);
+  for (int c0 = 0; c0 < n; c0 += kAhead) {
+    float mm[kAhead], ll[kAhead], aa[kAhead][kCh];
 #pragma unroll
-    for (int k = 0; k < kCh; ++k)
-      if (lane + k * kWave < D) acc[k] = __builtin_fmaf(p0[c * step + lane + k * kWave], w, acc[k]);
+    for (int u = 0; u < kAhead; ++u) {
+      const float* p = p0 + (c0 + u < n ? c0 + u : n - 1) * step;
+      mm[u] = p[D];
+      ll[u] = p[D + 1];
+#pragma unroll
+      for (int k = 0; k < kCh; ++k) aa[u][k] = lane + k * kWave < D ? p[lane + k * kWave] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kAhead; ++u) {
+      if (c0 + u < n) {
+        const float w = __builtin_amdgcn_exp2f(mm[u] - M);
+        l = __builtin_fmaf(ll[u], w, l);
+#pragma unroll
+        for (int k = 0; k < kCh; ++k) acc[k] = __builtin_fmaf(aa[u][k], w, acc[k]);
+      }
+    }
   }
 #pragma unroll
   for (int k = 0; k < kCh; ++k)
@@ -687,7 +724,8 @@ __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, fl
   if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
   const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], dtype, D);
   const uint32_t n_long = reinterpret_cast<const uint32_t*>(ws)[kCtrLongRows];
-  const int4* lr = reinterpret_cast<const int4*>(static_cast<char*>(ws) + pl.off_long);
+  uint32_t max_chunks;
+  const int4* lr = long_rows(pl, ws, max_chunks);
   const float* partials = reinterpret_cast<const float*>(static_cast<char*>(ws) + pl.off_partials);
   const int lane = threadIdx.x & (kWave - 1);
   const int wave = threadIdx.x / kWave;
@@ -700,7 +738,7 @@ __global__ __launch_bounds__(256) void gather_merge_kernel(T* __restrict__ O, fl
     merge_row_partials<T, D>(partials + ((int64_t)rec.y * H + h) * (D + 4), step, rec.z, O + h * L * D + i * D,
                              lse ? lse + h * L + i : nullptr, lane, accumulate != 0);
   }
-  if (reinterpret_cast<const uint32_t*>(ws)[kCtrMaxChunks] <= (uint32_t)kMaxSplit) return;
+  if (max_chunks <= (uint32_t)kMaxSplit) return;
   for (uint32_t r = blockIdx.x; r < n_long; r += gridDim.x) {      // (the same trips for the whole workgroup)
     const int4 rec = lr[r];
     if (rec.z <= kMaxSplit) continue;

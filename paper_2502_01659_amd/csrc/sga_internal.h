@@ -114,6 +114,9 @@ enum WsCounter : int {
   kCtrTilesBad = 5,         // tiles whose block lists overflowed (left to the gather path)
   kCtrMultiTiles = 6,       // multi-segment tiles recorded in the merge list
   kCtrMaxChunks = 7,        // most chunks any split row has (bounds the chunk kernel's unit loop)
+  kCtrFineNeeded = 8,       // the same three for the finer split (see row_split_shape)
+  kCtrFineAlloc = 9,
+  kCtrMaxChunksFine = 10,
   kNumCounters = 64
 };
 
@@ -176,7 +179,7 @@ __host__ __device__ inline WorkspacePlan plan_workspace(int64_t L, int32_t H, in
   if (nnz < 0) cap = (int64_t)kMaxImplicitGlobal * kMaxSplit;
   p.cap_items = cap;
   p.off_long = off;
-  off = (off + (size_t)cap * 16 + 255) & ~size_t(255);
+  off = (off + (size_t)cap * 32 + 255) & ~size_t(255);      // (the records of the finer split follow the cap records)
   p.off_partials = off;
   off = (off + (size_t)cap * H * (d + 4) * sizeof(float) + 255) & ~size_t(255);
   // tile path
@@ -224,9 +227,16 @@ __host__ __device__ inline bool row_is_split(int64_t deg, const WorkspacePlan& p
   return deg > kSplitThreshold || (p.l2_chunks && deg >= (int64_t)kL2ChunkEdges * p.l2_chunks);
 }
 // ... into nchunks chunks of len edges (the last one shorter), len a multiple of 32.
-__host__ __device__ inline void row_split_shape(int64_t deg, const WorkspacePlan& p, int32_t& nchunks,
+// The slots are sized for chunks of split_chunk edges with every row of the mask split; where
+// the split rows hold a small part of the edges (a few dense rows beside a window), the same
+// slots take chunks of kSplitChunkMin edges: the call uses this finer split (fine = true)
+// if the chunks of all its rows then still fit, else the coarser one for every row.  (One
+// global token at L = 65,536, 8 heads, fp32: 32 chunks of 2,048 edges per head kept 256
+// wavefronts busy for 0.29 ms, each waiting for its own gathers.)
+__host__ __device__ inline void row_split_shape(int64_t deg, const WorkspacePlan& p, bool fine, int32_t& nchunks,
                                                 int32_t& len) {
-  int64_t n = (deg + p.split_chunk - 1) / p.split_chunk;
+  const int chunk = fine ? kSplitChunkMin : p.split_chunk;
+  int64_t n = (deg + chunk - 1) / chunk;
   if (n > kMaxSplitLong) n = kMaxSplitLong;
   // (a row of more than kMaxSplit chunks by edge count keeps them: there are few such rows in a
   // call, and each has to spread over the chip before it can share an L2 with its neighbours)
