@@ -239,7 +239,8 @@ def roofline_of(wl, nnz, kern_ms, fwd_ms, path_used, kernel, prepared=False):
     edges = nnz * wl.H
     t, tf = kern_ms * 1e-3, fwd_ms * 1e-3
     split = path_used == "tile_split"
-    path_used = "gather" if path_used == "gather" else "tile"
+    # (the per-row kernels do their products on the vector unit, whichever path was asked for)
+    path_used = "gather" if path_used == "gather" or str(kernel).startswith("gather") else "tile"
     flops = FLOPS_PER_EDGE * edges
     kbytes = tensor_bytes(wl)
     fbytes = kbytes if prepared else algorithmic_bytes(wl, nnz)
@@ -682,23 +683,30 @@ def main():
 
     if not args.no_sweep:
         sweep = []
-        for name, w in WORKLOADS.items():
+        # the five workloads, and the random CSR of the microbenchmark grid (Section V-C) that runs
+        # on the per-row kernels
+        general_csr = "e2_random_24k_sf0100_f32"
+        for name, w in list(WORKLOADS.items()) + [(general_csr, E2_RANDOM_WORKLOADS[general_csr])]:
             if name == wl.name:
                 continue
             try:
                 r = Runner(w, path)
+                if name == general_csr:
+                    # no tile of this mask qualifies, and only a prepared graph knows that before
+                    # the launch: its forward brackets the per-row kernel that does the work
+                    r.prepare()
                 ms, f, b, km = r.timed(20, 5)      # (each of these steps takes 0.05 to 2.5 ms)
                 e = r.nnz * w.H
-                sweep.append({"workload": name, "L": w.L, "H": w.H, "dtype": w.dtype,
+                sweep.append({"workload": name, "L": w.L, "H": w.H, "dtype": w.dtype, "prepared": r.prepared,
                               "edges_per_step": e, "ms_per_step": ms, "forward_ms": f,
                               "forward_ms_min": r.min_forward_ms, "kernel_ms_min": r.min_kernel_ms,
                               "build_mask_ms": b, "ms_per_head": f / w.H,
                               "forward_edges_per_s": e / (f * 1e-3),
-                              "roofline": roofline_of(w, r.nnz, km, f, args.path, r.kernel)})
+                              "roofline": roofline_of(w, r.nnz, km, f, args.path, r.kernel, r.prepared)})
                 if fits_cache(w):
                     cf, ck = r.cold()
                     sweep[-1]["cold_cache"] = {"forward_ms": cf, "kernel_ms": ck}
-                if w.explicit:
+                if w.explicit and not r.prepared:
                     sweep[-1]["steady_state"] = steady_state(r, 20, 5, args.path)
                 del r
             except Exception as ex:    # a sweep entry must not lose the headline line

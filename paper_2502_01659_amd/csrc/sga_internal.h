@@ -20,7 +20,7 @@ constexpr int kSplitChunkMin = 256;   // ... of a call with little work in total
 constexpr int kMaxSplit = 64;         // at most this many chunks per row by L2 share, and ranges of an implicit global row
 // ... and by edge count: a row of millions of neighbours (one global token of a long sequence
 // whose tile does not qualify for the tile path) must spread over the chip, not over 64
-// wavefronts (L = 4,194,304, one global token, fp16: 2.65 -> 0.6 ms)
+// wavefronts (L = 4,194,304, one global token, fp16: 2.65 -> 0.8 ms)
 constexpr int kMaxSplitLong = 1024;
 // Keys whose K and V rows do not fit one L2 (each of the 8 XCDs has its own 4 MB): rows of at
 // least kL2ChunkEdges * n neighbours are then cut into n = l2_chunks() chunks, a multiple of 8, and
