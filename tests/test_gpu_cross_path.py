@@ -160,3 +160,77 @@ def test_implicit_nonlocal_tiles_at_length(dtype):
     tol = 1e-6 if dtype == "f32" else 1e-3
     assert (O3[has].float() - 1.0).abs().max().item() <= tol
     assert (O3[~has].float() == 0).all()
+
+
+def _scattered_mask(rng, seed, L):
+    """A dense boolean mask of scattered columns drawn on the device: even or falling fill, column
+    stripes, per-row fill, random blocks, or scattered columns next to dense rows, empty rows,
+    a band and full columns."""
+    import torch
+    g = torch.Generator(device="cuda:0")
+    g.manual_seed(seed)
+    u = torch.rand((L, L), generator=g, device="cuda:0")
+    j = torch.arange(L, device="cuda:0")[None, :]
+    i = torch.arange(L, device="cuda:0")[:, None]
+    kind = rng.choice(["even", "falling", "stripes", "mixed", "rowvar", "blocks"])
+    p = rng.choice([0.13, 0.2, 0.35, 0.5, 0.8, 0.97])
+    if kind == "even":
+        return kind, u < p
+    if kind == "falling":
+        return kind, u < p * (1 - j / L) ** rng.choice([1, 2, 4])
+    if kind == "stripes":
+        w = rng.choice([40, 333, 1024, 1500])
+        return kind, (u < p) & ((j // w) % rng.choice([2, 3]) == 0)
+    if kind == "rowvar":
+        return kind, u < (p * ((i * 7919) % 97) / 97.0)
+    if kind == "blocks":
+        b = rng.choice([32, 64, 100])
+        nb = (L + b - 1) // b
+        ub = torch.rand((nb, nb), generator=g, device="cuda:0")
+        return kind, (ub < 0.3).repeat_interleave(b, 0).repeat_interleave(b, 1)[:L, :L] & (u < max(p, 0.5))
+    m = u < p
+    for _ in range(rng.randint(1, 4)):
+        m[rng.randrange(L)] = True
+    for _ in range(rng.randint(1, 4)):
+        r = rng.randrange(L)
+        m[r:r + rng.randint(1, 40)] = False
+    r = rng.randrange(max(1, L - 64))
+    m[r:r + 64] = ((i - j).abs() <= rng.randint(0, 200))[r:r + 64]
+    c = rng.randrange(L)
+    m[:, c:c + rng.randint(1, 70)] = True
+    return kind, m
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_scattered_masks_tiles_agree_with_row_kernels_and_prepared_graphs(seed):
+    """Masks of scattered columns (the CSR -> tile pass builds their block words from an LDS
+    bitmap once a list's first blocks show scattered columns), at lengths whose lists span up to
+    nine windows of that walk, at d = 64 and 128."""
+    import torch
+    rng = random.Random(7000 + seed)
+    L = rng.choice([rng.randint(100, 700), rng.randint(700, 3000), rng.randint(3000, 9000)])
+    dtype = rng.choice(["f16", "f32"])
+    H = rng.choice([1, 2, 3])
+    d = rng.choice([64, 64, 128])
+    kind, m = _scattered_mask(rng, seed, L)
+    rp = torch.zeros(L + 1, dtype=torch.int64, device="cuda:0")
+    rp[1:] = m.sum(dim=1).cumsum(0)
+    ci = m.nonzero()[:, 1].to(torch.int32).contiguous()
+    del m
+    nnz = int(rp[-1])
+    if nnz == 0:
+        pytest.skip("empty mask")
+    sigma = rng.choice([0.3, 1.0])
+    scale = rng.choice([0.125, -0.125, 0.3]) * (64 / d) ** 0.5
+    print("case", seed, kind, "L", L, dtype, "H", H, "d", d, "nnz", nnz, flush=True)
+    Q, K, V = torch_qkv(H, L, d, dtype, sigma, seed, "cuda:0")
+    ws = sga.alloc_workspace(L, H, d, dtype, nnz)
+    O1, l1 = sga.attention_forward(Q, K, V, rp, ci, scale, workspace=ws, path=sga.PATH_TILE, want_lse=True)
+    O2, l2 = sga.attention_forward(Q, K, V, rp, ci, scale, path=sga.PATH_GATHER, want_lse=True)
+    ws2 = sga.alloc_workspace(L, H, d, dtype, nnz)
+    ws2.fill_(0x5A)
+    plan = sga.graph_prepare(rp, ci, H, d, dtype, ws2)
+    O3, l3 = sga.attention_forward_prepared(Q, K, V, rp, ci, scale, plan, ws2, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O3) and torch.equal(l1, l3)
+    _agree(O1, l1, O2, l2, dtype)
