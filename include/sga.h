@@ -139,6 +139,25 @@ sga_status sga_build_mask(const sga_mask_desc* desc, int64_t* row_ptr, int32_t* 
                           int64_t col_capacity, void* stream);
 
 /*
+ * Checks what the forward calls assume of an explicit mask (Section IV-B "CSR": row offsets
+ * and sorted column indices of a binary mask) and do not check themselves: row_ptr[0] = 0,
+ * row_ptr non-decreasing, row_ptr[L] <= col_capacity, every column in [0, L), the columns of a
+ * row strictly increasing (no duplicates).  A forward call on arrays that break this reads
+ * outside K and V or counts an edge twice.
+ *   row_ptr       device, int64 [L+1], read
+ *   col_idx       device, int32 [col_capacity], the first row_ptr[L] entries are read
+ *   scratch       device, at least 16 bytes, 8-byte aligned, overwritten (the start of a
+ *                 workspace will do; its contents are lost)
+ *   bad_row_out   host, may be null: -1 if the arrays are valid, else the smallest row that
+ *                 breaks the contract (L if row_ptr[0] or row_ptr[L] does)
+ * Enqueues three small kernels on `stream` and waits for them (it returns a verdict).
+ * Returns SGA_OK (valid), SGA_ERR_INVALID_ARG (null pointer, L < 1 or >= 2^31, negative
+ * capacity, or the contract is broken), SGA_ERR_HIP.
+ */
+sga_status sga_validate_csr(const int64_t* row_ptr, const int32_t* col_idx, int64_t L,
+                            int64_t col_capacity, void* scratch, int64_t* bad_row_out, void* stream);
+
+/*
  * Workspace size the forward calls can use for the given problem.
  *   nnz: edge count of the explicit mask, or -1 for the implicit entry point.
  * bytes_out (host) receives a size that is sufficient for every path; a smaller

@@ -72,6 +72,8 @@ def load():
     lib.sga_mask_nnz.argtypes = [P(_MaskDesc), P(ctypes.c_int64)]
     lib.sga_build_mask.restype = ctypes.c_int
     lib.sga_build_mask.argtypes = [P(_MaskDesc), vp, vp, i64, vp]
+    lib.sga_validate_csr.restype = ctypes.c_int
+    lib.sga_validate_csr.argtypes = [vp, vp, i64, i64, vp, P(ctypes.c_int64), vp]
     lib.sga_workspace_bytes.restype = ctypes.c_int
     lib.sga_workspace_bytes.argtypes = [i64, i32, i32, i32, i64, P(ctypes.c_size_t)]
     lib.sga_attention_forward.restype = ctypes.c_int
@@ -129,6 +131,13 @@ def sga_mask_nnz(spec: MaskSpec):
 def sga_build_mask(spec: MaskSpec, row_ptr_addr, col_idx_addr, col_capacity, stream):
     d = _desc(spec)
     return load().sga_build_mask(ctypes.byref(d), row_ptr_addr, col_idx_addr, col_capacity, stream)
+
+
+def sga_validate_csr(row_ptr_addr, col_idx_addr, L, col_capacity, scratch_addr, stream):
+    """-> (status, bad_row)"""
+    bad = ctypes.c_int64(-2)
+    st = load().sga_validate_csr(row_ptr_addr, col_idx_addr, L, col_capacity, scratch_addr, ctypes.byref(bad), stream)
+    return st, bad.value
 
 
 def sga_workspace_bytes(L, H, d, dtype_code, nnz):
@@ -251,6 +260,25 @@ def build_mask(spec: MaskSpec, device="cuda"):
     if st != 0:
         raise SgaError(st, "sga_build_mask")
     return row_ptr, col_idx[:nnz]
+
+
+def validate_csr(row_ptr, col_idx) -> int:
+    """-1 if (row_ptr, col_idx) is a valid mask for the forward calls, else the smallest row that
+    breaks the contract (L if row_ptr[0] or row_ptr[L] does).  Waits for the current stream."""
+    import torch
+    if not (row_ptr.is_cuda and col_idx.is_cuda and row_ptr.device == col_idx.device):
+        raise ValueError("row_ptr and col_idx must be tensors of one device")
+    if row_ptr.dtype != torch.int64 or col_idx.dtype != torch.int32 or row_ptr.dim() != 1 or col_idx.dim() != 1:
+        raise ValueError("row_ptr must be int64 [L+1], col_idx int32 [nnz]")
+    if not (row_ptr.is_contiguous() and col_idx.is_contiguous()) or row_ptr.numel() < 2:
+        raise ValueError("row_ptr and col_idx must be contiguous, L >= 1")
+    scratch = torch.empty(2, dtype=torch.int64, device=row_ptr.device)
+    with torch.cuda.device(row_ptr.device):
+        st, bad = sga_validate_csr(row_ptr.data_ptr(), _col_ptr(row_ptr, col_idx), row_ptr.numel() - 1,
+                                   col_idx.numel(), scratch.data_ptr(), _stream())
+    if st != 0 and bad < 0:
+        raise SgaError(st, "sga_validate_csr")
+    return bad
 
 
 def workspace_bytes(L, H, d, dtype, nnz=-1) -> int:

@@ -164,6 +164,24 @@ sga_status sga_build_mask(const sga_mask_desc* desc, int64_t* row_ptr, int32_t* 
   return launch_build_mask(*desc, row_ptr, col_idx, static_cast<hipStream_t>(stream));
 }
 
+sga_status sga_validate_csr(const int64_t* row_ptr, const int32_t* col_idx, int64_t L,
+                            int64_t col_capacity, void* scratch, int64_t* bad_row_out, void* stream) {
+  if (!row_ptr || !col_idx || !scratch || (reinterpret_cast<uintptr_t>(scratch) & 7)) return SGA_ERR_INVALID_ARG;
+  if (L < 1 || L >= (int64_t(1) << 31) || col_capacity < 0) return SGA_ERR_INVALID_ARG;
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  (void)hipGetLastError();   // drop stale errors of earlier, unrelated runtime calls
+  unsigned long long* verdict = static_cast<unsigned long long*>(scratch);
+  const sga_status launched = launch_validate_csr(row_ptr, col_idx, L, col_capacity, verdict, st);
+  if (launched != SGA_OK) return launched;
+  unsigned long long found[2] = {0, 0};   // in the row offsets, in the columns
+  if (hipMemcpyAsync(found, verdict, sizeof(found), hipMemcpyDeviceToHost, st) != hipSuccess ||
+      hipStreamSynchronize(st) != hipSuccess)
+    return SGA_ERR_HIP;
+  const unsigned long long bad = found[0] < found[1] ? found[0] : found[1];
+  if (bad_row_out) *bad_row_out = bad == ~0ull ? -1 : (int64_t)bad;
+  return bad == ~0ull ? SGA_OK : SGA_ERR_INVALID_ARG;
+}
+
 sga_status sga_workspace_bytes(int64_t L, int32_t H, int32_t d, int32_t dtype, int64_t nnz,
                                size_t* bytes_out) {
   if (!bytes_out) return SGA_ERR_INVALID_ARG;

@@ -299,6 +299,74 @@ sga_status mask_validate(const sga_mask_desc* d) {
   }
 }
 
+namespace {
+
+constexpr unsigned long long kNoBadRow = ~0ull;
+
+// verdict[0]: smallest bad row found in the row offsets, verdict[1]: in the columns.
+__global__ void validate_init_kernel(unsigned long long* verdict) {
+  verdict[0] = kNoBadRow;
+  verdict[1] = kNoBadRow;
+}
+
+// One thread per row offset: row_ptr[0] = 0, no offset below its predecessor, the last one
+// within the column array.  A violation of the first or the last kind is reported as row L.
+__global__ __launch_bounds__(256) void validate_rows_kernel(const int64_t* __restrict__ row_ptr, int64_t L,
+                                                            int64_t col_capacity, unsigned long long* verdict) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i > L) return;
+  if (i == L) {
+    if (row_ptr[0] != 0 || row_ptr[L] < 0 || row_ptr[L] > col_capacity) atomicMin(verdict, (unsigned long long)L);
+    return;
+  }
+  if (row_ptr[i] < 0 || row_ptr[i] > row_ptr[i + 1]) atomicMin(verdict, (unsigned long long)i);
+}
+
+// The row of edge e: the last row whose offset is <= e (rows without edges share an offset
+// with the row after them, and the last of them owns the edge).
+__device__ __forceinline__ int64_t row_of_edge(const int64_t* __restrict__ row_ptr, int64_t L, int64_t e) {
+  int64_t lo = 0, hi = L;                 // row_ptr[lo] <= e < row_ptr[hi]
+  while (hi - lo > 1) {
+    const int64_t mid = lo + ((hi - lo) >> 1);
+    if (row_ptr[mid] <= e) lo = mid; else hi = mid;
+  }
+  return lo;
+}
+
+// One thread per edge (grid-stride): the column lies in [0, L) and, unless the edge is the
+// first of its row, above the column before it.  Only an edge that fails the second test looks
+// its row up (about once per row: where the next row starts further left).  Runs only if the
+// row offsets passed, so every index it forms lies inside the arrays.
+__global__ __launch_bounds__(256) void validate_cols_kernel(const int64_t* __restrict__ row_ptr,
+                                                            const int32_t* __restrict__ col_idx, int64_t L,
+                                                            unsigned long long* verdict) {
+  if (verdict[0] != kNoBadRow) return;    // (written by the launch before this one only)
+  const int64_t nnz = row_ptr[L];
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < nnz; e += (int64_t)gridDim.x * blockDim.x) {
+    const int32_t c = col_idx[e];
+    const bool outside = c < 0 || c >= L;
+    const bool descends = e > 0 && c <= col_idx[e - 1];
+    if (outside || descends) {
+      const int64_t r = row_of_edge(row_ptr, L, e);
+      if (outside || row_ptr[r] != e) atomicMin(verdict + 1, (unsigned long long)r);
+    }
+  }
+}
+
+}  // namespace
+
+sga_status launch_validate_csr(const int64_t* row_ptr, const int32_t* col_idx, int64_t L, int64_t col_capacity,
+                               unsigned long long* verdict, hipStream_t stream) {
+  hipLaunchKernelGGL(validate_init_kernel, dim3(1), dim3(1), 0, stream, verdict);
+  hipLaunchKernelGGL(validate_rows_kernel, dim3((unsigned)((L + 1 + 255) / 256)), dim3(256), 0, stream, row_ptr, L,
+                     col_capacity, verdict);
+  int64_t wgs = (col_capacity + 255) / 256;
+  if (wgs > 16384) wgs = 16384;
+  if (wgs < 1) wgs = 1;
+  hipLaunchKernelGGL(validate_cols_kernel, dim3((unsigned)wgs), dim3(256), 0, stream, row_ptr, col_idx, L, verdict);
+  return hip_status(hipGetLastError());
+}
+
 int64_t mask_total_edges(const sga_mask_desc& d) {
   const MaskParams p = make_params(d);
   return row_offset(p, p.L);

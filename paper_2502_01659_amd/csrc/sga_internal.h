@@ -350,6 +350,10 @@ sga_status mask_validate(const sga_mask_desc* d);
 int64_t mask_total_edges(const sga_mask_desc& d);
 sga_status launch_build_mask(const sga_mask_desc& d, int64_t* row_ptr, int32_t* col_idx,
                              hipStream_t stream);
+// Enqueues the checks of sga_validate_csr; verdict[0] and verdict[1] (uint64) end as the smallest bad row
+// found in the row offsets and in the columns, or ~0.
+sga_status launch_validate_csr(const int64_t* row_ptr, const int32_t* col_idx, int64_t L, int64_t col_capacity,
+                               unsigned long long* verdict, hipStream_t stream);
 
 // Benchmark hook (api.hip): when enabled, brackets the dominant attention kernel of a forward
 // call with a pair of events on the call's stream.

@@ -128,3 +128,74 @@ def test_build_mask_capacity_error():
     ci = torch.empty(10, dtype=torch.int32, device="cuda")
     st = sga.sga_build_mask(spec, rp.data_ptr(), ci.data_ptr(), 10, None)
     assert st == -3
+
+
+@pytest.mark.parametrize("spec", SPECS, ids=lambda s: f"{s.name}-L{s.L}-w{s.window}{s.window_blocks}")
+def test_validate_csr_accepts_every_built_mask(spec):
+    rp, ci = sga.build_mask(spec)
+    assert sga.validate_csr(rp, ci) == -1
+
+
+def test_validate_csr_names_the_first_bad_row():
+    """Each way of breaking the contract of an explicit mask (Section IV-B "CSR": row offsets,
+    sorted column indices), planted into a copy of a valid mask with empty rows in it; the
+    oracle's CSR of the same dense mask is the valid starting point."""
+    import torch
+    L = 700
+    dense = np.random.default_rng(3).random((L, L)) < 0.05
+    dense[100:110] = False                      # empty rows: their offsets repeat
+    dense[300] = True
+    rp_h, ci_h = R.csr_from_dense(dense)
+    rp = torch.from_numpy(rp_h).cuda()
+    ci = torch.from_numpy(ci_h).cuda()
+    assert sga.validate_csr(rp, ci) == -1
+
+    def planted(edit_rp=None, edit_ci=None):
+        r, c = rp.clone(), ci.clone()
+        if edit_rp:
+            edit_rp(r)
+        if edit_ci:
+            edit_ci(c)
+        return sga.validate_csr(r, c)
+
+    e300 = int(rp_h[300])
+    assert planted(edit_ci=lambda c: c.__setitem__(e300 + 5, int(ci_h[e300 + 4]))) == 300          # duplicate
+    assert planted(edit_ci=lambda c: c.__setitem__(e300 + 5, int(ci_h[e300 + 3]))) == 300          # descending
+    assert planted(edit_ci=lambda c: c.__setitem__(int(rp_h[650]), L)) == 650                      # column = L
+    assert planted(edit_ci=lambda c: c.__setitem__(int(rp_h[12]), -1)) == 12                       # negative column
+    assert planted(edit_ci=lambda c: c.__setitem__(len(ci_h) - 1, 2 ** 31 - 1)) == L - 1           # last edge
+    # two violations: the smaller row is named
+    def two(c):
+        c[int(rp_h[500])] = L + 7
+        c[int(rp_h[40])] = -5
+    assert planted(edit_ci=two) == 40
+    # the first column of a row may lie left of the last column of the row before it, also
+    # across empty rows (rows 99 | 100..109 empty | 110), which is no violation: covered by the
+    # valid mask above; a row offset that steps back is one
+    assert planted(edit_rp=lambda r: r.__setitem__(200, int(rp_h[199]) - 1)) == 199
+    assert planted(edit_rp=lambda r: r.__setitem__(0, 1)) == L                                     # row_ptr[0] != 0
+    assert planted(edit_rp=lambda r: r.__setitem__(L, len(ci_h) + 1)) == L                         # beyond the columns
+    assert planted(edit_rp=lambda r: r.__setitem__(5, -3)) == 4                                    # (row 4 ends before it starts)
+    # raw C ABI: status and argument errors
+    scratch = torch.empty(2, dtype=torch.int64, device="cuda")
+    st, bad = sga.sga_validate_csr(rp.data_ptr(), ci.data_ptr(), L, ci.numel(), scratch.data_ptr(), None)
+    assert (st, bad) == (0, -1)
+    bad_ci = ci.clone()
+    bad_ci[e300 + 5] = int(ci_h[e300 + 4])
+    st, bad = sga.sga_validate_csr(rp.data_ptr(), bad_ci.data_ptr(), L, ci.numel(), scratch.data_ptr(), None)
+    assert (st, bad) == (-1, 300)
+    assert sga.sga_validate_csr(0, ci.data_ptr(), L, ci.numel(), scratch.data_ptr(), None)[0] == -1
+    assert sga.sga_validate_csr(rp.data_ptr(), ci.data_ptr(), 0, ci.numel(), scratch.data_ptr(), None)[0] == -1
+    assert sga.sga_validate_csr(rp.data_ptr(), ci.data_ptr(), L, ci.numel(), scratch.data_ptr() + 4, None)[0] == -1
+
+
+def test_validate_csr_at_size():
+    """Workload 4's mask (671,014,912 edges, rows of a million columns) passes, and one duplicate
+    column planted deep inside it is found."""
+    spec = WORKLOADS["cfg4_bigbird_1m"].mask
+    rp, ci = sga.build_mask(spec)
+    assert sga.validate_csr(rp, ci) == -1
+    row = 777_777
+    e = int(rp[row]) + 100
+    ci[e] = ci[e - 1]
+    assert sga.validate_csr(rp, ci) == row
