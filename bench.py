@@ -482,6 +482,85 @@ def suite_e2(path, dims=(64, 128, 256)):
     return {"suite": "e2", "unit": "ms per forward, one head, fp32", "rows": rows}
 
 
+def suite_vf(path, dtype="f32"):
+    """The masks of the paper's model comparison (Section V-F): local attention of 50 tokens each
+    way with three global tokens (Longformer), the same with a dilated window (every second
+    token, 100 each way), and local + global + uniformly random attention at S_f = 0.001
+    (BigBird), one head, d = 64, four context lengths.  Each mask runs as one CSR call (first
+    call and prepared graph); the first and the third also as the paper's sequence of calls on
+    one (O, lse) state: implicit local, implicit global (non-local), and for the third a CSR call
+    on the random edges that the first two do not cover.  The two forms are compared (largest
+    difference of O) as the paper does."""
+    import torch
+    import paper_2502_01659_amd as sga
+    from sga_inputs import MaskSpec, KIND_SLIDING, KIND_NONLOCAL, KIND_GLOBAL_LOCAL, torch_qkv, BASE_SEED
+    w, g, d, sf = 50, 3, 64, 0.001
+    scale = d ** -0.5
+    rows = []
+
+    def csr_of(dense):
+        rp = torch.zeros(dense.shape[0] + 1, dtype=torch.int64, device="cuda:0")
+        rp[1:] = dense.sum(dim=1).cumsum(0)
+        # (row blocks: one nonzero() over more than 2^31 entries is beyond the library routine)
+        cols = [dense[r0:r0 + 4096].nonzero()[:, 1].to(torch.int32) for r0 in range(0, dense.shape[0], 4096)]
+        return rp, torch.cat(cols).contiguous()
+
+    for L in (10_000, 20_000, 35_000, 50_000):
+        Q, K, V = torch_qkv(1, L, d, dtype, 1.0 if dtype == "f32" else 0.5, BASE_SEED, "cuda:0")
+        loc = MaskSpec(KIND_SLIDING, L, window=w)
+        nl = MaskSpec(KIND_NONLOCAL, L, window=w, n_global=g)
+        i = torch.arange(L, device="cuda:0")[:, None]
+        j = torch.arange(L, device="cuda:0")[None, :]
+        glob = (i < g) | (j < g)
+        gen = torch.Generator(device="cuda:0")
+        gen.manual_seed(BASE_SEED + 11)
+        rand = torch.rand((L, L), generator=gen, device="cuda:0") < sf
+        longformer = ((i - j).abs() <= w) | glob
+        masks = {
+            "longformer": (longformer, (loc, nl, None)),
+            "longformer_dilated": ((((i - j).abs() <= 2 * w) & ((i - j) % 2 == 0)) | glob, None),
+            "bigbird": (longformer | rand, (loc, nl, rand & ~longformer)),
+        }
+        del glob
+        wsi = sga.alloc_workspace(L, 1, d, dtype, -1)
+        for name, (dense, parts) in masks.items():
+            rp, ci = csr_of(dense)
+            del dense
+            edges = int(rp[-1])
+            ws = sga.alloc_workspace(L, 1, d, dtype, edges)
+            O1 = torch.empty_like(Q)
+            ms_csr = _time_calls(lambda: sga.attention_forward(Q, K, V, rp, ci, scale, O=O1, workspace=ws, path=path),
+                                 steps=15, warmup=10)
+            plan = sga.graph_prepare(rp, ci, 1, d, dtype, ws)
+            ms_prep = _time_calls(lambda: sga.attention_forward_prepared(Q, K, V, rp, ci, scale, plan, ws, O=O1),
+                                  steps=15, warmup=10)
+            row = {"mask": name, "L": L, "d": d, "dtype": dtype, "edges": edges, "S_f": edges / (L * L),
+                   "csr_ms": ms_csr, "csr_prepared_ms": ms_prep, "edges_per_s": edges / (ms_prep * 1e-3)}
+            if parts is not None:
+                p_loc, p_nl, extra = parts
+                O2 = torch.empty_like(Q)
+                lse = torch.empty((1, L), dtype=torch.float32, device="cuda:0")
+                if extra is not None:
+                    rp3, ci3 = csr_of(extra)
+                    ws3 = sga.alloc_workspace(L, 1, d, dtype, int(rp3[-1]))
+
+                def sequence():
+                    sga.attention_forward_implicit(Q, K, V, p_loc, scale, O=O2, lse=lse, workspace=wsi, path=path)
+                    sga.attention_accumulate_implicit(Q, K, V, p_nl, scale, O2, lse, workspace=wsi, path=path)
+                    if extra is not None:
+                        sga.attention_accumulate(Q, K, V, rp3, ci3, scale, O2, lse, workspace=ws3, path=path)
+                row["sequence_ms"] = _time_calls(sequence, steps=15, warmup=10)
+                row["sequence_calls"] = 2 if extra is None else 3
+                torch.cuda.synchronize()
+                row["max_abs_difference"] = (O1.float() - O2.float()).abs().max().item()
+            rows.append(row)
+            del rp, ci, ws
+            torch.cuda.empty_cache()
+        del masks, rand, longformer, Q, K, V
+        torch.cuda.empty_cache()
+    return {"suite": "vf", "unit": "ms per forward, one head, d = 64, " + dtype, "rows": rows}
+
+
 def fits_cache(wl):
     """One head's Q, K, V, O fit the 256 MB last-level cache."""
     return 4 * wl.d * (4 if wl.dtype == "f32" else 2) * wl.L <= (256 << 20)
@@ -594,9 +673,9 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache launches")
-    ap.add_argument("--suite", default=None, choices=["table3", "e2"],
-                    help="instead of the benchmark line, time the shapes of the paper's Table III "
-                         "or of its microbenchmark grid and print one JSON object")
+    ap.add_argument("--suite", default=None, choices=["table3", "e2", "vf"],
+                    help="instead of the benchmark line, time the shapes of the paper's Table III, "
+                         "of its microbenchmark grid or of its model masks (Section V-F) and print one JSON object")
     ap.add_argument("--dims", default="64,128,256",
                     help="head dimensions of --suite e2 (comma-separated)")
     ap.add_argument("--prepared", action="store_true",
@@ -638,6 +717,7 @@ def main():
     path = {"auto": 0, "gather": 1, "tile": 2, "tile_split": 3}[args.path]
     if args.suite:
         print(json.dumps(suite_table3(path) if args.suite == "table3"
+                         else suite_vf(path) if args.suite == "vf"
                          else suite_e2(path, tuple(int(x) for x in args.dims.split(",")))))
         return
     # (the long-context shapes of Table III can be named too, e.g. for a profile of one of them)
