@@ -785,8 +785,9 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
     hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled && a.H >= 8 ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
                        K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
     if (mark_chunks) profile_mark_end(a.stream);
-    // one wavefront per long row and head; a prepared graph knows how many there are
-    int64_t merge_wgs = a.prepared ? ((int64_t)a.plan_long_rows + 3) / 4 : (a.L + 3) / 4;
+    // one wavefront per long row and head, one workgroup for a row of more than kMaxSplit
+    // chunks; a prepared graph knows how many rows there are
+    int64_t merge_wgs = a.prepared ? (int64_t)a.plan_long_rows : (a.L + 3) / 4;
     const int64_t merge_cap = 4096 / a.H > 64 ? 4096 / a.H : 64;
     if (merge_wgs > merge_cap) merge_wgs = merge_cap;
     hipLaunchKernelGGL((gather_merge_kernel<T, D>), dim3((unsigned)merge_wgs, (unsigned)a.H), dim3(256), 0, a.stream, O,
