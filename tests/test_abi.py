@@ -89,6 +89,18 @@ def test_forward_argument_errors_without_touching_the_gpu():
     assert g(ok, ok, ok, spec, ok, 64, 1, 64, 0.1, None, 0, None, None, 0, 0) == -1
 
 
+def test_validate_csr_argument_errors_without_touching_the_gpu():
+    ok = 0x1000
+    v = sga.sga_validate_csr
+    assert v(None, ok, 64, 10, ok, None)[0] == -1
+    assert v(ok, None, 64, 10, ok, None)[0] == -1
+    assert v(ok, ok, 64, 10, None, None)[0] == -1
+    assert v(ok, ok, 64, 10, ok + 4, None)[0] == -1          # scratch not 8-byte aligned
+    assert v(ok, ok, 0, 10, ok, None)[0] == -1
+    assert v(ok, ok, 1 << 31, 10, ok, None)[0] == -1
+    assert v(ok, ok, 64, -1, ok, None)[0] == -1
+
+
 def test_prepared_graph_argument_errors_without_touching_the_gpu():
     ok = 0x1000
     prep = sga.sga_graph_prepare
