@@ -361,12 +361,13 @@ __device__ __forceinline__ bool row_done_by_tiles(const int64_t* row_ptr, int64_
   return tile_handled(pl, ws, row_ptr, L, dtype, i / kTile);
 }
 
+// (wg of n_wg: this workgroup's place among those that share the rows of a head)
 template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_csr_kernel(
+__device__ __forceinline__ void gather_csr_body(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
     float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
     int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split, int skip_tiled,
-    int accumulate) {
+    int accumulate, uint32_t wg, uint32_t n_wg) {
   const int lane = threadIdx.x & (kWave - 1);
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
@@ -398,8 +399,8 @@ __global__ __launch_bounds__(256) void gather_csr_kernel(
       }
     }
   }
-  for (int64_t u = (int64_t)blockIdx.x * waves + (threadIdx.x / kWave); u < n_units;
-       u += (int64_t)gridDim.x * waves) {
+  for (int64_t u = (int64_t)wg * waves + (threadIdx.x / kWave); u < n_units;
+       u += (int64_t)n_wg * waves) {
     int64_t i = u;
     if (listed) {
       const int64_t ti = u / kTile;
@@ -425,6 +426,16 @@ __global__ __launch_bounds__(256) void gather_csr_kernel(
       attend_columns<T, D, false>(K + hoff, V + hoff, q, col_idx + r0, 0, r1 - r0, lane, st);
     finish_row<T, D>(O + hoff + i * D, lse ? lse + h * L + i : nullptr, lane, st, accumulate != 0);
   }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_csr_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+    int64_t L, float scale, const void* ws, size_t ws_bytes, int use_split, int skip_tiled,
+    int accumulate) {
+  gather_csr_body<T, D>(Q, K, V, O, lse, row_ptr, col_idx, L, scale, ws, ws_bytes, use_split, skip_tiled,
+                        accumulate, blockIdx.x, gridDim.x);
 }
 
 template <typename T, int D>
@@ -615,10 +626,10 @@ __global__ __launch_bounds__(256) void nonlocal_merge_kernel(T* __restrict__ O, 
 // the pairs (long row s, j) with chunk c = x + 8j, numbered j * n_long + s (rows of few chunks
 // have no unit for the larger j) and dealt to the XCD's wavefronts in turn.
 template <typename T, int D>
-__global__ __launch_bounds__(256) void gather_chunk_kernel(
+__device__ __forceinline__ void gather_chunk_body(
     const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
     const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t L, float scale,
-    void* ws, size_t ws_bytes) {
+    void* ws, size_t ws_bytes, uint32_t wg, uint32_t n_wg) {
   const int32_t H = (int32_t)gridDim.y;
   constexpr int32_t dtype = DtypeOf<T>::code;
   if (!split_active(row_ptr, L, H, dtype, D, ws, ws_bytes)) return;
@@ -631,10 +642,10 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
   const int waves = blockDim.x / kWave;
   const int64_t h = blockIdx.y;
   const int64_t hoff = h * L * D;
-  const uint32_t xcd = blockIdx.x & 7;
+  const uint32_t xcd = wg & 7;
   const uint64_t n_units = (uint64_t)n_long * ((max_chunks + 7) / 8);
-  for (uint64_t u = (uint64_t)(blockIdx.x >> 3) * waves + threadIdx.x / kWave; u < n_units;
-       u += (uint64_t)(gridDim.x >> 3) * waves) {
+  for (uint64_t u = (uint64_t)(wg >> 3) * waves + threadIdx.x / kWave; u < n_units;
+       u += (uint64_t)(n_wg >> 3) * waves) {
     const int4 rec = lr[u % n_long];                         // {row, first partial slot, chunks, chunk length}
     const int32_t c = (int32_t)(xcd + 8 * (u / n_long));
     if (c >= rec.z) continue;
@@ -661,6 +672,31 @@ __global__ __launch_bounds__(256) void gather_chunk_kernel(
       p[D + 1] = st.l;
     }
   }
+}
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_chunk_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V,
+    const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx, int64_t L, float scale,
+    void* ws, size_t ws_bytes) {
+  gather_chunk_body<T, D>(Q, K, V, row_ptr, col_idx, L, scale, ws, ws_bytes, blockIdx.x, gridDim.x);
+}
+
+// The two kernels above in one launch (neither reads what the other writes): the first n_rows
+// workgroups of a head (a multiple of 8, so that the chunk workgroups keep their XCDs) take the
+// leftover rows, the others the chunks of the split rows.  For the call that does not know yet
+// whether anything is left for either: one launch that finds nothing to do instead of two.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gather_rows_and_chunks_kernel(
+    const T* __restrict__ Q, const T* __restrict__ K, const T* __restrict__ V, T* __restrict__ O,
+    float* __restrict__ lse, const int64_t* __restrict__ row_ptr, const int32_t* __restrict__ col_idx,
+    int64_t L, float scale, void* ws, size_t ws_bytes, int skip_tiled, int accumulate, uint32_t n_rows) {
+  if (blockIdx.x < n_rows)
+    gather_csr_body<T, D>(Q, K, V, O, lse, row_ptr, col_idx, L, scale, ws, ws_bytes, 1, skip_tiled, accumulate,
+                          blockIdx.x, n_rows);
+  else
+    gather_chunk_body<T, D>(Q, K, V, row_ptr, col_idx, L, scale, ws, ws_bytes, blockIdx.x - n_rows,
+                            gridDim.x - n_rows);
 }
 
 // Partial states p0[c * step + ...], c < n, combined in order into one partial state
@@ -775,16 +811,27 @@ sga_status run_explicit(const AttnArgs& a, bool allow_split, bool skip_tiled) {
   // kernel where a prepared graph has found every row left to it split
   const bool mark = !skip_tiled || (a.prepared && a.plan_no_tiles);
   const bool mark_chunks = mark && a.prepared && a.plan_long_rows > 0;
-  if (mark && !mark_chunks) profile_mark_begin(a.stream, "gather_csr_kernel");
-  hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
-                     a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
-                     skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
-  if (mark && !mark_chunks) profile_mark_end(a.stream);
+  const unsigned chunk_wgs = skip_tiled && a.H >= 8 ? 128 : 1024;
+  const bool fused = split && skip_tiled && !a.prepared;     // (after the tile path, nothing known about what is left)
+  if (fused) {
+    const unsigned n_rows = ((unsigned)nwg + 7u) & ~7u;
+    hipLaunchKernelGGL((gather_rows_and_chunks_kernel<T, D>), dim3(n_rows + chunk_wgs, (unsigned)a.H), dim3(256), 0,
+                       a.stream, Q, K, V, O, a.lse, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, 1,
+                       a.accumulate ? 1 : 0, n_rows);
+  } else {
+    if (mark && !mark_chunks) profile_mark_begin(a.stream, "gather_csr_kernel");
+    hipLaunchKernelGGL((gather_csr_kernel<T, D>), grid, dim3(256), 0, a.stream, Q, K, V, O, a.lse,
+                       a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes, split ? 1 : 0,
+                       skip_tiled ? 1 : 0, a.accumulate ? 1 : 0);
+    if (mark && !mark_chunks) profile_mark_end(a.stream);
+  }
   if (split && (!a.prepared || a.plan_long_rows > 0)) {
-    if (mark_chunks) profile_mark_begin(a.stream, "gather_chunk_kernel");
-    hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(skip_tiled && a.H >= 8 ? 128 : 1024, (unsigned)a.H), dim3(256), 0, a.stream, Q,
-                       K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
-    if (mark_chunks) profile_mark_end(a.stream);
+    if (!fused) {
+      if (mark_chunks) profile_mark_begin(a.stream, "gather_chunk_kernel");
+      hipLaunchKernelGGL((gather_chunk_kernel<T, D>), dim3(chunk_wgs, (unsigned)a.H), dim3(256), 0, a.stream, Q,
+                         K, V, a.row_ptr, a.col_idx, a.L, a.scale, a.ws, a.ws_bytes);
+      if (mark_chunks) profile_mark_end(a.stream);
+    }
     // one wavefront per long row and head, one workgroup for a row of more than kMaxSplit
     // chunks; a prepared graph knows how many rows there are
     int64_t merge_wgs = a.prepared ? (int64_t)a.plan_long_rows : (a.L + 3) / 4;
