@@ -2704,6 +2704,199 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
   }
 }
 
+// fp16 window masks, wide bands, d = 128: the ring of tile_window_band_kernel with key blocks of
+// 128 channels.  A block is staged as four 64-channel blocks in the layout CoreF16 reads (K
+// channels 0..63, K 64..127, V 0..63, V 64..127: 16 KB), once per workgroup of 128 queries; a
+// wavefront owns one 32-query sub-tile and all 128 channels of it: the scores of a block are one
+// chain of eight products over the two K halves, the softmax is done once, and the numerators
+// meet the two V halves in eight more products (16 matrix instructions per block against the
+// same vector work as at d = 64; the kernel that gives each 64-channel slice a wavefront of its
+// own repeats the softmax in every slice and exchanges the partial scores through LDS).  Four
+// slots, copies three blocks ahead: the barrier that opens block kb (every wavefront has waited
+// for its own four copies of block kb, and is done with block kb-1) is followed by the copy of
+// block kb+3 into the slot of block kb-1.
+constexpr int kBand128Slots = 4;
+constexpr int kBand128Ahead = 3;      // = kBand128Slots - 1
+
+__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_window_band128_kernel(
+    const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
+    __half* __restrict__ O, float* __restrict__ lse, int64_t L, int64_t W, int64_t s, int64_t n_groups,
+    float scale, int accumulate, int64_t seg_len) {
+  constexpr int kD = 2 * kHeadDim;
+  constexpr int kWaves = 4;          // (eight wavefronts, 256 queries and two copies each per block, were slower: 2.60 against 2.55 ms at +-2048)
+  constexpr int kBlk = CoreF16::kBlockBytes;
+  constexpr int kSlotBytes = 4 * kBlk;
+  __shared__ __attribute__((aligned(16))) char ring[kBand128Slots * kSlotBytes];
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  const int64_t chunk = gridDim.x / 8;
+  const int64_t bid = (int64_t)(blockIdx.x % 8) * chunk + blockIdx.x / 8;
+  WindowSlot slot;
+  if (!locate_window_slot(bid, L, s, n_groups, seg_len, slot)) return;      // (the whole workgroup leaves)
+  const int64_t p = slot.p, Lc = slot.Lc;
+  const int64_t q0 = slot.grp * (kWaves * kTile);
+  if (q0 >= Lc) return;
+  const int64_t hd = blockIdx.y;
+  const int64_t hoff = hd * L * kD;
+  const int64_t u0 = q0 + (int64_t)wave * kTile;
+  const int64_t vfirst = q0 - W > 0 ? q0 - W : 0;
+  const int64_t vlast = q0 + kWaves * kTile - 1 + W < Lc - 1 ? q0 + kWaves * kTile - 1 + W : Lc - 1;
+  const int nblk = (int)((vlast - vfirst) / kTile + 1);
+  // a wavefront whose queries lie past the end of the class (u0 >= Lc) still copies and meets the
+  // barriers; classify() then reports no block as its own
+  const WindowBlocks src{vfirst, Lc, s, p, u0, W};
+  const int64_t u = u0 + n;
+  const bool exists = u < Lc;
+  const int64_t qrow = s * (exists ? u : Lc - 1) + p;
+  CoreF16 lo, hi;                                  // channels 0..63 and 64..127 of the same queries
+  lo.load_q(Q + hoff + qrow * kD, h, scale < 0.f);
+  hi.load_q(Q + hoff + qrow * kD + kHeadDim, h, scale < 0.f);
+  wait_loads_except<0>();            // Q has arrived: from here on only the ring's copies are counted
+  lo.q_arrived();
+  hi.q_arrived();
+  // this wavefront's share of a block: keys 8w .. 8w+7 of all four 64-channel blocks, eight lanes
+  // of 16 bytes per 128-byte half row (the K chunks swizzled as CoreF16::read_k expects)
+  constexpr int kCopies = 4;                       // copies per wavefront and block
+  const int r_own = 8 * wave + (lane >> 3), c_own = lane & 7;
+  const char* Kb = reinterpret_cast<const char*>(K + hoff);
+  const char* Vb = reinterpret_cast<const char*>(V + hoff);
+  auto issue = [&](int kb) {
+    const int kc = kb < nblk ? kb : nblk - 1;
+    int64_t v = vfirst + (int64_t)kc * kTile + r_own;
+    v = v < Lc ? v : Lc - 1;                               // keys past the end re-read the last one (masked off)
+    const int64_t row_bytes = (s * v + p) * (kD * 2);
+    char* dst = ring + (kb % kBand128Slots) * kSlotBytes + wave * 1024;
+    const int k_at = (c_own ^ (r_own & 7)) * 16, v_at = c_own * 16;
+    copy16_to_lds_untracked(Kb + row_bytes + k_at, dst);
+    copy16_to_lds_untracked(Kb + row_bytes + kHeadDim * 2 + k_at, dst + kBlk);
+    copy16_to_lds_untracked(Vb + row_bytes + v_at, dst + 2 * kBlk);
+    copy16_to_lds_untracked(Vb + row_bytes + kHeadDim * 2 + v_at, dst + 3 * kBlk);
+  };
+  TileState st, st_hi;               // m and l live in st; st_hi holds the accumulators of channels 64..127
+  st.init();
+  st_hi.init();
+  const float c = softmax_factor(scale);
+  const char* vt0 = CoreF16::vt_base(ring + 2 * kBlk, lane, h);
+  // The barrier that opens block kb: every wavefront has waited for its own copies of blocks kb
+  // and kb+1 (the interior steps read K of block kb+1 for the score products they issue one block
+  // ahead), and everyone is done with block kb-1, whose slot takes the copy of block kb+3.
+  auto publish = [&](int kb) {
+    wait_loads_except<kCopies * (kBand128Ahead - 2)>();
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    issue(kb + kBand128Ahead);
+  };
+  // scores of block kb: one chain of eight products over the two K halves
+  auto products = [&](int kb, floatx16& sv) {
+    const char* ldsk = ring + (kb % kBand128Slots) * kSlotBytes;
+    half8 kf[4], kg[4];
+    CoreF16::read_k(ldsk, n, h, kf);
+    CoreF16::read_k(ldsk + kBlk, n, h, kg);
+    sv = floatx16{0};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) sv = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[t], lo.qf[t], sv, 0, 0, 0);
+#pragma unroll
+    for (int t = 0; t < 4; ++t) sv = __builtin_amdgcn_mfma_f32_32x32x16_f16(kg[t], hi.qf[t], sv, 0, 0, 0);
+  };
+  // numerators of a block (see softmax_block_h; the accumulators of the upper channels take the
+  // same factor when the running maximum is raised), then the products with the two V halves
+  auto weigh = [&](int kb, floatx16& sv) {
+    half8 ph[2];
+    const float l_before = st.l;
+    numerators_h(sv, c, st, ph);
+    if (__any(sum_overflowed(st))) {
+      st.l = l_before;
+      const float m_before = st.m;
+      rescale_state(st, block_max(sv, c, h));
+      const float alpha = __builtin_amdgcn_exp2f(m_before - st.m);
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        st_hi.o[0][r] *= alpha;
+        st_hi.o[1][r] *= alpha;
+      }
+      numerators_h(sv, c, st, ph);
+    }
+    const char* vt = vt0 + (kb % kBand128Slots) * kSlotBytes;
+#pragma unroll
+    for (int uu = 0; uu < 2; ++uu) {
+      const half8 a0 = CoreF16::read_va(vt, uu, 0), a1 = CoreF16::read_va(vt, uu, 1);
+      const half8 b0 = CoreF16::read_va(vt + kBlk, uu, 0), b1 = CoreF16::read_va(vt + kBlk, uu, 1);
+      st.o[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, ph[uu], st.o[0], 0, 0, 0);
+      st.o[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, ph[uu], st.o[1], 0, 0, 0);
+      st_hi.o[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b0, ph[uu], st_hi.o[0], 0, 0, 0);
+      st_hi.o[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(b1, ph[uu], st_hi.o[1], 0, 0, 0);
+    }
+  };
+  // a block on the edge of (or outside) this wavefront's window
+  auto step = [&](int kb) {
+    publish(kb);
+    const int cls = src.classify(kb);                      // wave-uniform
+    if (cls) {
+      floatx16 sv;
+      products(kb, sv);
+      if (cls != 2) mask_scores(sv, src.get(kb, n).word, h);
+      weigh(kb, sv);
+    }
+  };
+  // Interior blocks, software-pipelined as in tile_window_band_kernel: the score products of
+  // block kb+1 are issued ahead of the exponentials and the PV products of block kb; cur holds
+  // the scores of block kb on entry (first: the step computes them itself), nxt receives those of
+  // block kb+1 (next: it is interior too); successive steps swap the two.
+  auto piped = [&](int kb, floatx16& cur, floatx16& nxt, auto first, auto next) {
+    publish(kb);
+    if constexpr (decltype(first)::value) products(kb, cur);
+    if constexpr (decltype(next)::value) products(kb + 1, nxt);
+    weigh(kb, cur);
+  };
+  int k_lo = 0, k_hi = nblk;
+  while (k_lo < nblk && src.classify(k_lo) != 2) ++k_lo;
+  while (k_hi > k_lo && src.classify(k_hi - 1) != 2) --k_hi;
+  for (int kb = 0; kb < kBand128Ahead; ++kb) issue(kb);
+  int kb = 0;
+  for (; kb < k_lo; ++kb) step(kb);
+  if (kb < k_hi) {
+    constexpr std::true_type yes{};
+    constexpr std::false_type no{};
+    floatx16 s_a, s_b;
+    if (kb + 1 < k_hi) {
+      piped(kb, s_a, s_b, yes, yes);
+      ++kb;                                              // the scores of block kb are in s_b
+      for (; kb + 2 < k_hi; kb += 2) {
+        piped(kb, s_b, s_a, no, yes);
+        piped(kb + 1, s_a, s_b, no, yes);
+      }
+      if (kb + 1 < k_hi) {
+        piped(kb, s_b, s_a, no, yes);
+        piped(kb + 1, s_a, s_b, no, no);
+      } else {
+        piped(kb, s_b, s_a, no, no);
+      }
+    } else {
+      piped(kb, s_a, s_b, yes, no);
+    }
+    kb = k_hi;
+  }
+  for (; kb < nblk; ++kb) step(kb);
+  // the copies past the last block must have landed before the workgroup gives its LDS back
+  wait_loads_except<0>();
+  const float l = st.l + other_half(st.l, h);
+  if (!exists) return;
+  const bool empty = !(l > 0.f);
+  float inv = empty ? 0.f : 1.0f / l;
+  float lse_row = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(l)) * kLn2;
+  float w_prev = 0.f;
+  float* lse_h = lse ? lse + hd * L : nullptr;
+  if (accumulate) {                  // (both half-waves read the earlier lse before the first replaces it)
+    const CarryWeights cw = carry_weights(lse_h[qrow], lse_row);
+    inv *= cw.w_now;
+    w_prev = cw.w_prev;
+    lse_row = cw.lse;
+  }
+  CoreF16::store_row(O + hoff + qrow * kD, st, inv, w_prev, accumulate != 0, h);
+  CoreF16::store_row(O + hoff + qrow * kD + kHeadDim, st_hi, inv, w_prev, accumulate != 0, h);
+  if (lse_h && h == 0) lse_h[qrow] = lse_row;
+}
+
 // fp16 window masks narrow enough that the keys of 128 consecutive queries fit the LDS
 // (128 + 2W <= 256 keys: 8 key blocks; this kernel takes the windows of up to 6 blocks, K and V
 // side by side in 48 KB at most, tile_window_kv_kernel those of 7 and 8).  A workgroup owns 128 queries
@@ -3112,9 +3305,24 @@ sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
   constexpr int kSlices = kD / kHeadDim;
   clear_unselected_rows<T>(a);
+  const int acc = a.accumulate ? 1 : 0;
+  if constexpr (DtypeOf<T>::code == SGA_F16 && kD == 128) {
+    // wide bands on a call with workgroups enough to fill the chip: one wavefront per 32 queries
+    // with all 128 channels, key blocks staged once per 128 queries
+    const int64_t n_groups = (n_tiles + 3) / 4;
+    const int64_t n_wg128 = (n_groups * shape.n_slots + 7) / 8 * 8;
+    if (4 * kTile + 2 * (int64_t)a.window > kWgBlocks * kTile && n_groups * shape.n_slots * a.H >= 512) {
+      profile_mark_begin(a.stream, "tile_window_band128_kernel");
+      hipLaunchKernelGGL(tile_window_band128_kernel, dim3((unsigned)n_wg128, (unsigned)a.H), dim3(256), 0, a.stream,
+                         static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),
+                         static_cast<const __half*>(a.V), static_cast<__half*>(a.O), a.lse, a.L,
+                         (int64_t)a.window, s, n_groups, a.scale, acc, shape.seg_len);
+      profile_mark_end(a.stream);
+      return hip_status(hipGetLastError());
+    }
+  }
   float* parts = nullptr;
   const int nsplit = choose_window_split(a, n_wg * a.H, 2048 / kSlices, &parts);
-  const int acc = a.accumulate ? 1 : 0;
   profile_mark_begin(a.stream, "tile_window_wide_kernel");
   hipLaunchKernelGGL((tile_window_wide_kernel<T, kD, kPipe>), dim3((unsigned)(n_wg * nsplit), (unsigned)a.H),
                      dim3(kD), 0, a.stream, static_cast<const T*>(a.Q), static_cast<const T*>(a.K),

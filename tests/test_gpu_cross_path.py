@@ -234,3 +234,36 @@ def test_scattered_masks_tiles_agree_with_row_kernels_and_prepared_graphs(seed):
     torch.cuda.synchronize()
     assert torch.equal(O1, O3) and torch.equal(l1, l3)
     _agree(O1, l1, O2, l2, dtype)
+
+
+@pytest.mark.parametrize("case", range(8))
+def test_d128_wide_bands_agree_with_row_kernels(case):
+    """fp16, d = 128, windows wide enough and calls large enough for the kernel that gives a
+    wavefront all 128 channels of its sub-tile: sliding, dilated and 2-D dilated masks, a
+    negative scale, large scores, and a call that continues an earlier state."""
+    import torch
+    kind, L, H, kw, scale, sigma = [
+        (KIND_SLIDING, 20011, 4, dict(window=333), 0.0884, 0.5),
+        (KIND_SLIDING, 16384, 4, dict(window=65), -0.0884, 0.5),
+        (KIND_SLIDING, 9000, 8, dict(window=9000), 0.0884, 0.3),
+        (KIND_DILATED, 50000, 2, dict(window=100, stride=4), 0.0884, 1.0),
+        (KIND_DILATED, 30000, 4, dict(window=2000, stride=2), 0.3, 1.0),
+        (KIND_DILATED_2D, 48000, 4, dict(block=6000, stride=2), 0.0884, 0.5),
+        (KIND_DILATED_2D, 40000, 6, dict(block=777, stride=1), 0.0884, 0.5),
+        (KIND_SLIDING, 17000, 4, dict(window=200), 0.0884, 0.5),
+    ][case]
+    spec = MaskSpec(kind, L, **kw)
+    print("case", case, spec, "H", H, flush=True)
+    Q, K, V = torch_qkv(H, L, 128, "f16", sigma, 300 + case, "cuda:0")
+    amp = max(1.0, sigma * sigma * abs(scale) * 11.3 * 8)
+    O1, l1 = sga.attention_forward_implicit(Q, K, V, spec, scale, path=sga.PATH_TILE, want_lse=True)
+    O2, l2 = sga.attention_forward_implicit(Q, K, V, spec, scale, path=sga.PATH_GATHER, want_lse=True)
+    torch.cuda.synchronize()
+    _agree(O1, l1, O2, l2, "f16", amp)
+    if case == 7:
+        # the same window once more on the state of the first call: O unchanged, lse + ln 2
+        O3, l3 = O1.clone(), l1.clone()
+        sga.attention_accumulate_implicit(Q, K, V, spec, scale, O3, l3, path=sga.PATH_TILE)
+        torch.cuda.synchronize()
+        assert ((O3.float() - O1.float()).abs() / (1 + O1.float().abs())).max().item() <= 2 * TOL["f16"]
+        assert (l3 - l1 - 0.6931472).abs().max().item() <= 2e-3

@@ -196,3 +196,16 @@ def test_table3_1p6m_wide_band():
 def test_table3_160m_wide_band():
     # +-799 keys at 160M tokens: element offsets pass 2^31 and 2^33
     _table3_case(TABLE3_WORKLOADS["table3_160m"], n_random=16, edge=8)
+
+
+@pytest.mark.parametrize("L,H,W,s", [(40013, 4, 700, 1), (70001, 3, 200, 3), (33000, 8, 65, 1)])
+def test_d128_wide_band(L, H, W, s):
+    """Wide fp16 bands at d = 128 (the head size of the models of Table IV) on calls large enough
+    for the kernel that keeps all 128 channels of a sub-tile in one wavefront: ragged lengths,
+    a dilated window, and the narrowest window that takes it; sampled rows against the row-scan
+    oracle, V = ones and the Q = 0 moving average on every row."""
+    from sga_inputs import MaskSpec, Workload, KIND_SLIDING, KIND_DILATED
+    spec = MaskSpec(KIND_SLIDING if s == 1 else KIND_DILATED, L, window=W, stride=s)
+    wl = Workload(f"d128_L{L}_w{W}_s{s}", H=H, L=L, d=128, dtype="f16", sigma=0.5, mask=spec, explicit=False,
+                  seed=77)
+    _table3_case(wl, n_random=40, edge=40)
