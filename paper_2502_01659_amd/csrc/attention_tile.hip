@@ -2877,24 +2877,55 @@ __global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) voi
     kb = k_hi;
   }
   for (; kb < nblk; ++kb) step(kb);
-  // the copies past the last block must have landed before the workgroup gives its LDS back
+  // every copy has landed and every wavefront is done with the ring: its space takes the output tiles
   wait_loads_except<0>();
+  asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+  if (u0 >= Lc) return;
   const float l = st.l + other_half(st.l, h);
-  if (!exists) return;
   const bool empty = !(l > 0.f);
   float inv = empty ? 0.f : 1.0f / l;
   float lse_row = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(l)) * kLn2;
-  float w_prev = 0.f;
   float* lse_h = lse ? lse + hd * L : nullptr;
-  if (accumulate) {                  // (both half-waves read the earlier lse before the first replaces it)
+  if (accumulate) {
+    if (!exists) return;
+    // (both half-waves read the earlier lse before the first replaces it)
     const CarryWeights cw = carry_weights(lse_h[qrow], lse_row);
-    inv *= cw.w_now;
-    w_prev = cw.w_prev;
-    lse_row = cw.lse;
+    CoreF16::store_row(O + hoff + qrow * kD, st, inv * cw.w_now, cw.w_prev, true, h);
+    CoreF16::store_row(O + hoff + qrow * kD + kHeadDim, st_hi, inv * cw.w_now, cw.w_prev, true, h);
+    if (h == 0) lse_h[qrow] = cw.lse;
+    return;
   }
-  CoreF16::store_row(O + hoff + qrow * kD, st, inv, w_prev, accumulate != 0, h);
-  CoreF16::store_row(O + hoff + qrow * kD + kHeadDim, st_hi, inv, w_prev, accumulate != 0, h);
-  if (lse_h && h == 0) lse_h[qrow] = lse_row;
+  // A lane holds fragments of its own query's row; the tile goes through LDS and leaves as whole
+  // 256-byte rows, four per instruction (see CoreF16T::store_tile), with streaming stores.
+  constexpr int kPitch = kD * 2 + 16;
+  char* tile = ring + wave * (kTile * kPitch);
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+    const TileState& part = half ? st_hi : st;
+#pragma unroll
+    for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 w;
+        w.x = __builtin_bit_cast(uint32_t, __floats2half2_rn(part.o[cb][4 * g] * inv, part.o[cb][4 * g + 1] * inv));
+        w.y = __builtin_bit_cast(uint32_t,
+                                 __floats2half2_rn(part.o[cb][4 * g + 2] * inv, part.o[cb][4 * g + 3] * inv));
+        *reinterpret_cast<uint2*>(tile + n * kPitch + (half * kHeadDim + cb * 32 + 8 * g + 4 * h) * 2) = w;
+      }
+  }
+  __builtin_amdgcn_wave_barrier();
+  const int64_t left = Lc - u0;
+  const int n_rows = left < kTile ? (int)left : kTile;
+  const int64_t row0 = s * u0 + p;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const int r = (lane >> 4) + 4 * i;
+    const uint4 v = *reinterpret_cast<const uint4*>(tile + r * kPitch + (lane & 15) * 16);
+    if (r < n_rows)
+      __builtin_nontemporal_store(__builtin_bit_cast(half8, v),
+                                  reinterpret_cast<half8*>(O + hoff + (row0 + r * s) * kD + (lane & 15) * 8));
+  }
+  if (lse_h && h == 0 && n < n_rows) lse_h[row0 + n * s] = lse_row;
 }
 
 // fp16 window masks narrow enough that the keys of 128 consecutive queries fit the LDS
@@ -3311,7 +3342,7 @@ sga_status run_tile_implicit_wide_d(const AttnArgs& a) {
     // with all 128 channels, key blocks staged once per 128 queries
     const int64_t n_groups = (n_tiles + 3) / 4;
     const int64_t n_wg128 = (n_groups * shape.n_slots + 7) / 8 * 8;
-    if (4 * kTile + 2 * (int64_t)a.window > kWgBlocks * kTile && n_groups * shape.n_slots * a.H >= 512) {
+    if (n_groups * shape.n_slots * a.H >= 512) {
       profile_mark_begin(a.stream, "tile_window_band128_kernel");
       hipLaunchKernelGGL(tile_window_band128_kernel, dim3((unsigned)n_wg128, (unsigned)a.H), dim3(256), 0, a.stream,
                          static_cast<const __half*>(a.Q), static_cast<const __half*>(a.K),

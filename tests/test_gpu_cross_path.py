@@ -236,7 +236,7 @@ def test_scattered_masks_tiles_agree_with_row_kernels_and_prepared_graphs(seed):
     _agree(O1, l1, O2, l2, dtype)
 
 
-@pytest.mark.parametrize("case", range(8))
+@pytest.mark.parametrize("case", range(11))
 def test_d128_wide_bands_agree_with_row_kernels(case):
     """fp16, d = 128, windows wide enough and calls large enough for the kernel that gives a
     wavefront all 128 channels of its sub-tile: sliding, dilated and 2-D dilated masks, a
@@ -251,6 +251,9 @@ def test_d128_wide_bands_agree_with_row_kernels(case):
         (KIND_DILATED_2D, 48000, 4, dict(block=6000, stride=2), 0.0884, 0.5),
         (KIND_DILATED_2D, 40000, 6, dict(block=777, stride=1), 0.0884, 0.5),
         (KIND_SLIDING, 17000, 4, dict(window=200), 0.0884, 0.5),
+        (KIND_SLIDING, 70001, 1, dict(window=16), 0.0884, 0.5),
+        (KIND_DILATED, 33333, 4, dict(window=64, stride=2), 0.0884, 0.5),
+        (KIND_SLIDING, 16500, 4, dict(window=0), 0.0884, 0.5),
     ][case]
     spec = MaskSpec(kind, L, **kw)
     print("case", case, spec, "H", H, flush=True)
