@@ -422,6 +422,32 @@ def suite_table3(path):
     return {"suite": "table3", "unit": "ms per forward (sga_attention_forward_implicit)", "rows": rows}
 
 
+def suite_d128(path, n_shapes=5):
+    """Sliding windows at d = 128, fp16, the head size of the models in the paper's table of
+    context limits (Section V-D) and of most current ones: wide bands (matrix-core regime) and
+    narrow windows (HBM regime), implicit neighbours."""
+    import torch
+    import paper_2502_01659_amd as sga
+    from sga_inputs import MaskSpec, KIND_SLIDING, KIND_DILATED, torch_qkv, BASE_SEED
+    rows = []
+    for L, H, w, s in ((32768, 32, 2048, 1), (131072, 8, 1024, 1), (32768, 32, 256, 1),
+                       (1 << 20, 4, 64, 2), (1 << 20, 4, 16, 1))[:n_shapes]:
+        spec = MaskSpec(KIND_DILATED if s > 1 else KIND_SLIDING, L, window=w, stride=s)
+        Q, K, V = torch_qkv(H, L, 128, "f16", 0.5, BASE_SEED, "cuda:0")
+        O = torch.empty_like(Q)
+        ws = sga.alloc_workspace(L, H, 128, "f16", -1)
+        ms = _time_calls(lambda: sga.attention_forward_implicit(Q, K, V, spec, 128 ** -0.5, O=O, workspace=ws,
+                                                                path=path), steps=10, warmup=3)
+        edges = sga.mask_nnz(spec) * H
+        rows.append({"L": L, "H": H, "d": 128, "window": w, "stride": s, "dtype": "f16", "edges": edges, "ms": ms,
+                     "edges_per_s": edges / (ms * 1e-3),
+                     "hbm_algorithmic_GBps": 4 * L * H * 128 * 2 / (ms * 1e-3) / 1e9,
+                     "mfma_f16_TFLOPs": 4.0 * 128 * edges / (ms * 1e-3) / 1e12})
+        del Q, K, V, O, ws
+        torch.cuda.empty_cache()
+    return {"suite": "d128", "unit": "ms per forward (sga_attention_forward_implicit)", "rows": rows}
+
+
 def suite_e2(path, dims=(64, 128, 256)):
     """The shapes of the paper's microbenchmark (Section V-C): L in {8192, 16384, 24576}, one
     head, fp32, sparsity factors across (0, 1], masks sized to the sparsity factor: local,
@@ -673,9 +699,10 @@ def main():
     ap.add_argument("--no-sweep", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-cold", action="store_true", help="skip the cold-cache launches")
-    ap.add_argument("--suite", default=None, choices=["table3", "e2", "vf"],
+    ap.add_argument("--suite", default=None, choices=["table3", "e2", "vf", "d128"],
                     help="instead of the benchmark line, time the shapes of the paper's Table III, "
                          "of its microbenchmark grid or of its model masks (Section V-F) and print one JSON object")
+    ap.add_argument("--shapes", type=int, default=5, help="--suite d128: only the first N shapes (for a profile of one)")
     ap.add_argument("--dims", default="64,128,256",
                     help="head dimensions of --suite e2 (comma-separated)")
     ap.add_argument("--prepared", action="store_true",
@@ -718,6 +745,7 @@ def main():
     if args.suite:
         print(json.dumps(suite_table3(path) if args.suite == "table3"
                          else suite_vf(path) if args.suite == "vf"
+                         else suite_d128(path, args.shapes) if args.suite == "d128"
                          else suite_e2(path, tuple(int(x) for x in args.dims.split(",")))))
         return
     # (the long-context shapes of Table III can be named too, e.g. for a profile of one of them)
