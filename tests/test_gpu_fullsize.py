@@ -198,7 +198,8 @@ def test_table3_160m_wide_band():
     _table3_case(TABLE3_WORKLOADS["table3_160m"], n_random=16, edge=8)
 
 
-@pytest.mark.parametrize("L,H,W,s", [(40013, 4, 700, 1), (70001, 3, 200, 3), (33000, 8, 65, 1)])
+@pytest.mark.parametrize("L,H,W,s", [(40013, 4, 700, 1), (70001, 3, 200, 3), (33000, 8, 65, 1),
+                                     (50_000_017, 1, 300, 1)])      # (byte offsets past 2^33)
 def test_d128_wide_band(L, H, W, s):
     """Wide fp16 bands at d = 128 (the head size of the models of Table IV) on calls large enough
     for the kernel that keeps all 128 channels of a sub-tile in one wavefront: ragged lengths,
