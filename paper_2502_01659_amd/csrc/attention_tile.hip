@@ -2435,6 +2435,198 @@ __global__ __launch_bounds__(kD) void tile_window_wide_kernel(
                           accumulate != 0);
 }
 
+// fp16, d = 128, explicit masks: one wavefront per work item with all 128 channels of its 32
+// queries (tile_attend_wide_kernel gives each 64-channel slice a wavefront, which repeats the
+// softmax in every slice and exchanges the partial scores through LDS).  A key block is staged as
+// four 64-channel blocks in the layout CoreF16 reads (K channels 0..63, K 64..127, V 0..63,
+// V 64..127: 16 KB per wavefront), K one block ahead as in CoreF16T::run_ldsk; the scores of a
+// block are one chain of eight products over the two K halves, the softmax is done once, the
+// numerators meet the two V halves in eight more products.  Wavefronts claim items of their head
+// from the device counter.  Partial states of multi-segment tiles are written as the two slice
+// records tile_merge_kernel<__half, 128> reads.
+__global__ __attribute__((amdgpu_waves_per_eu(2, 2))) __launch_bounds__(256) void tile_attend128_f16_kernel(
+    const __half* __restrict__ Q, const __half* __restrict__ K, const __half* __restrict__ V,
+    __half* __restrict__ O, float* __restrict__ lse, const int64_t* __restrict__ row_ptr, int64_t L,
+    float scale, void* ws, size_t ws_bytes, int accumulate) {
+  using Core = CoreF16T<2 * kHeadDim>;
+  constexpr int kD = 2 * kHeadDim;
+  constexpr int kBlk = Core::kBlockBytes;
+  __shared__ __attribute__((aligned(16))) char lds_all[4][4 * kBlk];
+  const int32_t H = (int32_t)gridDim.x;
+  const WorkspacePlan pl = plan_workspace(L, H, row_ptr[L], SGA_F16, kD);
+  if (pl.total_bytes > ws_bytes) return;
+  const int lane = threadIdx.x & (kWave - 1);
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int n = lane & 31, h = lane >> 5;
+  char* ldsk = lds_all[wave];                    // K channels 0..63, then 64..127
+  char* ldsv = ldsk + 2 * kBlk;                  // V likewise
+  char* base_ws = static_cast<char*>(ws);
+  const bool negate = scale < 0.f;
+  const float c = softmax_factor(scale);
+  const TileItem* items = reinterpret_cast<const TileItem*>(base_ws + pl.off_items_rec);
+  const int32_t* tile_bad = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_bad);
+  const int32_t* tile_pbase = reinterpret_cast<const int32_t*>(base_ws + pl.off_tile_pbase);
+  const bool parts_fit = tile_parts_fit(pl, ws);
+  const int64_t head = blockIdx.x;
+  const int64_t hoff = head * L * kD;
+  uint32_t* work_next = reinterpret_cast<uint32_t*>(base_ws + pl.off_work_next) + head;
+  const __half* Kh = K + hoff;
+  const __half* Vh = V + hoff;
+  typename Core::Stage sm;
+  sm.init(1, lane);
+  const char* vt0 = Core::vt_base(ldsv, lane, h);
+  float* lse_h = lse ? lse + head * L : nullptr;
+  while (true) {
+    uint32_t claimed = 0;
+    if (lane == 0) claimed = atomicAdd(work_next, 1u);
+    const int64_t w_cur = __builtin_amdgcn_readfirstlane(claimed);
+    if (w_cur >= pl.n_work) {
+      if (lane == 0) claim_exit(work_next, H, gridDim.y * 4);
+      break;
+    }
+    const int4 r0 = reinterpret_cast<const int4*>(items + w_cur)[0];
+    const int64_t slot_raw = reinterpret_cast<const int64_t*>(items + w_cur)[2];
+    const int32_t t = __builtin_amdgcn_readfirstlane(r0.x);
+    const int32_t nblk = __builtin_amdgcn_readfirstlane(r0.y);
+    const int32_t seg = __builtin_amdgcn_readfirstlane(r0.z);
+    const int32_t nseg = __builtin_amdgcn_readfirstlane(r0.w);
+    const int64_t slot0 = uniform64(slot_raw);
+    if (t < 0 || nblk < 0) continue;         // idle item / list overflow: tile left to the gather path
+    if (nseg > 1 && (!parts_fit || tile_bad[t])) continue;
+    const int64_t row_first = (int64_t)t * kTile;
+    const ExplicitBlocks src{reinterpret_cast<const int32_t*>(base_ws + pl.off_pair_blk) + slot0,
+                             reinterpret_cast<const uint32_t*>(base_ws + pl.off_pair_mask) + slot0 * kTile, L};
+    const int64_t qrow = row_first + n;
+    const bool exists = qrow < L;
+    Core lo, hi;                             // channels 0..63 and 64..127 of the same queries
+    lo.load_q(Q + hoff + (exists ? qrow : L - 1) * kD, h, negate);
+    hi.load_q(Q + hoff + (exists ? qrow : L - 1) * kD + kHeadDim, h, negate);
+    TileState st, st_hi;                     // m and l live in st; st_hi holds the accumulators of channels 64..127
+    st.init();
+    st_hi.init();
+    if (nblk > 0) {
+      BlockInfo b = src.get(0, n);
+      BlockInfo b1 = src.get(nblk > 1 ? 1 : 0, n);
+      src.resolve(b);
+      __builtin_amdgcn_wave_barrier();       // reads of the buffers by the work item before are done
+      sm.stage_k(Kh, b, lane, ldsk);
+      sm.stage_k(Kh + kHeadDim, b, lane, ldsk + kBlk);
+      for (int k = 0; k < nblk; ++k) {
+        const bool more = k + 1 < nblk;      // wave-uniform
+        src.resolve(b1);
+        __builtin_amdgcn_wave_barrier();     // the previous block's reads of the staged V are done
+        sm.stage_v(Vh, b, lane, ldsv);
+        sm.stage_v(Vh + kHeadDim, b, lane, ldsv + kBlk);
+        BlockInfo b2 = b1;
+        if (k + 2 < nblk) b2 = src.get(k + 2, n);
+        wait_k_block<8, ExplicitBlocks::kGetLoads>(k + 2 < nblk);   // K block k: older than the V copies (and the record loads)
+        __builtin_amdgcn_wave_barrier();
+        half8 kf[4], kg[4];
+        Core::read_k(ldsk, n, h, kf);
+        Core::read_k(ldsk + kBlk, n, h, kg);
+        wait_lds_reads();                    // the K buffers may be overwritten now
+        __builtin_amdgcn_wave_barrier();
+        if (more) {
+          sm.stage_k(Kh, b1, lane, ldsk);
+          sm.stage_k(Kh + kHeadDim, b1, lane, ldsk + kBlk);
+        }
+        floatx16 sv = {0};
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sv = __builtin_amdgcn_mfma_f32_32x32x16_f16(kf[u], lo.qf[u], sv, 0, 0, 0);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) sv = __builtin_amdgcn_mfma_f32_32x32x16_f16(kg[u], hi.qf[u], sv, 0, 0, 0);
+        if (!b.full) mask_scores(sv, b.word, h);
+        half8 ph[2];
+        const float l_before = st.l;
+        numerators_h(sv, c, st, ph);
+        if (__any(sum_overflowed(st))) {
+          // (see softmax_block_h; the accumulators of the upper channels take the same factor)
+          st.l = l_before;
+          const float m_before = st.m;
+          rescale_state(st, block_max(sv, c, h));
+          const float alpha = __builtin_amdgcn_exp2f(m_before - st.m);
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            st_hi.o[0][r] *= alpha;
+            st_hi.o[1][r] *= alpha;
+          }
+          numerators_h(sv, c, st, ph);
+        }
+        // V block k (and any record load after it) is older than the 8 K copies issued above (if any)
+        wait_staged_v<8>(more);
+        __builtin_amdgcn_wave_barrier();
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+          const half8 a0 = Core::read_va(vt0, u, 0), a1 = Core::read_va(vt0, u, 1);
+          const half8 c0 = Core::read_va(vt0 + kBlk, u, 0), c1 = Core::read_va(vt0 + kBlk, u, 1);
+          st.o[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a0, ph[u], st.o[0], 0, 0, 0);
+          st.o[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1, ph[u], st.o[1], 0, 0, 0);
+          st_hi.o[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(c0, ph[u], st_hi.o[0], 0, 0, 0);
+          st_hi.o[1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(c1, ph[u], st_hi.o[1], 0, 0, 0);
+        }
+        b = b1;
+        b1 = b2;
+      }
+    }
+    if (nseg > 1) {
+      float* part = reinterpret_cast<float*>(base_ws + pl.off_tpartials) +
+                    ((((int64_t)tile_pbase[t] + seg) * H + head) * 2) * (int64_t)kTilePartialFloats;
+      st_hi.m = st.m;
+      st_hi.l = st.l;
+      store_partial(part, st, n, h);
+      store_partial(part + kTilePartialFloats, st_hi, n, h);
+      continue;
+    }
+    const float l = st.l + other_half(st.l, h);
+    const bool empty = !(l > 0.f);
+    const float inv = empty ? 0.f : 1.0f / l;
+    float lse_row = empty ? -INFINITY : (st.m + __builtin_amdgcn_logf(l)) * kLn2;
+    if (accumulate) {
+      if (exists) {
+        // (both half-waves read the earlier lse before the first replaces it)
+        const CarryWeights cw = carry_weights(lse_h[qrow], lse_row);
+        Core::store_row(O + hoff + qrow * kD, st, inv * cw.w_now, cw.w_prev, true, h);
+        Core::store_row(O + hoff + qrow * kD + kHeadDim, st_hi, inv * cw.w_now, cw.w_prev, true, h);
+        if (h == 0) lse_h[qrow] = cw.lse;
+      }
+      continue;
+    }
+    // The tile leaves through the wavefront's LDS (every copy has landed, every read is done) as
+    // whole 256-byte rows, four per instruction, with streaming stores (see CoreF16T::store_tile).
+    constexpr int kPitch = kD * 2 + 16;
+    static_assert(kTile * kPitch <= 4 * kBlk, "output tile fits the wavefront's LDS");
+    char* tile = ldsk;
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int half = 0; half < 2; ++half) {
+      const TileState& part = half ? st_hi : st;
+#pragma unroll
+      for (int cb = 0; cb < 2; ++cb)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          uint2 w;
+          w.x = __builtin_bit_cast(uint32_t, __floats2half2_rn(part.o[cb][4 * g] * inv, part.o[cb][4 * g + 1] * inv));
+          w.y = __builtin_bit_cast(uint32_t,
+                                   __floats2half2_rn(part.o[cb][4 * g + 2] * inv, part.o[cb][4 * g + 3] * inv));
+          *reinterpret_cast<uint2*>(tile + n * kPitch + (half * kHeadDim + cb * 32 + 8 * g + 4 * h) * 2) = w;
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+    const int64_t left = L - row_first;
+    const int n_rows = left < kTile ? (int)left : kTile;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int r = (lane >> 4) + 4 * i;
+      const uint4 v = *reinterpret_cast<const uint4*>(tile + r * kPitch + (lane & 15) * 16);
+      if (r < n_rows)
+        __builtin_nontemporal_store(__builtin_bit_cast(half8, v),
+                                    reinterpret_cast<half8*>(O + hoff + (row_first + r) * kD + (lane & 15) * 8));
+    }
+    if (lse_h && h == 0 && n < n_rows) lse_h[row_first + n] = lse_row;
+    wait_lds_reads();                        // (the tile has left before the next item stages into this space)
+  }
+}
+
 // The implicit non-local mask at head dimensions 128 and 256: the two kernels of the 64-channel
 // form (tile_nonlocal_cols_kernel, tile_nonlocal_rows_kernel) with one workgroup of kD / 64
 // wavefronts per tile, each on its 64-channel slice (see tile_attend_wide_kernel).
@@ -3249,10 +3441,20 @@ sga_status run_tile_explicit_wide_d(const AttnArgs& a) {
   if (per_head < 1) per_head = 1;
   if (per_head > n_tiles + 64) per_head = n_tiles + 64;
   constexpr int kPipe = DtypeOf<T>::code == SGA_F16 ? kPipeLdsK : kPipeRegK;
-  profile_mark_begin(a.stream, "tile_attend_wide_kernel");
-  hipLaunchKernelGGL((tile_attend_wide_kernel<T, kD, kPipe>), dim3((unsigned)a.H, (unsigned)per_head),
-                     dim3(kD), 0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes,
-                     a.accumulate ? 1 : 0);
+  if constexpr (DtypeOf<T>::code == SGA_F16 && kD == 128) {
+    // one wavefront per item with all 128 channels; two workgroups of four wavefronts per CU
+    int64_t wgs = 512 / a.H;
+    if (wgs < 1) wgs = 1;
+    if (wgs > (n_tiles + 3) / 4 + 16) wgs = (n_tiles + 3) / 4 + 16;
+    profile_mark_begin(a.stream, "tile_attend128_f16_kernel");
+    hipLaunchKernelGGL(tile_attend128_f16_kernel, dim3((unsigned)a.H, (unsigned)wgs), dim3(256), 0, a.stream, Q, K,
+                       V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes, a.accumulate ? 1 : 0);
+  } else {
+    profile_mark_begin(a.stream, "tile_attend_wide_kernel");
+    hipLaunchKernelGGL((tile_attend_wide_kernel<T, kD, kPipe>), dim3((unsigned)a.H, (unsigned)per_head),
+                       dim3(kD), 0, a.stream, Q, K, V, O, a.lse, a.row_ptr, a.L, a.scale, a.ws, a.ws_bytes,
+                       a.accumulate ? 1 : 0);
+  }
   profile_mark_end(a.stream);
   if (!a.prepared || a.plan_multi_tiles > 0)
     hipLaunchKernelGGL((tile_merge_kernel<T, kD>), dim3(16, (unsigned)a.H, kTile), dim3(256), 0, a.stream,

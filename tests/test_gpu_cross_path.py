@@ -270,3 +270,39 @@ def test_d128_wide_bands_agree_with_row_kernels(case):
         torch.cuda.synchronize()
         assert ((O3.float() - O1.float()).abs() / (1 + O1.float().abs())).max().item() <= 2 * TOL["f16"]
         assert (l3 - l1 - 0.6931472).abs().max().item() <= 2e-3
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_explicit_d128_tiles_agree_with_row_kernels_and_prepared_graphs(seed):
+    """The explicit fp16 kernel at d = 128 (one wavefront per work item with all 128 channels) on
+    the seeded masks of the d = 64 test: every mask family, multi-segment tiles (global rows,
+    BigBird global blocks), ragged lengths, negative scales; prepared graphs bit for bit."""
+    import torch
+    rng = random.Random(5000 + seed)
+    spec = _explicit_spec(rng, seed)
+    H = rng.choice([1, 2, 4])
+    sigma = rng.choice([0.3, 1.0])
+    scale = rng.choice([0.0884, -0.0884, 0.2])
+    print("case", seed, spec, "H", H, "sigma", sigma, "scale", scale, flush=True)
+    L = spec.L
+    Q, K, V = torch_qkv(H, L, 128, "f16", sigma, seed, "cuda:0")
+    rp, ci = sga.build_mask(spec)
+    nnz = int(rp[-1])
+    ws = sga.alloc_workspace(L, H, 128, "f16", nnz)
+    O1, l1 = sga.attention_forward(Q, K, V, rp, ci, scale, workspace=ws, path=sga.PATH_TILE, want_lse=True)
+    O2, l2 = sga.attention_forward(Q, K, V, rp, ci, scale, path=sga.PATH_GATHER, want_lse=True)
+    ws2 = sga.alloc_workspace(L, H, 128, "f16", nnz)
+    ws2.fill_(0x5A)
+    plan = sga.graph_prepare(rp, ci, H, 128, "f16", ws2)
+    O3, l3 = sga.attention_forward_prepared(Q, K, V, rp, ci, scale, plan, ws2, want_lse=True)
+    torch.cuda.synchronize()
+    assert torch.equal(O1, O3) and torch.equal(l1, l3)
+    _agree(O1, l1, O2, l2, "f16", max(1.0, sigma * sigma * abs(scale) * 11.3 * 8))
+    # a second call on the same state: O unchanged, lse + ln 2
+    O4, l4 = O1.clone(), l1.clone()
+    sga.attention_accumulate(Q, K, V, rp, ci, scale, O4, l4, workspace=ws, path=sga.PATH_TILE)
+    torch.cuda.synchronize()
+    fin = torch.isfinite(l1)
+    assert ((O4.float() - O1.float()).abs() / (1 + O1.float().abs())).max().item() <= 2 * TOL["f16"]
+    if fin.any():
+        assert (l4[fin] - l1[fin] - 0.6931472).abs().max().item() <= 2e-3
