@@ -445,7 +445,29 @@ def suite_d128(path, n_shapes=5):
                      "mfma_f16_TFLOPs": 4.0 * 128 * edges / (ms * 1e-3) / 1e12})
         del Q, K, V, O, ws
         torch.cuda.empty_cache()
-    return {"suite": "d128", "unit": "ms per forward (sga_attention_forward_implicit)", "rows": rows}
+    # explicit masks at the same head size, on a prepared graph: workload 4's and workload 2's masks
+    # and a +-512 window handed over as CSR
+    if n_shapes >= 5:
+        from sga_inputs import WORKLOADS
+        for name, spec, H in (("cfg4 mask", WORKLOADS["cfg4_bigbird_1m"].mask, 4),
+                              ("cfg2 mask", WORKLOADS["cfg2_longformer_64k"].mask, 8),
+                              ("sliding +-512 as CSR", MaskSpec(KIND_SLIDING, 1 << 18, window=512), 4)):
+            rp, ci = sga.build_mask(spec)
+            nnz = int(rp[-1])
+            Q, K, V = torch_qkv(H, spec.L, 128, "f16", 0.5, BASE_SEED, "cuda:0")
+            O = torch.empty_like(Q)
+            ws = sga.alloc_workspace(spec.L, H, 128, "f16", nnz)
+            plan = sga.graph_prepare(rp, ci, H, 128, "f16", ws)
+            ms = _time_calls(lambda: sga.attention_forward_prepared(Q, K, V, rp, ci, 128 ** -0.5, plan, ws, O=O),
+                             steps=10, warmup=3)
+            rows.append({"mask": name, "entry": "csr, prepared graph", "L": spec.L, "H": H, "d": 128, "dtype": "f16",
+                         "edges": nnz * H, "ms": ms, "edges_per_s": nnz * H / (ms * 1e-3),
+                         "hbm_algorithmic_GBps": 4 * spec.L * H * 128 * 2 / (ms * 1e-3) / 1e9,
+                         "mfma_f16_TFLOPs": 4.0 * 128 * nnz * H / (ms * 1e-3) / 1e12})
+            del Q, K, V, O, ws, rp, ci
+            torch.cuda.empty_cache()
+    return {"suite": "d128", "unit": "ms per forward (implicit windows, then explicit masks on prepared graphs)",
+            "rows": rows}
 
 
 def suite_e2(path, dims=(64, 128, 256)):
